@@ -1,0 +1,262 @@
+"""CPU oracle for the Proximity-FLAT retrieval step.  TEST INFRASTRUCTURE ONLY.
+
+This is a deliberately plain, slow, float64 restatement of what the retrieval
+step computes, written from the paper and sharing nothing with the GPU path:
+only tests, the smoke check and the benchmark's CPU-baseline leg may import it.
+The product (the HIP library and its Python binding) never calls into it.
+
+What it follows
+---------------
+* ``FlatCacheOracle.lookup`` is the cache lookup procedure of Algorithm 1
+  (Section 3.1), one query at a time, in the order the paper gives: distances
+  from the query to every cached key, the nearest key, the test against the
+  tolerance tau, and on a miss the database call, the eviction when the cache
+  already holds c entries, and the insertion of (query, result).
+* ``exact_knn`` is the database call for a flat index, i.e. the definition of
+  nearest-neighbour search in Section 2.2: the k stored vectors closest to the
+  query, returned as a ranked list of indices.  It is brute force: every
+  Euclidean distance in direct-difference form, then a full stable sort.
+* Eviction follows Section 3.3.2: FIFO removes the oldest inserted entry
+  whatever its use; LRU removes the entry unused for longest, where a hit
+  uses the matched entry and an insertion uses the new one.
+
+Readings where the paper is silent (each listed in the design notes):
+the hit test is ``<=``; an empty cache misses; equal nearest distances pick
+the older entry; only the matched entry is refreshed under LRU; a hit inserts
+nothing and returns the stored list unchanged (re-ranking factor 1); ranked
+lists order equal distances by document index and are padded with -1 / +inf
+when the index holds fewer than k vectors; capacity 0 disables caching.
+
+Parity status: every function here is pinned by tests that do not re-use its
+own formula (hand-worked eviction streams, reduction to textbook exact-match
+FIFO/LRU caches, brute-force loops, library nearest-neighbour routines, closed
+forms for tau = 0 and tau = infinity).  Document ids at full corpus scale have
+no independent pin beyond those small cases ("parity unpinned" at that scale).
+"""
+from __future__ import annotations
+
+from typing import Callable, List, Optional, Tuple
+
+import numpy as np
+
+POLICY_FIFO = 0
+POLICY_LRU = 1
+
+
+def as_f64_rows(a) -> np.ndarray:
+    """Exact widening of float32 (or already-float64) rows to float64."""
+    return np.asarray(a, dtype=np.float64)
+
+
+def l2_distances(q: np.ndarray, rows: np.ndarray) -> np.ndarray:
+    """Euclidean distance from q to every row: sqrt(sum_i (q_i - x_i)^2), float64."""
+    diff = as_f64_rows(rows) - as_f64_rows(q)[None, :]
+    return np.sqrt(np.sum(diff * diff, axis=1))
+
+
+def exact_knn(corpus: np.ndarray, q: np.ndarray, k: int,
+              chunk_rows: int = 1 << 18) -> Tuple[np.ndarray, np.ndarray]:
+    """Ranked k nearest corpus rows of q (Section 2.2): ids int64[k], dists float64[k].
+
+    Rows are independent, so distances are evaluated a block of rows at a time
+    only to bound memory; the ranking is one stable sort over all of them, so
+    equal distances keep ascending document index.
+    """
+    n = 0 if corpus is None else int(corpus.shape[0])
+    d = np.empty(n, dtype=np.float64)
+    for r0 in range(0, n, chunk_rows):
+        r1 = min(n, r0 + chunk_rows)
+        d[r0:r1] = l2_distances(q, corpus[r0:r1])
+    order = np.argsort(d, kind="stable")[:k]
+    ids = np.full(k, -1, dtype=np.int64)
+    dists = np.full(k, np.inf, dtype=np.float64)
+    ids[: len(order)] = order
+    dists[: len(order)] = d[order]
+    return ids, dists
+
+
+class _Entry:
+    __slots__ = ("key", "ids", "dists", "seq")
+
+    def __init__(self, key, ids, dists, seq):
+        self.key, self.ids, self.dists, self.seq = key, ids, dists, seq
+
+
+class FlatCacheOracle:
+    """Algorithm 1 with its stored state: tolerance per call, capacity c, database D, dict C.
+
+    ``entries`` is kept in eviction order: index 0 is the next victim.  For
+    FIFO that is insertion order; for LRU it is order of last use.
+    ``retrieve(q) -> (ids, dists)`` is the database call; by default the exact
+    flat search over ``corpus``.
+    """
+
+    def __init__(self, corpus: Optional[np.ndarray], capacity: int, k: int, policy: int,
+                 retrieve: Optional[Callable] = None):
+        if policy not in (POLICY_FIFO, POLICY_LRU):
+            raise ValueError("policy must be FIFO (0) or LRU (1)")
+        self.corpus = corpus
+        self.capacity = int(capacity)
+        self.k = int(k)
+        self.policy = int(policy)
+        self.retrieve = retrieve if retrieve is not None else (lambda q: exact_knn(corpus, q, self.k))
+        self.entries: List[_Entry] = []
+        self.n_queries = 0
+        self.n_hits = 0
+        self.n_misses = 0
+        self.n_inserts = 0
+        self.n_evictions = 0
+        self.n_scans = 0
+
+    # -- Algorithm 1 -------------------------------------------------------
+    def lookup(self, q, tau: float):
+        """Process one query.  Returns (ids, dists, hit, source_seq).
+
+        ``source_seq`` is the stream position of the query whose database
+        result is returned: the query itself on a miss, the matched key's
+        inserting query on a hit.
+        """
+        q64 = as_f64_rows(q).copy()
+        tau = float(tau)
+        seq = self.n_queries
+        self.n_queries += 1
+
+        best = -1
+        if self.entries:
+            keys = np.stack([e.key for e in self.entries])
+            dists = l2_distances(q64, keys)
+            min_dist = dists.min()
+            # nearest key; among equal distances the oldest insertion
+            cands = [i for i in range(len(self.entries)) if dists[i] == min_dist]
+            best = min(cands, key=lambda i: self.entries[i].seq)
+            if min_dist <= tau:
+                e = self.entries[best]
+                self.n_hits += 1
+                if self.policy == POLICY_LRU:
+                    self.entries.append(self.entries.pop(best))
+                return e.ids.copy(), e.dists.copy(), True, e.seq
+
+        ids, nd = self.retrieve(q64)
+        self.n_scans += 1
+        self.n_misses += 1
+        if self.capacity > 0:
+            if len(self.entries) >= self.capacity:
+                self.entries.pop(0)
+                self.n_evictions += 1
+            self.entries.append(_Entry(q64, np.asarray(ids).copy(), np.asarray(nd).copy(), seq))
+            self.n_inserts += 1
+        return np.asarray(ids).copy(), np.asarray(nd).copy(), False, seq
+
+    def lookup_stream(self, queries, tau: float):
+        """Process rows of ``queries`` in order.  Returns ids[n,k], dists[n,k], hit[n], source_seq[n]."""
+        n = len(queries)
+        ids = np.empty((n, self.k), dtype=np.int64)
+        dists = np.empty((n, self.k), dtype=np.float64)
+        hit = np.zeros(n, dtype=np.uint8)
+        src = np.empty(n, dtype=np.int64)
+        for t in range(n):
+            ids[t], dists[t], h, src[t] = self.lookup(queries[t], tau)
+            hit[t] = 1 if h else 0
+        return ids, dists, hit, src
+
+    # -- inspection ----------------------------------------------------------
+    def dump_seq(self) -> np.ndarray:
+        """Inserting-query positions of the live keys, next victim first."""
+        return np.array([e.seq for e in self.entries], dtype=np.int64)
+
+    def dump_keys(self) -> np.ndarray:
+        if not self.entries:
+            return np.zeros((0, 0), dtype=np.float64)
+        return np.stack([e.key for e in self.entries])
+
+    def dump_ids(self) -> np.ndarray:
+        if not self.entries:
+            return np.zeros((0, self.k), dtype=np.int64)
+        return np.stack([e.ids for e in self.entries])
+
+    def stats(self) -> dict:
+        return dict(queries=self.n_queries, hits=self.n_hits, misses=self.n_misses,
+                    inserts=self.n_inserts, evictions=self.n_evictions, scans=self.n_scans,
+                    size=len(self.entries))
+
+
+# ---------------------------------------------------------------------------
+# Deferred-scan form, for streams whose literal replay would take hours.
+#
+# The branch of Algorithm 1 reads only distances between the query and cached
+# keys, never a database result, so the sequence of hits, misses, insertions and
+# evictions can be replayed first with the database call left out, and the
+# database results filled in afterwards for the queries that missed.  The tests
+# show this gives the same outputs as the literal form on the small workload.
+# ---------------------------------------------------------------------------
+
+def simulate_decisions(queries, tau: float, capacity: int, policy: int,
+                       oracle: Optional[FlatCacheOracle] = None):
+    """Replay Algorithm 1's control flow only.  Returns (hit[n], source_seq[n], oracle)."""
+    k_dummy = 1
+    if oracle is None:
+        oracle = FlatCacheOracle(None, capacity, k_dummy, policy,
+                                 retrieve=lambda q: (np.full(k_dummy, -1, np.int64),
+                                                     np.full(k_dummy, np.inf)))
+    _, _, hit, src = oracle.lookup_stream(queries, tau)
+    return hit, src, oracle
+
+
+def batched_exact_knn(corpus: np.ndarray, queries: np.ndarray, k: int,
+                      chunk_rows: int = 1 << 16) -> Tuple[np.ndarray, np.ndarray]:
+    """Ranked exact k-NN for several queries at once, float64.
+
+    Squared distances come from the identity |q-x|^2 = |q|^2 + |x|^2 - 2 q.x with
+    a float64 matrix product per block of corpus rows; each block keeps its k
+    best by (distance, index), the survivors are ranked by one stable sort, and
+    the k winners' distances are then re-evaluated in direct-difference form.
+    """
+    q64 = as_f64_rows(queries)
+    m, n = q64.shape[0], (0 if corpus is None else int(corpus.shape[0]))
+    qn = np.sum(q64 * q64, axis=1)
+    cand_d2 = [np.empty(0) for _ in range(m)]
+    cand_id = [np.empty(0, dtype=np.int64) for _ in range(m)]
+    for r0 in range(0, n, chunk_rows):
+        r1 = min(n, r0 + chunk_rows)
+        x = as_f64_rows(corpus[r0:r1])
+        d2 = qn[:, None] + np.sum(x * x, axis=1)[None, :] - 2.0 * (q64 @ x.T)
+        kk = min(k, r1 - r0)
+        kth = np.partition(d2, kk - 1, axis=1)[:, kk - 1]
+        for i in range(m):
+            # every row of the block at or below the block's k-th smallest value:
+            # at least k of them, more only when values tie exactly
+            keep = np.flatnonzero(d2[i] <= kth[i])
+            cand_d2[i] = np.concatenate([cand_d2[i], d2[i, keep]])
+            cand_id[i] = np.concatenate([cand_id[i], keep + r0])
+    ids = np.full((m, k), -1, dtype=np.int64)
+    dists = np.full((m, k), np.inf)
+    for i in range(m):
+        # candidate ids ascend (blocks in order, rows in order), so a stable sort
+        # on distance ranks equal distances by document index
+        order = np.argsort(cand_d2[i], kind="stable")[:k]
+        best = cand_id[i][order]
+        ids[i, : len(best)] = best
+        if len(best):
+            dists[i, : len(best)] = l2_distances(q64[i], corpus[best])
+    return ids, dists
+
+
+def lookup_stream_deferred(corpus, queries, tau: float, capacity: int, k: int, policy: int,
+                           knn_chunk: int = 256):
+    """Outputs of ``FlatCacheOracle.lookup_stream`` computed decisions-first.
+
+    Returns ids[n,k], dists[n,k], hit[n], source_seq[n], decision_oracle.
+    """
+    hit, src, dec = simulate_decisions(queries, tau, capacity, policy)
+    n = len(queries)
+    miss_rows = np.flatnonzero(hit == 0)
+    ids = np.empty((n, k), dtype=np.int64)
+    dists = np.empty((n, k), dtype=np.float64)
+    for c0 in range(0, len(miss_rows), knn_chunk):
+        rows = miss_rows[c0:c0 + knn_chunk]
+        i_, d_ = batched_exact_knn(corpus, np.asarray(queries)[rows], k)
+        ids[rows], dists[rows] = i_, d_
+    hit_rows = np.flatnonzero(hit == 1)
+    ids[hit_rows] = ids[src[hit_rows]]
+    dists[hit_rows] = dists[src[hit_rows]]
+    return ids, dists, hit, src, dec

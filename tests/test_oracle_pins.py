@@ -1,0 +1,302 @@
+"""Pins for the CPU oracle: checks against things other than the oracle itself.
+
+Hand-worked eviction traces (tests/golden/eviction_streams.txt), reductions to
+textbook exact-match FIFO/LRU caches, brute-force loops, library
+nearest-neighbour routines and closed forms for the extreme tolerances.
+"""
+import collections
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import proximity_oracle as po
+from paper_2503_05530_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def line_vectors(xs, dim=4):
+    q = np.zeros((len(xs), dim), dtype=np.float32)
+    q[:, 0] = np.asarray(xs, dtype=np.float32)
+    return q
+
+
+def read_eviction_cases():
+    cases = []
+    with open(os.path.join(GOLDEN, "eviction_streams.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, policy, cap, tau, xs, flags, ev, left, src = [p.strip() for p in line.split("|")]
+            cases.append(dict(
+                name=name, policy=po.POLICY_FIFO if policy == "FIFO" else po.POLICY_LRU,
+                capacity=int(cap), tau=float(tau), xs=[float(v) for v in xs.split()],
+                flags=flags, evictions=int(ev), left=[int(v) for v in left.split()],
+                src=[int(v) for v in src.split()]))
+    return cases
+
+
+EVICTION_CASES = read_eviction_cases()
+
+
+def small_corpus(n=64, dim=4, seed=3):
+    return W.corpus_f32(n, dim, seed)
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1 + Section 3.3.2 against hand-worked traces
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("case", EVICTION_CASES, ids=[c["name"] for c in EVICTION_CASES])
+def test_hand_worked_eviction_traces(case):
+    corpus = small_corpus()
+    orc = po.FlatCacheOracle(corpus, case["capacity"], 3, case["policy"])
+    q = line_vectors(case["xs"])
+    ids, dists, hit, src = orc.lookup_stream(q, case["tau"])
+    assert "".join("H" if h else "M" for h in hit) == case["flags"]
+    assert orc.n_evictions == case["evictions"]
+    assert orc.dump_seq().tolist() == case["left"]
+    assert src.tolist() == case["src"]
+    # every returned list is the database result of the query named by `src`
+    for t in range(len(q)):
+        want, _ = po.exact_knn(corpus, q[src[t]], 3)
+        assert ids[t].tolist() == want.tolist()
+
+
+def test_two_similar_queries_walkthrough():
+    """Section 3.1's example: q1 misses and is stored; a close q2 gets q1's indices."""
+    corpus = small_corpus(200, 16, 5)
+    rng = np.random.default_rng(11)
+    q1 = rng.standard_normal(16).astype(np.float32)
+    q2 = (q1 + 1e-3 * rng.standard_normal(16)).astype(np.float32)
+    orc = po.FlatCacheOracle(corpus, 8, 5, po.POLICY_LRU)
+    i1, _, h1, _ = orc.lookup(q1, 0.5)
+    i2, _, h2, s2 = orc.lookup(q2, 0.5)
+    assert (h1, h2, s2) == (False, True, 0)
+    assert i1.tolist() == i2.tolist()
+    assert orc.stats()["scans"] == 1
+
+
+# ---------------------------------------------------------------------------
+# The database call against brute force and library routines
+# ---------------------------------------------------------------------------
+def test_exact_knn_matches_pure_python_loops():
+    rng = np.random.default_rng(0)
+    corpus = rng.standard_normal((37, 5)).astype(np.float32)
+    q = rng.standard_normal(5).astype(np.float32)
+    d = []
+    for j in range(37):
+        acc = 0.0
+        for i in range(5):
+            diff = float(q[i]) - float(corpus[j, i])
+            acc += diff * diff
+        d.append((math.sqrt(acc), j))
+    d.sort()
+    ids, dists = po.exact_knn(corpus, q, 7)
+    assert ids.tolist() == [j for _, j in d[:7]]
+    np.testing.assert_allclose(dists, [v for v, _ in d[:7]], rtol=1e-14)
+
+
+def test_exact_knn_matches_library_neighbours():
+    from scipy.spatial.distance import cdist
+    from sklearn.neighbors import NearestNeighbors
+
+    rng = np.random.default_rng(1)
+    corpus = rng.standard_normal((500, 24))
+    queries = rng.standard_normal((6, 24))
+    nn = NearestNeighbors(n_neighbors=9, algorithm="brute", metric="euclidean").fit(corpus)
+    lib_d, lib_i = nn.kneighbors(queries)
+    full = cdist(queries, corpus, metric="euclidean")
+    for r in range(6):
+        ids, dists = po.exact_knn(corpus, queries[r], 9)
+        assert ids.tolist() == lib_i[r].tolist()
+        np.testing.assert_allclose(dists, lib_d[r], rtol=1e-10)
+        np.testing.assert_allclose(dists, np.sort(full[r])[:9], rtol=1e-12)
+
+
+def test_unit_norm_ranking_is_inner_product_ranking():
+    """For unit rows |q-x|^2 = 2 - 2 q.x, so L2 order is descending inner-product order."""
+    corpus = W.corpus_f32(3000, 48, 7).astype(np.float64)
+    corpus /= np.linalg.norm(corpus, axis=1, keepdims=True)
+    q = W.base_queries(4, 48, 7)
+    for r in range(4):
+        ids, dists = po.exact_knn(corpus, q[r], 12)
+        ip = corpus @ q[r]
+        assert ids.tolist() == np.argsort(-ip, kind="stable")[:12].tolist()
+        np.testing.assert_allclose(dists ** 2, 2.0 - 2.0 * ip[ids], rtol=0, atol=1e-12)
+
+
+def test_exact_knn_ties_and_padding():
+    corpus = np.zeros((6, 3), dtype=np.float32)
+    corpus[:, 0] = [2, 1, 1, 5, 1, 2]          # three rows at distance 1, two at distance 2
+    ids, dists = po.exact_knn(corpus, np.zeros(3, np.float32), 4)
+    assert ids.tolist() == [1, 2, 4, 0]
+    assert dists.tolist() == [1.0, 1.0, 1.0, 2.0]
+    ids, dists = po.exact_knn(corpus, np.zeros(3, np.float32), 8)
+    assert ids.tolist() == [1, 2, 4, 0, 5, 3, -1, -1]
+    assert np.isinf(dists[6:]).all()
+    ids, dists = po.exact_knn(None, np.zeros(3, np.float32), 2)
+    assert ids.tolist() == [-1, -1] and np.isinf(dists).all()
+
+
+def test_batched_knn_equals_literal_knn_including_ties():
+    rng = np.random.default_rng(5)
+    corpus = rng.standard_normal((700, 16)).astype(np.float32)
+    corpus[100] = corpus[3]
+    corpus[650] = corpus[3]
+    queries = rng.standard_normal((9, 16)).astype(np.float32)
+    queries[0] = corpus[3]                      # distance 0 to three identical rows
+    b_ids, b_d = po.batched_exact_knn(corpus, queries, 11, chunk_rows=128)
+    for r in range(9):
+        ids, d = po.exact_knn(corpus, queries[r], 11)
+        assert b_ids[r].tolist() == ids.tolist()
+        np.testing.assert_allclose(b_d[r], d, rtol=1e-13, atol=1e-15)
+    assert b_ids[0, :3].tolist() == [3, 100, 650]
+
+
+# ---------------------------------------------------------------------------
+# Extreme tolerances and counters
+# ---------------------------------------------------------------------------
+def test_zero_tolerance_never_hits_without_repeats_and_returns_exact_knn():
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(2000, w.dim, w.seed)
+    q = W.stream_for(w, 60)
+    orc = po.FlatCacheOracle(corpus, 50, 10, po.POLICY_FIFO)
+    ids, dists, hit, src = orc.lookup_stream(q, 0.0)
+    assert hit.sum() == 0
+    from sklearn.neighbors import NearestNeighbors
+    nn = NearestNeighbors(n_neighbors=10, algorithm="brute").fit(corpus.astype(np.float64))
+    lib_d, lib_i = nn.kneighbors(q.astype(np.float64))
+    assert (ids == lib_i).all()
+    np.testing.assert_allclose(dists, lib_d, rtol=1e-9)
+
+
+def test_zero_tolerance_repeat_hits_and_still_returns_exact_knn():
+    corpus = small_corpus(300, 8, 2)
+    rng = np.random.default_rng(4)
+    a, b = rng.standard_normal((2, 8)).astype(np.float32)
+    orc = po.FlatCacheOracle(corpus, 4, 5, po.POLICY_LRU)
+    ids, _, hit, _ = orc.lookup_stream(np.stack([a, b, a, b, a]), 0.0)
+    assert hit.tolist() == [0, 0, 1, 1, 1]
+    assert ids[2].tolist() == po.exact_knn(corpus, a, 5)[0].tolist()
+    assert ids[3].tolist() == po.exact_knn(corpus, b, 5)[0].tolist()
+
+
+def test_huge_tolerance_hits_everything_after_the_first_query():
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(1500, w.dim, w.seed)
+    q = W.stream_for(w, 40)
+    for policy in (po.POLICY_FIFO, po.POLICY_LRU):
+        orc = po.FlatCacheOracle(corpus, 3, 10, policy)
+        ids, _, hit, src = orc.lookup_stream(q, 1e9)
+        assert hit.tolist() == [0] + [1] * 39
+        first = po.exact_knn(corpus, q[0], 10)[0]
+        assert (ids == first[None, :]).all()
+        assert (src == 0).all()
+
+
+@pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
+@pytest.mark.parametrize("capacity", [1, 7, 500])
+def test_counters_obey_algorithm_one(policy, capacity):
+    w = W.WORKLOADS["tiny"]
+    q = W.stream_for(w, 400)
+    hit, src, orc = po.simulate_decisions(q, 0.25, capacity, policy)
+    s = orc.stats()
+    assert s["hits"] + s["misses"] == s["queries"] == 400
+    assert s["misses"] == s["scans"] == s["inserts"]
+    assert s["evictions"] == max(0, s["misses"] - capacity)
+    assert s["size"] == min(capacity, s["misses"])
+    assert int(hit.sum()) == s["hits"]
+
+
+# ---------------------------------------------------------------------------
+# Reduction to textbook exact-match caches
+# ---------------------------------------------------------------------------
+def textbook_cache_flags(keys, capacity, policy):
+    """Hit/miss sequence of a classical exact-match FIFO or LRU cache over hashable keys."""
+    store = collections.OrderedDict()
+    flags = []
+    for key in keys:
+        if key in store:
+            flags.append(1)
+            if policy == po.POLICY_LRU:
+                store.move_to_end(key)
+        else:
+            flags.append(0)
+            if capacity > 0:
+                if len(store) >= capacity:
+                    store.popitem(last=False)
+                store[key] = True
+    return flags
+
+
+@pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
+def test_zero_tolerance_is_an_exact_match_cache(policy):
+    """Section 3.3.3: tau = 0 is a cache with exact matching."""
+    rng = np.random.default_rng(9)
+    vocab = rng.standard_normal((40, 12)).astype(np.float32)
+    which = rng.integers(0, 40, size=600)
+    hit, _, _ = po.simulate_decisions(vocab[which], 0.0, 9, policy)
+    assert hit.tolist() == textbook_cache_flags(which.tolist(), 9, policy)
+
+
+@pytest.mark.parametrize("name", ["tiny"])
+def test_tiny_stream_reduces_to_cache_over_base_ids(name):
+    """Rewordings of one base lie ~0.14 apart, different bases > 1.2 apart, so at
+    tau = 0.25 the approximate cache behaves as an exact-match cache keyed by base id."""
+    w = W.WORKLOADS[name]
+    idx = W.zipf_choice(w.n_stream, w.n_bases, w.zipf_s, w.seed)
+    q = W.stream_for(w)
+    for policy in (po.POLICY_FIFO, po.POLICY_LRU):
+        hit, _, orc = po.simulate_decisions(q, w.tau, w.capacity, policy)
+        assert hit.tolist() == textbook_cache_flags(idx.tolist(), w.capacity, policy)
+    hit, _, orc = po.simulate_decisions(q, w.tau, w.capacity, w.policy)
+    # counts an independent simulation of this recipe also reached
+    assert int(hit.sum()) == 697 and orc.n_evictions == 253
+    assert "".join(str(int(h)) for h in hit[:16]) == "0001101100100010"
+    hit0, _, orc0 = po.simulate_decisions(q, 0.1, w.capacity, w.policy)
+    assert int(hit0.sum()) == 0 and orc0.n_evictions == 950
+
+
+# ---------------------------------------------------------------------------
+# Deferred-scan form equals the literal form
+# ---------------------------------------------------------------------------
+def test_deferred_form_equals_literal_form():
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(4000, w.dim, w.seed)
+    q = W.stream_for(w, 300)
+    for policy, cap in ((po.POLICY_FIFO, 50), (po.POLICY_LRU, 20)):
+        lit = po.FlatCacheOracle(corpus, cap, 10, policy)
+        ids, dists, hit, src = lit.lookup_stream(q, 0.25)
+        d_ids, d_dists, d_hit, d_src, dec = po.lookup_stream_deferred(corpus, q, 0.25, cap, 10, policy)
+        assert (hit == d_hit).all() and (src == d_src).all()
+        assert (ids == d_ids).all()
+        np.testing.assert_allclose(dists, d_dists, rtol=1e-13)
+        assert dec.dump_seq().tolist() == lit.dump_seq().tolist()
+
+
+# ---------------------------------------------------------------------------
+# Input generators (recipe checks, not method arithmetic)
+# ---------------------------------------------------------------------------
+def test_generator_recipe_is_stable():
+    w = W.WORKLOADS["tiny"]
+    idx = W.zipf_choice(w.n_stream, w.n_bases, w.zipf_s, w.seed)
+    assert idx[:16].tolist() == [0, 3, 12, 0, 0, 2, 0, 3, 5, 1, 5, 74, 16, 19, 0, 76]
+    q = W.stream_for(w, 8)
+    np.testing.assert_allclose(q[0, :4], [0.00262298, -0.03258461, -0.02650609, -0.03384795], atol=2e-8)
+    np.testing.assert_allclose(np.linalg.norm(q.astype(np.float64), axis=1), 1.0, atol=1e-6)
+    assert (W.stream_for(w, 8) == W.stream_for(w)[:8]).all()
+    x = W.corpus_f32(100, 32, 1, chunk_rows=7)
+    assert (x == W.corpus_f32(100, 32, 1)).all()
+
+
+def test_bf16_rounding_is_nearest_even():
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.0e-39, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8],
+                 dtype=np.float32)
+    bits = W.f32_to_bf16_bits(x)
+    back = W.bf16_bits_to_f32(bits)
+    import torch
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert (back == ref).all()
