@@ -1,0 +1,194 @@
+/*
+ * proximity.h -- C ABI of the Proximity-FLAT retrieval step on one AMD Instinct GPU.
+ *
+ * The library implements the per-query retrieval step of an approximate
+ * key-value cache placed in front of a vector index (Algorithm 1, Section 3.1):
+ * each query embedding is compared with every cached query key (Euclidean
+ * distance); if the nearest key lies within the tolerance tau the cached list of
+ * document indices is returned, otherwise the index is searched exactly for the
+ * k nearest documents (the nearest-neighbour search of Section 2.2), the oldest
+ * (FIFO) or least recently used (LRU) entry is evicted when the cache already
+ * holds c entries (Section 3.3.2), and the query with its result is stored.
+ *
+ * Queries are an ordered stream (Section 3.1 processes one query at a time).
+ * A call may hand over many rows; the result is exactly what processing the
+ * rows one at a time in row order would give, including hits on keys inserted
+ * by earlier rows of the same call and evictions that happen between them.
+ *
+ * Conventions
+ *   - DEVICE pointers are HIP device memory on the handle's device; HOST
+ *     pointers are ordinary host memory.  The library never takes ownership of
+ *     a caller buffer.
+ *   - All matrices are dense row-major.
+ *   - Every function returns PROXIMITY_OK (0) or a negative error code.  No
+ *     C++ exception or abort crosses this boundary.  Argument errors are found
+ *     before any GPU work is enqueued and leave the handle unchanged; the text
+ *     of the last error is available from proximity_last_error().
+ *   - A handle is an ordered stream consumer and is not thread-safe.
+ *   - The library allocates all of its device memory in proximity_create().
+ *     proximity_search_batch() and proximity_knn_batch() allocate nothing and
+ *     never wait for the device: the number of misses is consumed on the
+ *     device, and results are valid once the given stream reaches the end of
+ *     the call's work.
+ */
+#ifndef PROXIMITY_H
+#define PROXIMITY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PROXIMITY_ABI_VERSION 1u
+
+enum {
+  PROXIMITY_OK = 0,
+  PROXIMITY_ERR_INVALID_ARG = -1,     /* null pointer, zero size, unsupported value        */
+  PROXIMITY_ERR_K_MISMATCH = -2,      /* k differs from the k fixed at creation            */
+  PROXIMITY_ERR_BATCH_TOO_LARGE = -3, /* n exceeds max_batch                               */
+  PROXIMITY_ERR_BAD_TAU = -4,         /* tau is NaN, infinite or negative                  */
+  PROXIMITY_ERR_HIP = -5,             /* a HIP runtime call failed                         */
+  PROXIMITY_ERR_OOM = -6              /* device memory for the instance could not be had   */
+};
+
+enum { PROXIMITY_DTYPE_F32 = 0, PROXIMITY_DTYPE_BF16 = 1 };
+enum { PROXIMITY_POLICY_FIFO = 0, PROXIMITY_POLICY_LRU = 1 };
+
+/* Limits checked by proximity_create(). */
+#define PROXIMITY_MAX_K 240u
+#define PROXIMITY_MAX_DIM 4096u
+#define PROXIMITY_MAX_BATCH 8192u
+#define PROXIMITY_MAX_CAPACITY (1u << 20)
+
+typedef struct proximity proximity_t;
+
+/*
+ * Parameters fixed for the life of an instance (Algorithm 1 "stored state";
+ * Section 3.1: k is "picked at the start"; Section 3.3.1: capacity c;
+ * Section 3.3.2: eviction policy).
+ */
+typedef struct proximity_config {
+  uint32_t struct_size;   /* sizeof(proximity_config), for ABI checking                       */
+  uint32_t dim;           /* embedding dimension d; multiple of 32, <= PROXIMITY_MAX_DIM     */
+  const void* corpus;     /* DEVICE [n_docs][dim], float32 or bfloat16; BORROWED: it must
+                             stay allocated and unchanged until proximity_destroy()          */
+  uint64_t n_docs;        /* < 2^31.  0 is allowed: misses then return ids -1 / dists +inf
+                             (for runs that time the cache probe alone)                      */
+  uint32_t corpus_dtype;  /* PROXIMITY_DTYPE_*.  Queries and cache keys are always float32   */
+  uint32_t capacity;      /* c; 0 disables the cache: every query misses, nothing is stored  */
+  uint32_t k;             /* neighbours per query, 1..PROXIMITY_MAX_K                         */
+  uint32_t policy;        /* PROXIMITY_POLICY_*                                               */
+  uint32_t max_batch;     /* largest n a call may pass, 1..PROXIMITY_MAX_BATCH                */
+  int32_t device;         /* HIP device ordinal                                               */
+} proximity_config;
+
+/* Counters since creation or the last proximity_clear(). */
+typedef struct proximity_stats_t {
+  uint64_t queries;        /* rows processed                                                 */
+  uint64_t hits;           /* rows answered from the cache                                   */
+  uint64_t misses;         /* rows that went to the index (= scans = inserts when c > 0)     */
+  uint64_t inserts;        /* keys stored                                                    */
+  uint64_t evictions;      /* keys removed to make room                                      */
+  uint64_t size;           /* keys resident now, <= capacity                                 */
+  uint64_t inbatch_hits;   /* hits on a key stored by an earlier row of the same call        */
+  uint64_t dense_resolves; /* rows whose nearest key was found by the full-row fallback      */
+  uint64_t reserved[8];
+} proximity_stats_t;
+
+/*
+ * One timed launch of the corpus-scan distance kernel (see proximity_profile_start).
+ * A launch handles the misses number first_query .. first_query+n_queries-1 of its
+ * call; it streamed the corpus only if the call had more than first_query misses
+ * (otherwise it returned at once), which the caller can tell from out_hit.
+ */
+typedef struct proximity_launch_t {
+  uint32_t call;         /* ordinal of the search/knn call since proximity_profile_start   */
+  uint32_t first_query;  /* index, within the call's miss list, of the launch's first query */
+  uint32_t n_queries;    /* queries the launch is compiled to handle at once               */
+  float ms;              /* duration from HIP events recorded on the call's stream         */
+} proximity_launch_t;
+
+uint32_t proximity_abi_version(void);
+
+/*
+ * Create an instance on cfg->device: computes the squared norm of every corpus
+ * row once (one streaming pass over the corpus) and allocates the cache
+ * (capacity x dim float32 keys, capacity x k values) and all workspaces, sized
+ * for max_batch.  *out receives the handle.  Blocks until the norms are done.
+ * Errors: INVALID_ARG (null, bad struct_size, dim/k/max_batch/capacity/n_docs
+ * outside the limits, unknown dtype/policy, corpus null with n_docs > 0), OOM,
+ * HIP.  On error *out is set to NULL.
+ */
+int proximity_create(const proximity_config* cfg, proximity_t** out);
+
+/* Frees everything the instance owns.  NULL is ignored.  Waits for the device. */
+void proximity_destroy(proximity_t* h);
+
+/*
+ * The lookup procedure of Algorithm 1 for n queries, with the semantics of
+ * processing rows 0..n-1 one after the other (and calls in call order).
+ *
+ *   queries    DEVICE [n][dim] float32
+ *   n          1..max_batch (0 is accepted and does nothing)
+ *   k          must equal cfg.k
+ *   tau        tolerance as Euclidean (not squared) distance; finite, >= 0.
+ *              A key at distance exactly tau is a hit.  May differ between calls.
+ *   out_ids    DEVICE [n][k] int64: ranked document indices (ascending distance,
+ *              equal distances by ascending index; -1 padding when n_docs < k).
+ *              On a hit: the list stored with the matched key, unchanged.
+ *   out_dists  DEVICE [n][k] float32 or NULL: Euclidean distances that go with
+ *              out_ids (+inf padding).  On a hit these are the stored distances
+ *              to the matched key, not to the query.
+ *   out_hit    DEVICE [n] uint8: 1 = answered from the cache, 0 = index searched
+ *   hip_stream the hipStream_t to enqueue on (NULL = the default stream).
+ *
+ * Asynchronous; see the conventions above.  Errors: INVALID_ARG, K_MISMATCH,
+ * BATCH_TOO_LARGE, BAD_TAU, HIP.
+ */
+int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uint32_t k, float tau,
+                           int64_t* out_ids, float* out_dists, uint8_t* out_hit, void* hip_stream);
+
+/*
+ * The index search alone (Section 2.2; the retrieveDocumentIndices call of
+ * Algorithm 1): exact k nearest corpus rows of each query, cache untouched.
+ * Same buffers and rules as proximity_search_batch, without tau and out_hit.
+ */
+int proximity_knn_batch(proximity_t* h, const float* queries, uint32_t n, uint32_t k,
+                        int64_t* out_ids, float* out_dists, void* hip_stream);
+
+/* Copies the counters to *out (HOST).  Waits for the handle's last stream. */
+int proximity_stats(const proximity_t* h, proximity_stats_t* out);
+
+/*
+ * Copies the cache contents to HOST arrays in eviction order (next victim
+ * first).  seq[i] is the position, counted from creation or the last clear, of
+ * the query that inserted entry i.  keys ([capacity][dim] float32) and ids
+ * ([capacity][k] int64) may be NULL.  *n_live receives the number of entries
+ * written.  Waits for the handle's last stream.
+ */
+int proximity_cache_dump(const proximity_t* h, uint64_t* seq, float* keys, int64_t* ids,
+                         uint32_t* n_live);
+
+/* Empties the cache and zeroes counters and the query position.  Waits for the device. */
+int proximity_clear(proximity_t* h);
+
+/*
+ * Kernel timing for roofline reports.  After proximity_profile_start() every
+ * launch of the corpus-scan distance kernel is bracketed with HIP events on the
+ * call's stream (at most 8192 launches; later ones are not timed).
+ * proximity_profile_stop() waits for the stream, writes up to cap records to
+ * the HOST array `records` (may be NULL with cap 0), sets *n_records to the
+ * number written, and stops timing.  Events are created by the start call,
+ * not by the search calls.
+ */
+int proximity_profile_start(proximity_t* h);
+int proximity_profile_stop(proximity_t* h, proximity_launch_t* records, uint32_t cap, uint32_t* n_records);
+
+/* Text of the last error on this handle (or of the last failed create when h is NULL). */
+const char* proximity_last_error(const proximity_t* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PROXIMITY_H */

@@ -1,0 +1,357 @@
+// Cache-side kernels: candidate extraction after the probe, the order-preserving
+// hit/miss/evict resolver, key insertion and result routing.
+//
+// Terms.  The cache has `c` slots.  A *source* that may answer row i of a batch
+// is either a slot that held a key when the batch started (source id = slot,
+// 0..c-1) or an earlier row j < i of the same batch that missed and was stored
+// (source id = c + j).  Every key carries the stream position ("seq") of the
+// query that inserted it; rows of the current batch have seq = base_seq + row.
+// A slot whose seq is >= base_seq was overwritten during this batch, by row
+// seq - base_seq.  Slots fill in index order and are never freed individually,
+// so the live slots are always 0..size-1.
+#pragma once
+
+#include "device_utils.hpp"
+
+namespace prox {
+
+struct CacheState {
+  int size;   // live keys
+  int head;   // next victim (front of the eviction order), -1 when empty
+  int tail;   // most recently inserted (FIFO) / used (LRU), -1 when empty
+  int pad;
+  unsigned long long queries, hits, misses, inserts, evictions, inbatch_hits, dense_resolves, pad2;
+};
+
+// Euclidean distance in float64, direct-difference form, computed by one wave.
+// The one routine every float64 decision in this file goes through.
+__device__ __forceinline__ double wave_dist64(const float* __restrict__ a, const float* __restrict__ b, int dim,
+                                              int lane) {
+  double acc = 0.0;
+  for (int i = lane; i < dim; i += 64) {
+    const double diff = double(a[i]) - double(b[i]);
+    acc += diff * diff;
+  }
+  return sqrt(wave_sum(acc));
+}
+
+// Float32 pre-filter bound for "distance <= tau".  The float32 probe value
+// d2 = (|s|^2 - 2 q.s) + |q|^2 carries an absolute error far below
+// 1e-5 * (|q|^2 + |s|^2); anything that could be within tau in exact arithmetic
+// passes this bound and is then decided in float64.
+__device__ __forceinline__ float prefilter_bound(double tau, float qn, float sn) {
+  const double b = tau * tau * (1.0 + 1e-3) + 1e-4 * (double(qn) + double(sn));
+  return b > 3.0e38 ? 3.0e38f : float(b);
+}
+
+// ---------------------------------------------------------------------------
+// Step "distances to all keys" of Algorithm 1, second half: from the dense
+// float32 probe row of each query keep the sources that can lie within tau, and
+// evaluate those in float64.  One block per batch row.
+//   D32[i*ldD + s]     score of row i against source s (slots 0..c-1, batch rows c..c+n-1)
+//   srcs[(s)*dim ..]   the source vectors (slot keys, then the batch rows)
+//   cand_cnt[i]        number of sources that passed (may exceed cap)
+//   cand_src/cand_d    first min(cnt,cap) of them, unordered, with float64 distances
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void probe_candidates_kernel(
+    const float* __restrict__ D32, long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm,
+    int dim, int c, int n, const CacheState* __restrict__ st, double tau, int cap, int* __restrict__ cand_cnt,
+    int* __restrict__ cand_src, double* __restrict__ cand_d) {
+  const int i = blockIdx.x;
+  if (i >= n) return;
+  __shared__ int count;
+  __shared__ int list[256];  // cap <= 256
+  if (threadIdx.x == 0) count = 0;
+  __syncthreads();
+  const int size0 = st->size;
+  const float qn = srcnrm[c + i];
+  const float* row = D32 + long(i) * ldD;
+  for (int s = threadIdx.x; s < size0; s += blockDim.x) {
+    if (row[s] + qn <= prefilter_bound(tau, qn, srcnrm[s])) {
+      const int pos = atomicAdd(&count, 1);
+      if (pos < cap) list[pos] = s;
+    }
+  }
+  for (int j = threadIdx.x; j < i; j += blockDim.x) {
+    const int s = c + j;
+    if (row[s] + qn <= prefilter_bound(tau, qn, srcnrm[s])) {
+      const int pos = atomicAdd(&count, 1);
+      if (pos < cap) list[pos] = s;
+    }
+  }
+  __syncthreads();
+  const int cnt = count;
+  if (threadIdx.x == 0) cand_cnt[i] = cnt;
+  const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+  const float* q = srcs + long(c + i) * dim;
+  const int m = cnt < cap ? cnt : cap;
+  for (int p = wib; p < m; p += 4) {
+    const int s = list[p];
+    const double d = wave_dist64(q, srcs + long(s) * dim, dim, lane);
+    if (lane == 0) {
+      cand_src[long(i) * cap + p] = s;
+      cand_d[long(i) * cap + p] = d;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Order-preserving resolver: lines 2-9 of Algorithm 1 for rows 0..n-1 in order,
+// given every row's candidate sources.  One wave walks the rows; the only
+// sequential state is which sources are live and the eviction order (a doubly
+// linked list over slots: FIFO appends on insert, LRU also moves a slot to the
+// back when it answers a query; Section 3.3.2).
+//
+// Per row: the nearest live source (ties: smaller seq) with float64 distance
+// <= tau is a hit.  Otherwise the row misses, takes the next free slot or the
+// slot at the front of the eviction order, and becomes a live source itself.
+// Rows with more candidates than the list holds are resolved from the dense
+// probe row over the live slots instead (float32 minimum, then float64 on the
+// near-minimal ones).
+//
+// Outputs per row: hit flag, answering source (or -1), slot taken (or -1);
+// the list of missing rows in row order and its length.
+// ---------------------------------------------------------------------------
+struct ResolverBest {
+  double d;
+  long long seq;
+  int src;
+};
+
+__device__ __forceinline__ void best_take(ResolverBest& b, double d, long long seq, int src) {
+  if (d < b.d || (d == b.d && seq < b.seq)) {
+    b.d = d;
+    b.seq = seq;
+    b.src = src;
+  }
+}
+
+__device__ __forceinline__ void best_wave_reduce(ResolverBest& b) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const double od = __shfl_xor(b.d, m, kWave);
+    const long long os = __shfl_xor(b.seq, m, kWave);
+    const int osrc = __shfl_xor(b.src, m, kWave);
+    best_take(b, od, os, osrc);
+  }
+}
+
+__global__ __launch_bounds__(64) void resolver_kernel(
+    int n, int c, int dim, int policy_lru, long long base_seq, double tau, CacheState* __restrict__ st,
+    long long* slot_seq, int* slot_next, int* slot_prev, const int* __restrict__ cand_cnt,
+    const int* __restrict__ cand_src, const double* __restrict__ cand_d, int cap, const float* __restrict__ D32,
+    long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm, uint8_t* __restrict__ hit_out,
+    int* __restrict__ src_out, int* row_slot, int* __restrict__ miss_list, int* __restrict__ miss_count) {
+  const int lane = threadIdx.x;
+  int size = st->size, head = st->head, tail = st->tail;
+  unsigned long long hits = 0, misses = 0, inserts = 0, evictions = 0, inbatch = 0, dense = 0;
+  int M = 0;
+  const double kInf = __longlong_as_double(0x7ff0000000000000ll);
+
+  for (int i = 0; i < n; ++i) {
+    const int cnt = cand_cnt ? cand_cnt[i] : 0;  // no probe ran when the cache is disabled
+    ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
+    if (cnt > 0 && cnt <= cap) {
+      for (int p0 = 0; p0 < cnt; p0 += 64) {
+        const int p = p0 + lane;
+        if (p < cnt) {
+          const int s = cand_src[long(i) * cap + p];
+          const double d = cand_d[long(i) * cap + p];
+          long long seq;
+          bool live;
+          if (s < c) {
+            seq = slot_seq[s];
+            live = seq < base_seq;  // still holds the key it had when the batch began
+          } else {
+            const int t = row_slot[s - c];
+            seq = base_seq + (s - c);
+            live = t >= 0 && slot_seq[t] == seq;  // that row missed, was stored, and is still there
+          }
+          if (live && d <= tau) best_take(best, d, seq, s);
+        }
+      }
+      best_wave_reduce(best);
+    } else if (cnt > cap) {
+      ++dense;
+      const float qn = srcnrm[c + i];
+      const float* row = D32 + long(i) * ldD;
+      float mn = 3.4e38f, snmax = 0.f;
+      for (int t = lane; t < size; t += 64) {
+        const long long sq = slot_seq[t];
+        const int s = sq >= base_seq ? c + int(sq - base_seq) : t;
+        mn = fminf(mn, row[s] + qn);
+        snmax = fmaxf(snmax, srcnrm[s]);
+      }
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, m, kWave));
+        snmax = fmaxf(snmax, __shfl_xor(snmax, m, kWave));
+      }
+      const float slack = 2e-4f * (qn + snmax);
+      if (mn <= prefilter_bound(tau, qn, snmax) + slack) {
+        const float near = mn + slack;
+        for (int t0 = 0; t0 < size; t0 += 64) {
+          const int t = t0 + lane;
+          int s = -1;
+          long long sq = 0;
+          bool is_near = false;
+          if (t < size) {
+            sq = slot_seq[t];
+            s = sq >= base_seq ? c + int(sq - base_seq) : t;
+            is_near = row[s] + qn <= near;
+          }
+          unsigned long long mask = __ballot(is_near);
+          while (mask) {
+            const int b = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            const int sb = __shfl(s, b, kWave);
+            const long long sqb = __shfl(sq, b, kWave);
+            const double d = wave_dist64(srcs + long(c + i) * dim, srcs + long(sb) * dim, dim, lane);
+            if (d <= tau) best_take(best, d, sqb, sb);
+          }
+        }
+      }
+    }
+
+    if (best.src >= 0) {
+      ++hits;
+      if (best.src >= c) ++inbatch;
+      const int t = best.src < c ? best.src : row_slot[best.src - c];
+      if (policy_lru && t != tail) {
+        const int p = slot_prev[t], nx = slot_next[t];  // nx >= 0 because t is not the tail
+        if (lane == 0) {
+          if (p >= 0) slot_next[p] = nx;
+          slot_prev[nx] = p;
+          slot_prev[t] = tail;
+          slot_next[t] = -1;
+          slot_next[tail] = t;
+        }
+        if (p < 0) head = nx;
+        tail = t;
+      }
+      if (lane == 0) {
+        hit_out[i] = 1;
+        src_out[i] = best.src;
+        row_slot[i] = -1;
+      }
+    } else {
+      ++misses;
+      int t = -1;
+      if (c > 0) {
+        if (size < c) {
+          t = size++;
+        } else {
+          t = head;
+          head = slot_next[t];
+          if (lane == 0 && head >= 0) slot_prev[head] = -1;
+          if (head < 0) tail = -1;
+          ++evictions;
+        }
+        if (lane == 0) {
+          slot_seq[t] = base_seq + i;
+          slot_prev[t] = tail;
+          slot_next[t] = -1;
+          if (tail >= 0) slot_next[tail] = t;
+        }
+        if (tail < 0) head = t;
+        tail = t;
+        ++inserts;
+      }
+      if (lane == 0) {
+        hit_out[i] = 0;
+        src_out[i] = -1;
+        row_slot[i] = t;
+        miss_list[M] = i;
+      }
+      ++M;
+    }
+  }
+  if (lane == 0) {
+    st->size = size;
+    st->head = head;
+    st->tail = tail;
+    st->queries += (unsigned long long)n;
+    st->hits += hits;
+    st->misses += misses;
+    st->inserts += inserts;
+    st->evictions += evictions;
+    st->inbatch_hits += inbatch;
+    st->dense_resolves += dense;
+    *miss_count = M;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// After the resolver, before the scan.  One block per batch row.
+//   - a row that missed and still owns its slot at the end of the batch copies
+//     its vector and squared norm into the slot (Algorithm 1, "C[q] <- I", key part);
+//   - a row that hit a key resident since before the batch copies that key's
+//     stored list to its output row now, before any list is overwritten.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void post_resolve_kernel(
+    int n, int c, int dim, int k, long long base_seq, float* srcs, float* srcnrm,
+    const long long* __restrict__ slot_seq, const uint8_t* __restrict__ hit, const int* __restrict__ src,
+    const int* __restrict__ row_slot, const int64_t* __restrict__ val_ids, const float* __restrict__ val_d,
+    int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
+  const int i = blockIdx.x;
+  if (i >= n) return;
+  if (hit[i]) {
+    const int s = src[i];
+    if (s < c) {
+      for (int e = threadIdx.x; e < k; e += blockDim.x) {
+        out_ids[long(i) * k + e] = val_ids[long(s) * k + e];
+        if (out_d) out_d[long(i) * k + e] = val_d[long(s) * k + e];
+      }
+    }
+  } else {
+    const int t = row_slot[i];
+    if (t >= 0 && slot_seq[t] == base_seq + i) {
+      const float4* from = reinterpret_cast<const float4*>(srcs + long(c + i) * dim);
+      float4* to = reinterpret_cast<float4*>(srcs + long(t) * dim);
+      for (int e = threadIdx.x; e < dim / 4; e += blockDim.x) to[e] = from[e];
+      if (threadIdx.x == 0) srcnrm[t] = srcnrm[c + i];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// After the scan.  One block per batch row.
+//   - a row that missed returns its scan result, and stores it as its key's
+//     value if the key is still resident (Algorithm 1, "C[q] <- I", value part);
+//   - a row that hit an earlier row of the same batch returns that row's result.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, long long base_seq,
+                                                       const long long* __restrict__ slot_seq,
+                                                       const uint8_t* __restrict__ hit,
+                                                       const int* __restrict__ src,
+                                                       const int* __restrict__ row_slot,
+                                                       const int64_t* __restrict__ res_ids,
+                                                       const float* __restrict__ res_d, int64_t* val_ids,
+                                                       float* val_d, int64_t* __restrict__ out_ids,
+                                                       float* __restrict__ out_d) {
+  const int i = blockIdx.x;
+  if (i >= n) return;
+  int from;
+  bool store = false;
+  int t = -1;
+  if (hit[i]) {
+    if (src[i] < c) return;
+    from = src[i] - c;
+  } else {
+    from = i;
+    t = row_slot[i];
+    store = t >= 0 && slot_seq[t] == base_seq + i;
+  }
+  for (int e = threadIdx.x; e < k; e += blockDim.x) {
+    const int64_t id = res_ids[long(from) * k + e];
+    const float d = res_d[long(from) * k + e];
+    out_ids[long(i) * k + e] = id;
+    if (out_d) out_d[long(i) * k + e] = d;
+    if (store) {
+      val_ids[long(t) * k + e] = id;
+      val_d[long(t) * k + e] = d;
+    }
+  }
+}
+
+}  // namespace prox

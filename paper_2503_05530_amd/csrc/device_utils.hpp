@@ -1,0 +1,111 @@
+// Small device-side helpers shared by the kernels of this library (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace prox {
+
+constexpr int kWave = 64;
+constexpr int kDtypeF32 = 0;
+constexpr int kDtypeBF16 = 1;
+
+// A candidate neighbour is a (score, id) pair packed into one 64-bit key whose
+// unsigned order is "ascending score, then ascending id".  The float is mapped
+// to an unsigned integer with the same order (sign bit flipped for
+// non-negatives, all bits flipped for negatives).
+__device__ __forceinline__ uint32_t float_to_ordered(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_to_float(uint32_t o) {
+  uint32_t u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+  return __uint_as_float(u);
+}
+__device__ __forceinline__ uint64_t pack_key(float score, uint32_t id) {
+  return (uint64_t(float_to_ordered(score)) << 32) | uint64_t(id);
+}
+__device__ __forceinline__ float key_score(uint64_t key) { return ordered_to_float(uint32_t(key >> 32)); }
+__device__ __forceinline__ int32_t key_id(uint64_t key) { return int32_t(uint32_t(key)); }
+
+// Padding entry: score +inf, id -1.  Sorts after every real entry.
+constexpr uint64_t kPadKey = 0xFF800000FFFFFFFFull;
+
+__device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+
+// Sum NV per-lane values across the 64 lanes of a wave with NV-1 + log2(64/NV)
+// exchanges instead of 6*NV.  Each exchange step halves the number of values a
+// lane carries: the lane whose bit `mask` is clear keeps the lower half of its
+// values and receives its partner's lower half, the other lane keeps the upper
+// half.  On return v[0] of lane l is the wave-wide sum of the input value with
+// index value_index_of_lane<NV>(l).
+template <int NV>
+__device__ __forceinline__ void wave_sum_transposed(float (&v)[NV], int lane) {
+  static_assert((NV & (NV - 1)) == 0 && NV >= 1 && NV <= 64, "NV must be a power of two");
+  int mask = 1;
+#pragma unroll
+  for (int n = NV; n > 1; n >>= 1) {
+    const bool upper = (lane & mask) != 0;
+#pragma unroll
+    for (int i = 0; i < n / 2; ++i) {
+      const float send = upper ? v[i] : v[i + n / 2];
+      const float keep = upper ? v[i + n / 2] : v[i];
+      v[i] = keep + __shfl_xor(send, mask, kWave);
+    }
+    mask <<= 1;
+  }
+#pragma unroll
+  for (int m = NV; m < kWave; m <<= 1) v[0] += __shfl_xor(v[0], m, kWave);
+}
+
+// Index of the input value whose total lane l holds after wave_sum_transposed<NV>.
+template <int NV>
+__device__ __forceinline__ int value_index_of_lane(int lane) {
+  int idx = 0;
+  int bit = 0;
+#pragma unroll
+  for (int n = NV; n > 1; n >>= 1) {
+    idx += ((lane >> bit) & 1) * (n / 2);
+    ++bit;
+  }
+  return idx;
+}
+
+// Ascending bitonic sort of P (power of two) 64-bit keys in LDS by all threads
+// of the block.  Ends with a barrier.
+__device__ __forceinline__ void block_bitonic_sort(uint64_t* keys, int P, int tid, int nthreads) {
+  for (int k = 2; k <= P; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (P >> 1); t += nthreads) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int p = i | j;
+        const bool asc = (i & k) == 0;
+        const uint64_t a = keys[i], b = keys[p];
+        if ((a > b) == asc) {
+          keys[i] = b;
+          keys[p] = a;
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+__device__ __forceinline__ int next_pow2(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+}  // namespace prox

@@ -1,0 +1,556 @@
+// Host runtime and C ABI of the Proximity-FLAT retrieval step (see include/proximity.h).
+//
+// One instance owns: the squared norms of the corpus rows, the cache (slot
+// arrays for keys, values and eviction order, all resident on the device) and
+// the per-batch workspaces.  A call enqueues, on the caller's stream and
+// without waiting for the device:
+//
+//   copy batch rows behind the slot keys -> row norms of the batch
+//   -> probe scores (batch rows x [slot keys, batch rows])      Algorithm 1, distances to all keys
+//   -> candidate extraction + float64 evaluation
+//   -> resolver (sequential semantics, hit / miss / evict)        Algorithm 1, nearest key, test, evict
+//   -> key insertion and hits answered from resident keys
+//   -> corpus scan for the rows that missed (scores, top-k, float64 ranking)   Algorithm 1, database call
+//   -> result routing and value insertion.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/proximity.h"
+#include "cache_kernels.hpp"
+#include "scan_kernels.hpp"
+#include "select_kernels.hpp"
+
+using namespace prox;
+
+namespace {
+
+constexpr int kSlack = 8;          // extra float32 candidates handed to the float64 ranking
+constexpr int kCandCap = 64;       // per-row candidate list length of the probe
+constexpr int kSelE = 16;          // elements per thread in a selection segment
+constexpr int kSelSeg = kSelE * kSelThreads;
+constexpr int kMaxProfiled = 8192;
+
+static_assert(sizeof(proximity_config) == 48, "proximity_config layout is part of the ABI");
+static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is part of the ABI");
+static_assert(sizeof(proximity_launch_t) == 16, "proximity_launch_t layout is part of the ABI");
+
+thread_local std::string g_create_error;
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) ok = false;
+    if (ok && prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+}  // namespace
+
+struct proximity {
+  proximity_config cfg{};
+  int n_cu = 256;
+  uint64_t next_seq = 0;
+  hipStream_t last_stream = nullptr;
+  std::string err;
+  std::vector<void*> allocs;
+
+  // corpus side
+  float* xnrm = nullptr;
+  float* S = nullptr;  // dense scan scores [8][ldS]
+  long ldS = 0;
+  uint64_t* pairs[2] = {nullptr, nullptr};
+  long pairs_elems = 0;
+  int64_t* res_ids = nullptr;
+  float* res_d = nullptr;
+
+  // cache side
+  float* srcs = nullptr;     // [capacity + max_batch][dim]: slot keys, then the current batch
+  float* srcnrm = nullptr;   // their squared norms
+  int64_t* val_ids = nullptr;
+  float* val_d = nullptr;
+  long long* slot_seq = nullptr;
+  int* slot_next = nullptr;
+  int* slot_prev = nullptr;
+  CacheState* state = nullptr;
+  float* D32 = nullptr;  // probe scores [max_batch][ldD]
+  long ldD = 0;
+  int* cand_cnt = nullptr;
+  int* cand_src = nullptr;
+  double* cand_d = nullptr;
+  uint8_t* hit = nullptr;
+  int* src = nullptr;
+  int* row_slot = nullptr;
+  int* miss_list = nullptr;
+  int* miss_count = nullptr;
+
+  // kernel timing
+  bool prof_on = false;
+  std::vector<hipEvent_t> ev0, ev1;
+  std::vector<proximity_launch_t> ev_info;
+  size_t ev_used = 0;
+  uint32_t prof_call = 0;
+};
+
+namespace {
+
+int fail(proximity* h, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (h)
+    h->err = buf;
+  else
+    g_create_error = buf;
+  return code;
+}
+
+#define HIP_TRY(h, expr)                                                                         \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess)                                                                        \
+      return fail(h, e_ == hipErrorOutOfMemory ? PROXIMITY_ERR_OOM : PROXIMITY_ERR_HIP,          \
+                  "%s failed: %s", #expr, hipGetErrorString(e_));                                \
+  } while (0)
+
+template <typename T>
+int dev_alloc(proximity* h, T** p, size_t count, bool zero) {
+  void* q = nullptr;
+  size_t bytes = count * sizeof(T);
+  if (bytes == 0) bytes = sizeof(T);
+  HIP_TRY(h, hipMalloc(&q, bytes));
+  h->allocs.push_back(q);
+  if (zero) HIP_TRY(h, hipMemset(q, 0, bytes));
+  *p = static_cast<T*>(q);
+  return PROXIMITY_OK;
+}
+
+// ---- launch helpers --------------------------------------------------------
+
+template <int DT>
+void launch_row_norms(const proximity* h, const void* X, long n_rows, int dim, float* nrm, hipStream_t s) {
+  if (n_rows <= 0) return;
+  long blocks = (n_rows + 3) / 4;
+  const long cap = long(h->n_cu) * 16;
+  if (blocks > cap) blocks = cap;
+  row_norms_kernel<DT><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(X, n_rows, dim, nrm);
+}
+
+// Largest group of queries one streaming pass handles for this problem.
+int stream_group(int dim, int n) {
+  int mq = n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : 8;
+  const bool fast = dim == 768 || dim == 384 || dim == 1024;
+  if (!fast)
+    while (mq > 1 && size_t(mq) * dim * sizeof(float) > 48 * 1024) mq >>= 1;
+  return mq;
+}
+
+template <int DT, int MQ>
+void launch_scores_stream_mq(const proximity* h, const void* X, const float* xnrm, long n_rows, int dim,
+                             const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
+                             int m_begin, float* S, long ldS, hipStream_t s) {
+  const long n_blocks64 = (n_rows + 63) / 64;
+  long grid = (n_blocks64 + 3) / 4;
+  const long cap = long(h->n_cu) * 8;
+  if (grid > cap) grid = cap;
+  if (grid < 1) grid = 1;
+  const dim3 g((unsigned)grid), b(256);
+#define PROX_STREAM_CASE(D)                                                                              \
+  case D:                                                                                                \
+    scores_stream_kernel<D, MQ, DT><<<g, b, 0, s>>>(X, xnrm, 0, n_rows, Qbase, qlist, m_count_ptr,      \
+                                                    m_limit, m_begin, S, ldS);                          \
+    return;
+  switch (dim) {
+    PROX_STREAM_CASE(768)
+    PROX_STREAM_CASE(384)
+    PROX_STREAM_CASE(1024)
+    default:
+      break;
+  }
+#undef PROX_STREAM_CASE
+  long ggrid = (n_rows + 3) / 4;
+  if (ggrid > cap) ggrid = cap;
+  if (ggrid < 1) ggrid = 1;
+  scores_stream_generic_kernel<MQ, DT><<<dim3((unsigned)ggrid), b, size_t(MQ) * dim * sizeof(float), s>>>(
+      X, xnrm, 0, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS);
+}
+
+template <int DT>
+void launch_scores_stream(const proximity* h, int mq, const void* X, const float* xnrm, long n_rows, int dim,
+                          const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
+                          int m_begin, float* S, long ldS, hipStream_t s) {
+  switch (mq) {
+    case 1:
+      launch_scores_stream_mq<DT, 1>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      break;
+    case 2:
+      launch_scores_stream_mq<DT, 2>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      break;
+    case 4:
+      launch_scores_stream_mq<DT, 4>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      break;
+    default:
+      launch_scores_stream_mq<DT, 8>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      break;
+  }
+}
+
+void prof_begin(proximity* h, hipStream_t s) {
+  if (h->prof_on && h->ev_used < h->ev0.size()) (void)hipEventRecord(h->ev0[h->ev_used], s);
+}
+void prof_end(proximity* h, hipStream_t s, int first_query, int n_queries) {
+  if (h->prof_on && h->ev_used < h->ev0.size()) {
+    (void)hipEventRecord(h->ev1[h->ev_used], s);
+    h->ev_info[h->ev_used] = proximity_launch_t{h->prof_call, uint32_t(first_query), uint32_t(n_queries), 0.f};
+    ++h->ev_used;
+  }
+}
+
+// The index search for the queries listed in qlist (or rows 0..m_limit-1 of
+// Qbase when qlist is null): scores, hierarchical top-k, float64 ranking.
+// Results land in row qlist[m] (or m) of res_ids / res_d.
+int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
+                 int64_t* res_ids, float* res_d, hipStream_t s) {
+  const int k = int(h->cfg.k), dim = int(h->cfg.dim);
+  const long N = long(h->cfg.n_docs);
+  if (N == 0) {
+    fill_empty_results_kernel<<<dim3(m_limit), dim3(64), 0, s>>>(qlist, m_count_ptr, m_limit, k, res_ids, res_d);
+    return PROXIMITY_OK;
+  }
+  const int kp = k + kSlack;
+  const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
+  const int mq = stream_group(dim, m_limit);
+  const int g1 = int((N + kSelSeg - 1) / kSelSeg);
+  for (int m0 = 0; m0 < m_limit; m0 += mq) {
+    prof_begin(h, s);
+    if (bf16)
+      launch_scores_stream<kDtypeBF16>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit, m0,
+                                       h->S, h->ldS, s);
+    else
+      launch_scores_stream<kDtypeF32>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit, m0,
+                                      h->S, h->ldS, s);
+    prof_end(h, s, m0, mq);
+    select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
+        h->S, h->ldS, N, 0, kp, h->pairs[0] + long(m0) * g1 * kp, g1, m_count_ptr, m_limit, m0);
+  }
+  int cur = 0;
+  long len = long(g1) * kp;
+  while (len > kp) {
+    const int g = int((len + kSelSeg - 1) / kSelSeg);
+    select_kernel<false, kSelE><<<dim3(g, m_limit), dim3(kSelThreads), 0, s>>>(
+        h->pairs[cur], len, len, 0, kp, h->pairs[cur ^ 1], g, m_count_ptr, m_limit, 0);
+    cur ^= 1;
+    len = long(g) * kp;
+  }
+  if (bf16)
+    rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(256), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
+                                                                     qlist, m_count_ptr, m_limit, res_ids, res_d);
+  else
+    rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(256), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
+                                                                    qlist, m_count_ptr, m_limit, res_ids, res_d);
+  return PROXIMITY_OK;
+}
+
+int check_launch(proximity* h, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(h, PROXIMITY_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return PROXIMITY_OK;
+}
+
+int validate_call(proximity* h, const float* queries, uint32_t n, uint32_t k, int64_t* out_ids) {
+  if (!h) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "handle is null");
+  if (k != h->cfg.k) return fail(h, PROXIMITY_ERR_K_MISMATCH, "k=%u but the instance was created with k=%u", k, h->cfg.k);
+  if (n > h->cfg.max_batch)
+    return fail(h, PROXIMITY_ERR_BATCH_TOO_LARGE, "n=%u exceeds max_batch=%u", n, h->cfg.max_batch);
+  if (n > 0 && (!queries || !out_ids)) return fail(h, PROXIMITY_ERR_INVALID_ARG, "queries or out_ids is null");
+  return PROXIMITY_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t proximity_abi_version(void) { return PROXIMITY_ABI_VERSION; }
+
+const char* proximity_last_error(const proximity_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+int proximity_create(const proximity_config* cfg, proximity_t** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "cfg or out is null");
+  if (cfg->struct_size != sizeof(proximity_config))
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "struct_size=%u, expected %zu", cfg->struct_size,
+                sizeof(proximity_config));
+  if (cfg->dim == 0 || cfg->dim % 32 != 0 || cfg->dim > PROXIMITY_MAX_DIM)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "dim=%u must be a multiple of 32 in 32..%u", cfg->dim,
+                PROXIMITY_MAX_DIM);
+  if (cfg->k == 0 || cfg->k > PROXIMITY_MAX_K)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "k=%u must be in 1..%u", cfg->k, PROXIMITY_MAX_K);
+  if (cfg->max_batch == 0 || cfg->max_batch > PROXIMITY_MAX_BATCH)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "max_batch=%u must be in 1..%u", cfg->max_batch,
+                PROXIMITY_MAX_BATCH);
+  if (cfg->capacity > PROXIMITY_MAX_CAPACITY)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "capacity=%u exceeds %u", cfg->capacity, PROXIMITY_MAX_CAPACITY);
+  if (cfg->n_docs >= (1ull << 31))
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "n_docs=%llu must be below 2^31", (unsigned long long)cfg->n_docs);
+  if (cfg->n_docs > 0 && !cfg->corpus) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "corpus is null but n_docs > 0");
+  if (cfg->corpus_dtype != PROXIMITY_DTYPE_F32 && cfg->corpus_dtype != PROXIMITY_DTYPE_BF16)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown corpus_dtype %u", cfg->corpus_dtype);
+  if (cfg->policy != PROXIMITY_POLICY_FIFO && cfg->policy != PROXIMITY_POLICY_LRU)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown policy %u", cfg->policy);
+  if (cfg->device < 0) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "device=%d is negative", cfg->device);
+
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || cfg->device >= n_dev)
+    return fail(nullptr, PROXIMITY_ERR_HIP, "device %d is not available (%d devices visible)", cfg->device, n_dev);
+
+  proximity* h = new (std::nothrow) proximity();
+  if (!h) return fail(nullptr, PROXIMITY_ERR_OOM, "host allocation failed");
+  h->cfg = *cfg;
+  DeviceGuard guard(cfg->device);
+  auto bail = [&](int code) {
+    g_create_error = h->err;
+    for (void* p : h->allocs) (void)hipFree(p);
+    delete h;
+    return code;
+  };
+  if (!guard.ok) {
+    h->err = "hipSetDevice failed";
+    return bail(PROXIMITY_ERR_HIP);
+  }
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, cfg->device) == hipSuccess && prop.multiProcessorCount > 0)
+    h->n_cu = prop.multiProcessorCount;
+
+  const size_t c = cfg->capacity, B = cfg->max_batch, d = cfg->dim, k = cfg->k, N = cfg->n_docs;
+  const int kp = int(k) + kSlack;
+  int rc;
+#define TRY_ALLOC(ptr, count, zero)                              \
+  if ((rc = dev_alloc(h, &(ptr), (count), (zero))) != PROXIMITY_OK) return bail(rc)
+  TRY_ALLOC(h->xnrm, N, false);
+  h->ldS = long((N + 63) / 64 * 64);
+  TRY_ALLOC(h->S, size_t(8) * size_t(h->ldS), false);
+  const size_t g1 = (N + kSelSeg - 1) / kSelSeg;
+  h->pairs_elems = long(B * (g1 > 0 ? g1 : 1) * kp);
+  TRY_ALLOC(h->pairs[0], size_t(h->pairs_elems), false);
+  TRY_ALLOC(h->pairs[1], size_t(h->pairs_elems), false);
+  TRY_ALLOC(h->res_ids, B * k, true);
+  TRY_ALLOC(h->res_d, B * k, true);
+  TRY_ALLOC(h->srcs, (c + B) * d, true);
+  TRY_ALLOC(h->srcnrm, c + B, true);
+  TRY_ALLOC(h->val_ids, c * k, true);
+  TRY_ALLOC(h->val_d, c * k, true);
+  TRY_ALLOC(h->slot_seq, c, true);
+  TRY_ALLOC(h->slot_next, c, true);
+  TRY_ALLOC(h->slot_prev, c, true);
+  TRY_ALLOC(h->state, 1, true);
+  h->ldD = long((c + B + 63) / 64 * 64);
+  TRY_ALLOC(h->D32, B * size_t(h->ldD), true);
+  TRY_ALLOC(h->cand_cnt, B, true);
+  TRY_ALLOC(h->cand_src, B * kCandCap, true);
+  TRY_ALLOC(h->cand_d, B * kCandCap, true);
+  TRY_ALLOC(h->hit, B, true);
+  TRY_ALLOC(h->src, B, true);
+  TRY_ALLOC(h->row_slot, B, true);
+  TRY_ALLOC(h->miss_list, B, true);
+  TRY_ALLOC(h->miss_count, 1, true);
+#undef TRY_ALLOC
+  CacheState init{};
+  init.head = init.tail = -1;
+  if (hipMemcpy(h->state, &init, sizeof init, hipMemcpyHostToDevice) != hipSuccess) {
+    h->err = "state upload failed";
+    return bail(PROXIMITY_ERR_HIP);
+  }
+  if (N > 0) {
+    if (cfg->corpus_dtype == PROXIMITY_DTYPE_BF16)
+      launch_row_norms<kDtypeBF16>(h, cfg->corpus, long(N), int(d), h->xnrm, nullptr);
+    else
+      launch_row_norms<kDtypeF32>(h, cfg->corpus, long(N), int(d), h->xnrm, nullptr);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      h->err = std::string("corpus norm pass failed: ") + hipGetErrorString(e);
+      return bail(PROXIMITY_ERR_HIP);
+    }
+  }
+  *out = h;
+  return PROXIMITY_OK;
+}
+
+void proximity_destroy(proximity_t* h) {
+  if (!h) return;
+  DeviceGuard guard(h->cfg.device);
+  (void)hipDeviceSynchronize();
+  for (hipEvent_t e : h->ev0) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->ev1) (void)hipEventDestroy(e);
+  for (void* p : h->allocs) (void)hipFree(p);
+  delete h;
+}
+
+int proximity_knn_batch(proximity_t* h, const float* queries, uint32_t n, uint32_t k, int64_t* out_ids,
+                        float* out_dists, void* hip_stream) {
+  int rc = validate_call(h, queries, n, k, out_ids);
+  if (rc != PROXIMITY_OK) return rc;
+  if (n == 0) return PROXIMITY_OK;
+  DeviceGuard guard(h->cfg.device);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  h->last_stream = s;
+  rc = enqueue_scan(h, queries, nullptr, nullptr, int(n), out_ids, out_dists ? out_dists : h->res_d, s);
+  if (h->prof_on) ++h->prof_call;
+  if (rc != PROXIMITY_OK) return rc;
+  return check_launch(h, "proximity_knn_batch");
+}
+
+int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uint32_t k, float tau,
+                           int64_t* out_ids, float* out_dists, uint8_t* out_hit, void* hip_stream) {
+  int rc = validate_call(h, queries, n, k, out_ids);
+  if (rc != PROXIMITY_OK) return rc;
+  if (!(tau >= 0.f) || std::isinf(tau)) return fail(h, PROXIMITY_ERR_BAD_TAU, "tau must be finite and >= 0");
+  if (n == 0) return PROXIMITY_OK;
+  if (!out_hit) return fail(h, PROXIMITY_ERR_INVALID_ARG, "out_hit is null");
+  DeviceGuard guard(h->cfg.device);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  h->last_stream = s;
+
+  const int c = int(h->cfg.capacity), dim = int(h->cfg.dim), kk = int(h->cfg.k), nn = int(n);
+  const long long base_seq = (long long)h->next_seq;
+  float* batch_rows = h->srcs + size_t(c) * dim;
+
+  HIP_TRY(h, hipMemcpyAsync(batch_rows, queries, size_t(n) * dim * sizeof(float), hipMemcpyDeviceToDevice, s));
+  launch_row_norms<kDtypeF32>(h, batch_rows, nn, dim, h->srcnrm + c, s);
+  int have_probe = 0;
+  if (c > 0) {
+    have_probe = 1;
+    const int mq = stream_group(dim, nn);
+    for (int m0 = 0; m0 < nn; m0 += mq)
+      launch_scores_stream<kDtypeF32>(h, mq, h->srcs, h->srcnrm, long(c) + nn, dim, batch_rows, nullptr, nullptr, nn,
+                                      m0, h->D32 + size_t(m0) * h->ldD, h->ldD, s);
+    probe_candidates_kernel<<<dim3(nn), dim3(256), 0, s>>>(h->D32, h->ldD, h->srcs, h->srcnrm, dim, c, nn, h->state,
+                                                           double(tau), kCandCap, h->cand_cnt, h->cand_src,
+                                                           h->cand_d);
+  }
+  resolver_kernel<<<dim3(1), dim3(64), 0, s>>>(nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq,
+                                               double(tau), h->state, h->slot_seq, h->slot_next, h->slot_prev,
+                                               have_probe ? h->cand_cnt : nullptr, h->cand_src, h->cand_d, kCandCap,
+                                               h->D32, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot,
+                                               h->miss_list, h->miss_count);
+  post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, base_seq, h->srcs, h->srcnrm, h->slot_seq,
+                                                     out_hit, h->src, h->row_slot, h->val_ids, h->val_d, out_ids,
+                                                     out_dists);
+  rc = enqueue_scan(h, batch_rows, h->miss_list, h->miss_count, nn, h->res_ids, h->res_d, s);
+  if (rc != PROXIMITY_OK) return rc;
+  finalize_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, kk, base_seq, h->slot_seq, out_hit, h->src, h->row_slot,
+                                                 h->res_ids, h->res_d, h->val_ids, h->val_d, out_ids, out_dists);
+  h->next_seq += n;
+  if (h->prof_on) ++h->prof_call;
+  return check_launch(h, "proximity_search_batch");
+}
+
+int proximity_stats(const proximity_t* h, proximity_stats_t* out) {
+  if (!h || !out) return fail(const_cast<proximity_t*>(h), PROXIMITY_ERR_INVALID_ARG, "handle or out is null");
+  proximity* hh = const_cast<proximity*>(h);
+  DeviceGuard guard(h->cfg.device);
+  HIP_TRY(hh, hipStreamSynchronize(h->last_stream));
+  CacheState st;
+  HIP_TRY(hh, hipMemcpy(&st, h->state, sizeof st, hipMemcpyDeviceToHost));
+  std::memset(out, 0, sizeof *out);
+  out->queries = st.queries;
+  out->hits = st.hits;
+  out->misses = st.misses;
+  out->inserts = st.inserts;
+  out->evictions = st.evictions;
+  out->size = uint64_t(st.size);
+  out->inbatch_hits = st.inbatch_hits;
+  out->dense_resolves = st.dense_resolves;
+  return PROXIMITY_OK;
+}
+
+int proximity_cache_dump(const proximity_t* h, uint64_t* seq, float* keys, int64_t* ids, uint32_t* n_live) {
+  if (!h || !n_live) return fail(const_cast<proximity_t*>(h), PROXIMITY_ERR_INVALID_ARG, "handle or n_live is null");
+  proximity* hh = const_cast<proximity*>(h);
+  DeviceGuard guard(h->cfg.device);
+  HIP_TRY(hh, hipStreamSynchronize(h->last_stream));
+  const size_t c = h->cfg.capacity, d = h->cfg.dim, k = h->cfg.k;
+  CacheState st;
+  HIP_TRY(hh, hipMemcpy(&st, h->state, sizeof st, hipMemcpyDeviceToHost));
+  std::vector<long long> sseq(c);
+  std::vector<int> snext(c);
+  if (c) {
+    HIP_TRY(hh, hipMemcpy(sseq.data(), h->slot_seq, c * sizeof(long long), hipMemcpyDeviceToHost));
+    HIP_TRY(hh, hipMemcpy(snext.data(), h->slot_next, c * sizeof(int), hipMemcpyDeviceToHost));
+  }
+  uint32_t count = 0;
+  for (int t = st.head; t >= 0 && count < c; t = snext[size_t(t)]) {
+    if (seq) seq[count] = uint64_t(sseq[size_t(t)]);
+    if (keys)
+      HIP_TRY(hh, hipMemcpy(keys + size_t(count) * d, h->srcs + size_t(t) * d, d * sizeof(float), hipMemcpyDeviceToHost));
+    if (ids)
+      HIP_TRY(hh, hipMemcpy(ids + size_t(count) * k, h->val_ids + size_t(t) * k, k * sizeof(int64_t),
+                            hipMemcpyDeviceToHost));
+    ++count;
+  }
+  *n_live = count;
+  return PROXIMITY_OK;
+}
+
+int proximity_clear(proximity_t* h) {
+  if (!h) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "handle is null");
+  DeviceGuard guard(h->cfg.device);
+  HIP_TRY(h, hipDeviceSynchronize());
+  CacheState init{};
+  init.head = init.tail = -1;
+  HIP_TRY(h, hipMemcpy(h->state, &init, sizeof init, hipMemcpyHostToDevice));
+  h->next_seq = 0;
+  return PROXIMITY_OK;
+}
+
+int proximity_profile_start(proximity_t* h) {
+  if (!h) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "handle is null");
+  DeviceGuard guard(h->cfg.device);
+  if (h->ev0.empty()) {
+    h->ev0.resize(kMaxProfiled);
+    h->ev1.resize(kMaxProfiled);
+    h->ev_info.resize(kMaxProfiled);
+    for (int i = 0; i < kMaxProfiled; ++i) {
+      HIP_TRY(h, hipEventCreate(&h->ev0[i]));
+      HIP_TRY(h, hipEventCreate(&h->ev1[i]));
+    }
+  }
+  h->ev_used = 0;
+  h->prof_call = 0;
+  h->prof_on = true;
+  return PROXIMITY_OK;
+}
+
+int proximity_profile_stop(proximity_t* h, proximity_launch_t* records, uint32_t cap, uint32_t* n_records) {
+  if (!h) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "handle is null");
+  if (n_records) *n_records = 0;
+  if (cap > 0 && !records) return fail(h, PROXIMITY_ERR_INVALID_ARG, "records is null but cap > 0");
+  DeviceGuard guard(h->cfg.device);
+  h->prof_on = false;
+  HIP_TRY(h, hipStreamSynchronize(h->last_stream));
+  uint32_t w = 0;
+  for (size_t i = 0; i < h->ev_used && w < cap; ++i) {
+    float ms = 0.f;
+    HIP_TRY(h, hipEventElapsedTime(&ms, h->ev0[i], h->ev1[i]));
+    records[w] = h->ev_info[i];
+    records[w].ms = ms;
+    ++w;
+  }
+  if (n_records) *n_records = w;
+  h->ev_used = 0;
+  return PROXIMITY_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+"""C-ABI checks that need no GPU: the library loads, exports every declared
+symbol, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    lib_path = os.path.join(ROOT, "paper_2503_05530_amd", "csrc", "libproximity.so")
+    if not os.path.exists(lib_path):
+        from paper_2503_05530_amd.build import build_library
+        build_library(verbose=False)
+    import paper_2503_05530_amd.binding as b
+    return b
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "proximity.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(proximity_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(binding):
+    names = declared_functions()
+    assert "proximity_create" in names and "proximity_search_batch" in names and "proximity_stats" in names
+    for name in names:
+        assert hasattr(binding.lib, name), f"{name} is declared in proximity.h but not exported"
+    assert sorted(binding.EXPORTED) == names
+
+
+def test_abi_version_and_struct_layout(binding):
+    assert binding.proximity_abi_version() == 1
+    assert C.sizeof(binding.ProximityConfig) == 48
+    assert C.sizeof(binding.ProximityStats) == 128
+    assert C.sizeof(binding.ProximityLaunch) == 16
+
+
+def make_cfg(b, **kw):
+    vals = dict(struct_size=C.sizeof(b.ProximityConfig), dim=768, corpus=None, n_docs=0, corpus_dtype=0,
+                capacity=10, k=10, policy=0, max_batch=8, device=0)
+    vals.update(kw)
+    return b.ProximityConfig(**vals)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(struct_size=8), dict(dim=0), dict(dim=100), dict(dim=8192), dict(k=0), dict(k=1000),
+    dict(max_batch=0), dict(max_batch=1 << 20), dict(capacity=(1 << 20) + 1), dict(n_docs=1 << 31),
+    dict(n_docs=5, corpus=None), dict(corpus_dtype=7), dict(policy=2), dict(device=-1),
+])
+def test_create_rejects_bad_config_before_any_gpu_work(binding, kw):
+    b = binding
+    h = C.c_void_p(123)
+    rc = b.lib.proximity_create(C.byref(make_cfg(b, **kw)), C.byref(h))
+    assert rc == b.ERR_INVALID_ARG
+    assert h.value is None
+    assert b.last_error(None) != ""
+
+
+def test_null_arguments(binding):
+    b = binding
+    h = C.c_void_p()
+    assert b.lib.proximity_create(None, C.byref(h)) == b.ERR_INVALID_ARG
+    assert b.lib.proximity_create(C.byref(make_cfg(b)), None) == b.ERR_INVALID_ARG
+    assert b.lib.proximity_search_batch(None, None, 1, 10, 0.5, None, None, None, None) == b.ERR_INVALID_ARG
+    assert b.lib.proximity_knn_batch(None, None, 1, 10, None, None, None) == b.ERR_INVALID_ARG
+    assert b.lib.proximity_stats(None, None) == b.ERR_INVALID_ARG
+    assert b.lib.proximity_clear(None) == b.ERR_INVALID_ARG
+    assert b.lib.proximity_profile_start(None) == b.ERR_INVALID_ARG
+    n = C.c_uint32(0)
+    assert b.lib.proximity_cache_dump(None, None, None, None, C.byref(n)) == b.ERR_INVALID_ARG
+    b.lib.proximity_destroy(None)  # must be a no-op

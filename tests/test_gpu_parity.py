@@ -1,0 +1,231 @@
+"""GPU-vs-oracle parity through the C ABI (element by element, same seeded inputs)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import proximity_oracle as po
+from paper_2503_05530_amd import workloads as W
+
+import parity as P
+from test_oracle_pins import EVICTION_CASES, line_vectors
+
+pytestmark = pytest.mark.gpu
+
+DEV = torch.device("cuda:0")
+
+
+@pytest.fixture(scope="module")
+def B():
+    import paper_2503_05530_amd.binding as b
+    return b
+
+
+def gpu_corpus(x: np.ndarray, bf16=False):
+    t = torch.from_numpy(x).to(DEV)
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+# ---------------------------------------------------------------------------
+# The index search alone (Section 2.2)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n_docs,dim,k,nq", [
+    (5000, 768, 10, 1), (5000, 768, 10, 3), (9001, 768, 32, 8), (4097, 384, 100, 5),
+    (700, 64, 7, 2), (70000, 768, 10, 13), (3, 32, 5, 2), (8191, 1024, 16, 4), (300, 4096, 3, 8),
+])
+def test_knn_matches_oracle_f32(B, n_docs, dim, k, nq):
+    corpus = W.corpus_f32(n_docs, dim, 3)
+    q = W.unit_rows(np.random.default_rng(5).standard_normal((nq, dim))).astype(np.float32)
+    px = B.Proximity(gpu_corpus(corpus), dim, 0, k, B.POLICY_FIFO, max(nq, 1))
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    ids, dists = ids.cpu().numpy(), dists.cpu().numpy()
+    o_ids, o_d = po.batched_exact_knn(corpus, q, k)
+    P.assert_lists_match(ids, dists, o_ids, o_d, corpus, q, what=f"knn {n_docs}x{dim}")
+    px.close()
+
+
+def test_knn_matches_oracle_bf16(B):
+    n_docs, dim, k, nq = 20000, 384, 100, 6
+    x32 = W.corpus_f32(n_docs, dim, 9)
+    bits = W.f32_to_bf16_bits(x32)
+    xb = W.bf16_bits_to_f32(bits)                       # exact values the GPU holds
+    t = torch.from_numpy(x32).to(DEV).to(torch.bfloat16)
+    assert (t.view(torch.int16).cpu().numpy().view(np.uint16) == bits).all()
+    q = W.unit_rows(np.random.default_rng(6).standard_normal((nq, dim))).astype(np.float32)
+    px = B.Proximity(t, dim, 0, k, B.POLICY_FIFO, nq)
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    o_ids, o_d = po.batched_exact_knn(xb, q, k)
+    P.assert_lists_match(ids.cpu().numpy(), dists.cpu().numpy(), o_ids, o_d, xb, q,
+                         dist_rtol=P.DIST_RTOL_BF16, what="knn bf16")
+    px.close()
+
+
+def test_knn_duplicate_rows_rank_by_index(B):
+    corpus = W.corpus_f32(6000, 768, 4)
+    corpus[4500] = corpus[17]
+    corpus[99] = corpus[17]
+    q = corpus[17:18].copy()
+    px = B.Proximity(gpu_corpus(corpus), 768, 0, 5, B.POLICY_FIFO, 1)
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    o_ids, o_d = po.exact_knn(corpus, q[0], 5)
+    assert ids.cpu().numpy()[0].tolist() == o_ids.tolist()
+    assert ids.cpu().numpy()[0, :3].tolist() == [17, 99, 4500]
+    assert dists.cpu().numpy()[0, :3].tolist() == [0.0, 0.0, 0.0]
+    px.close()
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1: hand-worked traces, as one batch per query and as one batch in all
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("case", EVICTION_CASES, ids=[c["name"] for c in EVICTION_CASES])
+@pytest.mark.parametrize("batch", [1, 2, 64])
+def test_hand_worked_traces(B, case, batch):
+    # rows of different lengths, so that the all-zero query has no near-tied neighbours
+    corpus = W.corpus_f32(257, 32, 3) * (1.0 + np.arange(257, dtype=np.float32)[:, None] / 64.0)
+    q = line_vectors(case["xs"], dim=32)
+    orc = po.FlatCacheOracle(corpus, case["capacity"], 3, case["policy"])
+    want = orc.lookup_stream(q, case["tau"])
+    assert "".join("H" if h else "M" for h in want[2]) == case["flags"]
+    px = B.Proximity(gpu_corpus(corpus), 32, case["capacity"], 3, case["policy"], 64)
+    got = P.run_stream(px, q, case["tau"], batch, DEV)
+    assert "".join("H" if h else "M" for h in got[2]) == case["flags"]
+    assert P.assert_stream_parity(got, want, corpus, q, what=case["name"]) == 0
+    seq, keys, ids = px.cache_dump(want_keys=True, want_ids=True)
+    assert seq.tolist() == case["left"]
+    if len(seq):
+        assert (keys == q[seq]).all()
+        assert (ids == orc.dump_ids()).all()
+    st = px.stats()
+    assert st["evictions"] == case["evictions"]
+    assert st["hits"] == case["flags"].count("H") and st["misses"] == case["flags"].count("M")
+    assert st["size"] == len(case["left"]) and st["queries"] == len(q)
+    px.close()
+
+
+# ---------------------------------------------------------------------------
+# Small workload end to end, several batch sizes (same results for any split)
+# ---------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def tiny():
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_for(w)
+    q = W.stream_for(w)
+    out = {}
+    for policy in (po.POLICY_FIFO, po.POLICY_LRU):
+        out[policy] = po.lookup_stream_deferred(corpus, q, w.tau, w.capacity, w.k, policy)
+    return w, corpus, q, out
+
+
+@pytest.mark.parametrize("batch", [1, 7, 64, 256])
+@pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
+def test_tiny_workload(B, tiny, batch, policy):
+    w, corpus, q, want = tiny
+    o_ids, o_d, o_hit, o_src, dec = want[policy]
+    px = B.Proximity(gpu_corpus(corpus), w.dim, w.capacity, w.k, policy, 256)
+    got = P.run_stream(px, q, w.tau, batch, DEV)
+    excused = P.assert_stream_parity(got, (o_ids, o_d, o_hit, o_src), corpus, q, what=f"tiny b{batch}")
+    assert excused == 0
+    seq, _, ids = px.cache_dump(want_ids=True)
+    assert seq.tolist() == dec.dump_seq().tolist()
+    assert (ids == o_ids[seq]).all()
+    st = px.stats()
+    assert st["hits"] == int(o_hit.sum()) and st["evictions"] == dec.n_evictions
+    if policy == w.policy:
+        assert st["hits"] == 697 and st["evictions"] == 253
+    px.close()
+
+
+def test_tau_zero_and_tau_huge(B, tiny):
+    w, corpus, q, _ = tiny
+    q = q[:200]
+    knn_ids, knn_d = po.batched_exact_knn(corpus, q, w.k)
+    px = B.Proximity(gpu_corpus(corpus), w.dim, w.capacity, w.k, w.policy, 64)
+    ids, dists, hit = P.run_stream(px, q, 0.0, 64, DEV)
+    assert hit.sum() == 0
+    P.assert_lists_match(ids, dists, knn_ids, knn_d, corpus, q, what="tau=0")
+    px.clear()
+    ids, dists, hit = P.run_stream(px, q, 1e9, 64, DEV)
+    assert hit.tolist() == [0] + [1] * 199
+    assert (ids == ids[0:1]).all() and (ids[0] == knn_ids[0]).all()
+    st = px.stats()
+    assert st["size"] == 1 and st["queries"] == 200
+    px.close()
+
+
+def test_repeated_vector_hits_at_tau_zero(B, tiny):
+    w, corpus, q, _ = tiny
+    stream = np.stack([q[0], q[1], q[0], q[1], q[0]])
+    px = B.Proximity(gpu_corpus(corpus), w.dim, 4, w.k, po.POLICY_LRU, 8)
+    for batch in (1, 5):
+        px.clear()
+        ids, dists, hit = P.run_stream(px, stream, 0.0, batch, DEV)
+        assert hit.tolist() == [0, 0, 1, 1, 1]
+        assert (ids[2] == ids[0]).all() and (ids[3] == ids[1]).all()
+    px.close()
+
+
+def test_many_candidates_take_the_dense_path(B):
+    """Rows with more in-tolerance sources than the candidate list holds."""
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(2000, w.dim, 2)
+    base = W.base_queries(3, w.dim, 8)
+    idx = np.random.default_rng(0).integers(0, 3, size=400)
+    q = W.perturbed_stream(base, idx, 0.1, 8)
+    for policy, cap in ((po.POLICY_LRU, 2), (po.POLICY_FIFO, 2), (po.POLICY_LRU, 200)):
+        want = po.lookup_stream_deferred(corpus, q, 0.25, cap, 5, policy)
+        px = B.Proximity(gpu_corpus(corpus), w.dim, cap, 5, policy, 400)
+        got = P.run_stream(px, q, 0.25, 400, DEV)
+        P.assert_stream_parity(got, want[:4], corpus, q, what="dense path")
+        seq, _, _ = px.cache_dump()
+        assert seq.tolist() == want[4].dump_seq().tolist()
+        assert px.stats()["dense_resolves"] > 0
+        px.close()
+
+
+def test_no_corpus_and_no_cache(B):
+    w = W.WORKLOADS["tiny"]
+    q = W.stream_for(w, 40)
+    px = B.Proximity(None, w.dim, 8, 4, po.POLICY_LRU, 16, device=DEV)
+    ids, dists, hit = P.run_stream(px, q, 0.25, 16, DEV)
+    o_hit, _, _ = po.simulate_decisions(q, 0.25, 8, po.POLICY_LRU)
+    assert (hit == o_hit).all() and (ids == -1).all() and np.isinf(dists).all()
+    px.close()
+    corpus = W.corpus_f32(1000, w.dim, 1)
+    px = B.Proximity(gpu_corpus(corpus), w.dim, 0, 4, po.POLICY_LRU, 16)
+    ids, dists, hit = P.run_stream(px, q, 1e9, 16, DEV)
+    assert hit.sum() == 0 and px.stats()["size"] == 0
+    o_ids, o_d = po.batched_exact_knn(corpus, q, 4)
+    P.assert_lists_match(ids, dists, o_ids, o_d, corpus, q, what="capacity 0")
+    px.close()
+
+
+def test_call_errors_leave_state_untouched(B, tiny):
+    w, corpus, q, _ = tiny
+    px = B.Proximity(gpu_corpus(corpus), w.dim, 4, w.k, po.POLICY_LRU, 8)
+    qd = torch.from_numpy(q[:8]).to(DEV)
+    ids = torch.empty((8, w.k), dtype=torch.int64, device=DEV)
+    hit = torch.empty(8, dtype=torch.uint8, device=DEV)
+    lib, h = B.lib, px.handle
+    assert lib.proximity_search_batch(h, qd.data_ptr(), 8, w.k + 1, 0.1, ids.data_ptr(), None, hit.data_ptr(), None) == B.ERR_K_MISMATCH
+    assert lib.proximity_search_batch(h, qd.data_ptr(), 9, w.k, 0.1, ids.data_ptr(), None, hit.data_ptr(), None) == B.ERR_BATCH_TOO_LARGE
+    for bad in (float("nan"), float("inf"), -1.0):
+        assert lib.proximity_search_batch(h, qd.data_ptr(), 8, w.k, bad, ids.data_ptr(), None, hit.data_ptr(), None) == B.ERR_BAD_TAU
+    assert lib.proximity_search_batch(h, None, 8, w.k, 0.1, ids.data_ptr(), None, hit.data_ptr(), None) == B.ERR_INVALID_ARG
+    assert lib.proximity_search_batch(h, qd.data_ptr(), 8, w.k, 0.1, ids.data_ptr(), None, None, None) == B.ERR_INVALID_ARG
+    assert "out_hit" in B.last_error(h)
+    assert px.stats()["queries"] == 0
+    assert lib.proximity_search_batch(h, qd.data_ptr(), 0, w.k, 0.1, None, None, None, None) == B.OK
+    px.close()
+
+
+def test_same_batch_three_times_is_bit_identical(B, tiny):
+    w, corpus, q, _ = tiny
+    outs = []
+    for _ in range(3):
+        px = B.Proximity(gpu_corpus(corpus), w.dim, w.capacity, w.k, w.policy, 128)
+        outs.append(P.run_stream(px, q[:512], w.tau, 128, DEV))
+        px.close()
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert (a == b).all()
