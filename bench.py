@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Throughput of the Proximity-FLAT retrieval step on one MI355X.
+
+A step is one proximity_search_batch call (cache probe, resolver, corpus scan
+for the misses, top-k, routing) on one batch of the seeded synthetic stream.
+The default workload is the 1 M x 768 float32 corpus with the Zipf(1.1) query
+stream, capacity 300, LRU, k = 10, tau = 0.25, one query per call.
+
+Prints one JSON line: whole-job queries/s, the roofline of the dominant kernel
+(the streaming corpus-scan distance kernel, timed with HIP events inside the
+library on the call's stream) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+F32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense float32 matrix, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed search_batch calls")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed calls before them")
+    ap.add_argument("--workload", default="mid", choices=["tiny", "mid"])
+    ap.add_argument("--tau", type=float, default=None)
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--n-docs", type=int, default=None, help="override corpus rows (debugging only)")
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=24, help="queries the oracle is timed on")
+    return ap.parse_args()
+
+
+def run_region(px, q_dev, tau, batch, first, n_calls, outs):
+    """Issue n_calls calls on consecutive batches starting at row `first`."""
+    ids, dists, hit = outs
+    for c in range(n_calls):
+        r0 = first + c * batch
+        px.search_batch(q_dev[r0:r0 + batch], tau, ids[r0:r0 + batch], dists[r0:r0 + batch], hit[r0:r0 + batch])
+
+
+def timed_run(torch, px, q_dev, tau, batch, warmup, steps, outs, device):
+    px.clear()
+    run_region(px, q_dev, tau, batch, 0, warmup, outs)
+    torch.cuda.synchronize(device)
+    t0 = time.perf_counter()
+    run_region(px, q_dev, tau, batch, warmup * batch, steps, outs)
+    torch.cuda.synchronize(device)
+    dt = time.perf_counter() - t0
+    hit = outs[2][warmup * batch:(warmup + steps) * batch]
+    return dt, float(hit.float().mean().item())
+
+
+def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, device):
+    """Re-run a stretch with per-launch HIP-event timing of the scan distance kernel."""
+    px.profile_start()
+    run_region(px, q_dev, tau, batch, first_call * batch, n_calls, outs)
+    rec = px.profile_stop()
+    hit = outs[2].cpu().numpy()
+    busy = []
+    for call, first_query, n_q, ms in rec:
+        r0 = (first_call + call) * batch
+        misses = int((hit[r0:r0 + batch] == 0).sum())
+        if misses > first_query:
+            busy.append((ms, min(n_q, misses - first_query)))
+    return busy
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2503_05530_amd import workloads as W
+    from paper_2503_05530_amd.binding import Proximity
+
+    device = torch.device("cuda:0")
+    w = W.WORKLOADS[args.workload]
+    tau = w.tau if args.tau is None else args.tau
+    batch = w.batch if args.batch is None else args.batch
+    n_docs = w.n_docs if args.n_docs is None else args.n_docs
+    steps = args.steps if args.steps is not None else (20000 if batch == 1 else 1000)
+    warmup = args.warmup if args.warmup is not None else (2000 if batch == 1 else 50)
+    if (steps + warmup) * batch > w.n_stream:
+        steps = w.n_stream // batch - warmup
+    max_batch = max(batch, 64)
+
+    t_gen = time.perf_counter()
+    corpus = W.corpus_for(w, n_docs)
+    queries = W.stream_for(w)
+    corpus_dev = torch.from_numpy(corpus).to(device)
+    q_dev = torch.from_numpy(queries).to(device)
+    t_gen = time.perf_counter() - t_gen
+
+    px = Proximity(corpus_dev, w.dim, w.capacity, w.k, w.policy, max_batch)
+    n_rows = len(queries)
+    outs = (torch.empty((n_rows, w.k), dtype=torch.int64, device=device),
+            torch.empty((n_rows, w.k), dtype=torch.float32, device=device),
+            torch.empty((n_rows,), dtype=torch.uint8, device=device))
+
+    dt, hit_rate = timed_run(torch, px, q_dev, tau, batch, warmup, steps, outs, device)
+    qps = steps * batch / dt
+
+    # roofline of the dominant kernel: single-query streaming scan, HBM-bound
+    n_prof = min(steps, 4000 // max(1, (batch + 7) // 8))
+    busy = profiled_scan(torch, px, q_dev, tau, batch, warmup + steps - n_prof, n_prof, outs, device)
+    bytes_per_launch = n_docs * w.dim * 4 + n_docs * 4      # corpus rows + their norms, read once
+    roofline = None
+    if busy:
+        avg_ms = sum(ms for ms, _ in busy) / len(busy)
+        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "kernel": "scores_stream_kernel", "launches_timed": len(busy),
+                    "avg_launch_ms": round(avg_ms, 5), "algorithmic_bytes_per_launch": bytes_per_launch,
+                    "queries_per_launch_avg": round(sum(q for _, q in busy) / len(busy), 3)}
+
+    sweep = []
+    if not args.no_sweep and args.workload == "mid":
+        for s_tau, s_batch, s_warm, s_steps in ((0.0, 1, 100, 2000), (0.25, 64, 30, 300), (0.0, 64, 4, 30)):
+            s_dt, s_hit = timed_run(torch, px, q_dev, s_tau, s_batch, s_warm, s_steps, outs, device)
+            sweep.append({"tau": s_tau, "batch": s_batch, "steps": s_steps, "warmup": s_warm,
+                          "queries_per_s": round(s_steps * s_batch / s_dt, 1), "hit_rate": round(s_hit, 4),
+                          "ms_per_step": round(1e3 * s_dt / s_steps, 4)})
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import proximity_oracle as po
+        first = warmup * batch
+        orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy,
+                                 retrieve=lambda q: (np.full(w.k, -1, np.int64), np.full(w.k, np.inf)))
+        orc.lookup_stream(queries[:first], tau)            # decisions only: brings the cache to the timed region's state
+        orc.retrieve = lambda q: po.exact_knn(corpus, q, w.k)
+        n_s = min(args.cpu_sample, len(queries) - first)
+        t0 = time.perf_counter()
+        o_ids, o_d, o_hit, _ = orc.lookup_stream(queries[first:first + n_s], tau)
+        cdt = time.perf_counter() - t0
+        cpu = {"value": round(n_s / cdt, 4), "unit": "queries/s", "cores": 1, "kind": "oracle",
+               "sample": f"stream rows {first}..{first + n_s - 1} of the same workload after a decisions-only "
+                         f"replay of rows 0..{first - 1}; {int((o_hit == 0).sum())} misses, "
+                         f"{cdt:.1f} s, float64 numpy (single-threaded element-wise code)",
+               "host_cpus": os.cpu_count()}
+
+    line = {
+        "metric": "retrieval_queries_per_sec", "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(1e3 * dt / steps, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: corpus {n_docs}x{w.dim} f32 unit Gaussian, Zipf({w.zipf_s}) stream of "
+                               f"{w.n_stream} over {w.n_bases} bases (perturbation {w.radius}), capacity "
+                               f"{w.capacity}, {'LRU' if w.policy else 'FIFO'}, k={w.k}",
+                   "tau": tau, "batch": batch, "hit_rate": round(hit_rate, 4),
+                   "queries_timed": steps * batch, "setup_s": round(t_gen, 1)},
+        "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
+    }
+    print(json.dumps(line))
+    px.close()
+
+
+if __name__ == "__main__":
+    main()
