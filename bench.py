@@ -76,6 +76,28 @@ def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, devic
     return busy
 
 
+def scan_roofline(busy, n_docs, dim, batch):
+    """Roofline entry from (duration ms, queries served) of the launches that streamed the corpus."""
+    if not busy:
+        return None
+    bytes_per_launch = n_docs * dim * 4 + n_docs * 4      # corpus rows + their norms, read once
+    avg_ms = sum(ms for ms, _ in busy) / len(busy)
+    avg_q = sum(q for _, q in busy) / len(busy)
+    gbs = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    tflops = sum(2.0 * q * n_docs * dim for _, q in busy) / (sum(ms for ms, _ in busy) * 1e-3) / 1e12
+    ridge_q = F32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) * 4 / 2   # queries per launch at the ridge
+    common = {"traffic": None, "kernel": "scores_stream_kernel" if batch <= 8 else "scan_mfma_topk_kernel",
+              "launches_timed": len(busy), "avg_launch_ms": round(avg_ms, 5),
+              "queries_per_launch_avg": round(avg_q, 3), "achieved_GBps": round(gbs, 1),
+              "achieved_TFLOPs": round(tflops, 2), "algorithmic_bytes_per_launch": bytes_per_launch,
+              "algorithmic_flops_per_launch_avg": 2.0 * avg_q * n_docs * dim}
+    if avg_q < ridge_q:
+        return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), **common}
+    return {"bound": "mfma", "achieved": round(tflops, 2), "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tflops / F32_MFMA_PEAK_TFLOPS, 4), **common}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -115,27 +137,22 @@ def main():
     dt, hit_rate = timed_run(torch, px, q_dev, tau, batch, warmup, steps, outs, device)
     qps = steps * batch / dt
 
-    # roofline of the dominant kernel: single-query streaming scan, HBM-bound
-    n_prof = min(steps, 4000 // max(1, (batch + 7) // 8))
+    # roofline of the dominant kernel, the corpus-scan distance kernel: HBM-bound while a launch serves
+    # few queries, matrix-core-bound once 2*M flops per 4 corpus bytes pass the ridge (157.3 TF / 8 TB/s)
+    n_prof = min(steps, 4000 if batch <= 8 else 400)
     busy = profiled_scan(torch, px, q_dev, tau, batch, warmup + steps - n_prof, n_prof, outs, device)
-    bytes_per_launch = n_docs * w.dim * 4 + n_docs * 4      # corpus rows + their norms, read once
-    roofline = None
-    if busy:
-        avg_ms = sum(ms for ms, _ in busy) / len(busy)
-        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                    "kernel": "scores_stream_kernel", "launches_timed": len(busy),
-                    "avg_launch_ms": round(avg_ms, 5), "algorithmic_bytes_per_launch": bytes_per_launch,
-                    "queries_per_launch_avg": round(sum(q for _, q in busy) / len(busy), 3)}
+    roofline = scan_roofline(busy, n_docs, w.dim, batch)
 
     sweep = []
     if not args.no_sweep and args.workload == "mid":
-        for s_tau, s_batch, s_warm, s_steps in ((0.0, 1, 100, 2000), (0.25, 64, 30, 300), (0.0, 64, 4, 30)):
+        for s_tau, s_batch, s_warm, s_steps in ((0.0, 1, 100, 2000), (0.25, 64, 30, 300), (0.0, 64, 10, 200)):
             s_dt, s_hit = timed_run(torch, px, q_dev, s_tau, s_batch, s_warm, s_steps, outs, device)
+            s_busy = profiled_scan(torch, px, q_dev, s_tau, s_batch, s_warm + s_steps - min(s_steps, 200),
+                                   min(s_steps, 200), outs, device)
             sweep.append({"tau": s_tau, "batch": s_batch, "steps": s_steps, "warmup": s_warm,
                           "queries_per_s": round(s_steps * s_batch / s_dt, 1), "hit_rate": round(s_hit, 4),
-                          "ms_per_step": round(1e3 * s_dt / s_steps, 4)})
+                          "ms_per_step": round(1e3 * s_dt / s_steps, 4),
+                          "roofline": scan_roofline(s_busy, n_docs, w.dim, s_batch)})
 
     cpu = None
     if not args.no_cpu_baseline:

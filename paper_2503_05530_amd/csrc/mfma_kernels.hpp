@@ -1,0 +1,379 @@
+// Batched query-by-rows contraction on the float32 matrix cores (v_mfma_f32_32x32x2_f32).
+//
+// The batched form of the distance step really is a dense GEMM:
+//   score[m][j] = |x_j|^2 - 2 * sum_k q_m[k] x_j[k]
+// for M queries against N stored rows.  Two kernels share one tiled main loop:
+//
+//   scan_mfma_topk_kernel   corpus scan fused with a running per-query top-k, so
+//                           the M x N score matrix is never written (Section 2.2's
+//                           search for many queries at once);
+//   probe_mfma_dense_kernel cache probe: batch rows against [slot keys ; batch
+//                           rows], scores written densely for the resolver
+//                           (Algorithm 1, distances to every key).
+//
+// Tiling.  A block of 256 threads (4 waves) computes a TR x TC tile of the
+// product A[TR x d] * B[TC x d]^T, both operands row-major with the contraction
+// along rows.  The contraction runs in slabs of 32: the 256 threads copy the
+// slab of both operands from global memory to registers (16-byte loads, eight
+// lanes cover 128 contiguous bytes of one row), then to LDS with a row stride
+// of 36 floats, which makes the 16-byte fragment reads below conflict-free.
+// Global loads for slab s+1 are issued before the matrix instructions of slab s.
+//
+// Fragment order.  v_mfma_f32_32x32x2_f32 takes A[i][k] from lane (i + 32k) and
+// B[k][j] from lane (j + 32k), k in {0,1}.  A lane reads four consecutive floats
+// of "its" row with one ds_read_b128: lanes 0-31 at slab columns 8t..8t+3, lanes
+// 32-63 at 8t+4..8t+7.  Register e of both fragments then pairs column 8t+e with
+// 8t+4+e; a dot product does not care in which order its terms are added, so
+// four matrix instructions consume the eight columns.  Result element v of lane
+// l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the 32 x 32 block.
+#pragma once
+
+#include <type_traits>
+
+#include "device_utils.hpp"
+
+namespace prox {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kSlabK = 32;   // contraction columns per slab
+constexpr int kLdsK = 36;    // LDS row stride in floats
+constexpr int kTopkCap = 512;  // per (block, query) candidate buffer entries
+
+// ---- operand slab movement ------------------------------------------------------
+// T rows x 32 columns of float32 = T*8 chunks of 16 bytes; thread t takes chunks
+// t, t+256, ...  Chunk c is row c/8, columns 4*(c%8)..+3.
+template <int T>
+struct SlabF32 {
+  static constexpr int NCH = T * 8 / 256;
+  float4 v[NCH];
+  // rows[i] points at column 0 of the row of chunk i (nullptr: row absent -> zeros)
+  __device__ __forceinline__ void load(const float* const (&rows)[NCH], int k0, int tid) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c4 = (tid + 256 * i) & 7;
+      v[i] = rows[i] ? *reinterpret_cast<const float4*>(rows[i] + k0 + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  __device__ __forceinline__ void store(float* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + 256 * i;
+      *reinterpret_cast<float4*>(lds + (c >> 3) * kLdsK + 4 * (c & 7)) = v[i];
+    }
+  }
+};
+
+// T rows x 32 columns of bfloat16 = T*4 chunks of 16 bytes (8 values); chunk c is
+// row c/4, columns 8*(c%4)..+7.  Widened to float32 on the way into LDS.
+template <int T>
+struct SlabBF16 {
+  static constexpr int NCH = (T * 4 + 255) / 256;
+  uint4 v[NCH];
+  __device__ __forceinline__ void load(const uint16_t* const (&rows)[NCH], int k0, int tid) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c8 = (tid + 256 * i) & 3;
+      v[i] = rows[i] ? *reinterpret_cast<const uint4*>(rows[i] + k0 + 8 * c8) : make_uint4(0, 0, 0, 0);
+    }
+  }
+  __device__ __forceinline__ void store(float* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + 256 * i;
+      if (c < T * 4) {
+        float* p = lds + (c >> 2) * kLdsK + 8 * (c & 3);
+        const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+        *reinterpret_cast<float4*>(p) =
+            make_float4(__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xffff0000u),
+                        __uint_as_float(w[1] << 16), __uint_as_float(w[1] & 0xffff0000u));
+        *reinterpret_cast<float4*>(p + 4) =
+            make_float4(__uint_as_float(w[2] << 16), __uint_as_float(w[2] & 0xffff0000u),
+                        __uint_as_float(w[3] << 16), __uint_as_float(w[3] & 0xffff0000u));
+      }
+    }
+  }
+};
+
+// ---- one slab of matrix instructions -------------------------------------------
+// The wave's RB x CB blocks of 32 x 32: rows from As starting at a_row0, columns
+// from Bs starting at b_row0.
+template <int RB, int CB>
+__device__ __forceinline__ void mfma_slab(const float* __restrict__ As, const float* __restrict__ Bs, int a_row0,
+                                          int b_row0, int lane, f32x16 (&acc)[RB][CB]) {
+  const int r = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int t = 0; t < kSlabK / 8; ++t) {
+    float4 a[RB], b[CB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+      a[i] = *reinterpret_cast<const float4*>(As + (a_row0 + 32 * i + r) * kLdsK + 8 * t + 4 * half);
+#pragma unroll
+    for (int j = 0; j < CB; ++j)
+      b[j] = *reinterpret_cast<const float4*>(Bs + (b_row0 + 32 * j + r) * kLdsK + 8 * t + 4 * half);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+#pragma unroll
+      for (int i = 0; i < RB; ++i)
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+          const float av = e == 0 ? a[i].x : e == 1 ? a[i].y : e == 2 ? a[i].z : a[i].w;
+          const float bv = e == 0 ? b[j].x : e == 1 ? b[j].y : e == 2 ? b[j].z : b[j].w;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+        }
+    }
+  }
+}
+
+// Wave-private ascending sort of P (power of two, <= 512) keys in LDS.
+__device__ __forceinline__ void wave_bitonic_sort_lds(uint64_t* keys, int P, int lane) {
+  for (int k = 2; k <= P; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = lane; t < (P >> 1); t += 64) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int p = i | j;
+        const bool asc = (i & k) == 0;
+        const uint64_t a = keys[i], b = keys[p];
+        if ((a > b) == asc) {
+          keys[i] = b;
+          keys[p] = a;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+// Reduce the candidate buffer of one query to its kp best, by one wave:
+// buf[0..n) -> sorted buf[0..min(n,kp)); returns the new count and updates the
+// query's bound when at least kp candidates exist.
+__device__ __forceinline__ int wave_compact_topk(uint64_t* buf, int n, int kp, uint64_t* scratch, float* bound,
+                                                 int lane) {
+  const int P = next_pow2(n < 2 ? 2 : n);
+  for (int i = lane; i < P; i += 64) scratch[i] = i < n ? buf[i] : kPadKey;
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  wave_bitonic_sort_lds(scratch, P, lane);
+  const int keep = n < kp ? n : kp;
+  for (int i = lane; i < keep; i += 64) buf[i] = scratch[i];
+  if (n >= kp && lane == 0) *bound = key_score(scratch[kp - 1]);
+  return keep;
+}
+
+// ---------------------------------------------------------------------------
+// Corpus scan fused with top-k.
+//
+// Operand A = corpus rows (TN per tile), operand B = the query tile (TM rows,
+// fixed for the block).  Grid: x = blocks sharing the corpus (each owns a
+// contiguous range of tiles), y = query tiles.  The kernel serves miss counts
+// M with m_lo < M <= m_hi and returns at once otherwise, so the host can launch
+// the tile shapes for small, medium and large M back to back without knowing M.
+//
+// A launch covers the queries m_base + blockIdx.y*TM + (0..TM-1) of the miss list.
+//
+// Running top-k per (block, query): a bound T (the kp-th best score seen by this
+// block, +inf until kp rows were seen) and a buffer of kTopkCap packed keys in
+// global memory.  After each tile every score below T is appended; when a
+// buffer could overflow on the next tile it is sorted and cut back to kp
+// entries by one wave, which also tightens T.  Rows are visited in ascending id
+// and a later row with score == T has a larger id than the kp entries at or
+// below T, so the strict comparison loses nothing.  At the end each query's
+// buffer is cut to kp sorted entries and written to
+//   out[((m0 + q) * gridDim.x + blockIdx.x) * kp ..]   (padded with kPadKey).
+// ---------------------------------------------------------------------------
+template <int TM, int TN, int DT>
+__global__ __launch_bounds__(256, 2) void scan_mfma_topk_kernel(
+    const void* __restrict__ X, const float* __restrict__ xnrm, long n_rows, int dim,
+    const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
+    int m_limit, int m_base, int m_lo, int m_hi, int kp, uint64_t* __restrict__ cand_buf,
+    uint64_t* __restrict__ out) {
+  constexpr int WR = TM >= 128 ? 2 : 4;        // waves along corpus rows
+  constexpr int WC = 4 / WR;                   // waves along queries
+  constexpr int RB = TN / WR / 32;             // 32-row blocks per wave
+  constexpr int CB = TM / WC / 32;             // 32-query blocks per wave
+  static_assert(RB >= 1 && CB >= 1, "tile too small for four waves");
+
+  const int M = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
+  if (M <= m_lo || M > m_hi) return;
+  const int m0 = m_base + blockIdx.y * TM;
+  if (m0 >= M) return;
+
+  __shared__ __attribute__((aligned(16))) float As[TN * kLdsK];
+  __shared__ __attribute__((aligned(16))) float Bs[TM * kLdsK];
+  __shared__ uint64_t sort_scratch[4][kTopkCap];
+  __shared__ float bound[TM];
+  __shared__ int count[TM];
+  __shared__ float tile_nrm[TN];
+
+  const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  const int wr = wib % WR, wc = wib / WR;
+  const int a_row0 = wr * (TN / WR), b_row0 = wc * (TM / WC);
+
+  for (int i = tid; i < TM; i += 256) {
+    bound[i] = __uint_as_float(0x7f800000u);
+    count[i] = 0;
+  }
+
+  // this block's share of the corpus tiles
+  const long n_tiles = (n_rows + TN - 1) / TN;
+  const long t_begin = n_tiles * blockIdx.x / gridDim.x;
+  const long t_end = n_tiles * (blockIdx.x + 1) / gridDim.x;
+  uint64_t* my_buf = cand_buf + (long(blockIdx.y) * gridDim.x + blockIdx.x) * long(TM) * kTopkCap;
+
+  // query rows of this block (operand B)
+  SlabF32<TM> qs;
+  const float* qrows[SlabF32<TM>::NCH];
+#pragma unroll
+  for (int i = 0; i < SlabF32<TM>::NCH; ++i) {
+    const int r = (tid + 256 * i) >> 3;
+    const int m = m0 + r;
+    qrows[i] = m < M ? Qbase + long(qlist ? qlist[m] : m) * dim : nullptr;
+  }
+
+  using SlabX = typename std::conditional<DT == kDtypeF32, SlabF32<TN>, SlabBF16<TN>>::type;
+  using XElem = typename std::conditional<DT == kDtypeF32, float, uint16_t>::type;
+  constexpr int XCH = SlabX::NCH;
+  constexpr int XCPR = DT == kDtypeF32 ? 8 : 4;  // chunks per row
+  SlabX xs;
+  const int n_slabs = dim / kSlabK;
+
+  for (long tile = t_begin; tile < t_end; ++tile) {
+    const long row0 = tile * TN;
+    const XElem* xrows[XCH];
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) {
+      const long r = row0 + (tid + 256 * i) / XCPR;
+      xrows[i] = (r < n_rows && (tid + 256 * i) < TN * XCPR) ? static_cast<const XElem*>(X) + r * dim : nullptr;
+    }
+    for (int i = tid; i < TN; i += 256) tile_nrm[i] = row0 + i < n_rows ? xnrm[row0 + i] : 0.f;
+
+    f32x16 acc[RB][CB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+      for (int j = 0; j < CB; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    xs.load(xrows, 0, tid);
+    qs.load(qrows, 0, tid);
+    for (int s = 0; s < n_slabs; ++s) {
+      __syncthreads();  // everyone is done reading the previous slab
+      xs.store(As, tid);
+      qs.store(Bs, tid);
+      __syncthreads();
+      if (s + 1 < n_slabs) {
+        xs.load(xrows, (s + 1) * kSlabK, tid);
+        qs.load(qrows, (s + 1) * kSlabK, tid);
+      }
+      mfma_slab<RB, CB>(As, Bs, a_row0, b_row0, lane, acc);
+    }
+
+    // epilogue: scores below the query's bound go to its buffer
+    float T[CB];
+#pragma unroll
+    for (int j = 0; j < CB; ++j) T[j] = bound[b_row0 + 32 * j + (lane & 31)];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int lr = a_row0 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        const long row = row0 + lr;
+        const float nr = tile_nrm[lr];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+          const int q = b_row0 + 32 * j + (lane & 31);
+          const float sc = nr - 2.f * acc[i][j][e];
+          if (sc < T[j] && row < n_rows && m0 + q < M) {
+            const int pos = atomicAdd(&count[q], 1);
+            my_buf[long(q) * kTopkCap + pos] = pack_key(sc, uint32_t(row));
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // cut back buffers that the next tile could overflow
+    for (int q = wib; q < TM; q += 4) {
+      const int n = count[q];
+      if (n > kTopkCap - TN) {
+        const int keep = wave_compact_topk(my_buf + long(q) * kTopkCap, n, kp, sort_scratch[wib], &bound[q], lane);
+        if (lane == 0) count[q] = keep;
+      }
+    }
+    // (the barrier at the top of the next slab loop orders these LDS writes before the next epilogue)
+  }
+
+  __syncthreads();
+  for (int q = wib; q < TM; q += 4) {
+    if (m0 + q >= M) continue;
+    const int n = count[q];
+    uint64_t* buf = my_buf + long(q) * kTopkCap;
+    const int keep = wave_compact_topk(buf, n, kp, sort_scratch[wib], &bound[q], lane);
+    uint64_t* o = out + (long(m0 + q) * gridDim.x + blockIdx.x) * kp;
+    for (int i = lane; i < kp; i += 64) o[i] = i < keep ? sort_scratch[wib][i] : kPadKey;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Cache probe, dense output.  Operand A = batch rows (queries), operand B =
+// sources [slot keys ; batch rows]; D[(m) * ldD + s] = |s|^2 - 2 q_m . s.
+// Grid: x = source tiles of 128, y = query tiles of 128.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 2) void probe_mfma_dense_kernel(const float* __restrict__ srcs,
+                                                                  const float* __restrict__ srcnrm, int n_src,
+                                                                  const float* __restrict__ Q, int n_q, int dim,
+                                                                  float* __restrict__ D, long ldD) {
+  constexpr int T = 128, RB = 2, CB = 2;
+  __shared__ __attribute__((aligned(16))) float As[T * kLdsK];
+  __shared__ __attribute__((aligned(16))) float Bs[T * kLdsK];
+  const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  const int a_row0 = (wib & 1) * 64, b_row0 = (wib >> 1) * 64;
+  const int q0 = blockIdx.y * T, s0 = blockIdx.x * T;
+
+  SlabF32<T> qa, sb;
+  const float* qrows[SlabF32<T>::NCH];
+  const float* srows[SlabF32<T>::NCH];
+#pragma unroll
+  for (int i = 0; i < SlabF32<T>::NCH; ++i) {
+    const int r = (tid + 256 * i) >> 3;
+    qrows[i] = q0 + r < n_q ? Q + long(q0 + r) * dim : nullptr;
+    srows[i] = s0 + r < n_src ? srcs + long(s0 + r) * dim : nullptr;
+  }
+  f32x16 acc[RB][CB];
+#pragma unroll
+  for (int i = 0; i < RB; ++i)
+#pragma unroll
+    for (int j = 0; j < CB; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int n_slabs = dim / kSlabK;
+  qa.load(qrows, 0, tid);
+  sb.load(srows, 0, tid);
+  for (int s = 0; s < n_slabs; ++s) {
+    __syncthreads();
+    qa.store(As, tid);
+    sb.store(Bs, tid);
+    __syncthreads();
+    if (s + 1 < n_slabs) {
+      qa.load(qrows, (s + 1) * kSlabK, tid);
+      sb.load(srows, (s + 1) * kSlabK, tid);
+    }
+    mfma_slab<RB, CB>(As, Bs, a_row0, b_row0, lane, acc);
+  }
+#pragma unroll
+  for (int j = 0; j < CB; ++j) {
+    const int sidx = s0 + b_row0 + 32 * j + (lane & 31);
+    const float sn = sidx < n_src ? srcnrm[sidx] : 0.f;
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int q = q0 + a_row0 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (q < n_q && sidx < n_src) D[long(q) * ldD + sidx] = sn - 2.f * acc[i][j][e];
+      }
+  }
+}
+
+}  // namespace prox

@@ -24,6 +24,7 @@
 
 #include "../../include/proximity.h"
 #include "cache_kernels.hpp"
+#include "mfma_kernels.hpp"
 #include "scan_kernels.hpp"
 #include "select_kernels.hpp"
 
@@ -36,6 +37,8 @@ constexpr int kCandCap = 64;       // per-row candidate list length of the probe
 constexpr int kSelE = 16;          // elements per thread in a selection segment
 constexpr int kSelSeg = kSelE * kSelThreads;
 constexpr int kMaxProfiled = 8192;
+constexpr int kStreamMaxQueries = 8;   // calls with at most this many rows use the streaming kernels
+constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
 
 static_assert(sizeof(proximity_config) == 48, "proximity_config layout is part of the ABI");
 static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is part of the ABI");
@@ -71,6 +74,8 @@ struct proximity {
   long ldS = 0;
   uint64_t* pairs[2] = {nullptr, nullptr};
   long pairs_elems = 0;
+  uint64_t* topk_buf = nullptr;  // batched scan: [query tiles][scan blocks][tile queries][kTopkCap]
+  int scan_blocks = 1;           // blocks that share the corpus in the batched scan
   int64_t* res_ids = nullptr;
   float* res_d = nullptr;
 
@@ -231,22 +236,52 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   }
   const int kp = k + kSlack;
   const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
-  const int mq = stream_group(dim, m_limit);
-  const int g1 = int((N + kSelSeg - 1) / kSelSeg);
-  for (int m0 = 0; m0 < m_limit; m0 += mq) {
-    prof_begin(h, s);
-    if (bf16)
-      launch_scores_stream<kDtypeBF16>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit, m0,
-                                       h->S, h->ldS, s);
-    else
-      launch_scores_stream<kDtypeF32>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit, m0,
-                                      h->S, h->ldS, s);
-    prof_end(h, s, m0, mq);
-    select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
-        h->S, h->ldS, N, 0, kp, h->pairs[0] + long(m0) * g1 * kp, g1, m_count_ptr, m_limit, m0);
+  long len;
+  if (m_limit <= kStreamMaxQueries) {
+    const int mq = stream_group(dim, m_limit);
+    const int g1 = int((N + kSelSeg - 1) / kSelSeg);
+    for (int m0 = 0; m0 < m_limit; m0 += mq) {
+      prof_begin(h, s);
+      if (bf16)
+        launch_scores_stream<kDtypeBF16>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
+                                         m0, h->S, h->ldS, s);
+      else
+        launch_scores_stream<kDtypeF32>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
+                                        m0, h->S, h->ldS, s);
+      prof_end(h, s, m0, mq);
+      select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
+          h->S, h->ldS, N, 0, kp, h->pairs[0] + long(m0) * g1 * kp, g1, m_count_ptr, m_limit, m0);
+    }
+    len = long(g1) * kp;
+  } else {
+    // Batched scan on the matrix cores.  The number of misses M is only known on
+    // the device: launch the tile shape for each range of M that this call can
+    // reach; the ones whose range does not contain M return at once.
+    const int G = h->scan_blocks;
+    for (int base = 0; base < m_limit; base += kScanPassQueries) {
+      const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
+      prof_begin(h, s);
+#define PROX_SCAN(TM, TN, LO, HI)                                                                              \
+  do {                                                                                                         \
+    const dim3 grid(G, (span + TM - 1) / TM);                                                                  \
+    if (bf16)                                                                                                  \
+      scan_mfma_topk_kernel<TM, TN, kDtypeBF16><<<grid, dim3(256), 0, s>>>(                                    \
+          h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, h->topk_buf,   \
+          h->pairs[0]);                                                                                        \
+    else                                                                                                       \
+      scan_mfma_topk_kernel<TM, TN, kDtypeF32><<<grid, dim3(256), 0, s>>>(                                     \
+          h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, h->topk_buf,   \
+          h->pairs[0]);                                                                                        \
+  } while (0)
+      PROX_SCAN(32, 256, 0, 32);
+      if (m_limit > 32) PROX_SCAN(64, 256, 32, 64);
+      if (m_limit > 64) PROX_SCAN(128, 128, 64, 0x7fffffff);
+#undef PROX_SCAN
+      prof_end(h, s, base, span);
+    }
+    len = long(G) * kp;
   }
   int cur = 0;
-  long len = long(g1) * kp;
   while (len > kp) {
     const int g = int((len + kSelSeg - 1) / kSelSeg);
     select_kernel<false, kSelE><<<dim3(g, m_limit), dim3(kSelThreads), 0, s>>>(
@@ -342,7 +377,15 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   h->ldS = long((N + 63) / 64 * 64);
   TRY_ALLOC(h->S, size_t(8) * size_t(h->ldS), false);
   const size_t g1 = (N + kSelSeg - 1) / kSelSeg;
-  h->pairs_elems = long(B * (g1 > 0 ? g1 : 1) * kp);
+  size_t lists = g1 > 0 ? g1 : 1;
+  if (B > size_t(kStreamMaxQueries) && N > 0) {
+    const size_t tiles256 = (N + 255) / 256;
+    h->scan_blocks = int(tiles256 < size_t(2 * h->n_cu) ? tiles256 : size_t(2 * h->n_cu));
+    if (size_t(h->scan_blocks) > lists) lists = size_t(h->scan_blocks);
+    const size_t pass_q = (B < size_t(kScanPassQueries) ? B : size_t(kScanPassQueries)) + 127;
+    TRY_ALLOC(h->topk_buf, size_t(h->scan_blocks) * pass_q * kTopkCap, false);
+  }
+  h->pairs_elems = long(B * lists * kp);
   TRY_ALLOC(h->pairs[0], size_t(h->pairs_elems), false);
   TRY_ALLOC(h->pairs[1], size_t(h->pairs_elems), false);
   TRY_ALLOC(h->res_ids, B * k, true);
@@ -432,10 +475,15 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   int have_probe = 0;
   if (c > 0) {
     have_probe = 1;
-    const int mq = stream_group(dim, nn);
-    for (int m0 = 0; m0 < nn; m0 += mq)
-      launch_scores_stream<kDtypeF32>(h, mq, h->srcs, h->srcnrm, long(c) + nn, dim, batch_rows, nullptr, nullptr, nn,
-                                      m0, h->D32 + size_t(m0) * h->ldD, h->ldD, s);
+    if (nn <= kStreamMaxQueries) {
+      const int mq = stream_group(dim, nn);
+      for (int m0 = 0; m0 < nn; m0 += mq)
+        launch_scores_stream<kDtypeF32>(h, mq, h->srcs, h->srcnrm, long(c) + nn, dim, batch_rows, nullptr, nullptr,
+                                        nn, m0, h->D32 + size_t(m0) * h->ldD, h->ldD, s);
+    } else {
+      probe_mfma_dense_kernel<<<dim3((c + nn + 127) / 128, (nn + 127) / 128), dim3(256), 0, s>>>(
+          h->srcs, h->srcnrm, c + nn, batch_rows, nn, dim, h->D32, h->ldD);
+    }
     probe_candidates_kernel<<<dim3(nn), dim3(256), 0, s>>>(h->D32, h->ldD, h->srcs, h->srcnrm, dim, c, nn, h->state,
                                                            double(tau), kCandCap, h->cand_cnt, h->cand_src,
                                                            h->cand_d);

@@ -33,6 +33,9 @@ def gpu_corpus(x: np.ndarray, bf16=False):
 @pytest.mark.parametrize("n_docs,dim,k,nq", [
     (5000, 768, 10, 1), (5000, 768, 10, 3), (9001, 768, 32, 8), (4097, 384, 100, 5),
     (700, 64, 7, 2), (70000, 768, 10, 13), (3, 32, 5, 2), (8191, 1024, 16, 4), (300, 4096, 3, 8),
+    # more than 8 queries: matrix-core scan, one tile shape per range of query counts
+    (50000, 768, 10, 9), (50000, 768, 10, 40), (50011, 768, 32, 100), (30000, 768, 10, 300),
+    (1000, 64, 7, 20), (200, 32, 100, 70), (131, 96, 5, 129),
 ])
 def test_knn_matches_oracle_f32(B, n_docs, dim, k, nq):
     corpus = W.corpus_f32(n_docs, dim, 3)
@@ -45,8 +48,9 @@ def test_knn_matches_oracle_f32(B, n_docs, dim, k, nq):
     px.close()
 
 
-def test_knn_matches_oracle_bf16(B):
-    n_docs, dim, k, nq = 20000, 384, 100, 6
+@pytest.mark.parametrize("nq", [6, 128])
+def test_knn_matches_oracle_bf16(B, nq):
+    n_docs, dim, k = 20000, 384, 100
     x32 = W.corpus_f32(n_docs, dim, 9)
     bits = W.f32_to_bf16_bits(x32)
     xb = W.bf16_bits_to_f32(bits)                       # exact values the GPU holds
