@@ -117,8 +117,8 @@ def main():
     n_docs = w.n_docs if args.n_docs is None else args.n_docs
     steps = args.steps if args.steps is not None else (20000 if batch == 1 else 1000)
     warmup = args.warmup if args.warmup is not None else (2000 if batch == 1 else 50)
-    if (steps + warmup) * batch > w.n_stream:
-        steps = w.n_stream // batch - warmup
+    if (steps + warmup) * batch > w.n_stream * 3 // 4:
+        steps = w.n_stream * 3 // 4 // batch - warmup
     max_batch = max(batch, 64)
 
     t_gen = time.perf_counter()
@@ -139,16 +139,16 @@ def main():
 
     # roofline of the dominant kernel, the corpus-scan distance kernel: HBM-bound while a launch serves
     # few queries, matrix-core-bound once 2*M flops per 4 corpus bytes pass the ridge (157.3 TF / 8 TB/s)
-    n_prof = min(steps, 4000 if batch <= 8 else 400)
-    busy = profiled_scan(torch, px, q_dev, tau, batch, warmup + steps - n_prof, n_prof, outs, device)
+    n_prof = min(steps, 4000 if batch <= 8 else 400, w.n_stream // batch - warmup - steps)
+    busy = profiled_scan(torch, px, q_dev, tau, batch, warmup + steps, n_prof, outs, device)
     roofline = scan_roofline(busy, n_docs, w.dim, batch)
 
     sweep = []
     if not args.no_sweep and args.workload == "mid":
         for s_tau, s_batch, s_warm, s_steps in ((0.0, 1, 100, 2000), (0.25, 64, 30, 300), (0.0, 64, 10, 200)):
             s_dt, s_hit = timed_run(torch, px, q_dev, s_tau, s_batch, s_warm, s_steps, outs, device)
-            s_busy = profiled_scan(torch, px, q_dev, s_tau, s_batch, s_warm + s_steps - min(s_steps, 200),
-                                   min(s_steps, 200), outs, device)
+            s_busy = profiled_scan(torch, px, q_dev, s_tau, s_batch, s_warm + s_steps, min(s_steps, 200), outs,
+                                   device)
             sweep.append({"tau": s_tau, "batch": s_batch, "steps": s_steps, "warmup": s_warm,
                           "queries_per_s": round(s_steps * s_batch / s_dt, 1), "hit_rate": round(s_hit, 4),
                           "ms_per_step": round(1e3 * s_dt / s_steps, 4),

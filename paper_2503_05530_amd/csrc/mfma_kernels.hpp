@@ -174,11 +174,12 @@ __device__ __forceinline__ int wave_compact_topk(uint64_t* buf, int n, int kp, u
 //
 // Running top-k per (block, query): a bound T (the kp-th best score seen by this
 // block, +inf until kp rows were seen) and a buffer of kTopkCap packed keys in
-// global memory.  After each tile every score below T is appended; when a
+// global memory.  After each tile every score at or below T is appended; when a
 // buffer could overflow on the next tile it is sorted and cut back to kp
-// entries by one wave, which also tightens T.  Rows are visited in ascending id
-// and a later row with score == T has a larger id than the kp entries at or
-// below T, so the strict comparison loses nothing.  At the end each query's
+// entries by one wave, which also tightens T.  T never drops below the true
+// kp-th best score, so no row of the final answer is ever filtered out; the
+// bound may start from the kp-th best score of a sample (`seed`: one sorted
+// kp-entry list per query, or null).  At the end each query's
 // buffer is cut to kp sorted entries and written to
 //   out[((m0 + q) * gridDim.x + blockIdx.x) * kp ..]   (padded with kPadKey).
 // ---------------------------------------------------------------------------
@@ -186,8 +187,8 @@ template <int TM, int TN, int DT>
 __global__ __launch_bounds__(256, 2) void scan_mfma_topk_kernel(
     const void* __restrict__ X, const float* __restrict__ xnrm, long n_rows, int dim,
     const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
-    int m_limit, int m_base, int m_lo, int m_hi, int kp, uint64_t* __restrict__ cand_buf,
-    uint64_t* __restrict__ out) {
+    int m_limit, int m_base, int m_lo, int m_hi, int kp, const uint64_t* __restrict__ seed,
+    uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out) {
   constexpr int WR = TM >= 128 ? 2 : 4;        // waves along corpus rows
   constexpr int WC = 4 / WR;                   // waves along queries
   constexpr int RB = TN / WR / 32;             // 32-row blocks per wave
@@ -211,7 +212,9 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_topk_kernel(
   const int a_row0 = wr * (TN / WR), b_row0 = wc * (TM / WC);
 
   for (int i = tid; i < TM; i += 256) {
-    bound[i] = __uint_as_float(0x7f800000u);
+    // starting bound: the kp-th best score of a sample of the corpus, if the caller has one
+    // (a padding key gives +inf); any value at or above the true kp-th best score is valid
+    bound[i] = (seed && m0 + i < M) ? key_score(seed[long(m0 + i) * kp + kp - 1]) : __uint_as_float(0x7f800000u);
     count[i] = 0;
   }
 
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_topk_kernel(
         for (int j = 0; j < CB; ++j) {
           const int q = b_row0 + 32 * j + (lane & 31);
           const float sc = nr - 2.f * acc[i][j][e];
-          if (sc < T[j] && row < n_rows && m0 + q < M) {
+          if (sc <= T[j] && row < n_rows && m0 + q < M) {
             const int pos = atomicAdd(&count[q], 1);
             my_buf[long(q) * kTopkCap + pos] = pack_key(sc, uint32_t(row));
           }
@@ -313,6 +316,267 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_topk_kernel(
     uint64_t* o = out + (long(m0 + q) * gridDim.x + blockIdx.x) * kp;
     for (int i = lane; i < kp; i += 64) o[i] = i < keep ? sort_scratch[wib][i] : kPadKey;
   }
+}
+
+__device__ __forceinline__ float f4_get(const float4& v, int e) {
+  return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+}
+
+// ---------------------------------------------------------------------------
+// Corpus scan fused with top-k, operands moved global -> LDS by the load unit
+// itself (global_load_lds_dwordx4, gfx950), three slabs deep.
+//
+// Same contract and running top-k as scan_mfma_topk_kernel.  Differences:
+//  * no register staging: each wave issues NL loads per slab whose 64 lanes
+//    write 1 KiB = 8 rows x 128 bytes straight into the slab's LDS stage;
+//  * LDS rows are 128 bytes with no padding; instead lane l of a load fetches
+//    the 16-byte column chunk (l%8) xor (l/8) of its row, so chunk c of row r sits
+//    at position c xor (r%8).  The eight lanes that read the same chunk of eight
+//    consecutive rows for the matrix instruction then hit eight different bank
+//    groups;
+//  * a ring of three stages: while slab s is multiplied, slabs s+1 and s+2 are
+//    in flight, and one barrier per slab suffices (it both publishes slab s and
+//    retires the stage that slab s+2 will overwrite);
+//  * a stage is (TN + TM) x 128 bytes = 24 KiB at most, so two blocks fit a CU
+//    and hide each other's barriers.
+// The compaction scratch is the stage that was consumed last, which stays free
+// until the next slab's loads are issued.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void lds_dma16(const float* gptr, float* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+template <int TM>
+__global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
+    const float* __restrict__ X, const float* __restrict__ xnrm, long n_rows, int dim,
+    const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
+    int m_limit, int m_base, int m_lo, int m_hi, int kp, const uint64_t* __restrict__ seed,
+    uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out) {
+  constexpr int TN = TM >= 128 ? 64 : 128;      // corpus rows per tile
+  constexpr int WR = TN / 32;                   // waves along corpus rows (32 rows each)
+  constexpr int WC = 4 / WR;                    // waves along queries
+  constexpr int CB = TM / WC / 32;              // 32-query blocks per wave
+  constexpr int ROWS = TN + TM;                 // rows of one stage: corpus tile, then query tile
+  constexpr int NL = ROWS / 8 / 4;              // loads per wave per slab
+  constexpr int STAGE = ROWS * 32;              // floats per stage
+  static_assert(ROWS % 32 == 0 && STAGE * 4 >= 4 * kTopkCap * 8, "stage must hold the compaction scratch");
+
+  const int M = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
+  if (M <= m_lo || M > m_hi) return;
+  const int m0 = m_base + blockIdx.y * TM;
+  if (m0 >= M) return;
+
+  // three stages as three objects, so that the compiler can tell that reading one stage does not
+  // depend on the loads in flight into another (it then adds no vmcnt wait of its own)
+  __shared__ __attribute__((aligned(1024))) float ring0[STAGE];
+  __shared__ __attribute__((aligned(1024))) float ring1[STAGE];
+  __shared__ __attribute__((aligned(1024))) float ring2[STAGE];
+#define PROX_RING(s) ((s) == 0 ? ring0 : (s) == 1 ? ring1 : ring2)
+  __shared__ float bound[TM];
+  __shared__ int count[TM];
+  __shared__ __attribute__((aligned(256))) float nrm_ring[2][4][64];  // [tile parity][wave][row], filled by DMA
+
+  const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  const int r32 = lane & 31, half = lane >> 5;
+  const int a_row0 = (wib % WR) * 32;                   // this wave's corpus rows within the tile
+  const int b_row0 = TN + (wib / WR) * (TM / WC);       // this wave's query rows within the stage
+
+  for (int i = tid; i < TM; i += 256) {
+    // starting bound: the kp-th best score of a sample of the corpus, if the caller has one
+    // (a padding key gives +inf); any value at or above the true kp-th best score is valid
+    bound[i] = (seed && m0 + i < M) ? key_score(seed[long(m0 + i) * kp + kp - 1]) : __uint_as_float(0x7f800000u);
+    count[i] = 0;
+  }
+
+  const long n_tiles = (n_rows + TN - 1) / TN;
+  const long t_begin = n_tiles * blockIdx.x / gridDim.x;
+  const long t_end = n_tiles * (blockIdx.x + 1) / gridDim.x;
+  const long total = (t_end - t_begin) * (dim / kSlabK);  // slabs this block multiplies
+  uint64_t* my_buf = cand_buf + (long(blockIdx.y) * gridDim.x + blockIdx.x) * long(TM) * kTopkCap;
+  const int n_slabs = dim / kSlabK;
+
+  // load duty of this lane: NL loads per slab, load i covers stage rows 8*(wib*NL+i) .. +7
+  const int my_chunk = (lane & 7) ^ (lane >> 3);
+  const float* src[NL];
+  bool is_x[NL];
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int srow = 8 * (wib * NL + i) + (lane >> 3);
+    is_x[i] = srow < TN;
+    if (!is_x[i]) {
+      int m = m0 + srow - TN;
+      m = m < M ? m : M - 1;
+      src[i] = Qbase + long(qlist ? qlist[m] : m) * dim + 4 * my_chunk;
+    }
+  }
+  auto point_at_tile = [&](long tile) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+      if (is_x[i]) {
+        long r = tile * TN + 8 * (wib * NL + i) + (lane >> 3);
+        r = r < n_rows ? r : n_rows - 1;
+        src[i] = X + r * dim + 4 * my_chunk;
+      }
+  };
+  // issue stream: slab number `is` (flat over this block's tiles), one group of NL loads per call
+  long is = 0;
+  long itile = t_begin;
+  int islab = 0;
+  auto issue = [&](float* stage) {
+    if (is >= total) return;
+    if (islab == 0) {
+      point_at_tile(itile);
+      // norms of this wave's 32 rows of the tile, parked in LDS until the tile's scores are filtered
+      // (with at least two slabs per tile only two tiles are ever live: the one multiplied and the next)
+      long rn = itile * TN + a_row0 + r32;
+      rn = rn < n_rows ? rn : n_rows - 1;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xnrm + rn),
+                                       (__attribute__((address_space(3))) void*)&nrm_ring[itile & 1][wib][0], 4, 0,
+                                       0);
+    }
+    float* base = stage + (wib * NL) * 256;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) lds_dma16(src[i] + islab * kSlabK, base + i * 256);
+    ++is;
+    if (++islab == n_slabs) {
+      islab = 0;
+      ++itile;
+    }
+  };
+
+  f32x16 acc[CB];
+#pragma unroll
+  for (int j = 0; j < CB; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+  auto multiply = [&](const float* st) {
+    const int sw = r32 & 7;  // (stage row) % 8 of every row this lane reads: row offsets are multiples of 32
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int pos = ((2 * t + half) ^ sw) * 4;
+      const float4 a = *reinterpret_cast<const float4*>(st + (a_row0 + r32) * 32 + pos);
+      float4 b[CB];
+#pragma unroll
+      for (int j = 0; j < CB; ++j) b[j] = *reinterpret_cast<const float4*>(st + (b_row0 + 32 * j + r32) * 32 + pos);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int j = 0; j < CB; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(a, e), f4_get(b[j], e), acc[j], 0, 0, 0);
+    }
+  };
+
+  long ctile = t_begin;
+  int cslab = 0;
+  // A buffer is cut back as soon as it holds clearly more than kp entries (so that the bound
+  // tightens early), and in any case before the next tile could overflow it.
+  const int trigger = min(kTopkCap - TN, max(2 * kp, 64));
+  const uint32_t count_lds = uint32_t(uintptr_t((__attribute__((address_space(3))) int*)&count[0]));
+  auto end_of_tile = [&](float* consumed_stage) {
+    const long row0 = ctile * TN + a_row0;
+    const int qb0 = b_row0 - TN;
+    // pass 1: turn accumulators into scores and note which ones beat the query's bound
+    uint32_t pass[CB];
+#pragma unroll
+    for (int j = 0; j < CB; ++j) pass[j] = 0;
+    float T[CB];
+#pragma unroll
+    for (int j = 0; j < CB; ++j) T[j] = (m0 + qb0 + 32 * j + r32 < M) ? bound[qb0 + 32 * j + r32] : -__builtin_inff();
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int lr = 8 * (e >> 2) + 4 * half + (e & 3);
+      const float nr = nrm_ring[ctile & 1][wib][lr];
+      const bool row_ok = row0 + lr < n_rows;
+#pragma unroll
+      for (int j = 0; j < CB; ++j) {
+        const float sc = nr - 2.f * acc[j][e];
+        acc[j][e] = sc;
+        pass[j] |= (sc <= T[j] && row_ok) ? (1u << e) : 0u;
+      }
+    }
+    // pass 2: one LDS counter update per (lane, query) reserves room, then plain stores.
+    // The counter update is written in assembly so that the compiler does not guard it with a
+    // wait for the global->LDS loads in flight (they never touch the counters).
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+      if (pass[j]) {
+        const int q = qb0 + 32 * j + r32;
+        uint32_t pos;
+        asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)"
+                     : "=v"(pos)
+                     : "v"(count_lds + 4u * uint32_t(q)), "v"(uint32_t(__builtin_popcount(pass[j])))
+                     : "memory");
+        uint64_t* dst = my_buf + long(q) * kTopkCap;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          if (pass[j] & (1u << e)) {
+            const int lr = 8 * (e >> 2) + 4 * half + (e & 3);
+            dst[pos++] = pack_key(acc[j][e], uint32_t(row0 + lr));
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < CB; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    // Do any buffers have to be cut back before the next tile?  Every wave reads the same counts
+    // after a plain barrier (no memory fence: loads in flight stay in flight), so all agree.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    bool mine = false;
+    for (int q = lane; q < TM; q += 64) mine |= count[q] > trigger;
+    if (__any(mine)) {
+      __syncthreads();  // full fence: the candidates other waves appended must be visible
+      uint64_t* scratch = reinterpret_cast<uint64_t*>(consumed_stage) + wib * kTopkCap;
+      for (int q = wib; q < TM; q += 4) {
+        const int n = count[q];
+        if (n > trigger) {
+          const int keep = wave_compact_topk(my_buf + long(q) * kTopkCap, n, kp, scratch, &bound[q], lane);
+          if (lane == 0) count[q] = keep;
+        }
+      }
+    }
+    // the barrier at the top of the next slab orders these LDS writes
+  };
+
+  issue(ring0);
+  issue(ring1);
+  for (long it = 0; it < total;) {
+#pragma unroll
+    for (int stage = 0; stage < 3; ++stage) {
+      if (it < total) {
+        // slab `it` must have landed; the group issued after it (slab it+1) may stay in flight.
+        // Plain barrier: it publishes slab `it` to all waves and retires the stage that slab
+        // it+2 is about to overwrite.
+        if (it + 1 < total)
+          asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NL) : "memory");
+        else
+          asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        issue(PROX_RING((stage + 2) % 3));
+        multiply(PROX_RING(stage));
+        if (++cslab == n_slabs) {
+          end_of_tile(PROX_RING(stage));
+          cslab = 0;
+          ++ctile;
+        }
+        ++it;
+      }
+    }
+  }
+
+  __syncthreads();
+  uint64_t* scratch = reinterpret_cast<uint64_t*>(ring0) + wib * kTopkCap;
+  for (int q = wib; q < TM; q += 4) {
+    if (m0 + q >= M) continue;
+    const int n = count[q];
+    uint64_t* buf = my_buf + long(q) * kTopkCap;
+    const int keep = wave_compact_topk(buf, n, kp, scratch, &bound[q], lane);
+    uint64_t* o = out + (long(m0 + q) * gridDim.x + blockIdx.x) * kp;
+    for (int i = lane; i < kp; i += 64) o[i] = i < keep ? scratch[i] : kPadKey;
+  }
+#undef PROX_RING
 }
 
 // ---------------------------------------------------------------------------

@@ -39,6 +39,7 @@ constexpr int kSelSeg = kSelE * kSelThreads;
 constexpr int kMaxProfiled = 8192;
 constexpr int kStreamMaxQueries = 8;   // calls with at most this many rows use the streaming kernels
 constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
+constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
 static_assert(sizeof(proximity_config) == 48, "proximity_config layout is part of the ABI");
 static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is part of the ABI");
@@ -223,6 +224,53 @@ void prof_end(proximity* h, hipStream_t s, int first_query, int n_queries) {
   }
 }
 
+// One pass of the matrix-core scan over corpus rows [0, n_rows), shared by G blocks, for the
+// queries base .. base+span-1 of the miss list.  The number of misses M is only known on the
+// device: the tile shape for each range of M that this call can reach is launched, and the ones
+// whose range does not contain M return at once.  Per-query lists of G*kp keys land in `out`.
+void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, const int* qlist,
+                         const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
+                         uint64_t* out, hipStream_t s) {
+  const int dim = int(h->cfg.dim);
+  const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
+  const bool dma = !bf16 && dim >= 64;  // the global->LDS pipeline needs float32 rows and two slabs per tile
+#define PROX_SCAN(TM, TN, LO, HI)                                                                              \
+  do {                                                                                                         \
+    const dim3 grid(G, (span + TM - 1) / TM);                                                                  \
+    if (dma)                                                                                                   \
+      scan_mfma_dma_kernel<TM><<<grid, dim3(256), 0, s>>>(static_cast<const float*>(h->cfg.corpus), h->xnrm,   \
+                                                          n_rows, dim, Qbase, qlist, m_count_ptr, m_limit,     \
+                                                          base, LO, HI, kp, seed, h->topk_buf, out);           \
+    else if (bf16)                                                                                             \
+      scan_mfma_topk_kernel<TM, TN, kDtypeBF16><<<grid, dim3(256), 0, s>>>(                                    \
+          h->cfg.corpus, h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, seed,     \
+          h->topk_buf, out);                                                                                   \
+    else                                                                                                       \
+      scan_mfma_topk_kernel<TM, TN, kDtypeF32><<<grid, dim3(256), 0, s>>>(                                     \
+          h->cfg.corpus, h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, seed,     \
+          h->topk_buf, out);                                                                                   \
+  } while (0)
+  PROX_SCAN(32, 256, 0, 32);
+  if (m_limit > 32) PROX_SCAN(64, 256, 32, 64);
+  if (m_limit > 64) PROX_SCAN(128, 128, 64, 0x7fffffff);
+#undef PROX_SCAN
+}
+
+// Merge per-query lists of `len` keys in pairs[cur] down to one sorted list of kp keys per
+// query, ping-ponging between the two key buffers.  Returns the index of the buffer that
+// holds the result.
+int enqueue_merge_levels(proximity* h, int cur, long len, int kp, const int* m_count_ptr, int m_limit,
+                         hipStream_t s) {
+  while (len > kp) {
+    const int g = int((len + kSelSeg - 1) / kSelSeg);
+    select_kernel<false, kSelE><<<dim3(g, m_limit), dim3(kSelThreads), 0, s>>>(
+        h->pairs[cur], len, len, 0, kp, h->pairs[cur ^ 1], g, m_count_ptr, m_limit, 0);
+    cur ^= 1;
+    len = long(g) * kp;
+  }
+  return cur;
+}
+
 // The index search for the queries listed in qlist (or rows 0..m_limit-1 of
 // Qbase when qlist is null): scores, hierarchical top-k, float64 ranking.
 // Results land in row qlist[m] (or m) of res_ids / res_d.
@@ -236,7 +284,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   }
   const int kp = k + kSlack;
   const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
-  long len;
+  int cur = 0;
   if (m_limit <= kStreamMaxQueries) {
     const int mq = stream_group(dim, m_limit);
     const int g1 = int((N + kSelSeg - 1) / kSelSeg);
@@ -252,42 +300,32 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
           h->S, h->ldS, N, 0, kp, h->pairs[0] + long(m0) * g1 * kp, g1, m_count_ptr, m_limit, m0);
     }
-    len = long(g1) * kp;
+    cur = enqueue_merge_levels(h, 0, long(g1) * kp, kp, m_count_ptr, m_limit, s);
   } else {
-    // Batched scan on the matrix cores.  The number of misses M is only known on
-    // the device: launch the tile shape for each range of M that this call can
-    // reach; the ones whose range does not contain M return at once.
+    // Batched scan on the matrix cores, in two steps.  First the head of the corpus
+    // (kSeedRows rows) is scanned and merged on its own: its kp-th best score per query is a
+    // valid bound for the whole corpus and lets the full scan drop almost every row at once
+    // instead of learning a bound block by block.  Then the full scan, then the merge.
+    const uint64_t* seed = nullptr;
+    if (N >= 8L * kSeedRows) {
+      const int gs = kSeedRows / 128;
+      for (int base = 0; base < m_limit; base += kScanPassQueries) {
+        const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
+        launch_batched_scan(h, kSeedRows, gs, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, nullptr,
+                            h->pairs[0], s);
+      }
+      cur = enqueue_merge_levels(h, 0, long(gs) * kp, kp, m_count_ptr, m_limit, s);
+      seed = h->pairs[cur];
+      cur ^= 1;  // the full scan writes into the other buffer
+    }
     const int G = h->scan_blocks;
     for (int base = 0; base < m_limit; base += kScanPassQueries) {
       const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
       prof_begin(h, s);
-#define PROX_SCAN(TM, TN, LO, HI)                                                                              \
-  do {                                                                                                         \
-    const dim3 grid(G, (span + TM - 1) / TM);                                                                  \
-    if (bf16)                                                                                                  \
-      scan_mfma_topk_kernel<TM, TN, kDtypeBF16><<<grid, dim3(256), 0, s>>>(                                    \
-          h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, h->topk_buf,   \
-          h->pairs[0]);                                                                                        \
-    else                                                                                                       \
-      scan_mfma_topk_kernel<TM, TN, kDtypeF32><<<grid, dim3(256), 0, s>>>(                                     \
-          h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, h->topk_buf,   \
-          h->pairs[0]);                                                                                        \
-  } while (0)
-      PROX_SCAN(32, 256, 0, 32);
-      if (m_limit > 32) PROX_SCAN(64, 256, 32, 64);
-      if (m_limit > 64) PROX_SCAN(128, 128, 64, 0x7fffffff);
-#undef PROX_SCAN
+      launch_batched_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], s);
       prof_end(h, s, base, span);
     }
-    len = long(G) * kp;
-  }
-  int cur = 0;
-  while (len > kp) {
-    const int g = int((len + kSelSeg - 1) / kSelSeg);
-    select_kernel<false, kSelE><<<dim3(g, m_limit), dim3(kSelThreads), 0, s>>>(
-        h->pairs[cur], len, len, 0, kp, h->pairs[cur ^ 1], g, m_count_ptr, m_limit, 0);
-    cur ^= 1;
-    len = long(g) * kp;
+    cur = enqueue_merge_levels(h, cur, long(G) * kp, kp, m_count_ptr, m_limit, s);
   }
   if (bf16)
     rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(256), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
