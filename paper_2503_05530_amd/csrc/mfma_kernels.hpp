@@ -341,13 +341,16 @@ __device__ __forceinline__ float f4_get(const float4& v, int e) {
 //    and hide each other's barriers.
 // The compaction scratch is the stage that was consumed last, which stays free
 // until the next slab's loads are issued.
+// DUMP = true turns the selection off: every score is written as a key to
+// out[query * n_rows + row] (used on a short head of the corpus, whose merged
+// kp-th best score then seeds the bounds of the full scan).
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void lds_dma16(const float* gptr, float* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
-template <int TM>
+template <int TM, bool DUMP>
 __global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
     const float* __restrict__ X, const float* __restrict__ xnrm, long n_rows, int dim,
     const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
@@ -477,6 +480,21 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
   auto end_of_tile = [&](float* consumed_stage) {
     const long row0 = ctile * TN + a_row0;
     const int qb0 = b_row0 - TN;
+    if (DUMP) {
+      // no selection here: every score goes out as a key, out[query][row], for the merge kernels
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int lr = 8 * (e >> 2) + 4 * half + (e & 3);
+        const float nr = nrm_ring[ctile & 1][wib][lr];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+          const int q = m0 + qb0 + 32 * j + r32;
+          if (q < M && row0 + lr < n_rows) out[long(q) * n_rows + row0 + lr] = pack_key(nr - 2.f * acc[j][e], uint32_t(row0 + lr));
+          acc[j][e] = 0.f;
+        }
+      }
+      return;
+    }
     // pass 1: turn accumulators into scores and note which ones beat the query's bound
     uint32_t pass[CB];
 #pragma unroll
@@ -566,6 +584,7 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
     }
   }
 
+  if (DUMP) return;
   __syncthreads();
   uint64_t* scratch = reinterpret_cast<uint64_t*>(ring0) + wib * kTopkCap;
   for (int q = wib; q < TM; q += 4) {

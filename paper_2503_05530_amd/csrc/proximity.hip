@@ -230,17 +230,21 @@ void prof_end(proximity* h, hipStream_t s, int first_query, int n_queries) {
 // whose range does not contain M return at once.  Per-query lists of G*kp keys land in `out`.
 void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, const int* qlist,
                          const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
-                         uint64_t* out, hipStream_t s) {
+                         uint64_t* out, bool dump_all, hipStream_t s) {
   const int dim = int(h->cfg.dim);
   const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
   const bool dma = !bf16 && dim >= 64;  // the global->LDS pipeline needs float32 rows and two slabs per tile
 #define PROX_SCAN(TM, TN, LO, HI)                                                                              \
   do {                                                                                                         \
     const dim3 grid(G, (span + TM - 1) / TM);                                                                  \
-    if (dma)                                                                                                   \
-      scan_mfma_dma_kernel<TM><<<grid, dim3(256), 0, s>>>(static_cast<const float*>(h->cfg.corpus), h->xnrm,   \
-                                                          n_rows, dim, Qbase, qlist, m_count_ptr, m_limit,     \
-                                                          base, LO, HI, kp, seed, h->topk_buf, out);           \
+    if (dma && dump_all)                                                                                       \
+      scan_mfma_dma_kernel<TM, true><<<grid, dim3(256), 0, s>>>(                                               \
+          static_cast<const float*>(h->cfg.corpus), h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit,  \
+          base, LO, HI, kp, seed, h->topk_buf, out);                                                           \
+    else if (dma)                                                                                              \
+      scan_mfma_dma_kernel<TM, false><<<grid, dim3(256), 0, s>>>(                                              \
+          static_cast<const float*>(h->cfg.corpus), h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit,  \
+          base, LO, HI, kp, seed, h->topk_buf, out);                                                           \
     else if (bf16)                                                                                             \
       scan_mfma_topk_kernel<TM, TN, kDtypeBF16><<<grid, dim3(256), 0, s>>>(                                    \
           h->cfg.corpus, h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, seed,     \
@@ -309,12 +313,14 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     const uint64_t* seed = nullptr;
     if (N >= 8L * kSeedRows) {
       const int gs = kSeedRows / 128;
+      // float32 rows: the head's scores are written out whole and merged; otherwise per-block lists
+      const bool dump_seed = !bf16 && dim >= 64;
       for (int base = 0; base < m_limit; base += kScanPassQueries) {
         const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
         launch_batched_scan(h, kSeedRows, gs, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, nullptr,
-                            h->pairs[0], s);
+                            h->pairs[0], dump_seed, s);
       }
-      cur = enqueue_merge_levels(h, 0, long(gs) * kp, kp, m_count_ptr, m_limit, s);
+      cur = enqueue_merge_levels(h, 0, dump_seed ? long(kSeedRows) : long(gs) * kp, kp, m_count_ptr, m_limit, s);
       seed = h->pairs[cur];
       cur ^= 1;  // the full scan writes into the other buffer
     }
@@ -322,16 +328,17 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     for (int base = 0; base < m_limit; base += kScanPassQueries) {
       const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
       prof_begin(h, s);
-      launch_batched_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], s);
+      launch_batched_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], false,
+                          s);
       prof_end(h, s, base, span);
     }
     cur = enqueue_merge_levels(h, cur, long(G) * kp, kp, m_count_ptr, m_limit, s);
   }
   if (bf16)
-    rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(256), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
+    rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
                                                                      qlist, m_count_ptr, m_limit, res_ids, res_d);
   else
-    rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(256), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
+    rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
                                                                     qlist, m_count_ptr, m_limit, res_ids, res_d);
   return PROXIMITY_OK;
 }
@@ -420,6 +427,7 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     const size_t tiles256 = (N + 255) / 256;
     h->scan_blocks = int(tiles256 < size_t(2 * h->n_cu) ? tiles256 : size_t(2 * h->n_cu));
     if (size_t(h->scan_blocks) > lists) lists = size_t(h->scan_blocks);
+    if (size_t(kSeedRows + kp - 1) / kp > lists) lists = size_t(kSeedRows + kp - 1) / kp;  // dumped head scores
     const size_t pass_q = (B < size_t(kScanPassQueries) ? B : size_t(kScanPassQueries)) + 127;
     TRY_ALLOC(h->topk_buf, size_t(h->scan_blocks) * pass_q * kTopkCap, false);
   }

@@ -83,13 +83,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const void* __restr
   for (int i = tid; i < kp; i += kSelThreads) o[i] = list[i];
 }
 
-// Final ranking in float64.  One block per query: for each of the kp float32
-// candidates recompute the Euclidean distance to the query in direct-difference
-// form in float64 (one wave per candidate row), rank the candidates by
+// Final ranking in float64.  One block of 16 waves per query: for each of the kp
+// float32 candidates recompute the Euclidean distance to the query in direct-difference
+// form in float64 (one wave per candidate row, rows fetched concurrently), rank the candidates by
 // (distance, id) and write the first k ids and distances to row `qrow` of the
 // result arrays.  Padding candidates (id -1) get distance +inf and id -1.
+constexpr int kRerankThreads = 1024;
 template <int DT>
-__global__ __launch_bounds__(256) void rerank_f64_kernel(const uint64_t* __restrict__ cand, int kp, int k,
+__global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64_t* __restrict__ cand, int kp, int k,
                                                          const void* __restrict__ X, int dim,
                                                          const float* __restrict__ Qbase,
                                                          const int* __restrict__ qlist,
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(256) void rerank_f64_kernel(const uint64_t* __restr
   __shared__ double d64[256];
   __shared__ int ids[256];
 
-  for (int c = wib; c < kp; c += 4) {
+  for (int c = wib; c < kp; c += kRerankThreads / 64) {
     const int id = key_id(cand[long(m) * kp + c]);
     double acc = 0.0;
     if (id >= 0) {
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(256) void rerank_f64_kernel(const uint64_t* __restr
     }
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < kp; c += 256) {
+  for (int c = threadIdx.x; c < kp; c += kRerankThreads) {
     const double d = d64[c];
     const int id = ids[c];
     int rank = 0;
