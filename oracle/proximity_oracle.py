@@ -260,3 +260,39 @@ def lookup_stream_deferred(corpus, queries, tau: float, capacity: int, k: int, p
     ids[hit_rows] = ids[src[hit_rows]]
     dists[hit_rows] = dists[src[hit_rows]]
     return ids, dists, hit, src, dec
+
+
+def exact_knn_over_chunks(chunks, queries, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """``batched_exact_knn`` for a corpus that arrives as (first_row, rows) blocks in row order.
+
+    For corpora too large to hold twice in host memory.  Same arithmetic: per block the
+    float64 matrix-product form of the squared distance, every row at or below the block's
+    k-th smallest kept, one stable sort over the survivors, and the winners' distances
+    re-evaluated in direct-difference form from the rows saved while their block was at hand.
+    """
+    q64 = as_f64_rows(queries)
+    m = q64.shape[0]
+    qn = np.sum(q64 * q64, axis=1)
+    cand_d2 = [np.empty(0) for _ in range(m)]
+    cand_id = [np.empty(0, dtype=np.int64) for _ in range(m)]
+    cand_row = [np.empty((0, q64.shape[1])) for _ in range(m)]
+    for r0, block in chunks:
+        x = as_f64_rows(block)
+        d2 = qn[:, None] + np.sum(x * x, axis=1)[None, :] - 2.0 * (q64 @ x.T)
+        kk = min(k, x.shape[0])
+        kth = np.partition(d2, kk - 1, axis=1)[:, kk - 1]
+        for i in range(m):
+            keep = np.flatnonzero(d2[i] <= kth[i])
+            d2_all = np.concatenate([cand_d2[i], d2[i, keep]])
+            id_all = np.concatenate([cand_id[i], keep + r0])
+            row_all = np.concatenate([cand_row[i], x[keep]])
+            order = np.argsort(d2_all, kind="stable")[:k]   # ids ascend, so ties rank by index
+            cand_d2[i], cand_id[i], cand_row[i] = d2_all[order], id_all[order], row_all[order]
+    ids = np.full((m, k), -1, dtype=np.int64)
+    dists = np.full((m, k), np.inf)
+    for i in range(m):
+        n = len(cand_id[i])
+        ids[i, :n] = cand_id[i]
+        if n:
+            dists[i, :n] = l2_distances(q64[i], cand_row[i])
+    return ids, dists
