@@ -31,7 +31,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed search_batch calls")
     ap.add_argument("--warmup", type=int, default=None, help="untimed calls before them")
-    ap.add_argument("--workload", default="mid", choices=["tiny", "mid"])
+    ap.add_argument("--workload", default="mid", choices=["tiny", "mid", "large", "lowreuse", "probe"],
+                    help="mid is the headline workload; the others are the remaining benchmark configurations")
     ap.add_argument("--tau", type=float, default=None)
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--n-docs", type=int, default=None, help="override corpus rows (debugging only)")
@@ -76,16 +77,16 @@ def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, devic
     return busy
 
 
-def scan_roofline(busy, n_docs, dim, batch):
+def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
     """Roofline entry from (duration ms, queries served) of the launches that streamed the corpus."""
     if not busy:
         return None
-    bytes_per_launch = n_docs * dim * 4 + n_docs * 4      # corpus rows + their norms, read once
+    bytes_per_launch = n_docs * dim * elem_bytes + n_docs * 4      # corpus rows + their norms, read once
     avg_ms = sum(ms for ms, _ in busy) / len(busy)
     avg_q = sum(q for _, q in busy) / len(busy)
     gbs = bytes_per_launch / (avg_ms * 1e-3) / 1e9
     tflops = sum(2.0 * q * n_docs * dim for _, q in busy) / (sum(ms for ms, _ in busy) * 1e-3) / 1e12
-    ridge_q = F32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) * 4 / 2   # queries per launch at the ridge
+    ridge_q = F32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) * elem_bytes / 2   # queries per launch at the ridge
     common = {"traffic": None, "kernel": "scores_stream_kernel" if batch <= 8 else "scan_mfma_topk_kernel",
               "launches_timed": len(busy), "avg_launch_ms": round(avg_ms, 5),
               "queries_per_launch_avg": round(avg_q, 3), "achieved_GBps": round(gbs, 1),
@@ -96,6 +97,47 @@ def scan_roofline(busy, n_docs, dim, batch):
                 "frac": round(gbs / HBM_PEAK_GBS, 4), **common}
     return {"bound": "mfma", "achieved": round(tflops, 2), "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(tflops / F32_MFMA_PEAK_TFLOPS, 4), **common}
+
+
+def probe_microbench(args, torch, np, W, Proximity, device):
+    """Cache probe alone: 10 000 resident keys, batches of 4 096 queries, no corpus behind the cache."""
+    n_keys, dim, batch, tau = W.PROBE_KEYS, W.PROBE_DIM, W.PROBE_BATCH, W.PROBE_TAU
+    steps = args.steps if args.steps is not None else 20
+    warmup = args.warmup if args.warmup is not None else 2
+    px = Proximity(None, dim, n_keys, 1, W.POLICY_LRU, batch, device=device)
+    keys = torch.from_numpy(W.probe_warm_keys(n_keys, dim, 0)).to(device)
+    for b0 in range(0, n_keys, batch):
+        px.search_batch(keys[b0:b0 + batch], tau)
+    mix = W.ProbeMix(dim, 0)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    total_ms, hits = 0.0, 0
+    for step in range(warmup + steps):
+        _, resident, _ = px.cache_dump(want_keys=True)     # the batch is drawn against the keys resident now
+        q = torch.from_numpy(mix.batch(resident, batch)).to(device)
+        torch.cuda.synchronize(device)
+        ev0.record()
+        _, _, hit = px.search_batch(q, tau)
+        ev1.record()
+        torch.cuda.synchronize(device)
+        if step >= warmup:
+            total_ms += ev0.elapsed_time(ev1)
+            hits += int(hit.sum().item())
+    flops = 2.0 * batch * (n_keys + batch) * dim
+    ms = total_ms / steps
+    line = {"metric": "cache_probes_per_sec", "value": round(batch / (ms * 1e-3), 1), "unit": "queries/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"probe: {n_keys} resident keys x {dim} f32, batches of {batch} (half perturbed "
+                                   f"resident keys, radius U(0,{W.PROBE_MAX_RADIUS}); half fresh), tau={tau}, LRU, "
+                                   "insert on miss, no corpus", "hit_rate": round(hits / (steps * batch), 4)},
+            "roofline": {"bound": "mfma", "achieved": round(flops / (ms * 1e-3) / 1e12, 2),
+                         "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(flops / (ms * 1e-3) / 1e12 / F32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                         "note": "whole call (probe contraction, candidate extraction, resolver, insertion) "
+                                 "against the probe contraction's 2*B*(c+B)*d flops"},
+            "cpu_baseline": None}
+    print(json.dumps(line))
+    px.close()
 
 
 def main():
@@ -111,6 +153,8 @@ def main():
     from paper_2503_05530_amd.binding import Proximity
 
     device = torch.device("cuda:0")
+    if args.workload == "probe":
+        return probe_microbench(args, torch, np, W, Proximity, device)
     w = W.WORKLOADS[args.workload]
     tau = w.tau if args.tau is None else args.tau
     batch = w.batch if args.batch is None else args.batch
@@ -122,11 +166,20 @@ def main():
     max_batch = max(batch, 64)
 
     t_gen = time.perf_counter()
-    corpus = W.corpus_for(w, n_docs)
     queries = W.stream_for(w)
-    corpus_dev = torch.from_numpy(corpus).to(device)
+    on_device = n_docs >= 8_000_000          # large corpora are drawn on the device, chunk by chunk
+    if on_device:
+        corpus = None
+        corpus_dev = torch.empty((n_docs, w.dim), device=device,
+                                 dtype=torch.bfloat16 if w.corpus_dtype == W.DTYPE_BF16 else torch.float32)
+        for r0, chunk in W.device_corpus_chunks(n_docs, w.dim, w.seed, device, w.corpus_dtype):
+            corpus_dev[r0:r0 + chunk.shape[0]] = chunk
+    else:
+        corpus = W.corpus_for(w, n_docs)
+        corpus_dev = torch.from_numpy(corpus).to(device)
     q_dev = torch.from_numpy(queries).to(device)
     t_gen = time.perf_counter() - t_gen
+    elem = 2 if w.corpus_dtype == W.DTYPE_BF16 else 4
 
     px = Proximity(corpus_dev, w.dim, w.capacity, w.k, w.policy, max_batch)
     n_rows = len(queries)
@@ -141,7 +194,7 @@ def main():
     # few queries, matrix-core-bound once 2*M flops per 4 corpus bytes pass the ridge (157.3 TF / 8 TB/s)
     n_prof = min(steps, 4000 if batch <= 8 else 400, w.n_stream // batch - warmup - steps)
     busy = profiled_scan(torch, px, q_dev, tau, batch, warmup + steps, n_prof, outs, device)
-    roofline = scan_roofline(busy, n_docs, w.dim, batch)
+    roofline = scan_roofline(busy, n_docs, w.dim, batch, elem)
 
     sweep = []
     if not args.no_sweep and args.workload == "mid":
@@ -152,10 +205,10 @@ def main():
             sweep.append({"tau": s_tau, "batch": s_batch, "steps": s_steps, "warmup": s_warm,
                           "queries_per_s": round(s_steps * s_batch / s_dt, 1), "hit_rate": round(s_hit, 4),
                           "ms_per_step": round(1e3 * s_dt / s_steps, 4),
-                          "roofline": scan_roofline(s_busy, n_docs, w.dim, s_batch)})
+                          "roofline": scan_roofline(s_busy, n_docs, w.dim, s_batch, elem)})
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and corpus is not None:
         from oracle import proximity_oracle as po
         first = warmup * batch
         orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy,
@@ -176,7 +229,8 @@ def main():
         "metric": "retrieval_queries_per_sec", "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(1e3 * dt / steps, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: corpus {n_docs}x{w.dim} f32 unit Gaussian, Zipf({w.zipf_s}) stream of "
+        "config": {"workload": f"{w.name}: corpus {n_docs}x{w.dim} {'bf16' if elem == 2 else 'f32'} unit Gaussian, "
+                               f"{w.choice}({w.zipf_s}) stream of "
                                f"{w.n_stream} over {w.n_bases} bases (perturbation {w.radius}), capacity "
                                f"{w.capacity}, {'LRU' if w.policy else 'FIFO'}, k={w.k}",
                    "tau": tau, "batch": batch, "hit_rate": round(hit_rate, 4),
