@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=24, help="queries the oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -153,6 +155,15 @@ def main():
     from paper_2503_05530_amd.binding import Proximity
 
     device = torch.device("cuda:0")
+    if args.calibrate_copy:
+        src = torch.full((1 << 28,), 1.5, dtype=torch.float32, device=device)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize(device)
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4,
+                          "copies": 5}))
+        return
     if args.workload == "probe":
         return probe_microbench(args, torch, np, W, Proximity, device)
     w = W.WORKLOADS[args.workload]
