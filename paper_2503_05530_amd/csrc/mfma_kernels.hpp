@@ -349,6 +349,11 @@ __device__ __forceinline__ void lds_dma16(const float* gptr, float* lds_wave_bas
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
+// the same with the nontemporal cache policy (aux bit 1), for rows that are read once
+__device__ __forceinline__ void lds_dma16_once(const float* gptr, float* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 2);
+}
 
 template <int TM, bool DUMP>
 __global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
@@ -440,7 +445,12 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
     }
     float* base = stage + (wib * NL) * 256;
 #pragma unroll
-    for (int i = 0; i < NL; ++i) lds_dma16(src[i] + islab * kSlabK, base + i * 256);
+    for (int i = 0; i < NL; ++i) {
+      if (is_x[i])
+        lds_dma16_once(src[i] + islab * kSlabK, base + i * 256);  // corpus rows: streamed once
+      else
+        lds_dma16(src[i] + islab * kSlabK, base + i * 256);       // query rows: re-read by every block
+    }
     ++is;
     if (++islab == n_slabs) {
       islab = 0;

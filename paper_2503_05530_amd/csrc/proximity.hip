@@ -37,7 +37,7 @@ constexpr int kCandCap = 64;       // per-row candidate list length of the probe
 constexpr int kSelE = 16;          // elements per thread in a selection segment
 constexpr int kSelSeg = kSelE * kSelThreads;
 constexpr int kMaxProfiled = 8192;
-constexpr int kStreamMaxQueries = 8;   // calls with at most this many rows use the streaming kernels
+constexpr int kStreamMaxQueries = 4;   // calls with at most this many rows use the streaming kernels
 constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
@@ -163,7 +163,7 @@ int stream_group(int dim, int n) {
   return mq;
 }
 
-template <int DT, int MQ>
+template <int DT, int MQ, bool ONCE>
 void launch_scores_stream_mq(const proximity* h, const void* X, const float* xnrm, long n_rows, int dim,
                              const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
                              int m_begin, float* S, long ldS, hipStream_t s) {
@@ -175,7 +175,7 @@ void launch_scores_stream_mq(const proximity* h, const void* X, const float* xnr
   const dim3 g((unsigned)grid), b(256);
 #define PROX_STREAM_CASE(D)                                                                              \
   case D:                                                                                                \
-    scores_stream_kernel<D, MQ, DT><<<g, b, 0, s>>>(X, xnrm, 0, n_rows, Qbase, qlist, m_count_ptr,      \
+    scores_stream_kernel<D, MQ, DT, ONCE><<<g, b, 0, s>>>(X, xnrm, 0, n_rows, Qbase, qlist, m_count_ptr,      \
                                                     m_limit, m_begin, S, ldS);                          \
     return;
   switch (dim) {
@@ -193,22 +193,22 @@ void launch_scores_stream_mq(const proximity* h, const void* X, const float* xnr
       X, xnrm, 0, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS);
 }
 
-template <int DT>
+template <int DT, bool ONCE>
 void launch_scores_stream(const proximity* h, int mq, const void* X, const float* xnrm, long n_rows, int dim,
                           const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
                           int m_begin, float* S, long ldS, hipStream_t s) {
   switch (mq) {
     case 1:
-      launch_scores_stream_mq<DT, 1>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      launch_scores_stream_mq<DT, 1, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
       break;
     case 2:
-      launch_scores_stream_mq<DT, 2>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      launch_scores_stream_mq<DT, 2, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
       break;
     case 4:
-      launch_scores_stream_mq<DT, 4>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      launch_scores_stream_mq<DT, 4, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
       break;
     default:
-      launch_scores_stream_mq<DT, 8>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      launch_scores_stream_mq<DT, 8, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
       break;
   }
 }
@@ -295,10 +295,10 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     for (int m0 = 0; m0 < m_limit; m0 += mq) {
       prof_begin(h, s);
       if (bf16)
-        launch_scores_stream<kDtypeBF16>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
+        launch_scores_stream<kDtypeBF16, true>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
                                          m0, h->S, h->ldS, s);
       else
-        launch_scores_stream<kDtypeF32>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
+        launch_scores_stream<kDtypeF32, true>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
                                         m0, h->S, h->ldS, s);
       prof_end(h, s, m0, mq);
       select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
@@ -524,7 +524,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     if (nn <= kStreamMaxQueries) {
       const int mq = stream_group(dim, nn);
       for (int m0 = 0; m0 < nn; m0 += mq)
-        launch_scores_stream<kDtypeF32>(h, mq, h->srcs, h->srcnrm, long(c) + nn, dim, batch_rows, nullptr, nullptr,
+        launch_scores_stream<kDtypeF32, false>(h, mq, h->srcs, h->srcnrm, long(c) + nn, dim, batch_rows, nullptr, nullptr,
                                         nn, m0, h->D32 + size_t(m0) * h->ldD, h->ldD, s);
     } else {
       probe_mfma_dense_kernel<<<dim3((c + nn + 127) / 128, (nn + 127) / 128), dim3(256), 0, s>>>(

@@ -61,6 +61,7 @@ __global__ __launch_bounds__(256) void row_norms_kernel(const void* __restrict__
 //
 // Queries are rows qlist[m_begin + m] of Qbase (qlist == nullptr: row m_begin+m);
 // only the first *m_count_ptr list entries exist (m_count_ptr == nullptr: m_limit).
+// ONCE = true marks the rows as read-once (the corpus); false keeps them cacheable (cached keys).
 // Output S[m * ldS + (row - row_begin)] for m < MQ; queries past the count give
 // unspecified values in their rows of S and are never read.
 // ---------------------------------------------------------------------------
@@ -73,6 +74,12 @@ struct RowChunk<kDtypeF32> {
   __device__ __forceinline__ void load(const void* X, long elem) {
     v = *reinterpret_cast<const float4*>(static_cast<const float*>(X) + elem);
   }
+  // read-once data: a nontemporal load keeps the row from displacing what the caches hold
+  __device__ __forceinline__ void load_once(const void* X, long elem) {
+    typedef float vf4 __attribute__((ext_vector_type(4)));
+    const vf4 t = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(static_cast<const float*>(X) + elem));
+    v = make_float4(t.x, t.y, t.z, t.w);
+  }
   __device__ __forceinline__ void zero() { v = make_float4(0.f, 0.f, 0.f, 0.f); }
   __device__ __forceinline__ float dot(const float* q) const {
     return v.x * q[0] + v.y * q[1] + v.z * q[2] + v.w * q[3];
@@ -84,6 +91,11 @@ struct RowChunk<kDtypeBF16> {
   uint4 v;
   __device__ __forceinline__ void load(const void* X, long elem) {
     v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(X) + elem);
+  }
+  __device__ __forceinline__ void load_once(const void* X, long elem) {
+    typedef unsigned vu4 __attribute__((ext_vector_type(4)));
+    const vu4 t = __builtin_nontemporal_load(reinterpret_cast<const vu4*>(static_cast<const uint16_t*>(X) + elem));
+    v = make_uint4(t.x, t.y, t.z, t.w);
   }
   __device__ __forceinline__ void zero() { v = make_uint4(0, 0, 0, 0); }
   __device__ __forceinline__ float dot(const float* q) const {
@@ -98,7 +110,7 @@ struct RowChunk<kDtypeBF16> {
   }
 };
 
-template <int DIM, int MQ, int DT>
+template <int DIM, int MQ, int DT, bool ONCE>
 __global__ __launch_bounds__(256) void scores_stream_kernel(
     const void* __restrict__ X, const float* __restrict__ xnrm, long row_begin, long n_rows,
     const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
@@ -149,7 +161,12 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(
         for (int s = 0; s < NSEG; ++s) {
           const int col = s * SEG + lane * COLS;
           if (row < n_rows && col < DIM)
-            x[r][s].load(X, (row_begin + row) * long(DIM) + col);
+          {
+            if (ONCE)
+              x[r][s].load_once(X, (row_begin + row) * long(DIM) + col);
+            else
+              x[r][s].load(X, (row_begin + row) * long(DIM) + col);
+          }
           else
             x[r][s].zero();
         }
