@@ -354,4 +354,192 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, long
   }
 }
 
+// ---------------------------------------------------------------------------
+// Calls with a handful of rows (n <= kSmallRows): the whole cache side in one launch.
+//
+// Phase 1, all blocks: Euclidean distance from every row of the call to every
+// resident key, directly in float64 (direct-difference form, one wave per key):
+// with so few rows there is nothing to pre-filter.  D64[i * c + s].
+// Phase 2, the block that finishes last (a ticket counter tells which): rows in
+// order, exactly as resolver_kernel does -- nearest live source within tau (ties:
+// smaller seq) is a hit, otherwise evict/insert -- with distances between rows of
+// the call evaluated on the spot.  The same block then copies the keys of rows
+// that missed and still own their slot, and answers hits on resident keys from the
+// stored lists (what post_resolve_kernel does for large calls).
+// The rows are read from the caller's buffer; nothing is staged.
+// ---------------------------------------------------------------------------
+constexpr int kSmallRows = 4;
+
+__global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
+    const float* __restrict__ queries, int n, int c, int dim, int k, int policy_lru, long long base_seq, double tau,
+    CacheState* st, long long* slot_seq, int* slot_next, int* slot_prev, float* srcs, float* srcnrm,
+    const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, double* D64, unsigned* ticket,
+    uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
+    int* __restrict__ miss_count, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
+  const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  constexpr int NW = 16;
+  __shared__ bool is_last;
+  __shared__ double red_d[NW];
+  __shared__ long long red_seq[NW];
+  __shared__ int red_src[NW];
+  __shared__ double pair_d[kSmallRows];
+
+  const int size0 = st->size;
+  // phase 1
+  for (int s = blockIdx.x * NW + wib; s < size0; s += gridDim.x * NW) {
+    const float* key = srcs + long(s) * dim;
+    double acc[kSmallRows];
+#pragma unroll
+    for (int i = 0; i < kSmallRows; ++i) acc[i] = 0.0;
+    for (int e = lane; e < dim; e += 64) {
+      const double kv = double(key[e]);
+#pragma unroll
+      for (int i = 0; i < kSmallRows; ++i)
+        if (i < n) {
+          const double diff = double(queries[long(i) * dim + e]) - kv;
+          acc[i] += diff * diff;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kSmallRows; ++i)
+      if (i < n) {
+        const double d = sqrt(wave_sum(acc[i]));
+        if (lane == 0) D64[long(i) * c + s] = d;
+      }
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned t = atomicAdd(ticket, 1u);
+    is_last = t == gridDim.x - 1;
+    if (is_last) *ticket = 0;   // ready for the next call (launches on one stream do not overlap)
+  }
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();
+
+  // phase 2
+  int size = size0, head = st->head, tail = st->tail;
+  unsigned long long hits = 0, misses = 0, inserts = 0, evictions = 0, inbatch = 0;
+  int M = 0;
+  const double kInf = __longlong_as_double(0x7ff0000000000000ll);
+  for (int i = 0; i < n; ++i) {
+    // distances to earlier rows of this call (at most three), one wave each
+    if (wib < i) {
+      const double d = wave_dist64(queries + long(i) * dim, queries + long(wib) * dim, dim, lane);
+      if (lane == 0) pair_d[wib] = d;
+    }
+    __syncthreads();
+    ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
+    for (int s = tid; s < size0; s += 1024) {
+      const long long seq = slot_seq[s];
+      if (seq < base_seq) {   // still the key it held when the call began
+        const double d = D64[long(i) * c + s];
+        if (d <= tau) best_take(best, d, seq, s);
+      }
+    }
+    if (tid < i) {
+      const int t = row_slot[tid];
+      const long long seq = base_seq + tid;
+      if (t >= 0 && slot_seq[t] == seq && pair_d[tid] <= tau) best_take(best, pair_d[tid], seq, c + tid);
+    }
+    best_wave_reduce(best);
+    if (lane == 0) {
+      red_d[wib] = best.d;
+      red_seq[wib] = best.seq;
+      red_src[wib] = best.src;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      ResolverBest b{kInf, 0x7fffffffffffffffll, -1};
+      for (int w = 0; w < NW; ++w)
+        if (red_src[w] >= 0) best_take(b, red_d[w], red_seq[w], red_src[w]);
+      if (b.src >= 0) {
+        ++hits;
+        if (b.src >= c) ++inbatch;
+        const int t = b.src < c ? b.src : row_slot[b.src - c];
+        if (policy_lru && t != tail) {
+          const int p = slot_prev[t], nx = slot_next[t];
+          if (p >= 0) slot_next[p] = nx; else head = nx;
+          slot_prev[nx] = p;
+          slot_prev[t] = tail;
+          slot_next[t] = -1;
+          slot_next[tail] = t;
+          tail = t;
+        }
+        hit_out[i] = 1;
+        src_out[i] = b.src;
+        row_slot[i] = -1;
+      } else {
+        ++misses;
+        int t = -1;
+        if (c > 0) {
+          if (size < c) {
+            t = size++;
+          } else {
+            t = head;
+            head = slot_next[t];
+            if (head >= 0) slot_prev[head] = -1; else tail = -1;
+            ++evictions;
+          }
+          slot_seq[t] = base_seq + i;
+          slot_prev[t] = tail;
+          slot_next[t] = -1;
+          if (tail >= 0) slot_next[tail] = t; else head = t;
+          tail = t;
+          ++inserts;
+        }
+        hit_out[i] = 0;
+        src_out[i] = -1;
+        row_slot[i] = t;
+        miss_list[M++] = i;
+      }
+    }
+    __syncthreads();   // (also a memory fence: the state written by thread 0 is visible to the next row)
+  }
+  if (tid == 0) {
+    st->size = size;
+    st->head = head;
+    st->tail = tail;
+    st->queries += (unsigned long long)n;
+    st->hits += hits;
+    st->misses += misses;
+    st->inserts += inserts;
+    st->evictions += evictions;
+    st->inbatch_hits += inbatch;
+    *miss_count = M;
+  }
+  __syncthreads();
+  // keys of rows that missed and still own their slot; hits on keys resident before the call
+  for (int i = 0; i < n; ++i) {
+    if (hit_out[i]) {
+      const int s = src_out[i];
+      if (s < c)
+        for (int e = tid; e < k; e += 1024) {
+          out_ids[long(i) * k + e] = val_ids[long(s) * k + e];
+          if (out_d) out_d[long(i) * k + e] = val_d[long(s) * k + e];
+        }
+    } else {
+      const int t = row_slot[i];
+      if (t >= 0 && slot_seq[t] == base_seq + i) {
+        float sq = 0.f;
+        for (int e = tid; e < dim; e += 1024) {
+          const float v = queries[long(i) * dim + e];
+          srcs[long(t) * dim + e] = v;
+          sq += v * v;
+        }
+        sq = wave_sum(sq);
+        __syncthreads();
+        if (lane == 0) red_d[wib] = double(sq);
+        __syncthreads();
+        if (tid == 0) {
+          float total = 0.f;
+          for (int w = 0; w < NW; ++w) total += float(red_d[w]);
+          srcnrm[t] = total;
+        }
+      }
+    }
+  }
+}
+
 }  // namespace prox

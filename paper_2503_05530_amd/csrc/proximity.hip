@@ -38,6 +38,7 @@ constexpr int kSelE = 16;          // elements per thread in a selection segment
 constexpr int kSelSeg = kSelE * kSelThreads;
 constexpr int kMaxProfiled = 8192;
 constexpr int kStreamMaxQueries = 4;   // calls with at most this many rows use the streaming kernels
+static_assert(kStreamMaxQueries == kSmallRows, "the fused small-call kernels pair with the streaming scan");
 constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
@@ -99,6 +100,8 @@ struct proximity {
   int* row_slot = nullptr;
   int* miss_list = nullptr;
   int* miss_count = nullptr;
+  double* D64 = nullptr;        // small calls: float64 distances [kSmallRows][capacity]
+  unsigned* tickets = nullptr;  // last-block counters: [0] probe, [1..] one per query of a small call
 
   // kernel timing
   bool prof_on = false;
@@ -279,7 +282,7 @@ int enqueue_merge_levels(proximity* h, int cur, long len, int kp, const int* m_c
 // Qbase when qlist is null): scores, hierarchical top-k, float64 ranking.
 // Results land in row qlist[m] (or m) of res_ids / res_d.
 int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
-                 int64_t* res_ids, float* res_d, hipStream_t s) {
+                 int64_t* res_ids, float* res_d, const SmallRouting* small_routing, hipStream_t s) {
   const int k = int(h->cfg.k), dim = int(h->cfg.dim);
   const long N = long(h->cfg.n_docs);
   if (N == 0) {
@@ -301,9 +304,23 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
         launch_scores_stream<kDtypeF32, true>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
                                         m0, h->S, h->ldS, s);
       prof_end(h, s, m0, mq);
-      select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
-          h->S, h->ldS, N, 0, kp, h->pairs[0] + long(m0) * g1 * kp, g1, m_count_ptr, m_limit, m0);
+      if (small_routing) {
+        // a handful of queries: selection, float64 ranking and routing in one launch;
+        // res_ids / res_d are then the caller's output rows
+        if (bf16)
+          select_finish_small_kernel<kDtypeBF16, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
+              h->S, h->ldS, N, kp, k, h->pairs[0], g1, h->tickets + 1, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr,
+              m_limit, m0, *small_routing, res_ids, res_d);
+        else
+          select_finish_small_kernel<kDtypeF32, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
+              h->S, h->ldS, N, kp, k, h->pairs[0], g1, h->tickets + 1, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr,
+              m_limit, m0, *small_routing, res_ids, res_d);
+      } else {
+        select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
+            h->S, h->ldS, N, 0, kp, h->pairs[0] + long(m0) * g1 * kp, g1, m_count_ptr, m_limit, m0);
+      }
     }
+    if (small_routing) return PROXIMITY_OK;
     cur = enqueue_merge_levels(h, 0, long(g1) * kp, kp, m_count_ptr, m_limit, s);
   } else {
     // Batched scan on the matrix cores, in two steps.  First the head of the corpus
@@ -454,6 +471,8 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   TRY_ALLOC(h->row_slot, B, true);
   TRY_ALLOC(h->miss_list, B, true);
   TRY_ALLOC(h->miss_count, 1, true);
+  TRY_ALLOC(h->D64, size_t(kSmallRows) * (c > 0 ? c : 1), false);
+  TRY_ALLOC(h->tickets, 1 + kSmallRows, true);
 #undef TRY_ALLOC
   CacheState init{};
   init.head = init.tail = -1;
@@ -495,7 +514,9 @@ int proximity_knn_batch(proximity_t* h, const float* queries, uint32_t n, uint32
   DeviceGuard guard(h->cfg.device);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   h->last_stream = s;
-  rc = enqueue_scan(h, queries, nullptr, nullptr, int(n), out_ids, out_dists ? out_dists : h->res_d, s);
+  SmallRouting no_cache{};
+  rc = enqueue_scan(h, queries, nullptr, nullptr, int(n), out_ids, out_dists ? out_dists : h->res_d,
+                    int(n) <= kSmallRows ? &no_cache : nullptr, s);
   if (h->prof_on) ++h->prof_call;
   if (rc != PROXIMITY_OK) return rc;
   return check_launch(h, "proximity_knn_batch");
@@ -515,6 +536,23 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   const int c = int(h->cfg.capacity), dim = int(h->cfg.dim), kk = int(h->cfg.k), nn = int(n);
   const long long base_seq = (long long)h->next_seq;
   float* batch_rows = h->srcs + size_t(c) * dim;
+
+  if (nn <= kSmallRows && h->cfg.n_docs > 0) {
+    // A handful of rows: three launches in all.  Cache side (probe in float64, resolver, key
+    // insertion, hits on resident keys), streaming scan for the rows that missed, and
+    // selection + float64 ranking + routing.  The rows are read from the caller's buffer.
+    const int grid = c > 0 ? ((c + 15) / 16 < h->n_cu ? (c + 15) / 16 : h->n_cu) : 1;
+    probe_resolve_small_kernel<<<dim3(grid), dim3(1024), 0, s>>>(
+        queries, nn, c, dim, kk, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state,
+        h->slot_seq, h->slot_next, h->slot_prev, h->srcs, h->srcnrm, h->val_ids, h->val_d, h->D64, h->tickets,
+        out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
+    const SmallRouting rt{out_hit, h->src, h->row_slot, h->slot_seq, h->val_ids, h->val_d, base_seq, nn, c};
+    rc = enqueue_scan(h, queries, h->miss_list, h->miss_count, nn, out_ids, out_dists, &rt, s);
+    if (rc != PROXIMITY_OK) return rc;
+    h->next_seq += n;
+    if (h->prof_on) ++h->prof_call;
+    return check_launch(h, "proximity_search_batch");
+  }
 
   HIP_TRY(h, hipMemcpyAsync(batch_rows, queries, size_t(n) * dim * sizeof(float), hipMemcpyDeviceToDevice, s));
   launch_row_norms<kDtypeF32>(h, batch_rows, nn, dim, h->srcnrm + c, s);
@@ -542,7 +580,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, base_seq, h->srcs, h->srcnrm, h->slot_seq,
                                                      out_hit, h->src, h->row_slot, h->val_ids, h->val_d, out_ids,
                                                      out_dists);
-  rc = enqueue_scan(h, batch_rows, h->miss_list, h->miss_count, nn, h->res_ids, h->res_d, s);
+  rc = enqueue_scan(h, batch_rows, h->miss_list, h->miss_count, nn, h->res_ids, h->res_d, nullptr, s);
   if (rc != PROXIMITY_OK) return rc;
   finalize_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, kk, base_seq, h->slot_seq, out_hit, h->src, h->row_slot,
                                                  h->res_ids, h->res_d, h->val_ids, h->val_d, out_ids, out_dists);
