@@ -355,30 +355,31 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, long
 }
 
 // ---------------------------------------------------------------------------
-// Calls with a handful of rows (n <= kSmallRows): the whole cache side in one launch.
+// Calls with a handful of rows (n <= kSmallRows): the whole cache side in two launches of
+// this kernel.
 //
-// Phase 1, all blocks: Euclidean distance from every row of the call to every
+// phase == 1, a grid of blocks: Euclidean distance from every row of the call to every
 // resident key, directly in float64 (direct-difference form, one wave per key):
 // with so few rows there is nothing to pre-filter.  D64[i * c + s].
-// Phase 2, the block that finishes last (a ticket counter tells which): rows in
-// order, exactly as resolver_kernel does -- nearest live source within tau (ties:
-// smaller seq) is a hit, otherwise evict/insert -- with distances between rows of
-// the call evaluated on the spot.  The same block then copies the keys of rows
-// that missed and still own their slot, and answers hits on resident keys from the
+// phase == 2, one block: rows in order, exactly as resolver_kernel does -- nearest live
+// source within tau (ties: smaller seq) is a hit, otherwise evict/insert -- with distances
+// between rows of the call evaluated on the spot.  The same block then copies the keys of
+// rows that missed and still own their slot, and answers hits on resident keys from the
 // stored lists (what post_resolve_kernel does for large calls).
 // The rows are read from the caller's buffer; nothing is staged.
+// (A single launch whose last block does phase 2 was slower: the device-wide fences that
+// hand the distances from block to block cost more than a second launch.)
 // ---------------------------------------------------------------------------
 constexpr int kSmallRows = 4;
 
 __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
     const float* __restrict__ queries, int n, int c, int dim, int k, int policy_lru, long long base_seq, double tau,
     CacheState* st, long long* slot_seq, int* slot_next, int* slot_prev, float* srcs, float* srcnrm,
-    const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, double* D64, unsigned* ticket,
+    const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, double* D64, int phase,
     uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
     int* __restrict__ miss_count, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
   constexpr int NW = 16;
-  __shared__ bool is_last;
   __shared__ double red_d[NW];
   __shared__ long long red_seq[NW];
   __shared__ int red_src[NW];
@@ -386,6 +387,7 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
 
   const int size0 = st->size;
   // phase 1
+  if (phase != 2)
   for (int s = blockIdx.x * NW + wib; s < size0; s += gridDim.x * NW) {
     const float* key = srcs + long(s) * dim;
     double acc[kSmallRows];
@@ -407,16 +409,7 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
         if (lane == 0) D64[long(i) * c + s] = d;
       }
   }
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const unsigned t = atomicAdd(ticket, 1u);
-    is_last = t == gridDim.x - 1;
-    if (is_last) *ticket = 0;   // ready for the next call (launches on one stream do not overlap)
-  }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
+  if (phase == 1) return;
 
   // phase 2
   int size = size0, head = st->head, tail = st->tail;

@@ -102,6 +102,47 @@ __device__ __forceinline__ void block_bitonic_sort(uint64_t* keys, int P, int ti
   }
 }
 
+// Ascending sort of one 64-bit key per lane across a wave (bitonic network on shuffles, no LDS,
+// no barrier).  On return lane l holds the (l+1)-th smallest key.
+__device__ __forceinline__ uint64_t wave_sort64(uint64_t v, int lane) {
+#pragma unroll
+  for (int k = 2; k <= kWave; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      const uint64_t other = __shfl_xor(v, j, kWave);
+      const bool keep_small = ((lane & k) == 0) == ((lane & j) == 0);
+      const uint64_t lo = v < other ? v : other, hi = v < other ? other : v;
+      v = keep_small ? lo : hi;
+    }
+  }
+  return v;
+}
+
+// A bound B with at least kp of the block's per-thread keys at or below it (kp <= 4 * 64):
+// every wave sorts its 64 keys in registers and offers its ceil(kp/NW)-th smallest; the largest
+// offer qualifies.  Close to the exact kp-th smallest at a fraction of a block-wide sort.
+// `slots` is NW words of LDS; one barrier inside.
+template <int NW>
+__device__ __forceinline__ uint64_t block_bound_for_kp(uint64_t thread_key, int kp, uint64_t* slots, int tid) {
+  const int lane = tid & 63, wib = tid >> 6;
+  const uint64_t sorted = wave_sort64(thread_key, lane);
+  const int r = (kp + NW - 1) / NW;
+  const uint64_t offer = __shfl(sorted, r - 1, kWave);
+  if (lane == 0) slots[wib] = offer;
+  __syncthreads();
+  uint64_t b = slots[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) b = slots[w] > b ? slots[w] : b;
+  return b;
+}
+
+// Ascending sort of P <= 64 keys held in LDS, done by the first wave in registers; all threads
+// of the block must call it.  Ends with a barrier.
+__device__ __forceinline__ void block_sort_upto64(uint64_t* keys, int tid) {
+  if (tid < kWave) keys[tid] = wave_sort64(keys[tid], tid);
+  __syncthreads();
+}
+
 __device__ __forceinline__ int next_pow2(int v) {
   int p = 1;
   while (p < v) p <<= 1;

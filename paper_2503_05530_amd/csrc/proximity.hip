@@ -101,7 +101,6 @@ struct proximity {
   int* miss_list = nullptr;
   int* miss_count = nullptr;
   double* D64 = nullptr;        // small calls: float64 distances [kSmallRows][capacity]
-  unsigned* tickets = nullptr;  // last-block counters: [0] probe, [1..] one per query of a small call
 
   // kernel timing
   bool prof_on = false;
@@ -307,14 +306,17 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       if (small_routing) {
         // a handful of queries: selection, float64 ranking and routing in one launch;
         // res_ids / res_d are then the caller's output rows
-        if (bf16)
-          select_finish_small_kernel<kDtypeBF16, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
-              h->S, h->ldS, N, kp, k, h->pairs[0], g1, h->tickets + 1, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr,
-              m_limit, m0, *small_routing, res_ids, res_d);
-        else
-          select_finish_small_kernel<kDtypeF32, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
-              h->S, h->ldS, N, kp, k, h->pairs[0], g1, h->tickets + 1, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr,
-              m_limit, m0, *small_routing, res_ids, res_d);
+        for (int phase = 1; phase <= 2; ++phase) {
+          const dim3 grid(phase == 2 ? 1 : g1, mq);
+          if (bf16)
+            select_finish_small_kernel<kDtypeBF16, kSelE><<<grid, dim3(kSelThreads), 0, s>>>(
+                h->S, h->ldS, N, kp, k, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
+                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d);
+          else
+            select_finish_small_kernel<kDtypeF32, kSelE><<<grid, dim3(kSelThreads), 0, s>>>(
+                h->S, h->ldS, N, kp, k, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
+                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d);
+        }
       } else {
         select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
             h->S, h->ldS, N, 0, kp, h->pairs[0] + long(m0) * g1 * kp, g1, m_count_ptr, m_limit, m0);
@@ -472,7 +474,6 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   TRY_ALLOC(h->miss_list, B, true);
   TRY_ALLOC(h->miss_count, 1, true);
   TRY_ALLOC(h->D64, size_t(kSmallRows) * (c > 0 ? c : 1), false);
-  TRY_ALLOC(h->tickets, 1 + kSmallRows, true);
 #undef TRY_ALLOC
   CacheState init{};
   init.head = init.tail = -1;
@@ -538,14 +539,16 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   float* batch_rows = h->srcs + size_t(c) * dim;
 
   if (nn <= kSmallRows && h->cfg.n_docs > 0) {
-    // A handful of rows: three launches in all.  Cache side (probe in float64, resolver, key
+    // A handful of rows: five launches in all.  Cache side (probe in float64; then resolver, key
     // insertion, hits on resident keys), streaming scan for the rows that missed, and
-    // selection + float64 ranking + routing.  The rows are read from the caller's buffer.
+    // selection; then merge + float64 ranking + routing.  The rows are read from the caller's buffer.
     const int grid = c > 0 ? ((c + 15) / 16 < h->n_cu ? (c + 15) / 16 : h->n_cu) : 1;
-    probe_resolve_small_kernel<<<dim3(grid), dim3(1024), 0, s>>>(
-        queries, nn, c, dim, kk, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state,
-        h->slot_seq, h->slot_next, h->slot_prev, h->srcs, h->srcnrm, h->val_ids, h->val_d, h->D64, h->tickets,
-        out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
+    for (int phase = 1; phase <= 2; ++phase) {
+      probe_resolve_small_kernel<<<dim3(phase == 2 ? 1 : grid), dim3(1024), 0, s>>>(
+          queries, nn, c, dim, kk, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state,
+          h->slot_seq, h->slot_next, h->slot_prev, h->srcs, h->srcnrm, h->val_ids, h->val_d, h->D64,
+          phase, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
+    }
     const SmallRouting rt{out_hit, h->src, h->row_slot, h->slot_seq, h->val_ids, h->val_d, base_seq, nn, c};
     rc = enqueue_scan(h, queries, h->miss_list, h->miss_count, nn, out_ids, out_dists, &rt, s);
     if (rc != PROXIMITY_OK) return rc;

@@ -9,6 +9,8 @@
 // (rerank_f64_kernel) so float32 rounding cannot reorder the k winners.
 #pragma once
 
+#include <type_traits>
+
 #include "device_utils.hpp"
 
 namespace prox {
@@ -23,11 +25,11 @@ constexpr int kSelThreads = 256;
 // padded with kPadKey when the segment holds fewer than kp elements.
 //
 // Method: every thread keeps its E elements in registers and finds its own
-// minimum; the kp-th smallest of the 256 thread minima bounds the kp-th smallest
-// element from above (kp distinct elements lie at or below it), so only
-// elements at or below that bound are compacted into LDS and sorted.  With kp
-// up to 256 the expected number of survivors is about 2*kp; exact ties can make
-// it as large as the segment, which the LDS list is sized for.
+// minimum; a value with at least kp of the 256 thread minima at or below it
+// bounds the kp-th smallest element from above (kp distinct elements lie at or
+// below it), so only elements at or below that bound are compacted into LDS and
+// sorted.  The expected number of survivors is a few times kp; exact ties can
+// make it as large as the segment, which the LDS list is sized for.
 template <bool DENSE, int E>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const void* __restrict__ in, long in_ld, long len,
                                                              long id_base, int kp, uint64_t* __restrict__ out,
@@ -60,11 +62,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const void* __restr
     key[e] = kv;
     tmin = kv < tmin ? kv : tmin;
   }
-  mins[tid] = tmin;
   if (tid == 0) count = 0;
-  __syncthreads();
-  block_bitonic_sort(mins, kSelThreads, tid, kSelThreads);
-  const uint64_t bound = mins[kp - 1];  // kp <= 256
+  const uint64_t bound = block_bound_for_kp<kSelThreads / 64>(tmin, kp, mins, tid);  // kp <= 256
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const long j = seg0 + e * kSelThreads + tid;
@@ -76,11 +75,62 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const void* __restr
   __syncthreads();
   const int cnt = count;
   const int P = next_pow2(cnt > kp ? cnt : kp);  // <= SEG because kp <= 256 <= SEG
-  for (int i = cnt + tid; i < P; i += kSelThreads) list[i] = kPadKey;
+  for (int i = cnt + tid; i < (P < 64 ? 64 : P); i += kSelThreads) list[i] = kPadKey;
   __syncthreads();
-  block_bitonic_sort(list, P, tid, kSelThreads);
+  if (P <= 64)
+    block_sort_upto64(list, tid);
+  else
+    block_bitonic_sort(list, P, tid, kSelThreads);
   uint64_t* o = out + (long(q) * n_seg + g) * kp;
   for (int i = tid; i < kp; i += kSelThreads) o[i] = list[i];
+}
+
+
+// Float64 Euclidean distance (direct-difference form) from query q to each of the kp candidate
+// rows named by `keys`, by the NW waves of a block; four candidates per wave are in flight at
+// once so that their row fetches overlap.  d64[c] / cid[c] receive distance and id of candidate
+// c (padding candidates: +inf and INT_MAX).  The caller synchronises afterwards.
+template <int DT, int NW>
+__device__ __forceinline__ void block_candidate_distances(const uint64_t* keys, int kp, const float* __restrict__ q,
+                                                          const void* __restrict__ X, int dim, double* d64, int* cid,
+                                                          int tid) {
+  using Elem = typename std::conditional<DT == kDtypeF32, float, uint16_t>::type;
+  const int lane = tid & 63, wib = tid >> 6;
+  constexpr int G = 4;
+  for (int c0 = wib; c0 < kp; c0 += NW * G) {
+    int id[G];
+    const Elem* row[G];
+    double acc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const int c = c0 + g * NW;
+      id[g] = c < kp ? key_id(keys[c]) : -1;
+      row[g] = static_cast<const Elem*>(X) + long(id[g] >= 0 ? id[g] : 0) * dim;
+      acc[g] = 0.0;
+    }
+    for (int i = lane; i < dim; i += 64) {
+      const double qv = double(q[i]);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        double xv;
+        if (DT == kDtypeF32)
+          xv = double(reinterpret_cast<const float*>(row[g])[i]);
+        else
+          xv = double(bf16_to_float(reinterpret_cast<const uint16_t*>(row[g])[i]));
+        const double diff = qv - xv;
+        acc[g] += diff * diff;
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const int c = c0 + g * NW;
+      const double total = wave_sum(acc[g]);
+      if (lane == 0 && c < kp) {
+        d64[c] = id[g] >= 0 ? sqrt(total) : __longlong_as_double(0x7ff0000000000000ll);
+        cid[c] = id[g] >= 0 ? id[g] : 0x7fffffff;
+      }
+    }
+  }
 }
 
 // Final ranking in float64.  One block of 16 waves per query: for each of the kp
@@ -107,30 +157,7 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
   __shared__ double d64[256];
   __shared__ int ids[256];
 
-  for (int c = wib; c < kp; c += kRerankThreads / 64) {
-    const int id = key_id(cand[long(m) * kp + c]);
-    double acc = 0.0;
-    if (id >= 0) {
-      if (DT == kDtypeF32) {
-        const float* x = static_cast<const float*>(X) + long(id) * dim;
-        for (int i = lane; i < dim; i += 64) {
-          const double diff = double(q[i]) - double(x[i]);
-          acc += diff * diff;
-        }
-      } else {
-        const uint16_t* x = static_cast<const uint16_t*>(X) + long(id) * dim;
-        for (int i = lane; i < dim; i += 64) {
-          const double diff = double(q[i]) - double(bf16_to_float(x[i]));
-          acc += diff * diff;
-        }
-      }
-      acc = wave_sum(acc);
-    }
-    if (lane == 0) {
-      d64[c] = id >= 0 ? sqrt(acc) : __longlong_as_double(0x7ff0000000000000ll);
-      ids[c] = id >= 0 ? id : 0x7fffffff;
-    }
-  }
+  block_candidate_distances<DT, kRerankThreads / 64>(cand + long(m) * kp, kp, q, X, dim, d64, ids, threadIdx.x);
   __syncthreads();
   for (int c = threadIdx.x; c < kp; c += kRerankThreads) {
     const double d = d64[c];
@@ -164,11 +191,11 @@ __global__ void fill_empty_results_kernel(const int* __restrict__ qlist, const i
 }
 
 // ---------------------------------------------------------------------------
-// Calls with a handful of queries: the whole ranking side in one launch.
+// Calls with a handful of queries: the whole ranking side in two launches of this kernel.
 //
-// Every block does what select_kernel<true> does for its segment of the dense
-// score row.  The block that finishes last for a query (ticket counter per
-// query) then merges the per-segment lists, re-ranks the kp survivors in
+// phase == 1, grid (segments, queries): every block does what select_kernel<true> does
+// for its segment of the dense score row.  phase == 2, grid (1, queries): one block per
+// query merges the per-segment lists, re-ranks the kp survivors in
 // float64 like rerank_f64_kernel, and routes the result like finalize_kernel:
 // the query's own row, the rows of the same call that hit it, and its cache slot
 // if it still owns one.  With hit == nullptr there is no cache (plain k-NN call).
@@ -192,11 +219,8 @@ __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ 
     const uint64_t kv = in[j];
     tmin = kv < tmin ? kv : tmin;
   }
-  mins[tid] = tmin;
   if (tid == 0) *count = 0;
-  __syncthreads();
-  block_bitonic_sort(mins, kSelThreads, tid, kSelThreads);
-  const uint64_t bound = mins[kp - 1];
+  const uint64_t bound = block_bound_for_kp<kSelThreads / 64>(tmin, kp, mins, tid);
   for (long j = tid; j < len; j += kSelThreads) {
     const uint64_t kv = in[j];
     if (kv <= bound) {
@@ -208,9 +232,12 @@ __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ 
   const int cnt = *count;
   if (cnt <= list_cap) {
     const int P = next_pow2(cnt > kp ? cnt : kp);
-    for (int i = cnt + tid; i < P; i += kSelThreads) list[i] = kPadKey;
+    for (int i = cnt + tid; i < (P < 64 ? 64 : P); i += kSelThreads) list[i] = kPadKey;
     __syncthreads();
-    block_bitonic_sort(list, P, tid, kSelThreads);
+    if (P <= 64)
+      block_sort_upto64(list, tid);
+    else
+      block_bitonic_sort(list, P, tid, kSelThreads);
     return;
   }
   // exact ties made the survivor set larger than the list: keep a running best-kp list and
@@ -230,7 +257,7 @@ __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ 
 template <int DT, int E>
 __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
     const float* __restrict__ S, long ldS, long len, int kp, int k, uint64_t* __restrict__ lists, int n_seg,
-    unsigned* tickets, const void* __restrict__ X, int dim, const float* __restrict__ Qbase,
+    int phase, const void* __restrict__ X, int dim, const float* __restrict__ Qbase,
     const int* __restrict__ qlist, const int* __restrict__ m_count_ptr, int m_limit, int m_begin, SmallRouting rt,
     int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   constexpr int SEG = E * kSelThreads;
@@ -242,12 +269,12 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
   __shared__ uint64_t list[SEG];
   __shared__ uint64_t mins[kSelThreads];
   __shared__ int count;
-  __shared__ bool is_last;
   __shared__ double d64[256];
   __shared__ int cid[256];
   __shared__ int64_t fin_ids[256];
   __shared__ float fin_d[256];
 
+  if (phase != 2) {
   // ---- this block's segment of the dense scores -> kp sorted keys (as select_kernel<true>) ----
   const long seg0 = long(g) * SEG;
   uint64_t key[E];
@@ -260,11 +287,8 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
     key[e] = kv;
     tmin = kv < tmin ? kv : tmin;
   }
-  mins[tid] = tmin;
   if (tid == 0) count = 0;
-  __syncthreads();
-  block_bitonic_sort(mins, kSelThreads, tid, kSelThreads);
-  const uint64_t bound = mins[kp - 1];
+  const uint64_t bound = block_bound_for_kp<kSelThreads / 64>(tmin, kp, mins, tid);
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     const long j = seg0 + e * kSelThreads + tid;
@@ -274,22 +298,17 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
   {
     const int cnt = count;
     const int P = next_pow2(cnt > kp ? cnt : kp);
-    for (int i = cnt + tid; i < P; i += kSelThreads) list[i] = kPadKey;
+    for (int i = cnt + tid; i < (P < 64 ? 64 : P); i += kSelThreads) list[i] = kPadKey;
     __syncthreads();
-    block_bitonic_sort(list, P, tid, kSelThreads);
+    if (P <= 64)
+      block_sort_upto64(list, tid);
+    else
+      block_bitonic_sort(list, P, tid, kSelThreads);
     uint64_t* o = lists + (long(q) * n_seg + g) * kp;
     for (int i = tid; i < kp; i += kSelThreads) o[i] = list[i];
   }
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const unsigned t = atomicAdd(&tickets[q], 1u);
-    is_last = t == unsigned(n_seg) - 1;
-    if (is_last) tickets[q] = 0;
   }
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
+  if (phase == 1) return;
 
   // ---- merge all segments' lists ----
   block_topk_of_keys(lists + long(q) * n_seg * kp, long(n_seg) * kp, kp, list, SEG, mins, &count, tid);
@@ -297,30 +316,7 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
   // ---- float64 ranking of the kp survivors (as rerank_f64_kernel) ----
   const int qrow = qlist ? qlist[q] : q;
   const float* qv = Qbase + long(qrow) * dim;
-  for (int c = wib; c < kp; c += kSelThreads / 64) {
-    const int id = key_id(list[c]);
-    double acc = 0.0;
-    if (id >= 0) {
-      if (DT == kDtypeF32) {
-        const float* x = static_cast<const float*>(X) + long(id) * dim;
-        for (int i = lane; i < dim; i += 64) {
-          const double diff = double(qv[i]) - double(x[i]);
-          acc += diff * diff;
-        }
-      } else {
-        const uint16_t* x = static_cast<const uint16_t*>(X) + long(id) * dim;
-        for (int i = lane; i < dim; i += 64) {
-          const double diff = double(qv[i]) - double(bf16_to_float(x[i]));
-          acc += diff * diff;
-        }
-      }
-      acc = wave_sum(acc);
-    }
-    if (lane == 0) {
-      d64[c] = id >= 0 ? sqrt(acc) : __longlong_as_double(0x7ff0000000000000ll);
-      cid[c] = id >= 0 ? id : 0x7fffffff;
-    }
-  }
+  block_candidate_distances<DT, kSelThreads / 64>(list, kp, qv, X, dim, d64, cid, tid);
   __syncthreads();
   for (int c = tid; c < kp; c += kSelThreads) {
     const double d = d64[c];
