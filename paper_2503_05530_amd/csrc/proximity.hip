@@ -40,6 +40,7 @@ constexpr int kMaxProfiled = 8192;
 constexpr int kStreamMaxQueries = 4;   // calls with at most this many rows use the streaming kernels
 static_assert(kStreamMaxQueries == kSmallRows, "the fused small-call kernels pair with the streaming scan");
 constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
+constexpr size_t kResolverLdsMax = 158 * 1024;  // dynamic LDS the LDS-state resolver may ask for
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
 static_assert(sizeof(proximity_config) == 48, "proximity_config layout is part of the ABI");
@@ -475,6 +476,11 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   TRY_ALLOC(h->miss_count, 1, true);
   TRY_ALLOC(h->D64, size_t(kSmallRows) * (c > 0 ? c : 1), false);
 #undef TRY_ALLOC
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(resolver_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          int(kResolverLdsMax)) != hipSuccess) {
+    h->err = "could not raise the dynamic LDS limit of the resolver";
+    return bail(PROXIMITY_ERR_HIP);
+  }
   CacheState init{};
   init.head = init.tail = -1;
   if (hipMemcpy(h->state, &init, sizeof init, hipMemcpyHostToDevice) != hipSuccess) {
@@ -575,11 +581,21 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
                                                            double(tau), kCandCap, h->cand_cnt, h->cand_src,
                                                            h->cand_d);
   }
-  resolver_kernel<<<dim3(1), dim3(64), 0, s>>>(nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq,
-                                               double(tau), h->state, h->slot_seq, h->slot_next, h->slot_prev,
-                                               have_probe ? h->cand_cnt : nullptr, h->cand_src, h->cand_d, kCandCap,
-                                               h->D32, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot,
-                                               h->miss_list, h->miss_count);
+  // the sequential resolver: with its state in LDS when the batch is large enough to pay for
+  // copying the eviction order in and out, and the state fits
+  const size_t lds_state = (size_t(3) * c + nn) * sizeof(int);
+  if (have_probe && nn >= 64 && lds_state <= kResolverLdsMax) {
+    resolver_lds_kernel<<<dim3(1), dim3(256), lds_state, s>>>(
+        nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state, h->slot_seq,
+        h->slot_next, h->slot_prev, h->cand_cnt, h->cand_src, h->cand_d, kCandCap, h->D32, h->ldD, h->srcs, h->srcnrm,
+        out_hit, h->src, h->row_slot, h->miss_list, h->miss_count);
+  } else {
+    resolver_kernel<<<dim3(1), dim3(64), 0, s>>>(nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq,
+                                                 double(tau), h->state, h->slot_seq, h->slot_next, h->slot_prev,
+                                                 have_probe ? h->cand_cnt : nullptr, h->cand_src, h->cand_d, kCandCap,
+                                                 h->D32, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot,
+                                                 h->miss_list, h->miss_count);
+  }
   post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, base_seq, h->srcs, h->srcnrm, h->slot_seq,
                                                      out_hit, h->src, h->row_slot, h->val_ids, h->val_d, out_ids,
                                                      out_dists);
@@ -625,14 +641,22 @@ int proximity_cache_dump(const proximity_t* h, uint64_t* seq, float* keys, int64
     HIP_TRY(hh, hipMemcpy(sseq.data(), h->slot_seq, c * sizeof(long long), hipMemcpyDeviceToHost));
     HIP_TRY(hh, hipMemcpy(snext.data(), h->slot_next, c * sizeof(int), hipMemcpyDeviceToHost));
   }
+  // whole arrays in one copy each, then gathered in eviction order on the host
+  std::vector<float> all_keys;
+  std::vector<int64_t> all_ids;
+  if (keys && c) {
+    all_keys.resize(c * d);
+    HIP_TRY(hh, hipMemcpy(all_keys.data(), h->srcs, c * d * sizeof(float), hipMemcpyDeviceToHost));
+  }
+  if (ids && c) {
+    all_ids.resize(c * k);
+    HIP_TRY(hh, hipMemcpy(all_ids.data(), h->val_ids, c * k * sizeof(int64_t), hipMemcpyDeviceToHost));
+  }
   uint32_t count = 0;
   for (int t = st.head; t >= 0 && count < c; t = snext[size_t(t)]) {
     if (seq) seq[count] = uint64_t(sseq[size_t(t)]);
-    if (keys)
-      HIP_TRY(hh, hipMemcpy(keys + size_t(count) * d, h->srcs + size_t(t) * d, d * sizeof(float), hipMemcpyDeviceToHost));
-    if (ids)
-      HIP_TRY(hh, hipMemcpy(ids + size_t(count) * k, h->val_ids + size_t(t) * k, k * sizeof(int64_t),
-                            hipMemcpyDeviceToHost));
+    if (keys) std::memcpy(keys + size_t(count) * d, all_keys.data() + size_t(t) * d, d * sizeof(float));
+    if (ids) std::memcpy(ids + size_t(count) * k, all_ids.data() + size_t(t) * k, k * sizeof(int64_t));
     ++count;
   }
   *n_live = count;
