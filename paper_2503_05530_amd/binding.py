@@ -20,6 +20,7 @@ ERR_INVALID_ARG, ERR_K_MISMATCH, ERR_BATCH_TOO_LARGE, ERR_BAD_TAU, ERR_HIP, ERR_
 DTYPE_F32, DTYPE_BF16 = 0, 1
 POLICY_FIFO, POLICY_LRU = 0, 1
 ABI_VERSION = 1
+MAX_K, MAX_DIM, MAX_BATCH, MAX_CAPACITY = 240, 4096, 8192, 1 << 20   # PROXIMITY_MAX_* of the header
 
 
 class ProximityConfig(C.Structure):

@@ -38,6 +38,11 @@ def test_abi_version_and_struct_layout(binding):
     assert C.sizeof(binding.ProximityConfig) == 48
     assert C.sizeof(binding.ProximityStats) == 128
     assert C.sizeof(binding.ProximityLaunch) == 16
+    text = open(os.path.join(ROOT, "include", "proximity.h")).read()
+    limits = {m.group(1): eval(m.group(2).replace("u", "")) for m in
+              re.finditer(r"#define PROXIMITY_MAX_(\w+)\s+(\(?[0-9u <]+\)?)", text)}
+    assert limits == {"K": binding.MAX_K, "DIM": binding.MAX_DIM, "BATCH": binding.MAX_BATCH,
+                      "CAPACITY": binding.MAX_CAPACITY}
 
 
 def make_cfg(b, **kw):

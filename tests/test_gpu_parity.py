@@ -65,6 +65,18 @@ def test_knn_matches_oracle_bf16(B, nq):
     px.close()
 
 
+@pytest.mark.parametrize("nq", [1, 4, 70])
+def test_knn_at_the_largest_k(B, nq):
+    n_docs, dim, k = 40000, 768, B.MAX_K
+    corpus = W.corpus_f32(n_docs, dim, 11)
+    q = W.unit_rows(np.random.default_rng(12).standard_normal((nq, dim))).astype(np.float32)
+    px = B.Proximity(gpu_corpus(corpus), dim, 0, k, B.POLICY_FIFO, nq)
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    o_ids, o_d = po.batched_exact_knn(corpus, q, k)
+    P.assert_lists_match(ids.cpu().numpy(), dists.cpu().numpy(), o_ids, o_d, corpus, q, what=f"knn k={k}")
+    px.close()
+
+
 def test_knn_duplicate_rows_rank_by_index(B):
     corpus = W.corpus_f32(6000, 768, 4)
     corpus[4500] = corpus[17]
@@ -137,6 +149,23 @@ def test_tiny_workload(B, tiny, batch, policy):
     assert st["hits"] == int(o_hit.sum()) and st["evictions"] == dec.n_evictions
     if policy == w.policy:
         assert st["hits"] == 697 and st["evictions"] == 253
+    px.close()
+
+
+def test_one_call_of_the_largest_batch(B):
+    """8192 rows in a single call give what the same stream gives one row at a time in the oracle."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS["tiny"], n_stream=B.MAX_BATCH, n_bases=1500, seed=21)
+    corpus = W.corpus_f32(6000, w.dim, 21)
+    q = W.stream_for(w)
+    assert len(q) == B.MAX_BATCH
+    want = po.lookup_stream_deferred(corpus, q, w.tau, 300, w.k, po.POLICY_LRU)
+    px = B.Proximity(gpu_corpus(corpus), w.dim, 300, w.k, po.POLICY_LRU, B.MAX_BATCH)
+    got = P.run_stream(px, q, w.tau, B.MAX_BATCH, DEV)
+    P.assert_stream_parity(got, want[:4], corpus, q, what="largest batch")
+    seq, _, _ = px.cache_dump()
+    assert seq.tolist() == want[4].dump_seq().tolist()
+    assert 0 < px.stats()["hits"] < B.MAX_BATCH and px.stats()["evictions"] > 0
     px.close()
 
 
