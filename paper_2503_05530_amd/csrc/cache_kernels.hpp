@@ -282,217 +282,6 @@ __global__ __launch_bounds__(64) void resolver_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// The same resolver for large batches, with the sequential state in LDS.
-//
-// Walking thousands of rows one after the other, every dependent access to global memory
-// costs a microsecond.  Here the block first copies the eviction order (next/prev per
-// slot) into LDS, keeps "which row of this batch overwrote slot t" (-1: none) and "which
-// slot row j took" there as well, lets its first wave walk the rows, and writes the state
-// back at the end.  The wave also fetches the candidate count and the first candidate of
-// 64 rows at a time, so that the common cases (no candidate: miss; one candidate) touch
-// LDS only.  Rows with several candidates or with more than the list holds take the same
-// paths as resolver_kernel.  Needs (3c + n) * 4 bytes of dynamic LDS.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void resolver_lds_kernel(
-    int n, int c, int dim, int policy_lru, long long base_seq, double tau, CacheState* __restrict__ st,
-    long long* slot_seq, int* slot_next, int* slot_prev, const int* __restrict__ cand_cnt,
-    const int* __restrict__ cand_src, const double* __restrict__ cand_d, int cap, const float* __restrict__ D32,
-    long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm, uint8_t* __restrict__ hit_out,
-    int* __restrict__ src_out, int* __restrict__ row_slot, int* __restrict__ miss_list,
-    int* __restrict__ miss_count) {
-  extern __shared__ int lds_state[];
-  int* lnext = lds_state;        // [c]
-  int* lprev = lds_state + c;    // [c]
-  int* lrow = lds_state + 2 * c; // [c]  row of this batch that overwrote the slot, -1 if none
-  int* lslot = lds_state + 3 * c;  // [n]  slot taken by a row that missed, -1 otherwise
-  const int tid = threadIdx.x, lane = tid & 63;
-  for (int s = tid; s < c; s += 256) {
-    lnext[s] = slot_next[s];
-    lprev[s] = slot_prev[s];
-    lrow[s] = -1;
-  }
-  __syncthreads();
-
-  if (tid < 64) {
-    int size = st->size, head = st->head, tail = st->tail;
-    unsigned long long hits = 0, misses = 0, inserts = 0, evictions = 0, inbatch = 0, dense = 0;
-    int M = 0;
-    const double kInf = __longlong_as_double(0x7ff0000000000000ll);
-    for (int i0 = 0; i0 < n; i0 += 64) {
-      const int my_i = i0 + lane;
-      int my_cnt = 0, my_s0 = -1;
-      double my_d0 = kInf;
-      if (my_i < n) {
-        my_cnt = cand_cnt[my_i];
-        if (my_cnt >= 1 && my_cnt <= cap) {
-          my_s0 = cand_src[long(my_i) * cap];
-          my_d0 = cand_d[long(my_i) * cap];
-        }
-      }
-      int my_hit = 0, my_src = -1;
-      const int rows = n - i0 < 64 ? n - i0 : 64;
-      for (int r = 0; r < rows; ++r) {
-        const int i = i0 + r;
-        // r is wave-uniform: readlane moves the prefetched values without a trip through LDS
-        const int cnt = __builtin_amdgcn_readlane(my_cnt, r);
-        int best_src = -1;
-        if (cnt == 1) {
-          const int s = __builtin_amdgcn_readlane(my_s0, r);
-          const long long dbits = __double_as_longlong(my_d0);
-          const unsigned dlo = unsigned(__builtin_amdgcn_readlane(int(dbits & 0xffffffffll), r));
-          const unsigned dhi = unsigned(__builtin_amdgcn_readlane(int(dbits >> 32), r));
-          const double d = __longlong_as_double((long long)((unsigned long long)dhi << 32 | dlo));
-          bool live;
-          if (s < c) {
-            live = lrow[s] < 0;
-          } else {
-            const int t = lslot[s - c];
-            live = t >= 0 && lrow[t] == s - c;
-          }
-          if (live && d <= tau) best_src = s;
-        } else if (cnt >= 2 && cnt <= cap) {
-          ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
-          for (int p0 = 0; p0 < cnt; p0 += 64) {
-            const int p = p0 + lane;
-            if (p < cnt) {
-              const int s = cand_src[long(i) * cap + p];
-              const double d = cand_d[long(i) * cap + p];
-              long long seq;
-              bool live;
-              if (s < c) {
-                live = lrow[s] < 0;
-                seq = live ? slot_seq[s] : 0;   // untouched this batch, so still its own seq
-              } else {
-                const int t = lslot[s - c];
-                seq = base_seq + (s - c);
-                live = t >= 0 && lrow[t] == s - c;
-              }
-              if (live && d <= tau) best_take(best, d, seq, s);
-            }
-          }
-          best_wave_reduce(best);
-          best_src = best.src;
-        } else if (cnt > cap) {
-          ++dense;
-          ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
-          const float qn = srcnrm[c + i];
-          const float* row = D32 + long(i) * ldD;
-          float mn = 3.4e38f, snmax = 0.f;
-          for (int t = lane; t < size; t += 64) {
-            const int s = lrow[t] >= 0 ? c + lrow[t] : t;
-            mn = fminf(mn, row[s] + qn);
-            snmax = fmaxf(snmax, srcnrm[s]);
-          }
-#pragma unroll
-          for (int m = 32; m >= 1; m >>= 1) {
-            mn = fminf(mn, __shfl_xor(mn, m, kWave));
-            snmax = fmaxf(snmax, __shfl_xor(snmax, m, kWave));
-          }
-          const float slack = 2e-4f * (qn + snmax);
-          if (mn <= prefilter_bound(tau, qn, snmax) + slack) {
-            const float near = mn + slack;
-            for (int t0 = 0; t0 < size; t0 += 64) {
-              const int t = t0 + lane;
-              int s = -1;
-              bool is_near = false;
-              if (t < size) {
-                s = lrow[t] >= 0 ? c + lrow[t] : t;
-                is_near = row[s] + qn <= near;
-              }
-              unsigned long long mask = __ballot(is_near);
-              while (mask) {
-                const int b = __ffsll((long long)mask) - 1;
-                mask &= mask - 1;
-                const int sb = __shfl(s, b, kWave);
-                const long long sqb = sb < c ? slot_seq[sb] : base_seq + (sb - c);
-                const double d = wave_dist64(srcs + long(c + i) * dim, srcs + long(sb) * dim, dim, lane);
-                if (d <= tau) best_take(best, d, sqb, sb);
-              }
-            }
-          }
-          best_src = best.src;
-        }
-
-        if (best_src >= 0) {
-          ++hits;
-          if (best_src >= c) ++inbatch;
-          const int t = best_src < c ? best_src : lslot[best_src - c];
-          if (policy_lru && t != tail) {
-            const int p = lprev[t], nx = lnext[t];  // nx >= 0 because t is not the tail
-            if (lane == 0) {
-              if (p >= 0) lnext[p] = nx;
-              lprev[nx] = p;
-              lprev[t] = tail;
-              lnext[t] = -1;
-              lnext[tail] = t;
-            }
-            if (p < 0) head = nx;
-            tail = t;
-          }
-          if (lane == 0) lslot[i] = -1;
-          if (lane == r) {
-            my_hit = 1;
-            my_src = best_src;
-          }
-        } else {
-          ++misses;
-          int t = -1;
-          if (c > 0) {
-            if (size < c) {
-              t = size++;
-            } else {
-              t = head;
-              head = lnext[t];
-              if (lane == 0 && head >= 0) lprev[head] = -1;
-              if (head < 0) tail = -1;
-              ++evictions;
-            }
-            if (lane == 0) {
-              lrow[t] = i;
-              lprev[t] = tail;
-              lnext[t] = -1;
-              if (tail >= 0) lnext[tail] = t;
-            }
-            if (tail < 0) head = t;
-            tail = t;
-            ++inserts;
-          }
-          if (lane == 0) {
-            lslot[i] = t;
-            miss_list[M] = i;
-          }
-          ++M;
-        }
-      }
-      if (my_i < n) {
-        hit_out[my_i] = uint8_t(my_hit);
-        src_out[my_i] = my_src;
-      }
-    }
-    if (lane == 0) {
-      st->size = size;
-      st->head = head;
-      st->tail = tail;
-      st->queries += (unsigned long long)n;
-      st->hits += hits;
-      st->misses += misses;
-      st->inserts += inserts;
-      st->evictions += evictions;
-      st->inbatch_hits += inbatch;
-      st->dense_resolves += dense;
-      *miss_count = M;
-    }
-  }
-  __syncthreads();
-  for (int s = tid; s < c; s += 256) {
-    slot_next[s] = lnext[s];
-    slot_prev[s] = lprev[s];
-    if (lrow[s] >= 0) slot_seq[s] = base_seq + lrow[s];
-  }
-  for (int i = tid; i < n; i += 256) row_slot[i] = lslot[i];
-}
-
-// ---------------------------------------------------------------------------
 // After the resolver, before the scan.  One block per batch row.
 //   - a row that missed and still owns its slot at the end of the batch copies
 //     its vector and squared norm into the slot (Algorithm 1, "C[q] <- I", key part);

@@ -25,6 +25,7 @@
 #include "../../include/proximity.h"
 #include "cache_kernels.hpp"
 #include "mfma_kernels.hpp"
+#include "resolver_lds.hpp"
 #include "scan_kernels.hpp"
 #include "select_kernels.hpp"
 
@@ -40,7 +41,8 @@ constexpr int kMaxProfiled = 8192;
 constexpr int kStreamMaxQueries = 4;   // calls with at most this many rows use the streaming kernels
 static_assert(kStreamMaxQueries == kSmallRows, "the fused small-call kernels pair with the streaming scan");
 constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
-constexpr size_t kResolverLdsMax = 158 * 1024;  // dynamic LDS the LDS-state resolver may ask for
+constexpr size_t kResolverLdsMax = 147 * 1024;  // dynamic LDS the LDS-state resolver may ask for
+static_assert(kResolverLdsMax + kResolverStaticLds <= 160 * 1024 - 256, "the resolver block must fit the LDS of one CU");
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
 static_assert(sizeof(proximity_config) == 48, "proximity_config layout is part of the ABI");
@@ -581,10 +583,9 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
                                                            double(tau), kCandCap, h->cand_cnt, h->cand_src,
                                                            h->cand_d);
   }
-  // the sequential resolver: with its state in LDS when the batch is large enough to pay for
-  // copying the eviction order in and out, and the state fits
+  // the sequential resolver: with its state in LDS whenever that fits
   const size_t lds_state = (size_t(3) * c + nn) * sizeof(int);
-  if (have_probe && nn >= 64 && lds_state <= kResolverLdsMax) {
+  if (have_probe && lds_state <= kResolverLdsMax) {
     resolver_lds_kernel<<<dim3(1), dim3(256), lds_state, s>>>(
         nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state, h->slot_seq,
         h->slot_next, h->slot_prev, h->cand_cnt, h->cand_src, h->cand_d, kCandCap, h->D32, h->ldD, h->srcs, h->srcnrm,

@@ -169,6 +169,44 @@ def test_one_call_of_the_largest_batch(B):
     px.close()
 
 
+@pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
+def test_cache_too_large_for_on_chip_state(B, policy):
+    """13 000 keys: the eviction order no longer fits on chip and the resolver works from device memory."""
+    # The literal oracle needs minutes at this cache size.  At tau = 0 a query hits exactly when the
+    # same vector is resident, so Algorithm 1 is a textbook FIFO/LRU cache keyed by vector identity
+    # (test_oracle_pins shows the oracle equal to that model); the model is the expectation here, and
+    # the oracle itself is compared on a prefix.
+    from collections import OrderedDict
+    dim, cap = 32, 13000
+    rng = np.random.default_rng(31)
+    vecs = W.unit_rows(rng.standard_normal((13600, dim))).astype(np.float32)
+    which = np.concatenate([np.arange(13300), rng.integers(0, 13300, size=700), np.arange(13300, 13600),
+                            rng.integers(0, 13600, size=700)])
+    q = vecs[which]
+    model, want_hit, evictions = OrderedDict(), [], 0
+    for t, key in enumerate(which.tolist()):
+        if key in model:
+            want_hit.append(1)
+            if policy == po.POLICY_LRU:
+                model.move_to_end(key)
+        else:
+            want_hit.append(0)
+            if len(model) >= cap:
+                model.popitem(last=False)
+                evictions += 1
+            model[key] = t
+    assert evictions > 100 and 300 < sum(want_hit) < 1400
+    px = B.Proximity(None, dim, cap, 3, policy, 512, device=DEV)
+    _, _, hit = P.run_stream(px, q, 0.0, 512, DEV)
+    assert hit.tolist() == want_hit
+    seq, _, _ = px.cache_dump()
+    assert seq.tolist() == list(model.values())
+    assert px.stats()["evictions"] == evictions
+    px.close()
+    o_hit, _, _ = po.simulate_decisions(q[:600], 0.0, cap, policy)
+    assert hit[:600].tolist() == o_hit.tolist()
+
+
 def test_tau_zero_and_tau_huge(B, tiny):
     w, corpus, q, _ = tiny
     q = q[:200]
