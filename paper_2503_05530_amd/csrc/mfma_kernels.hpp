@@ -669,4 +669,64 @@ __global__ __launch_bounds__(256, 2) void probe_mfma_dense_kernel(const float* _
   }
 }
 
+// ---------------------------------------------------------------------------
+// The same probe for shapes too small to fill the chip with 128 x 128 tiles, where the time
+// of the kernel above is the latency of one block walking the whole contraction.
+// A block owns 32 sources x 32 queries; its four waves each take a quarter of the columns
+// (dim must be a multiple of 32) and feed the matrix instruction straight from global memory:
+// per step of 8 columns a lane reads 16 bytes of its source row and of its query row (lanes
+// 0-31 columns 8t..8t+3, lanes 32-63 columns 8t+4..8t+7; register e of both operands pairs
+// column 8t+e with 8t+4+e).  The four partial tiles are added through LDS.
+// Grid: x = source tiles of 32, y = query tiles of 32.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void probe_mfma_small_kernel(const float* __restrict__ srcs,
+                                                               const float* __restrict__ srcnrm, int n_src,
+                                                               const float* __restrict__ Q, int n_q, int dim,
+                                                               float* __restrict__ D, long ldD) {
+  constexpr int U = 8;  // steps whose loads are issued together
+  __shared__ float part[4][16][64];
+  const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  const int r32 = lane & 31, half = lane >> 5;
+  const int s0 = blockIdx.x * 32, q0 = blockIdx.y * 32;
+  const int steps = dim / 32;  // steps of 8 columns per wave
+  const int srow = s0 + r32 < n_src ? s0 + r32 : n_src - 1;   // rows past the end repeat the last one;
+  const int qrow = q0 + r32 < n_q ? q0 + r32 : n_q - 1;       // their results are not written
+  const float* ps = srcs + long(srow) * dim + wib * (dim / 4) + 4 * half;
+  const float* pq = Q + long(qrow) * dim + wib * (dim / 4) + 4 * half;
+
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (int t0 = 0; t0 < steps; t0 += U) {
+    float4 a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (t0 + u < steps) {
+        a[u] = *reinterpret_cast<const float4*>(pq + 8 * (t0 + u));
+        b[u] = *reinterpret_cast<const float4*>(ps + 8 * (t0 + u));
+      } else {
+        a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        b[u] = a[u];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f4_get(a[u], e), f4_get(b[u], e), acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) part[wib][e][lane] = acc[e];
+  __syncthreads();
+  // element e of lane l is query 8*(e/4) + 4*(l/32) + e%4 against source l%32
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int e = wib + 4 * i;
+    const float dot = part[0][e][lane] + part[1][e][lane] + part[2][e][lane] + part[3][e][lane];
+    const int q = q0 + 8 * (e >> 2) + 4 * half + (e & 3);
+    const int sidx = s0 + r32;
+    if (q < n_q && sidx < n_src) D[long(q) * ldD + sidx] = srcnrm[sidx] - 2.f * dot;
+  }
+}
+
 }  // namespace prox

@@ -43,6 +43,7 @@ static_assert(kStreamMaxQueries == kSmallRows, "the fused small-call kernels pai
 constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
 constexpr size_t kResolverLdsMax = 147 * 1024;  // dynamic LDS the LDS-state resolver may ask for
 static_assert(kResolverLdsMax + kResolverStaticLds <= 160 * 1024 - 256, "the resolver block must fit the LDS of one CU");
+constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32 tiles use the split-column kernel
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
 static_assert(sizeof(proximity_config) == 48, "proximity_config layout is part of the ABI");
@@ -259,8 +260,9 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
           h->cfg.corpus, h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, seed,     \
           h->topk_buf, out);                                                                                   \
   } while (0)
-  PROX_SCAN(32, 256, 0, 32);
-  if (m_limit > 32) PROX_SCAN(64, 256, 32, 64);
+  const bool known = m_count_ptr == nullptr;  // then M = m_limit and only its own shape is launched
+  if (!known || m_limit <= 32) PROX_SCAN(32, 256, 0, 32);
+  if (m_limit > 32 && (!known || m_limit <= 64)) PROX_SCAN(64, 256, 32, 64);
   if (m_limit > 64) PROX_SCAN(128, 128, 64, 0x7fffffff);
 #undef PROX_SCAN
 }
@@ -575,6 +577,9 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
       for (int m0 = 0; m0 < nn; m0 += mq)
         launch_scores_stream<kDtypeF32, false>(h, mq, h->srcs, h->srcnrm, long(c) + nn, dim, batch_rows, nullptr, nullptr,
                                         nn, m0, h->D32 + size_t(m0) * h->ldD, h->ldD, s);
+    } else if (long((c + nn + 31) / 32) * ((nn + 31) / 32) <= kProbeSmallBlocks) {
+      probe_mfma_small_kernel<<<dim3((c + nn + 31) / 32, (nn + 31) / 32), dim3(256), 0, s>>>(
+          h->srcs, h->srcnrm, c + nn, batch_rows, nn, dim, h->D32, h->ldD);
     } else {
       probe_mfma_dense_kernel<<<dim3((c + nn + 127) / 128, (nn + 127) / 128), dim3(256), 0, s>>>(
           h->srcs, h->srcnrm, c + nn, batch_rows, nn, dim, h->D32, h->ldD);
