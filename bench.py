@@ -79,6 +79,17 @@ def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, devic
     return busy
 
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/*.md), scaled by what the
+# same counters read for a 1 GiB copy (FETCH_SIZE: 2 KiB per count, WRITE_SIZE: 1 KiB per count).
+# Keyed by (kernel, query-tile shape, corpus rows, dim, element bytes); anything else reports null.
+COUNTER_TRAFFIC = {
+    ("scores_stream_kernel", 0, 1_000_000, 768, 4):
+        {"fetch_bytes": 1_501_992 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scores_stream_mid_b1.md"},
+    ("scan_mfma_dma_kernel", 64, 1_000_000, 768, 4):
+        {"fetch_bytes": 1_504_668 * 2048, "write_bytes": 7_037 * 1024, "source": "profiles/scan_mfma_mid_b64.md"},
+}
+
+
 def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
     """Roofline entry from (duration ms, queries served) of the launches that streamed the corpus."""
     if not busy:
@@ -89,7 +100,14 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
     gbs = bytes_per_launch / (avg_ms * 1e-3) / 1e9
     tflops = sum(2.0 * q * n_docs * dim for _, q in busy) / (sum(ms for ms, _ in busy) * 1e-3) / 1e12
     ridge_q = F32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) * elem_bytes / 2   # queries per launch at the ridge
-    common = {"traffic": None, "kernel": "scores_stream_kernel" if batch <= 8 else "scan_mfma_topk_kernel",
+    if batch <= 4:
+        kernel = "scores_stream_kernel"
+    else:
+        kernel = "scan_mfma_dma_kernel" if elem_bytes == 4 and dim >= 64 else "scan_mfma_topk_kernel"
+    tile = 0 if batch <= 4 else (32 if avg_q <= 32 else 64 if avg_q <= 64 else 128)
+    counted = COUNTER_TRAFFIC.get((kernel, tile, n_docs, dim, elem_bytes))
+    common = {"traffic": None if counted is None else counted["fetch_bytes"] + counted["write_bytes"],
+              "traffic_counters": counted, "kernel": kernel,
               "launches_timed": len(busy), "avg_launch_ms": round(avg_ms, 5),
               "queries_per_launch_avg": round(avg_q, 3), "achieved_GBps": round(gbs, 1),
               "achieved_TFLOPs": round(tflops, 2), "algorithmic_bytes_per_launch": bytes_per_launch,
