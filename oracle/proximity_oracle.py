@@ -19,13 +19,20 @@ What it follows
 * Eviction follows Section 3.3.2: FIFO removes the oldest inserted entry
   whatever its use; LRU removes the entry unused for longest, where a hit
   uses the matched entry and an insertion uses the new one.
+* ``rerank_factor`` is the re-ranking factor rho of Section 3.3.4: the database
+  call asks for rho * k neighbours, all of them are stored with the key, a miss
+  hands the first k to the caller, and a hit orders the stored rho * k documents
+  by their distance to the *current* query (``rerank_stored``) and hands out the
+  k nearest.  rho = 1 is the plain procedure: nothing is re-ranked.
 
 Readings where the paper is silent (each listed in the design notes):
 the hit test is ``<=``; an empty cache misses; equal nearest distances pick
 the older entry; only the matched entry is refreshed under LRU; a hit inserts
 nothing and returns the stored list unchanged (re-ranking factor 1); ranked
 lists order equal distances by document index and are padded with -1 / +inf
-when the index holds fewer than k vectors; capacity 0 disables caching.
+when the index holds fewer than k vectors; capacity 0 disables caching; with
+rho > 1 a hit ranks by (distance to the current query, document index) and
+reports those distances, and rho is a whole number.
 
 Parity status: every function here is pinned by tests that do not re-use its
 own formula (hand-worked eviction streams, reduction to textbook exact-match
@@ -75,6 +82,20 @@ def exact_knn(corpus: np.ndarray, q: np.ndarray, k: int,
     return ids, dists
 
 
+def rerank_stored(corpus: np.ndarray, q: np.ndarray, stored_ids: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Section 3.3.4, the hit side: of the documents stored with the matched key, the k
+    nearest to the current query, ranked; ids int64[k], dists float64[k] (padded -1 / +inf)."""
+    valid = np.asarray([i for i in np.asarray(stored_ids).tolist() if i >= 0], dtype=np.int64)
+    ids = np.full(k, -1, dtype=np.int64)
+    dists = np.full(k, np.inf, dtype=np.float64)
+    if len(valid):
+        d = l2_distances(q, corpus[valid])
+        order = sorted(range(len(valid)), key=lambda j: (d[j], int(valid[j])))[:k]
+        ids[: len(order)] = valid[order]
+        dists[: len(order)] = d[order]
+    return ids, dists
+
+
 class _Entry:
     __slots__ = ("key", "ids", "dists", "seq")
 
@@ -92,14 +113,18 @@ class FlatCacheOracle:
     """
 
     def __init__(self, corpus: Optional[np.ndarray], capacity: int, k: int, policy: int,
-                 retrieve: Optional[Callable] = None):
+                 retrieve: Optional[Callable] = None, rerank_factor: int = 1):
         if policy not in (POLICY_FIFO, POLICY_LRU):
             raise ValueError("policy must be FIFO (0) or LRU (1)")
+        if int(rerank_factor) != rerank_factor or rerank_factor < 1:
+            raise ValueError("rerank_factor must be a whole number >= 1")
         self.corpus = corpus
         self.capacity = int(capacity)
         self.k = int(k)
+        self.rho = int(rerank_factor)
+        self.k_store = self.rho * self.k          # neighbours asked of the database and kept per key
         self.policy = int(policy)
-        self.retrieve = retrieve if retrieve is not None else (lambda q: exact_knn(corpus, q, self.k))
+        self.retrieve = retrieve if retrieve is not None else (lambda q: exact_knn(corpus, q, self.k_store))
         self.entries: List[_Entry] = []
         self.n_queries = 0
         self.n_hits = 0
@@ -134,7 +159,10 @@ class FlatCacheOracle:
                 self.n_hits += 1
                 if self.policy == POLICY_LRU:
                     self.entries.append(self.entries.pop(best))
-                return e.ids.copy(), e.dists.copy(), True, e.seq
+                if self.rho == 1:
+                    return e.ids.copy(), e.dists.copy(), True, e.seq
+                r_ids, r_d = rerank_stored(self.corpus, q64, e.ids, self.k)
+                return r_ids, r_d, True, e.seq
 
         ids, nd = self.retrieve(q64)
         self.n_scans += 1
@@ -145,7 +173,7 @@ class FlatCacheOracle:
                 self.n_evictions += 1
             self.entries.append(_Entry(q64, np.asarray(ids).copy(), np.asarray(nd).copy(), seq))
             self.n_inserts += 1
-        return np.asarray(ids).copy(), np.asarray(nd).copy(), False, seq
+        return np.asarray(ids)[: self.k].copy(), np.asarray(nd)[: self.k].copy(), False, seq
 
     def lookup_stream(self, queries, tau: float):
         """Process rows of ``queries`` in order.  Returns ids[n,k], dists[n,k], hit[n], source_seq[n]."""
@@ -171,7 +199,7 @@ class FlatCacheOracle:
 
     def dump_ids(self) -> np.ndarray:
         if not self.entries:
-            return np.zeros((0, self.k), dtype=np.int64)
+            return np.zeros((0, self.k_store), dtype=np.int64)
         return np.stack([e.ids for e in self.entries])
 
     def stats(self) -> dict:
@@ -242,24 +270,33 @@ def batched_exact_knn(corpus: np.ndarray, queries: np.ndarray, k: int,
 
 
 def lookup_stream_deferred(corpus, queries, tau: float, capacity: int, k: int, policy: int,
-                           knn_chunk: int = 256):
+                           knn_chunk: int = 256, rerank_factor: int = 1):
     """Outputs of ``FlatCacheOracle.lookup_stream`` computed decisions-first.
 
-    Returns ids[n,k], dists[n,k], hit[n], source_seq[n], decision_oracle.
+    Returns ids[n,k], dists[n,k], hit[n], source_seq[n], decision_oracle; with
+    ``rerank_factor`` > 1 a sixth item, stored_ids[n, rerank_factor*k]: what each query that
+    missed stored with its key.
     """
     hit, src, dec = simulate_decisions(queries, tau, capacity, policy)
     n = len(queries)
+    k_store = int(rerank_factor) * k
     miss_rows = np.flatnonzero(hit == 0)
-    ids = np.empty((n, k), dtype=np.int64)
-    dists = np.empty((n, k), dtype=np.float64)
+    stored_ids = np.full((n, k_store), -1, dtype=np.int64)
+    stored_d = np.full((n, k_store), np.inf, dtype=np.float64)
     for c0 in range(0, len(miss_rows), knn_chunk):
         rows = miss_rows[c0:c0 + knn_chunk]
-        i_, d_ = batched_exact_knn(corpus, np.asarray(queries)[rows], k)
-        ids[rows], dists[rows] = i_, d_
+        i_, d_ = batched_exact_knn(corpus, np.asarray(queries)[rows], k_store)
+        stored_ids[rows], stored_d[rows] = i_, d_
+    ids = stored_ids[:, :k].copy()
+    dists = stored_d[:, :k].copy()
     hit_rows = np.flatnonzero(hit == 1)
-    ids[hit_rows] = ids[src[hit_rows]]
-    dists[hit_rows] = dists[src[hit_rows]]
-    return ids, dists, hit, src, dec
+    if rerank_factor == 1:
+        ids[hit_rows] = ids[src[hit_rows]]
+        dists[hit_rows] = dists[src[hit_rows]]
+        return ids, dists, hit, src, dec
+    for t in hit_rows:
+        ids[t], dists[t] = rerank_stored(corpus, as_f64_rows(queries[t]), stored_ids[src[t]], k)
+    return ids, dists, hit, src, dec, stored_ids
 
 
 def exact_knn_over_chunks(chunks, queries, k: int) -> Tuple[np.ndarray, np.ndarray]:

@@ -330,10 +330,11 @@ __device__ __forceinline__ float f4_get(const float4& v, int e) {
 //  * no register staging: each wave issues NL loads per slab whose 64 lanes
 //    write 1 KiB = 8 rows x 128 bytes straight into the slab's LDS stage;
 //  * LDS rows are 128 bytes with no padding; instead lane l of a load fetches
-//    the 16-byte column chunk (l%8) xor (l/8) of its row, so chunk c of row r sits
-//    at position c xor (r%8).  The eight lanes that read the same chunk of eight
-//    consecutive rows for the matrix instruction then hit eight different bank
-//    groups;
+//    the 16-byte column chunk (l%8) xor ((r/2)%8) of its stage row r, so chunk c of
+//    row r sits at position c xor ((r/2)%8).  A 16-byte LDS read is served 16 lanes
+//    at a time; the sixteen lanes that read the same chunk of sixteen consecutive
+//    rows for the matrix instruction then cover all 64 banks exactly once (with
+//    c xor (r%8) rows r and r+8 collide and every read takes twice as long);
 //  * a ring of three stages: while slab s is multiplied, slabs s+1 and s+2 are
 //    in flight, and one barrier per slab suffices (it both publishes slab s and
 //    retires the stage that slab s+2 will overwrite);
@@ -404,18 +405,20 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
   uint64_t* my_buf = cand_buf + (long(blockIdx.y) * gridDim.x + blockIdx.x) * long(TM) * kTopkCap;
   const int n_slabs = dim / kSlabK;
 
-  // load duty of this lane: NL loads per slab, load i covers stage rows 8*(wib*NL+i) .. +7
-  const int my_chunk = (lane & 7) ^ (lane >> 3);
+  // load duty of this lane: NL loads per slab, load i covers stage rows 8*(wib*NL+i) .. +7;
+  // the lane fetches column chunk (l%8) xor swizzle(stage row) of its row
   const float* src[NL];
   bool is_x[NL];
+  int my_chunk[NL];
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
     const int srow = 8 * (wib * NL + i) + (lane >> 3);
+    my_chunk[i] = (lane & 7) ^ ((srow >> 1) & 7);
     is_x[i] = srow < TN;
     if (!is_x[i]) {
       int m = m0 + srow - TN;
       m = m < M ? m : M - 1;
-      src[i] = Qbase + long(qlist ? qlist[m] : m) * dim + 4 * my_chunk;
+      src[i] = Qbase + long(qlist ? qlist[m] : m) * dim + 4 * my_chunk[i];
     }
   }
   auto point_at_tile = [&](long tile) {
@@ -424,7 +427,7 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
       if (is_x[i]) {
         long r = tile * TN + 8 * (wib * NL + i) + (lane >> 3);
         r = r < n_rows ? r : n_rows - 1;
-        src[i] = X + r * dim + 4 * my_chunk;
+        src[i] = X + r * dim + 4 * my_chunk[i];
       }
   };
   // issue stream: slab number `is` (flat over this block's tiles), one group of NL loads per call
@@ -465,7 +468,7 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
     for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
 
   auto multiply = [&](const float* st) {
-    const int sw = r32 & 7;  // (stage row) % 8 of every row this lane reads: row offsets are multiples of 32
+    const int sw = (r32 >> 1) & 7;  // swizzle of every row this lane reads: row offsets are multiples of 32
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int pos = ((2 * t + half) ^ sw) * 4;

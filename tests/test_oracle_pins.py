@@ -278,6 +278,89 @@ def test_deferred_form_equals_literal_form():
 
 
 # ---------------------------------------------------------------------------
+# Re-ranking factor (Section 3.3.4)
+# ---------------------------------------------------------------------------
+def test_rerank_factor_one_is_the_plain_procedure():
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(2000, w.dim, w.seed)
+    q = W.stream_for(w, 200)
+    a = po.FlatCacheOracle(corpus, 20, 10, po.POLICY_LRU).lookup_stream(q, 0.25)
+    b = po.FlatCacheOracle(corpus, 20, 10, po.POLICY_LRU, rerank_factor=1).lookup_stream(q, 0.25)
+    for x, y in zip(a, b):
+        assert (x == y).all()
+
+
+def test_rerank_hand_worked_line():
+    """Documents at 0,1,..,9 on a line, k=2, rho=2 (4 stored per key), tau=3, capacity 4.
+    q=4.4 misses: stores [4,5,3,6] (distances .4,.6,1.4,1.6), returns [4,5].
+    q=5.6 hits (1.2 away): of the stored 4,5,3,6 the nearest are 6 (.4) and 5 (.6) -> [6,5].
+    q=2.0 hits (2.4 away): nearest of the stored are 3 (1.0), then 4 (2.0) -> [3,4]; the true
+    neighbours 2 and 1 are not among the stored and cannot come back.
+    q=4.5 hits: 4 and 5 tie at .5 -> lower index first -> [4,5]."""
+    corpus = line_vectors(range(10))
+    orc = po.FlatCacheOracle(corpus, 4, 2, po.POLICY_FIFO, rerank_factor=2)
+    ids, dists, hit, _ = orc.lookup_stream(line_vectors([4.4, 5.6, 2.0, 4.5]), 3.0)
+    assert hit.tolist() == [0, 1, 1, 1]
+    assert ids.tolist() == [[4, 5], [6, 5], [3, 4], [4, 5]]
+    np.testing.assert_allclose(dists, [[0.4, 0.6], [0.4, 0.6], [1.0, 2.0], [0.5, 0.5]], rtol=1e-6)
+    assert orc.dump_ids().tolist() == [[4, 5, 3, 6]]
+
+
+def test_rerank_of_the_whole_index_is_exact_search():
+    """When rho * k covers every document, a hit re-ranks the whole index: its answer is the exact
+    k-NN of the current query, whatever key it matched."""
+    sk = pytest.importorskip("sklearn.neighbors")
+    corpus = small_corpus(40, 8, 5)
+    rng = np.random.default_rng(9)
+    q = rng.standard_normal((30, 8)).astype(np.float32)
+    orc = po.FlatCacheOracle(corpus, 3, 5, po.POLICY_LRU, rerank_factor=8)     # 8 * 5 = 40 = N
+    ids, dists, hit, _ = orc.lookup_stream(q, 1e9)
+    assert hit.tolist() == [0] + [1] * 29
+    nn = sk.NearestNeighbors(n_neighbors=5, algorithm="brute").fit(corpus.astype(np.float64))
+    want_d, want_i = nn.kneighbors(q.astype(np.float64))
+    assert (ids == want_i).all()
+    np.testing.assert_allclose(dists, want_d, rtol=1e-12)
+
+
+def test_rerank_matches_pure_python_and_keeps_to_the_stored_documents():
+    corpus = small_corpus(500, 6, 7)
+    rng = np.random.default_rng(10)
+    base = rng.standard_normal(6)
+    q = (base[None, :] + 0.3 * rng.standard_normal((25, 6))).astype(np.float32)
+    k, rho = 4, 3
+    orc = po.FlatCacheOracle(corpus, 2, k, po.POLICY_FIFO, rerank_factor=rho)
+    ids, dists, hit, src = orc.lookup_stream(q, 1e9)
+    stored = po.exact_knn(corpus, q[0], k * rho)[0].tolist()
+    assert ids[0].tolist() == stored[:k]                         # a miss hands out the first k of what it stores
+    for t in range(1, 25):
+        assert hit[t] == 1 and src[t] == 0
+        scored = []
+        for j in stored:                                         # plain loops: distance of q[t] to each stored document
+            s = 0.0
+            for a, b in zip(q[t].tolist(), corpus[j].tolist()):
+                s += (float(np.float32(a)) - float(np.float32(b))) ** 2
+            scored.append((math.sqrt(s), j))
+        scored.sort()
+        assert ids[t].tolist() == [j for _, j in scored[:k]]
+        np.testing.assert_allclose(dists[t], [d for d, _ in scored[:k]], rtol=1e-12)
+
+
+def test_rerank_deferred_form_equals_literal_form():
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(3000, w.dim, w.seed)
+    q = W.stream_for(w, 250)
+    for policy, cap in ((po.POLICY_FIFO, 30), (po.POLICY_LRU, 10)):
+        lit = po.FlatCacheOracle(corpus, cap, 5, policy, rerank_factor=4)
+        ids, dists, hit, src = lit.lookup_stream(q, 0.25)
+        d_ids, d_dists, d_hit, d_src, dec, stored = po.lookup_stream_deferred(corpus, q, 0.25, cap, 5, policy,
+                                                                              rerank_factor=4)
+        assert (hit == d_hit).all() and (src == d_src).all() and (ids == d_ids).all()
+        np.testing.assert_allclose(dists, d_dists, rtol=1e-13)
+        assert (lit.dump_ids() == stored[lit.dump_seq()]).all()
+        assert hit.sum() > 50
+
+
+# ---------------------------------------------------------------------------
 # Input generators (recipe checks, not method arithmetic)
 # ---------------------------------------------------------------------------
 def test_generator_recipe_is_stable():
