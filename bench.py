@@ -35,6 +35,8 @@ def parse_args():
                     help="mid is the headline workload; the others are the remaining benchmark configurations")
     ap.add_argument("--tau", type=float, default=None)
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--rho", type=int, default=1,
+                    help="re-ranking factor (Section 3.3.4): rho*k neighbours stored per key, hits re-ranked")
     ap.add_argument("--n-docs", type=int, default=None, help="override corpus rows (debugging only)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -210,7 +212,7 @@ def main():
     t_gen = time.perf_counter() - t_gen
     elem = 2 if w.corpus_dtype == W.DTYPE_BF16 else 4
 
-    px = Proximity(corpus_dev, w.dim, w.capacity, w.k, w.policy, max_batch)
+    px = Proximity(corpus_dev, w.dim, w.capacity, w.k, w.policy, max_batch, rerank_factor=args.rho)
     n_rows = len(queries)
     outs = (torch.empty((n_rows, w.k), dtype=torch.int64, device=device),
             torch.empty((n_rows, w.k), dtype=torch.float32, device=device),
@@ -240,10 +242,11 @@ def main():
     if not args.no_cpu_baseline and corpus is not None:
         from oracle import proximity_oracle as po
         first = warmup * batch
-        orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy,
-                                 retrieve=lambda q: (np.full(w.k, -1, np.int64), np.full(w.k, np.inf)))
+        k_store = args.rho * w.k
+        orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy, rerank_factor=args.rho,
+                                 retrieve=lambda q: (np.full(k_store, -1, np.int64), np.full(k_store, np.inf)))
         orc.lookup_stream(queries[:first], tau)            # decisions only: brings the cache to the timed region's state
-        orc.retrieve = lambda q: po.exact_knn(corpus, q, w.k)
+        orc.retrieve = lambda q: po.exact_knn(corpus, q, k_store)
         n_s = min(args.cpu_sample, len(queries) - first)
         t0 = time.perf_counter()
         o_ids, o_d, o_hit, _ = orc.lookup_stream(queries[first:first + n_s], tau)
@@ -262,7 +265,7 @@ def main():
                                f"{w.choice}({w.zipf_s}) stream of "
                                f"{w.n_stream} over {w.n_bases} bases (perturbation {w.radius}), capacity "
                                f"{w.capacity}, {'LRU' if w.policy else 'FIFO'}, k={w.k}",
-                   "tau": tau, "batch": batch, "hit_rate": round(hit_rate, 4),
+                   "tau": tau, "batch": batch, "rerank_factor": args.rho, "hit_rate": round(hit_rate, 4),
                    "queries_timed": steps * batch, "setup_s": round(t_gen, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
     }

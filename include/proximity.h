@@ -40,7 +40,7 @@
 extern "C" {
 #endif
 
-#define PROXIMITY_ABI_VERSION 1u
+#define PROXIMITY_ABI_VERSION 2u
 
 enum {
   PROXIMITY_OK = 0,
@@ -81,6 +81,13 @@ typedef struct proximity_config {
   uint32_t policy;        /* PROXIMITY_POLICY_*                                               */
   uint32_t max_batch;     /* largest n a call may pass, 1..PROXIMITY_MAX_BATCH                */
   int32_t device;         /* HIP device ordinal                                               */
+  uint32_t rerank_factor; /* rho of Section 3.3.4, a whole number >= 1 (0 is read as 1): the
+                             index is asked for rho * k neighbours (<= PROXIMITY_MAX_K), all
+                             are stored with the key, a miss returns the first k, and a hit
+                             returns the k of the stored rho * k documents nearest to the
+                             current query, ranked by (distance, index), with those
+                             distances.  1: a hit returns the stored list unchanged        */
+  uint32_t reserved;      /* must be 0                                                        */
 } proximity_config;
 
 /* Counters since creation or the last proximity_clear(). */
@@ -114,10 +121,11 @@ uint32_t proximity_abi_version(void);
 /*
  * Create an instance on cfg->device: computes the squared norm of every corpus
  * row once (one streaming pass over the corpus) and allocates the cache
- * (capacity x dim float32 keys, capacity x k values) and all workspaces, sized
- * for max_batch.  *out receives the handle.  Blocks until the norms are done.
- * Errors: INVALID_ARG (null, bad struct_size, dim/k/max_batch/capacity/n_docs
- * outside the limits, unknown dtype/policy, corpus null with n_docs > 0), OOM,
+ * (capacity x dim float32 keys, capacity x rerank_factor*k values) and all
+ * workspaces, sized for max_batch.  *out receives the handle.  Blocks until the norms are done.
+ * Errors: INVALID_ARG (null, bad struct_size, dim/k/max_batch/capacity/n_docs/
+ * rerank_factor*k outside the limits, unknown dtype/policy, reserved not 0,
+ * corpus null with n_docs > 0), OOM,
  * HIP.  On error *out is set to NULL.
  */
 int proximity_create(const proximity_config* cfg, proximity_t** out);
@@ -136,10 +144,13 @@ void proximity_destroy(proximity_t* h);
  *              A key at distance exactly tau is a hit.  May differ between calls.
  *   out_ids    DEVICE [n][k] int64: ranked document indices (ascending distance,
  *              equal distances by ascending index; -1 padding when n_docs < k).
- *              On a hit: the list stored with the matched key, unchanged.
+ *              On a hit: the list stored with the matched key, unchanged
+ *              (rerank_factor 1), or the k of the stored documents nearest to
+ *              this query (rerank_factor > 1, Section 3.3.4).
  *   out_dists  DEVICE [n][k] float32 or NULL: Euclidean distances that go with
- *              out_ids (+inf padding).  On a hit these are the stored distances
- *              to the matched key, not to the query.
+ *              out_ids (+inf padding).  On a hit with rerank_factor 1 these are
+ *              the stored distances to the matched key, not to the query; with
+ *              rerank_factor > 1 they are distances to the query.
  *   out_hit    DEVICE [n] uint8: 1 = answered from the cache, 0 = index searched
  *   hip_stream the hipStream_t to enqueue on (NULL = the default stream).
  *
@@ -164,7 +175,7 @@ int proximity_stats(const proximity_t* h, proximity_stats_t* out);
  * Copies the cache contents to HOST arrays in eviction order (next victim
  * first).  seq[i] is the position, counted from creation or the last clear, of
  * the query that inserted entry i.  keys ([capacity][dim] float32) and ids
- * ([capacity][k] int64) may be NULL.  *n_live receives the number of entries
+ * ([capacity][rerank_factor * k] int64) may be NULL.  *n_live receives the number of entries
  * written.  Waits for the handle's last stream.
  */
 int proximity_cache_dump(const proximity_t* h, uint64_t* seq, float* keys, int64_t* ids,

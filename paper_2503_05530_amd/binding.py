@@ -19,14 +19,15 @@ OK = 0
 ERR_INVALID_ARG, ERR_K_MISMATCH, ERR_BATCH_TOO_LARGE, ERR_BAD_TAU, ERR_HIP, ERR_OOM = -1, -2, -3, -4, -5, -6
 DTYPE_F32, DTYPE_BF16 = 0, 1
 POLICY_FIFO, POLICY_LRU = 0, 1
-ABI_VERSION = 1
+ABI_VERSION = 2
 MAX_K, MAX_DIM, MAX_BATCH, MAX_CAPACITY = 240, 4096, 8192, 1 << 20   # PROXIMITY_MAX_* of the header
 
 
 class ProximityConfig(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("dim", C.c_uint32), ("corpus", C.c_void_p),
                 ("n_docs", C.c_uint64), ("corpus_dtype", C.c_uint32), ("capacity", C.c_uint32),
-                ("k", C.c_uint32), ("policy", C.c_uint32), ("max_batch", C.c_uint32), ("device", C.c_int32)]
+                ("k", C.c_uint32), ("policy", C.c_uint32), ("max_batch", C.c_uint32), ("device", C.c_int32),
+                ("rerank_factor", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ProximityStats(C.Structure):
@@ -98,7 +99,7 @@ class Proximity:
     """One cache-plus-index instance.  Method names follow the C entry points."""
 
     def __init__(self, corpus: Optional[torch.Tensor], dim: int, capacity: int, k: int, policy: int,
-                 max_batch: int, device: Optional[torch.device] = None):
+                 max_batch: int, device: Optional[torch.device] = None, rerank_factor: int = 1):
         if corpus is not None:
             if not corpus.is_cuda or not corpus.is_contiguous() or corpus.dim() != 2:
                 raise ValueError("corpus must be a contiguous 2-D device tensor")
@@ -118,9 +119,10 @@ class Proximity:
         self.device = device
         self.corpus = corpus          # keeps the borrowed memory alive
         self.dim, self.capacity, self.k, self.policy, self.max_batch = dim, capacity, k, policy, max_batch
+        self.rerank_factor = max(1, int(rerank_factor))
         cfg = ProximityConfig(C.sizeof(ProximityConfig), dim, corpus.data_ptr() if corpus is not None else None,
                               n_docs, dtype, capacity, k, policy, max_batch,
-                              device.index if device.index is not None else 0)
+                              device.index if device.index is not None else 0, int(rerank_factor), 0)
         self.handle = _H()
         rc = lib.proximity_create(C.byref(cfg), C.byref(self.handle))
         if rc != OK:
@@ -165,7 +167,7 @@ class Proximity:
     def cache_dump(self, want_keys: bool = False, want_ids: bool = False):
         seq = np.zeros(max(self.capacity, 1), dtype=np.uint64)
         keys = np.zeros((max(self.capacity, 1), self.dim), dtype=np.float32) if want_keys else None
-        ids = np.zeros((max(self.capacity, 1), self.k), dtype=np.int64) if want_ids else None
+        ids = np.zeros((max(self.capacity, 1), self.k * self.rerank_factor), dtype=np.int64) if want_ids else None
         n_live = C.c_uint32(0)
         rc = lib.proximity_cache_dump(self.handle, seq.ctypes.data_as(C.c_void_p),
                                       keys.ctypes.data_as(C.c_void_p) if want_keys else None,

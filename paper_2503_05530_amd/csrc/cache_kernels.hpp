@@ -12,6 +12,7 @@
 #pragma once
 
 #include "device_utils.hpp"
+#include "select_kernels.hpp"
 
 namespace prox {
 
@@ -285,22 +286,39 @@ __global__ __launch_bounds__(64) void resolver_kernel(
 // After the resolver, before the scan.  One block per batch row.
 //   - a row that missed and still owns its slot at the end of the batch copies
 //     its vector and squared norm into the slot (Algorithm 1, "C[q] <- I", key part);
-//   - a row that hit a key resident since before the batch copies that key's
-//     stored list to its output row now, before any list is overwritten.
+//   - a row that hit a key resident since before the batch answers from that key's
+//     stored list now, before any list is overwritten: the list itself (K == k), or
+//     with a re-ranking factor above 1 (K = rho * k stored per key, Section 3.3.4) the
+//     k stored documents nearest to the row's own query.
+// X / corpus_dtype: the corpus, read only for re-ranking.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void post_resolve_kernel(
-    int n, int c, int dim, int k, long long base_seq, float* srcs, float* srcnrm,
+    int n, int c, int dim, int k, int K, long long base_seq, float* srcs, float* srcnrm,
     const long long* __restrict__ slot_seq, const uint8_t* __restrict__ hit, const int* __restrict__ src,
     const int* __restrict__ row_slot, const int64_t* __restrict__ val_ids, const float* __restrict__ val_d,
-    int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
+    const void* __restrict__ X, int corpus_dtype, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   const int i = blockIdx.x;
   if (i >= n) return;
   if (hit[i]) {
     const int s = src[i];
     if (s < c) {
-      for (int e = threadIdx.x; e < k; e += blockDim.x) {
-        out_ids[long(i) * k + e] = val_ids[long(s) * k + e];
-        if (out_d) out_d[long(i) * k + e] = val_d[long(s) * k + e];
+      if (K == k || X == nullptr) {  // nothing to re-rank, or no corpus (every stored id is padding)
+        for (int e = threadIdx.x; e < k; e += blockDim.x) {
+          out_ids[long(i) * k + e] = val_ids[long(s) * K + e];
+          if (out_d) out_d[long(i) * k + e] = val_d[long(s) * K + e];
+        }
+      } else {
+        __shared__ uint64_t keys[256];
+        __shared__ double d64[256];
+        __shared__ int cid[256];
+        const float* q = srcs + long(c + i) * dim;
+        float* od = out_d ? out_d + long(i) * k : nullptr;
+        if (corpus_dtype == kDtypeBF16)
+          block_rerank_stored<kDtypeBF16>(val_ids + long(s) * K, K, k, q, X, dim, out_ids + long(i) * k, od, keys, d64,
+                                          cid, threadIdx.x);
+        else
+          block_rerank_stored<kDtypeF32>(val_ids + long(s) * K, K, k, q, X, dim, out_ids + long(i) * k, od, keys, d64,
+                                         cid, threadIdx.x);
       }
     }
   } else {
@@ -318,38 +336,58 @@ __global__ __launch_bounds__(256) void post_resolve_kernel(
 // After the scan.  One block per batch row.
 //   - a row that missed returns its scan result, and stores it as its key's
 //     value if the key is still resident (Algorithm 1, "C[q] <- I", value part);
-//   - a row that hit an earlier row of the same batch returns that row's result.
+//   - a row that hit an earlier row of the same batch answers from that row's result.
+// A scan result has K entries (K = rho * k with a re-ranking factor rho, Section 3.3.4): the
+// row that missed returns the first k and stores all K; a hit returns the stored list itself
+// when K == k, else the k stored documents nearest to its own query (batch_rows[i]).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, long long base_seq,
+__global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, int K, long long base_seq,
                                                        const long long* __restrict__ slot_seq,
                                                        const uint8_t* __restrict__ hit,
                                                        const int* __restrict__ src,
                                                        const int* __restrict__ row_slot,
                                                        const int64_t* __restrict__ res_ids,
                                                        const float* __restrict__ res_d, int64_t* val_ids,
-                                                       float* val_d, int64_t* __restrict__ out_ids,
-                                                       float* __restrict__ out_d) {
+                                                       float* val_d, const float* __restrict__ batch_rows, int dim,
+                                                       const void* __restrict__ X, int corpus_dtype,
+                                                       int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   const int i = blockIdx.x;
   if (i >= n) return;
-  int from;
-  bool store = false;
-  int t = -1;
   if (hit[i]) {
     if (src[i] < c) return;
-    from = src[i] - c;
-  } else {
-    from = i;
-    t = row_slot[i];
-    store = t >= 0 && slot_seq[t] == base_seq + i;
+    const int from = src[i] - c;
+    if (K == k || X == nullptr) {  // nothing to re-rank, or no corpus (every stored id is padding)
+      for (int e = threadIdx.x; e < k; e += blockDim.x) {
+        out_ids[long(i) * k + e] = res_ids[long(from) * K + e];
+        if (out_d) out_d[long(i) * k + e] = res_d[long(from) * K + e];
+      }
+    } else {
+      __shared__ uint64_t keys[256];
+      __shared__ double d64[256];
+      __shared__ int cid[256];
+      const float* q = batch_rows + long(i) * dim;
+      float* od = out_d ? out_d + long(i) * k : nullptr;
+      if (corpus_dtype == kDtypeBF16)
+        block_rerank_stored<kDtypeBF16>(res_ids + long(from) * K, K, k, q, X, dim, out_ids + long(i) * k, od, keys, d64,
+                                        cid, threadIdx.x);
+      else
+        block_rerank_stored<kDtypeF32>(res_ids + long(from) * K, K, k, q, X, dim, out_ids + long(i) * k, od, keys, d64,
+                                       cid, threadIdx.x);
+    }
+    return;
   }
-  for (int e = threadIdx.x; e < k; e += blockDim.x) {
-    const int64_t id = res_ids[long(from) * k + e];
-    const float d = res_d[long(from) * k + e];
-    out_ids[long(i) * k + e] = id;
-    if (out_d) out_d[long(i) * k + e] = d;
+  const int t = row_slot[i];
+  const bool store = t >= 0 && slot_seq[t] == base_seq + i;
+  for (int e = threadIdx.x; e < K; e += blockDim.x) {
+    const int64_t id = res_ids[long(i) * K + e];
+    const float d = res_d[long(i) * K + e];
+    if (e < k) {
+      out_ids[long(i) * k + e] = id;
+      if (out_d) out_d[long(i) * k + e] = d;
+    }
     if (store) {
-      val_ids[long(t) * k + e] = id;
-      val_d[long(t) * k + e] = d;
+      val_ids[long(t) * K + e] = id;
+      val_d[long(t) * K + e] = d;
     }
   }
 }

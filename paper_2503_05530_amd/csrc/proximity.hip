@@ -46,7 +46,7 @@ static_assert(kResolverLdsMax + kResolverStaticLds <= 160 * 1024 - 256, "the res
 constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32 tiles use the split-column kernel
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
-static_assert(sizeof(proximity_config) == 48, "proximity_config layout is part of the ABI");
+static_assert(sizeof(proximity_config) == 56, "proximity_config layout is part of the ABI");
 static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is part of the ABI");
 static_assert(sizeof(proximity_launch_t) == 16, "proximity_launch_t layout is part of the ABI");
 
@@ -68,6 +68,7 @@ struct DeviceGuard {
 
 struct proximity {
   proximity_config cfg{};
+  int K = 0;  // neighbours asked of the index and stored per key: rerank_factor * k (Section 3.3.4)
   int n_cu = 256;
   uint64_t next_seq = 0;
   hipStream_t last_stream = nullptr;
@@ -284,10 +285,10 @@ int enqueue_merge_levels(proximity* h, int cur, long len, int kp, const int* m_c
 
 // The index search for the queries listed in qlist (or rows 0..m_limit-1 of
 // Qbase when qlist is null): scores, hierarchical top-k, float64 ranking.
-// Results land in row qlist[m] (or m) of res_ids / res_d.
-int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
+// Results (k entries per query, k <= the instance's K) land in row qlist[m] (or m) of res_ids / res_d.
+int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit, int k,
                  int64_t* res_ids, float* res_d, const SmallRouting* small_routing, hipStream_t s) {
-  const int k = int(h->cfg.k), dim = int(h->cfg.dim);
+  const int dim = int(h->cfg.dim);
   const long N = long(h->cfg.n_docs);
   if (N == 0) {
     fill_empty_results_kernel<<<dim3(m_limit), dim3(64), 0, s>>>(qlist, m_count_ptr, m_limit, k, res_ids, res_d);
@@ -401,6 +402,11 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
                 PROXIMITY_MAX_DIM);
   if (cfg->k == 0 || cfg->k > PROXIMITY_MAX_K)
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "k=%u must be in 1..%u", cfg->k, PROXIMITY_MAX_K);
+  const uint32_t rho = cfg->rerank_factor == 0 ? 1u : cfg->rerank_factor;
+  if (rho > PROXIMITY_MAX_K || rho * cfg->k > PROXIMITY_MAX_K)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "rerank_factor * k = %u * %u exceeds %u", rho, cfg->k,
+                PROXIMITY_MAX_K);
+  if (cfg->reserved != 0) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "reserved must be 0");
   if (cfg->max_batch == 0 || cfg->max_batch > PROXIMITY_MAX_BATCH)
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "max_batch=%u must be in 1..%u", cfg->max_batch,
                 PROXIMITY_MAX_BATCH);
@@ -422,6 +428,8 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   proximity* h = new (std::nothrow) proximity();
   if (!h) return fail(nullptr, PROXIMITY_ERR_OOM, "host allocation failed");
   h->cfg = *cfg;
+  h->cfg.rerank_factor = rho;
+  h->K = int(rho * cfg->k);
   DeviceGuard guard(cfg->device);
   auto bail = [&](int code) {
     g_create_error = h->err;
@@ -437,8 +445,8 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   if (hipGetDeviceProperties(&prop, cfg->device) == hipSuccess && prop.multiProcessorCount > 0)
     h->n_cu = prop.multiProcessorCount;
 
-  const size_t c = cfg->capacity, B = cfg->max_batch, d = cfg->dim, k = cfg->k, N = cfg->n_docs;
-  const int kp = int(k) + kSlack;
+  const size_t c = cfg->capacity, B = cfg->max_batch, d = cfg->dim, k = size_t(h->K), N = cfg->n_docs;
+  const int kp = int(k) + kSlack;  // sized for the K = rerank_factor * k neighbours a search call asks for
   int rc;
 #define TRY_ALLOC(ptr, count, zero)                              \
   if ((rc = dev_alloc(h, &(ptr), (count), (zero))) != PROXIMITY_OK) return bail(rc)
@@ -526,7 +534,7 @@ int proximity_knn_batch(proximity_t* h, const float* queries, uint32_t n, uint32
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   h->last_stream = s;
   SmallRouting no_cache{};
-  rc = enqueue_scan(h, queries, nullptr, nullptr, int(n), out_ids, out_dists ? out_dists : h->res_d,
+  rc = enqueue_scan(h, queries, nullptr, nullptr, int(n), int(k), out_ids, out_dists ? out_dists : h->res_d,
                     int(n) <= kSmallRows ? &no_cache : nullptr, s);
   if (h->prof_on) ++h->prof_call;
   if (rc != PROXIMITY_OK) return rc;
@@ -548,7 +556,8 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   const long long base_seq = (long long)h->next_seq;
   float* batch_rows = h->srcs + size_t(c) * dim;
 
-  if (nn <= kSmallRows && h->cfg.n_docs > 0) {
+  const int K = h->K;
+  if (nn <= kSmallRows && h->cfg.n_docs > 0 && K == kk) {
     // A handful of rows: five launches in all.  Cache side (probe in float64; then resolver, key
     // insertion, hits on resident keys), streaming scan for the rows that missed, and
     // selection; then merge + float64 ranking + routing.  The rows are read from the caller's buffer.
@@ -560,7 +569,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
           phase, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
     }
     const SmallRouting rt{out_hit, h->src, h->row_slot, h->slot_seq, h->val_ids, h->val_d, base_seq, nn, c};
-    rc = enqueue_scan(h, queries, h->miss_list, h->miss_count, nn, out_ids, out_dists, &rt, s);
+    rc = enqueue_scan(h, queries, h->miss_list, h->miss_count, nn, kk, out_ids, out_dists, &rt, s);
     if (rc != PROXIMITY_OK) return rc;
     h->next_seq += n;
     if (h->prof_on) ++h->prof_call;
@@ -602,13 +611,16 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
                                                  h->D32, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot,
                                                  h->miss_list, h->miss_count);
   }
-  post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, base_seq, h->srcs, h->srcnrm, h->slot_seq,
-                                                     out_hit, h->src, h->row_slot, h->val_ids, h->val_d, out_ids,
-                                                     out_dists);
-  rc = enqueue_scan(h, batch_rows, h->miss_list, h->miss_count, nn, h->res_ids, h->res_d, nullptr, s);
+  const void* X = h->cfg.n_docs > 0 ? h->cfg.corpus : nullptr;
+  const int xdt = int(h->cfg.corpus_dtype);
+  post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, K, base_seq, h->srcs, h->srcnrm, h->slot_seq,
+                                                     out_hit, h->src, h->row_slot, h->val_ids, h->val_d, X, xdt,
+                                                     out_ids, out_dists);
+  rc = enqueue_scan(h, batch_rows, h->miss_list, h->miss_count, nn, K, h->res_ids, h->res_d, nullptr, s);
   if (rc != PROXIMITY_OK) return rc;
-  finalize_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, kk, base_seq, h->slot_seq, out_hit, h->src, h->row_slot,
-                                                 h->res_ids, h->res_d, h->val_ids, h->val_d, out_ids, out_dists);
+  finalize_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, kk, K, base_seq, h->slot_seq, out_hit, h->src, h->row_slot,
+                                                 h->res_ids, h->res_d, h->val_ids, h->val_d, batch_rows, dim, X, xdt,
+                                                 out_ids, out_dists);
   h->next_seq += n;
   if (h->prof_on) ++h->prof_call;
   return check_launch(h, "proximity_search_batch");
@@ -638,7 +650,7 @@ int proximity_cache_dump(const proximity_t* h, uint64_t* seq, float* keys, int64
   proximity* hh = const_cast<proximity*>(h);
   DeviceGuard guard(h->cfg.device);
   HIP_TRY(hh, hipStreamSynchronize(h->last_stream));
-  const size_t c = h->cfg.capacity, d = h->cfg.dim, k = h->cfg.k;
+  const size_t c = h->cfg.capacity, d = h->cfg.dim, k = size_t(h->K);  // K = rerank_factor * k ids per key
   CacheState st;
   HIP_TRY(hh, hipMemcpy(&st, h->state, sizeof st, hipMemcpyDeviceToHost));
   std::vector<long long> sseq(c);

@@ -133,6 +133,50 @@ __device__ __forceinline__ void block_candidate_distances(const uint64_t* keys, 
   }
 }
 
+// Ranks n (distance, id) pairs held in LDS by (distance, id) and writes the first k ids and
+// distances (id INT_MAX stands for "no document": id -1, distance +inf).  out_d may be null.
+__device__ __forceinline__ void block_write_ranked(const double* d64, const int* ids, int n, int k,
+                                                   int64_t* __restrict__ out_ids, float* __restrict__ out_d, int tid,
+                                                   int nthreads) {
+  for (int c = tid; c < n; c += nthreads) {
+    const double d = d64[c];
+    const int id = ids[c];
+    int rank = 0;
+    for (int o = 0; o < n; ++o) {
+      const double od = d64[o];
+      const int oid = ids[o];
+      rank += (od < d || (od == d && oid < id) || (od == d && oid == id && o < c)) ? 1 : 0;
+    }
+    if (rank < k) {
+      out_ids[rank] = id == 0x7fffffff ? -1ll : int64_t(id);
+      if (out_d) out_d[rank] = float(d);
+    }
+  }
+  for (int r = n + tid; r < k; r += nthreads) {  // fewer entries than k: pad
+    out_ids[r] = -1ll;
+    if (out_d) out_d[r] = __uint_as_float(0x7f800000u);
+  }
+}
+
+// The hit side of the re-ranking factor (Section 3.3.4): of the K documents stored with the
+// matched key, the k nearest to the current query q, by float64 direct-difference distance,
+// equal distances by index.  Stored ids below 0 are padding.  One block of 256 threads;
+// keys / d64 / cid are LDS arrays of at least K entries.  Ends with the writes issued, no barrier.
+template <int DT>
+__device__ __forceinline__ void block_rerank_stored(const int64_t* __restrict__ stored, int K, int k,
+                                                    const float* __restrict__ q, const void* __restrict__ X, int dim,
+                                                    int64_t* __restrict__ out_ids, float* __restrict__ out_d,
+                                                    uint64_t* keys, double* d64, int* cid, int tid) {
+  for (int e = tid; e < K; e += 256) {
+    const int64_t id = stored[e];
+    keys[e] = id >= 0 ? pack_key(0.f, uint32_t(id)) : kPadKey;
+  }
+  __syncthreads();
+  block_candidate_distances<DT, 4>(keys, K, q, X, dim, d64, cid, tid);
+  __syncthreads();
+  block_write_ranked(d64, cid, K, k, out_ids, out_d, tid, 256);
+}
+
 // Final ranking in float64.  One block of 16 waves per query: for each of the kp
 // float32 candidates recompute the Euclidean distance to the query in direct-difference
 // form in float64 (one wave per candidate row, rows fetched concurrently), rank the candidates by
@@ -159,20 +203,8 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
 
   block_candidate_distances<DT, kRerankThreads / 64>(cand + long(m) * kp, kp, q, X, dim, d64, ids, threadIdx.x);
   __syncthreads();
-  for (int c = threadIdx.x; c < kp; c += kRerankThreads) {
-    const double d = d64[c];
-    const int id = ids[c];
-    int rank = 0;
-    for (int o = 0; o < kp; ++o) {
-      const double od = d64[o];
-      const int oid = ids[o];
-      rank += (od < d || (od == d && oid < id) || (od == d && oid == id && o < c)) ? 1 : 0;
-    }
-    if (rank < k) {
-      res_ids[long(qrow) * k + rank] = id == 0x7fffffff ? -1ll : int64_t(id);
-      res_dists[long(qrow) * k + rank] = float(d);
-    }
-  }
+  block_write_ranked(d64, ids, kp, k, res_ids + long(qrow) * k, res_dists + long(qrow) * k, threadIdx.x,
+                     kRerankThreads);
 }
 
 // Fills result rows of the listed queries with "no document" (used when the

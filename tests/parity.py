@@ -52,11 +52,13 @@ def assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref_queries, dist_rto
     return excused
 
 
-def assert_stream_parity(gpu, oracle_out, corpus, queries, dist_rtol=DIST_RTOL_F32, what=""):
+def assert_stream_parity(gpu, oracle_out, corpus, queries, dist_rtol=DIST_RTOL_F32, what="", reranked=False):
+    """`reranked`: the instance re-ranks on a hit (re-ranking factor above 1), so every row's
+    distances refer to its own query; otherwise a hit row's distances refer to the matched key."""
     ids, dists, hit = gpu
     o_ids, o_dists, o_hit, o_src = oracle_out
     assert hit.dtype == np.uint8
     mism = np.flatnonzero(hit != o_hit)
     assert len(mism) == 0, f"{what}: hit/miss flags differ first at row {mism[:5]}"
-    ref = np.asarray(queries)[o_src]
+    ref = np.asarray(queries) if reranked else np.asarray(queries)[o_src]
     return assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref, dist_rtol, what)

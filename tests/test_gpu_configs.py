@@ -86,6 +86,44 @@ def test_mid_workload(B, mid, tau, batch):
     px.close()
 
 
+@pytest.mark.parametrize("batch", [1, 64])
+def test_mid_workload_with_reranking(B, mid, batch):
+    """Re-ranking factor 4 (Section 3.3.4) at the mid workload's size: 40 neighbours stored per key."""
+    w, corpus, corpus_dev, q, knn_ids, knn_d, decisions = mid
+    rho, tau = 4, 0.25
+    if "knn" not in _MID_RERANK:
+        _MID_RERANK["knn"] = po.batched_exact_knn(corpus, q[:MID_WINDOW], rho * w.k, chunk_rows=1 << 17)
+    big_ids, big_d = _MID_RERANK["knn"]
+    assert (big_ids[:, :w.k] == knn_ids).all()
+    o_hit, o_src, dec = decisions[tau]
+    px = B.Proximity(corpus_dev, w.dim, w.capacity, w.k, w.policy, 64, rerank_factor=rho)
+    ids, dists, hit = P.run_stream(px, q, tau, batch, DEV)
+    assert (hit == o_hit).all()
+    rows = np.flatnonzero(o_src < MID_WINDOW)
+    want_ids = np.empty((len(rows), w.k), dtype=np.int64)
+    want_d = np.empty((len(rows), w.k))
+    for j, t in enumerate(rows):
+        if o_hit[t]:
+            want_ids[j], want_d[j] = po.rerank_stored(corpus, po.as_f64_rows(q[t]), big_ids[o_src[t]], w.k)
+        else:
+            want_ids[j], want_d[j] = big_ids[t, :w.k], big_d[t, :w.k]
+    assert o_hit[rows].sum() > 500
+    excused = P.assert_lists_match(ids[rows], dists[rows], want_ids, want_d, corpus, q[rows], P.DIST_RTOL_F32,
+                                   f"mid rho=4 batch={batch}")
+    assert excused == 0
+    seq, _, stored = px.cache_dump(want_ids=True)
+    assert seq.tolist() == dec.dump_seq().tolist()
+    early = seq < MID_WINDOW
+    assert (stored[early] == big_ids[seq[early]]).all()
+    st, os_ = px.stats(), dec.stats()
+    for key in ("queries", "hits", "misses", "inserts", "evictions", "size"):
+        assert st[key] == os_[key]
+    px.close()
+
+
+_MID_RERANK = {}
+
+
 def test_mid_any_split_gives_the_same_result(B, mid):
     w, corpus, corpus_dev, q, *_ = mid
     outs = []

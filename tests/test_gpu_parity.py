@@ -207,6 +207,68 @@ def test_cache_too_large_for_on_chip_state(B, policy):
     assert hit[:600].tolist() == o_hit.tolist()
 
 
+# ---------------------------------------------------------------------------
+# Re-ranking factor (Section 3.3.4)
+# ---------------------------------------------------------------------------
+_RERANK_WANT = {}   # oracle outputs per policy, computed once
+
+
+@pytest.mark.parametrize("batch", [1, 7, 64, 256])
+@pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
+def test_tiny_workload_with_reranking(B, tiny, batch, policy):
+    w, corpus, q, _ = tiny
+    rho = 4
+    if policy not in _RERANK_WANT:
+        _RERANK_WANT[policy] = po.lookup_stream_deferred(corpus, q, w.tau, w.capacity, w.k, policy, rerank_factor=rho)
+    o_ids, o_d, o_hit, o_src, dec, stored = _RERANK_WANT[policy]
+    px = B.Proximity(gpu_corpus(corpus), w.dim, w.capacity, w.k, policy, 256, rerank_factor=rho)
+    got = P.run_stream(px, q, w.tau, batch, DEV)
+    excused = P.assert_stream_parity(got, (o_ids, o_d, o_hit, o_src), corpus, q, what=f"rho=4 b{batch}", reranked=True)
+    assert excused == 0
+    seq, _, ids = px.cache_dump(want_ids=True)
+    assert seq.tolist() == dec.dump_seq().tolist()
+    assert ids.shape[1] == rho * w.k and (ids == stored[seq]).all()
+    # the re-ranked answers are not simply the stored lists' heads
+    hit_rows = np.flatnonzero(o_hit == 1)
+    assert (o_ids[hit_rows] != stored[o_src[hit_rows], :w.k]).any()
+    px.close()
+
+
+@pytest.mark.parametrize("batch", [1, 4])
+def test_reranking_hand_worked_line(B, batch):
+    """The line example of the oracle's pins: documents at 0..9, k=2, rho=2, tau=3."""
+    corpus = line_vectors(range(10), dim=32)
+    q = line_vectors([4.4, 5.6, 2.0, 4.5], dim=32)
+    px = B.Proximity(gpu_corpus(corpus), 32, 4, 2, po.POLICY_FIFO, 4, rerank_factor=2)
+    ids, dists, hit = P.run_stream(px, q, 3.0, batch, DEV)
+    assert hit.tolist() == [0, 1, 1, 1]
+    assert ids.tolist() == [[4, 5], [6, 5], [3, 4], [4, 5]]
+    np.testing.assert_allclose(dists, [[0.4, 0.6], [0.4, 0.6], [1.0, 2.0], [0.5, 0.5]], rtol=1e-5)
+    _, _, stored = px.cache_dump(want_ids=True)
+    assert stored.tolist() == [[4, 5, 3, 6]]
+    px.close()
+
+
+def test_reranking_bf16_corpus_and_no_corpus(B):
+    n_docs, dim, k, rho = 20000, 384, 10, 3
+    x32 = W.corpus_f32(n_docs, dim, 9)
+    xb = W.bf16_bits_to_f32(W.f32_to_bf16_bits(x32))
+    base = W.base_queries(40, dim, 3)
+    idx = np.random.default_rng(1).integers(0, 40, size=300)
+    q = W.perturbed_stream(base, idx, 0.05, 3)
+    want = po.lookup_stream_deferred(xb, q, 0.2, 16, k, po.POLICY_LRU, rerank_factor=rho)
+    px = B.Proximity(torch.from_numpy(x32).to(DEV).to(torch.bfloat16), dim, 16, k, po.POLICY_LRU, 64,
+                     rerank_factor=rho)
+    got = P.run_stream(px, q, 0.2, 64, DEV)
+    P.assert_stream_parity(got, want[:4], xb, q, dist_rtol=P.DIST_RTOL_BF16, what="rho=3 bf16", reranked=True)
+    assert want[2].sum() > 100
+    px.close()
+    px = B.Proximity(None, dim, 16, k, po.POLICY_LRU, 64, device=DEV, rerank_factor=rho)
+    ids, dists, hit = P.run_stream(px, q, 0.2, 64, DEV)
+    assert (hit == want[2]).all() and (ids == -1).all() and np.isinf(dists).all()
+    px.close()
+
+
 def test_tau_zero_and_tau_huge(B, tiny):
     w, corpus, q, _ = tiny
     q = q[:200]
