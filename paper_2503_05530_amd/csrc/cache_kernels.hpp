@@ -313,12 +313,8 @@ __global__ __launch_bounds__(256) void post_resolve_kernel(
         __shared__ int cid[256];
         const float* q = srcs + long(c + i) * dim;
         float* od = out_d ? out_d + long(i) * k : nullptr;
-        if (corpus_dtype == kDtypeBF16)
-          block_rerank_stored<kDtypeBF16>(val_ids + long(s) * K, K, k, q, X, dim, out_ids + long(i) * k, od, keys, d64,
-                                          cid, threadIdx.x);
-        else
-          block_rerank_stored<kDtypeF32>(val_ids + long(s) * K, K, k, q, X, dim, out_ids + long(i) * k, od, keys, d64,
-                                         cid, threadIdx.x);
+        block_rerank_stored_any<256>(corpus_dtype, val_ids + long(s) * K, K, k, q, X, dim, out_ids + long(i) * k, od,
+                                     keys, d64, cid, threadIdx.x);
       }
     }
   } else {
@@ -367,12 +363,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, int 
       __shared__ int cid[256];
       const float* q = batch_rows + long(i) * dim;
       float* od = out_d ? out_d + long(i) * k : nullptr;
-      if (corpus_dtype == kDtypeBF16)
-        block_rerank_stored<kDtypeBF16>(res_ids + long(from) * K, K, k, q, X, dim, out_ids + long(i) * k, od, keys, d64,
-                                        cid, threadIdx.x);
-      else
-        block_rerank_stored<kDtypeF32>(res_ids + long(from) * K, K, k, q, X, dim, out_ids + long(i) * k, od, keys, d64,
-                                       cid, threadIdx.x);
+      block_rerank_stored_any<256>(corpus_dtype, res_ids + long(from) * K, K, k, q, X, dim, out_ids + long(i) * k, od,
+                                   keys, d64, cid, threadIdx.x);
     }
     return;
   }
@@ -411,13 +403,17 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, int 
 constexpr int kSmallRows = 4;
 
 __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
-    const float* __restrict__ queries, int n, int c, int dim, int k, int policy_lru, long long base_seq, double tau,
-    CacheState* st, long long* slot_seq, int* slot_next, int* slot_prev, float* srcs, float* srcnrm,
-    const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, double* D64, int phase,
+    const float* __restrict__ queries, int n, int c, int dim, int k, int K, int policy_lru, long long base_seq,
+    double tau, CacheState* st, long long* slot_seq, int* slot_next, int* slot_prev, float* srcs, float* srcnrm,
+    const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, const void* __restrict__ X,
+    int corpus_dtype, double* D64, int phase,
     uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
     int* __restrict__ miss_count, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
   constexpr int NW = 16;
+  __shared__ uint64_t rr_keys[256];  // re-ranking of a stored list
+  __shared__ double rr_d[256];
+  __shared__ int rr_id[256];
   __shared__ double red_d[NW];
   __shared__ long long red_seq[NW];
   __shared__ int red_src[NW];
@@ -545,11 +541,20 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
   for (int i = 0; i < n; ++i) {
     if (hit_out[i]) {
       const int s = src_out[i];
-      if (s < c)
-        for (int e = tid; e < k; e += 1024) {
-          out_ids[long(i) * k + e] = val_ids[long(s) * k + e];
-          if (out_d) out_d[long(i) * k + e] = val_d[long(s) * k + e];
+      if (s < c) {
+        if (K == k) {
+          for (int e = tid; e < k; e += 1024) {
+            out_ids[long(i) * k + e] = val_ids[long(s) * k + e];
+            if (out_d) out_d[long(i) * k + e] = val_d[long(s) * k + e];
+          }
+        } else {
+          // re-ranking factor above 1 (Section 3.3.4): the stored documents nearest to this row's query
+          block_rerank_stored_any<1024>(corpus_dtype, val_ids + long(s) * K, K, k, queries + long(i) * dim, X, dim,
+                                        out_ids + long(i) * k, out_d ? out_d + long(i) * k : nullptr, rr_keys, rr_d,
+                                        rr_id, tid);
+          __syncthreads();  // the LDS arrays serve the next row
         }
+      }
     } else {
       const int t = row_slot[i];
       if (t >= 0 && slot_seq[t] == base_seq + i) {

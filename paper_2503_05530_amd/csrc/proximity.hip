@@ -286,8 +286,10 @@ int enqueue_merge_levels(proximity* h, int cur, long len, int kp, const int* m_c
 // The index search for the queries listed in qlist (or rows 0..m_limit-1 of
 // Qbase when qlist is null): scores, hierarchical top-k, float64 ranking.
 // Results (k entries per query, k <= the instance's K) land in row qlist[m] (or m) of res_ids / res_d.
+// With small_routing (a handful of queries) res_ids / res_d are the caller's rows of k_out <= k entries
+// and the k ranked entries go to the cache; otherwise k_out is not used.
 int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit, int k,
-                 int64_t* res_ids, float* res_d, const SmallRouting* small_routing, hipStream_t s) {
+                 int k_out, int64_t* res_ids, float* res_d, const SmallRouting* small_routing, hipStream_t s) {
   const int dim = int(h->cfg.dim);
   const long N = long(h->cfg.n_docs);
   if (N == 0) {
@@ -316,11 +318,11 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
           const dim3 grid(phase == 2 ? 1 : g1, mq);
           if (bf16)
             select_finish_small_kernel<kDtypeBF16, kSelE><<<grid, dim3(kSelThreads), 0, s>>>(
-                h->S, h->ldS, N, kp, k, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
+                h->S, h->ldS, N, kp, k, k_out, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
                 m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d);
           else
             select_finish_small_kernel<kDtypeF32, kSelE><<<grid, dim3(kSelThreads), 0, s>>>(
-                h->S, h->ldS, N, kp, k, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
+                h->S, h->ldS, N, kp, k, k_out, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
                 m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d);
         }
       } else {
@@ -534,7 +536,7 @@ int proximity_knn_batch(proximity_t* h, const float* queries, uint32_t n, uint32
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   h->last_stream = s;
   SmallRouting no_cache{};
-  rc = enqueue_scan(h, queries, nullptr, nullptr, int(n), int(k), out_ids, out_dists ? out_dists : h->res_d,
+  rc = enqueue_scan(h, queries, nullptr, nullptr, int(n), int(k), int(k), out_ids, out_dists ? out_dists : h->res_d,
                     int(n) <= kSmallRows ? &no_cache : nullptr, s);
   if (h->prof_on) ++h->prof_call;
   if (rc != PROXIMITY_OK) return rc;
@@ -557,19 +559,20 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   float* batch_rows = h->srcs + size_t(c) * dim;
 
   const int K = h->K;
-  if (nn <= kSmallRows && h->cfg.n_docs > 0 && K == kk) {
+  if (nn <= kSmallRows && h->cfg.n_docs > 0) {
     // A handful of rows: five launches in all.  Cache side (probe in float64; then resolver, key
     // insertion, hits on resident keys), streaming scan for the rows that missed, and
     // selection; then merge + float64 ranking + routing.  The rows are read from the caller's buffer.
     const int grid = c > 0 ? ((c + 15) / 16 < h->n_cu ? (c + 15) / 16 : h->n_cu) : 1;
     for (int phase = 1; phase <= 2; ++phase) {
       probe_resolve_small_kernel<<<dim3(phase == 2 ? 1 : grid), dim3(1024), 0, s>>>(
-          queries, nn, c, dim, kk, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state,
-          h->slot_seq, h->slot_next, h->slot_prev, h->srcs, h->srcnrm, h->val_ids, h->val_d, h->D64,
-          phase, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
+          queries, nn, c, dim, kk, K, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state,
+          h->slot_seq, h->slot_next, h->slot_prev, h->srcs, h->srcnrm, h->val_ids, h->val_d, h->cfg.corpus,
+          int(h->cfg.corpus_dtype), h->D64, phase, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids,
+          out_dists);
     }
     const SmallRouting rt{out_hit, h->src, h->row_slot, h->slot_seq, h->val_ids, h->val_d, base_seq, nn, c};
-    rc = enqueue_scan(h, queries, h->miss_list, h->miss_count, nn, kk, out_ids, out_dists, &rt, s);
+    rc = enqueue_scan(h, queries, h->miss_list, h->miss_count, nn, K, kk, out_ids, out_dists, &rt, s);
     if (rc != PROXIMITY_OK) return rc;
     h->next_seq += n;
     if (h->prof_on) ++h->prof_call;
@@ -616,7 +619,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, K, base_seq, h->srcs, h->srcnrm, h->slot_seq,
                                                      out_hit, h->src, h->row_slot, h->val_ids, h->val_d, X, xdt,
                                                      out_ids, out_dists);
-  rc = enqueue_scan(h, batch_rows, h->miss_list, h->miss_count, nn, K, h->res_ids, h->res_d, nullptr, s);
+  rc = enqueue_scan(h, batch_rows, h->miss_list, h->miss_count, nn, K, K, h->res_ids, h->res_d, nullptr, s);
   if (rc != PROXIMITY_OK) return rc;
   finalize_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, kk, K, base_seq, h->slot_seq, out_hit, h->src, h->row_slot,
                                                  h->res_ids, h->res_d, h->val_ids, h->val_d, batch_rows, dim, X, xdt,

@@ -160,21 +160,33 @@ __device__ __forceinline__ void block_write_ranked(const double* d64, const int*
 
 // The hit side of the re-ranking factor (Section 3.3.4): of the K documents stored with the
 // matched key, the k nearest to the current query q, by float64 direct-difference distance,
-// equal distances by index.  Stored ids below 0 are padding.  One block of 256 threads;
+// equal distances by index.  Stored ids below 0 are padding.  One block of NT threads;
 // keys / d64 / cid are LDS arrays of at least K entries.  Ends with the writes issued, no barrier.
-template <int DT>
+template <int DT, int NT>
 __device__ __forceinline__ void block_rerank_stored(const int64_t* __restrict__ stored, int K, int k,
                                                     const float* __restrict__ q, const void* __restrict__ X, int dim,
                                                     int64_t* __restrict__ out_ids, float* __restrict__ out_d,
                                                     uint64_t* keys, double* d64, int* cid, int tid) {
-  for (int e = tid; e < K; e += 256) {
+  for (int e = tid; e < K; e += NT) {
     const int64_t id = stored[e];
     keys[e] = id >= 0 ? pack_key(0.f, uint32_t(id)) : kPadKey;
   }
   __syncthreads();
-  block_candidate_distances<DT, 4>(keys, K, q, X, dim, d64, cid, tid);
+  block_candidate_distances<DT, NT / 64>(keys, K, q, X, dim, d64, cid, tid);
   __syncthreads();
-  block_write_ranked(d64, cid, K, k, out_ids, out_d, tid, 256);
+  block_write_ranked(d64, cid, K, k, out_ids, out_d, tid, NT);
+}
+// the same with the corpus type chosen at run time
+template <int NT>
+__device__ __forceinline__ void block_rerank_stored_any(int corpus_dtype, const int64_t* __restrict__ stored, int K,
+                                                        int k, const float* __restrict__ q,
+                                                        const void* __restrict__ X, int dim,
+                                                        int64_t* __restrict__ out_ids, float* __restrict__ out_d,
+                                                        uint64_t* keys, double* d64, int* cid, int tid) {
+  if (corpus_dtype == kDtypeBF16)
+    block_rerank_stored<kDtypeBF16, NT>(stored, K, k, q, X, dim, out_ids, out_d, keys, d64, cid, tid);
+  else
+    block_rerank_stored<kDtypeF32, NT>(stored, K, k, q, X, dim, out_ids, out_d, keys, d64, cid, tid);
 }
 
 // Final ranking in float64.  One block of 16 waves per query: for each of the kp
@@ -288,8 +300,8 @@ __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ 
 
 template <int DT, int E>
 __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
-    const float* __restrict__ S, long ldS, long len, int kp, int k, uint64_t* __restrict__ lists, int n_seg,
-    int phase, const void* __restrict__ X, int dim, const float* __restrict__ Qbase,
+    const float* __restrict__ S, long ldS, long len, int kp, int k, int k_out, uint64_t* __restrict__ lists,
+    int n_seg, int phase, const void* __restrict__ X, int dim, const float* __restrict__ Qbase,
     const int* __restrict__ qlist, const int* __restrict__ m_count_ptr, int m_limit, int m_begin, SmallRouting rt,
     int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   constexpr int SEG = E * kSelThreads;
@@ -366,10 +378,11 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
   }
   __syncthreads();
 
-  // ---- routing (as finalize_kernel) ----
-  for (int e = tid; e < k; e += kSelThreads) {
-    out_ids[long(qrow) * k + e] = fin_ids[e];
-    if (out_d) out_d[long(qrow) * k + e] = fin_d[e];
+  // ---- routing (as finalize_kernel): k ranked entries are this query's result; the caller gets
+  // the first k_out, the cache slot all k (k > k_out with a re-ranking factor, Section 3.3.4) ----
+  for (int e = tid; e < k_out; e += kSelThreads) {
+    out_ids[long(qrow) * k_out + e] = fin_ids[e];
+    if (out_d) out_d[long(qrow) * k_out + e] = fin_d[e];
   }
   if (rt.hit) {
     const int t = rt.row_slot[qrow];
@@ -379,11 +392,20 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
         rt.val_d[long(t) * k + e] = fin_d[e];
       }
     for (int i = qrow + 1; i < rt.n; ++i)
-      if (rt.hit[i] && rt.src[i] == rt.c + qrow)
-        for (int e = tid; e < k; e += kSelThreads) {
-          out_ids[long(i) * k + e] = fin_ids[e];
-          if (out_d) out_d[long(i) * k + e] = fin_d[e];
+      if (rt.hit[i] && rt.src[i] == rt.c + qrow) {
+        if (k == k_out) {
+          for (int e = tid; e < k; e += kSelThreads) {
+            out_ids[long(i) * k + e] = fin_ids[e];
+            if (out_d) out_d[long(i) * k + e] = fin_d[e];
+          }
+        } else {
+          // a later row of the call hit this one: the stored documents nearest to that row's query
+          __syncthreads();
+          block_rerank_stored<DT, kSelThreads>(fin_ids, k, k_out, Qbase + long(i) * dim, X, dim,
+                                               out_ids + long(i) * k_out, out_d ? out_d + long(i) * k_out : nullptr,
+                                               list, d64, cid, tid);
         }
+      }
   }
 }
 
