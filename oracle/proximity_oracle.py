@@ -19,6 +19,11 @@ What it follows
 * Eviction follows Section 3.3.2: FIFO removes the oldest inserted entry
   whatever its use; LRU removes the entry unused for longest, where a hit
   uses the matched entry and an insertion uses the new one.
+* ``LshCacheOracle`` is the bucketed variant of Section 3.2: ``lsh_bucket`` turns
+  the signs of the query's inner products with L given hyperplane normals into
+  an L-bit code, the code names a bucket, and each bucket is a cache of the
+  kind above (capacity b, its own FIFO/LRU order) that sees only the queries
+  with its code.  The normals are an input: the oracle draws nothing.
 * ``rerank_factor`` is the re-ranking factor rho of Section 3.3.4: the database
   call asks for rho * k neighbours, all of them are stored with the key, a miss
   hands the first k to the caller, and a hit orders the stored rho * k documents
@@ -32,7 +37,9 @@ nothing and returns the stored list unchanged (re-ranking factor 1); ranked
 lists order equal distances by document index and are padded with -1 / +inf
 when the index holds fewer than k vectors; capacity 0 disables caching; with
 rho > 1 a hit ranks by (distance to the current query, document index) and
-reports those distances, and rho is a whole number.
+reports those distances, and rho is a whole number; an inner product of
+exactly zero gives hash bit 1 (the paper's ">= 0"), bit i of the code has
+weight 2^i, and L = 0 means a single bucket.
 
 Parity status: every function here is pinned by tests that do not re-use its
 own formula (hand-worked eviction streams, reduction to textbook exact-match
@@ -134,16 +141,19 @@ class FlatCacheOracle:
         self.n_scans = 0
 
     # -- Algorithm 1 -------------------------------------------------------
-    def lookup(self, q, tau: float):
+    def lookup(self, q, tau: float, seq: Optional[int] = None):
         """Process one query.  Returns (ids, dists, hit, source_seq).
 
         ``source_seq`` is the stream position of the query whose database
         result is returned: the query itself on a miss, the matched key's
-        inserting query on a hit.
+        inserting query on a hit.  ``seq`` is this query's stream position when
+        the cache sees only part of a stream (a bucket of ``LshCacheOracle``);
+        by default the number of queries this cache has processed.
         """
         q64 = as_f64_rows(q).copy()
         tau = float(tau)
-        seq = self.n_queries
+        if seq is None:
+            seq = self.n_queries
         self.n_queries += 1
 
         best = -1
@@ -209,6 +219,81 @@ class FlatCacheOracle:
 
 
 # ---------------------------------------------------------------------------
+# Section 3.2: the bucketed variant.
+# ---------------------------------------------------------------------------
+
+def lsh_bucket(q, planes) -> int:
+    """The L-bit code of q read as an integer: bit i is 1 exactly when q . r_i >= 0, r_i = planes[i]."""
+    planes = np.asarray(planes, dtype=np.float64)
+    if planes.size == 0:
+        return 0
+    dots = planes.reshape(-1, len(q)) @ as_f64_rows(q)
+    return int(sum(1 << i for i, v in enumerate(dots) if v >= 0.0))
+
+
+class LshCacheOracle:
+    """One cache of capacity ``bucket_capacity`` per hash code; a query is looked up, and on a miss
+    stored, only in the bucket its code names, and each bucket evicts on its own (Section 3.2).
+
+    Same call surface as ``FlatCacheOracle``.  ``dump_*`` list the buckets in ascending code, each in its
+    own eviction order (next victim first).
+    """
+
+    def __init__(self, corpus: Optional[np.ndarray], planes, bucket_capacity: int, k: int, policy: int,
+                 retrieve: Optional[Callable] = None, rerank_factor: int = 1):
+        self.corpus, self.planes = corpus, np.asarray(planes, dtype=np.float64)
+        self.bucket_capacity, self.k, self.policy, self.rho = int(bucket_capacity), int(k), int(policy), int(rerank_factor)
+        self.k_store = self.rho * self.k
+        self.retrieve = retrieve
+        self.buckets = {}
+        self.n_queries = 0
+
+    def _bucket(self, code: int) -> FlatCacheOracle:
+        if code not in self.buckets:
+            self.buckets[code] = FlatCacheOracle(self.corpus, self.bucket_capacity, self.k, self.policy,
+                                                 retrieve=self.retrieve, rerank_factor=self.rho)
+        return self.buckets[code]
+
+    def lookup(self, q, tau: float):
+        seq = self.n_queries
+        self.n_queries += 1
+        cache = self._bucket(lsh_bucket(as_f64_rows(q), self.planes))
+        if self.retrieve is not None:
+            cache.retrieve = self.retrieve            # the caller may swap the database call between queries
+        return cache.lookup(q, tau, seq=seq)
+
+    def lookup_stream(self, queries, tau: float):
+        n = len(queries)
+        ids = np.empty((n, self.k), dtype=np.int64)
+        dists = np.empty((n, self.k), dtype=np.float64)
+        hit = np.zeros(n, dtype=np.uint8)
+        src = np.empty(n, dtype=np.int64)
+        for t in range(n):
+            ids[t], dists[t], h, src[t] = self.lookup(queries[t], tau)
+            hit[t] = 1 if h else 0
+        return ids, dists, hit, src
+
+    def dump_seq(self) -> np.ndarray:
+        parts = [self.buckets[c].dump_seq() for c in sorted(self.buckets)]
+        return np.concatenate(parts) if parts else np.zeros(0, dtype=np.int64)
+
+    def dump_ids(self) -> np.ndarray:
+        parts = [self.buckets[c].dump_ids() for c in sorted(self.buckets) if self.buckets[c].entries]
+        return np.concatenate(parts) if parts else np.zeros((0, self.k_store), dtype=np.int64)
+
+    def stats(self) -> dict:
+        total = dict(queries=0, hits=0, misses=0, inserts=0, evictions=0, scans=0, size=0)
+        for cache in self.buckets.values():
+            for key, v in cache.stats().items():
+                total[key] += v
+        return total
+
+    @property
+    def n_evictions(self) -> int:
+        return self.stats()["evictions"]
+
+
+# ---------------------------------------------------------------------------
 # Deferred-scan form, for streams whose literal replay would take hours.
 #
 # The branch of Algorithm 1 reads only distances between the query and cached
@@ -219,9 +304,13 @@ class FlatCacheOracle:
 # ---------------------------------------------------------------------------
 
 def simulate_decisions(queries, tau: float, capacity: int, policy: int,
-                       oracle: Optional[FlatCacheOracle] = None):
-    """Replay Algorithm 1's control flow only.  Returns (hit[n], source_seq[n], oracle)."""
+                       oracle: Optional[FlatCacheOracle] = None, planes=None):
+    """Replay Algorithm 1's control flow only.  Returns (hit[n], source_seq[n], oracle).
+    With ``planes`` the cache is the bucketed one and ``capacity`` is per bucket."""
     k_dummy = 1
+    no_db = lambda q: (np.full(k_dummy, -1, np.int64), np.full(k_dummy, np.inf))
+    if oracle is None and planes is not None:
+        oracle = LshCacheOracle(None, planes, capacity, k_dummy, policy, retrieve=no_db)
     if oracle is None:
         oracle = FlatCacheOracle(None, capacity, k_dummy, policy,
                                  retrieve=lambda q: (np.full(k_dummy, -1, np.int64),
@@ -270,14 +359,14 @@ def batched_exact_knn(corpus: np.ndarray, queries: np.ndarray, k: int,
 
 
 def lookup_stream_deferred(corpus, queries, tau: float, capacity: int, k: int, policy: int,
-                           knn_chunk: int = 256, rerank_factor: int = 1):
+                           knn_chunk: int = 256, rerank_factor: int = 1, planes=None):
     """Outputs of ``FlatCacheOracle.lookup_stream`` computed decisions-first.
 
     Returns ids[n,k], dists[n,k], hit[n], source_seq[n], decision_oracle; with
     ``rerank_factor`` > 1 a sixth item, stored_ids[n, rerank_factor*k]: what each query that
     missed stored with its key.
     """
-    hit, src, dec = simulate_decisions(queries, tau, capacity, policy)
+    hit, src, dec = simulate_decisions(queries, tau, capacity, policy, planes=planes)
     n = len(queries)
     k_store = int(rerank_factor) * k
     miss_rows = np.flatnonzero(hit == 0)

@@ -29,6 +29,7 @@ TAG_BASES = 1
 TAG_CHOICE = 2
 TAG_PERTURB = 3
 TAG_PROBE_MIX = 4
+TAG_LSH_PLANES = 5
 
 POLICY_FIFO = 0
 POLICY_LRU = 1
@@ -163,6 +164,12 @@ def corpus_for(w: Workload, n_docs: Optional[int] = None) -> np.ndarray:
     rows are not re-normalised after rounding.
     """
     return corpus_f32(w.n_docs if n_docs is None else int(n_docs), w.dim, w.seed)
+
+
+def lsh_planes(n_bits: int, dim: int, seed: int) -> np.ndarray:
+    """Normals of ``n_bits`` random hyperplanes through the origin (standard Gaussian), float32 [n_bits][dim].
+    They are an input of the bucketed cache, handed to the oracle and to the library alike."""
+    return _rng(seed, TAG_LSH_PLANES).standard_normal((n_bits, dim)).astype(np.float32)
 
 
 def probe_warm_keys(n_keys: int, dim: int, seed: int) -> np.ndarray:

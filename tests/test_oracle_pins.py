@@ -361,6 +361,106 @@ def test_rerank_deferred_form_equals_literal_form():
 
 
 # ---------------------------------------------------------------------------
+# Bucketed variant (Section 3.2)
+# ---------------------------------------------------------------------------
+def test_lsh_code_by_hand_and_by_loops():
+    planes = np.zeros((2, 4), dtype=np.float32)
+    planes[0, 0] = 1.0                       # bit 0: first coordinate >= 0
+    planes[1, 1] = 1.0                       # bit 1: second coordinate >= 0
+    for vec, code in (((1, 1), 3), ((-1, 1), 2), ((1, -1), 1), ((-1, -1), 0), ((0, -1), 1), ((-2, 0), 2)):
+        q = np.zeros(4, dtype=np.float32)
+        q[:2] = vec
+        assert po.lsh_bucket(q, planes) == code
+    rng = np.random.default_rng(3)
+    planes = W.lsh_planes(7, 16, 1)
+    for q in rng.standard_normal((50, 16)).astype(np.float32):
+        code = 0
+        for i in range(7):
+            s = 0.0
+            for a, b in zip(q.tolist(), planes[i].tolist()):
+                s += a * b
+            if s >= 0:
+                code += 2 ** i
+        assert po.lsh_bucket(q, planes) == code
+    assert po.lsh_bucket(rng.standard_normal(16), np.zeros((0, 16))) == 0
+
+
+def test_lsh_hand_worked_buckets_are_isolated():
+    """One hyperplane (sign of the first coordinate), one entry per bucket, tau = 1.5.
+    0.5 M (bucket +); -0.5 M (1.0 from 0.5, but the other bucket); 0.6 H; -10 M evicts -0.5 in bucket -;
+    -0.6 M (its bucket now holds only -10) evicts -10; 0.4 H (bucket + was never disturbed).
+    A single flat cache of the same total size would have hit on the second query."""
+    planes = np.zeros((1, 4), dtype=np.float32)
+    planes[0, 0] = 1.0
+    xs = [0.5, -0.5, 0.6, -10.0, -0.6, 0.4]
+    q = line_vectors(xs)
+    corpus = line_vectors(range(-10, 10))
+    orc = po.LshCacheOracle(corpus, planes, 1, 2, po.POLICY_FIFO)
+    ids, _, hit, src = orc.lookup_stream(q, 1.5)
+    assert "".join("H" if h else "M" for h in hit) == "MMHMMH"
+    assert src.tolist() == [0, 1, 0, 3, 4, 0]
+    assert orc.stats()["evictions"] == 2 and orc.dump_seq().tolist() == [4, 0]   # bucket 0 (negative side) first
+    assert ids[2].tolist() == ids[0].tolist() == [10, 11]                         # documents 0 and 1 sit at rows 10, 11
+    flat = po.FlatCacheOracle(corpus, 2, 2, po.POLICY_FIFO)
+    assert flat.lookup_stream(q, 1.5)[2].tolist()[:2] == [0, 1]
+
+
+def test_lsh_without_hyperplanes_is_the_flat_cache():
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(1500, w.dim, w.seed)
+    q = W.stream_for(w, 300)
+    for policy in (po.POLICY_FIFO, po.POLICY_LRU):
+        a = po.FlatCacheOracle(corpus, 12, 5, policy).lookup_stream(q, 0.25)
+        lsh = po.LshCacheOracle(corpus, np.zeros((0, w.dim)), 12, 5, policy)
+        b = lsh.lookup_stream(q, 0.25)
+        for x, y in zip(a, b):
+            assert (x == y).all()
+
+
+@pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
+def test_lsh_equals_one_flat_cache_per_code(policy):
+    """Splitting the stream by hash code beforehand and giving each part to its own flat cache is the same thing."""
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(1200, w.dim, w.seed)
+    q = W.stream_for(w, 400)
+    planes = W.lsh_planes(3, w.dim, 0)
+    codes = ((q.astype(np.float64) @ planes.astype(np.float64).T) >= 0).astype(np.int64) @ (1 << np.arange(3))
+    lsh = po.LshCacheOracle(corpus, planes, 4, 5, policy)
+    ids, dists, hit, src = lsh.lookup_stream(q, 0.25)
+    assert len(set(codes.tolist())) > 3 and 30 < hit.sum() < 390
+    for code in sorted(set(codes.tolist())):
+        rows = np.flatnonzero(codes == code)
+        f_ids, f_d, f_hit, f_src = po.FlatCacheOracle(corpus, 4, 5, policy).lookup_stream(q[rows], 0.25)
+        assert (hit[rows] == f_hit).all() and (ids[rows] == f_ids).all()
+        assert (src[rows] == rows[f_src]).all()                 # positions within the part map back to the stream
+
+
+@pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
+def test_lsh_zero_tolerance_is_a_set_associative_cache(policy):
+    """tau = 0: a textbook b-way set-associative cache keyed by vector identity, set = hash code."""
+    rng = np.random.default_rng(8)
+    vecs = rng.standard_normal((60, 8)).astype(np.float32)
+    planes = W.lsh_planes(2, 8, 4)
+    which = rng.integers(0, 60, size=500)
+    sets = {}
+    want = []
+    for key in which.tolist():
+        code = po.lsh_bucket(vecs[key], planes)
+        way = sets.setdefault(code, collections.OrderedDict())
+        if key in way:
+            want.append(1)
+            if policy == po.POLICY_LRU:
+                way.move_to_end(key)
+        else:
+            want.append(0)
+            if len(way) >= 3:
+                way.popitem(last=False)
+            way[key] = True
+    hit, _, _ = po.simulate_decisions(vecs[which], 0.0, 3, policy, planes=planes)
+    assert hit.tolist() == want and 50 < sum(want) < 450
+
+
+# ---------------------------------------------------------------------------
 # Input generators (recipe checks, not method arithmetic)
 # ---------------------------------------------------------------------------
 def test_generator_recipe_is_stable():
