@@ -87,7 +87,16 @@ typedef struct proximity_config {
                              returns the k of the stored rho * k documents nearest to the
                              current query, ranked by (distance, index), with those
                              distances.  1: a hit returns the stored list unchanged        */
-  uint32_t reserved;      /* must be 0                                                        */
+  uint32_t lsh_bits;      /* L of Section 3.2.  0: one flat cache of `capacity` entries.  1..16: the
+                             bucketed cache: 2^L buckets, each a cache of `capacity` entries
+                             (b in the paper) with its own FIFO/LRU order; a query is looked
+                             up and stored only in the bucket named by its L-bit code.
+                             capacity << lsh_bits must not exceed PROXIMITY_MAX_CAPACITY and
+                             capacity must be 1..256 then                                    */
+  const float* lsh_planes;/* DEVICE [lsh_bits][dim] float32: normals of the L hyperplanes through
+                             the origin; bit i of a query's code is 1 exactly when its inner
+                             product with row i is >= 0 (evaluated in float64).  Copied at
+                             creation; NULL when lsh_bits is 0                               */
 } proximity_config;
 
 /* Counters since creation or the last proximity_clear(). */
@@ -124,8 +133,8 @@ uint32_t proximity_abi_version(void);
  * (capacity x dim float32 keys, capacity x rerank_factor*k values) and all
  * workspaces, sized for max_batch.  *out receives the handle.  Blocks until the norms are done.
  * Errors: INVALID_ARG (null, bad struct_size, dim/k/max_batch/capacity/n_docs/
- * rerank_factor*k outside the limits, unknown dtype/policy, reserved not 0,
- * corpus null with n_docs > 0), OOM,
+ * rerank_factor*k/lsh_bits outside the limits, unknown dtype/policy, lsh_planes
+ * null with lsh_bits > 0, corpus null with n_docs > 0), OOM,
  * HIP.  On error *out is set to NULL.
  */
 int proximity_create(const proximity_config* cfg, proximity_t** out);
@@ -173,9 +182,11 @@ int proximity_stats(const proximity_t* h, proximity_stats_t* out);
 
 /*
  * Copies the cache contents to HOST arrays in eviction order (next victim
- * first).  seq[i] is the position, counted from creation or the last clear, of
+ * first; the bucketed cache: bucket by bucket in ascending code, each bucket
+ * in its own eviction order).  seq[i] is the position, counted from creation or the last clear, of
  * the query that inserted entry i.  keys ([capacity][dim] float32) and ids
- * ([capacity][rerank_factor * k] int64) may be NULL.  *n_live receives the number of entries
+ * ([capacity][rerank_factor * k] int64; capacity << lsh_bits rows for the
+ * bucketed cache) may be NULL.  *n_live receives the number of entries
  * written.  Waits for the handle's last stream.
  */
 int proximity_cache_dump(const proximity_t* h, uint64_t* seq, float* keys, int64_t* ids,

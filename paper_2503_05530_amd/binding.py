@@ -27,7 +27,7 @@ class ProximityConfig(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("dim", C.c_uint32), ("corpus", C.c_void_p),
                 ("n_docs", C.c_uint64), ("corpus_dtype", C.c_uint32), ("capacity", C.c_uint32),
                 ("k", C.c_uint32), ("policy", C.c_uint32), ("max_batch", C.c_uint32), ("device", C.c_int32),
-                ("rerank_factor", C.c_uint32), ("reserved", C.c_uint32)]
+                ("rerank_factor", C.c_uint32), ("lsh_bits", C.c_uint32), ("lsh_planes", C.c_void_p)]
 
 
 class ProximityStats(C.Structure):
@@ -99,7 +99,10 @@ class Proximity:
     """One cache-plus-index instance.  Method names follow the C entry points."""
 
     def __init__(self, corpus: Optional[torch.Tensor], dim: int, capacity: int, k: int, policy: int,
-                 max_batch: int, device: Optional[torch.device] = None, rerank_factor: int = 1):
+                 max_batch: int, device: Optional[torch.device] = None, rerank_factor: int = 1,
+                 lsh_planes: Optional[torch.Tensor] = None):
+        """``lsh_planes`` (device float32 [L][dim]) selects the bucketed cache of Section 3.2: 2^L buckets of
+        ``capacity`` entries each."""
         if corpus is not None:
             if not corpus.is_cuda or not corpus.is_contiguous() or corpus.dim() != 2:
                 raise ValueError("corpus must be a contiguous 2-D device tensor")
@@ -120,9 +123,17 @@ class Proximity:
         self.corpus = corpus          # keeps the borrowed memory alive
         self.dim, self.capacity, self.k, self.policy, self.max_batch = dim, capacity, k, policy, max_batch
         self.rerank_factor = max(1, int(rerank_factor))
+        self.lsh_bits = 0
+        if lsh_planes is not None and lsh_planes.shape[0] > 0:
+            if (not lsh_planes.is_cuda) or lsh_planes.dtype != torch.float32 or not lsh_planes.is_contiguous() \
+                    or lsh_planes.dim() != 2 or lsh_planes.shape[1] != dim:
+                raise ValueError("lsh_planes must be a contiguous float32 device tensor [L][dim]")
+            self.lsh_bits = int(lsh_planes.shape[0])
+        self.slots = capacity << self.lsh_bits if capacity > 0 else 0
         cfg = ProximityConfig(C.sizeof(ProximityConfig), dim, corpus.data_ptr() if corpus is not None else None,
                               n_docs, dtype, capacity, k, policy, max_batch,
-                              device.index if device.index is not None else 0, int(rerank_factor), 0)
+                              device.index if device.index is not None else 0, int(rerank_factor), self.lsh_bits,
+                              lsh_planes.data_ptr() if self.lsh_bits else None)
         self.handle = _H()
         rc = lib.proximity_create(C.byref(cfg), C.byref(self.handle))
         if rc != OK:
@@ -165,9 +176,10 @@ class Proximity:
         return {n: int(getattr(st, n)) for n, _ in ProximityStats._fields_ if n != "reserved"}
 
     def cache_dump(self, want_keys: bool = False, want_ids: bool = False):
-        seq = np.zeros(max(self.capacity, 1), dtype=np.uint64)
-        keys = np.zeros((max(self.capacity, 1), self.dim), dtype=np.float32) if want_keys else None
-        ids = np.zeros((max(self.capacity, 1), self.k * self.rerank_factor), dtype=np.int64) if want_ids else None
+        rows = max(self.slots, 1)
+        seq = np.zeros(rows, dtype=np.uint64)
+        keys = np.zeros((rows, self.dim), dtype=np.float32) if want_keys else None
+        ids = np.zeros((rows, self.k * self.rerank_factor), dtype=np.int64) if want_ids else None
         n_live = C.c_uint32(0)
         rc = lib.proximity_cache_dump(self.handle, seq.ctypes.data_as(C.c_void_p),
                                       keys.ctypes.data_as(C.c_void_p) if want_keys else None,

@@ -285,7 +285,8 @@ __global__ __launch_bounds__(64) void resolver_kernel(
 // ---------------------------------------------------------------------------
 // After the resolver, before the scan.  One block per batch row.
 //   - a row that missed and still owns its slot at the end of the batch copies
-//     its vector and squared norm into the slot (Algorithm 1, "C[q] <- I", key part);
+//     its vector and squared norm into the slot (Algorithm 1, "C[q] <- I", key part;
+//     copy_keys == 0: the resolver has already written the keys);
 //   - a row that hit a key resident since before the batch answers from that key's
 //     stored list now, before any list is overwritten: the list itself (K == k), or
 //     with a re-ranking factor above 1 (K = rho * k stored per key, Section 3.3.4) the
@@ -293,7 +294,7 @@ __global__ __launch_bounds__(64) void resolver_kernel(
 // X / corpus_dtype: the corpus, read only for re-ranking.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void post_resolve_kernel(
-    int n, int c, int dim, int k, int K, long long base_seq, float* srcs, float* srcnrm,
+    int n, int c, int dim, int k, int K, int copy_keys, long long base_seq, float* srcs, float* srcnrm,
     const long long* __restrict__ slot_seq, const uint8_t* __restrict__ hit, const int* __restrict__ src,
     const int* __restrict__ row_slot, const int64_t* __restrict__ val_ids, const float* __restrict__ val_d,
     const void* __restrict__ X, int corpus_dtype, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(256) void post_resolve_kernel(
                                      keys, d64, cid, threadIdx.x);
       }
     }
-  } else {
+  } else if (copy_keys) {
     const int t = row_slot[i];
     if (t >= 0 && slot_seq[t] == base_seq + i) {
       const float4* from = reinterpret_cast<const float4*>(srcs + long(c + i) * dim);

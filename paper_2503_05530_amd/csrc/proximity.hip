@@ -24,6 +24,7 @@
 
 #include "../../include/proximity.h"
 #include "cache_kernels.hpp"
+#include "lsh_kernels.hpp"
 #include "mfma_kernels.hpp"
 #include "resolver_lds.hpp"
 #include "scan_kernels.hpp"
@@ -46,7 +47,7 @@ static_assert(kResolverLdsMax + kResolverStaticLds <= 160 * 1024 - 256, "the res
 constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32 tiles use the split-column kernel
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
-static_assert(sizeof(proximity_config) == 56, "proximity_config layout is part of the ABI");
+static_assert(sizeof(proximity_config) == 64, "proximity_config layout is part of the ABI");
 static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is part of the ABI");
 static_assert(sizeof(proximity_launch_t) == 16, "proximity_launch_t layout is part of the ABI");
 
@@ -69,6 +70,15 @@ struct DeviceGuard {
 struct proximity {
   proximity_config cfg{};
   int K = 0;  // neighbours asked of the index and stored per key: rerank_factor * k (Section 3.3.4)
+  // bucketed cache (Section 3.2): lsh_bits > 0; slots = capacity << lsh_bits, bucket g owns g*b .. g*b+b-1
+  int lsh_bits = 0;
+  int slots = 0;               // all key slots: capacity, or capacity << lsh_bits
+  float* lsh_planes = nullptr; // [lsh_bits][dim], the library's own copy
+  int* lsh_code = nullptr;     // [max_batch] code of each batch row
+  uint32_t* lsh_sorted = nullptr;  // [max_batch] (code, row) pairs grouped by code
+  int* bkt_size = nullptr;     // per bucket: live keys, front and back of its eviction order (-1: empty)
+  int* bkt_head = nullptr;
+  int* bkt_tail = nullptr;
   int n_cu = 256;
   uint64_t next_seq = 0;
   hipStream_t last_stream = nullptr;
@@ -408,7 +418,17 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   if (rho > PROXIMITY_MAX_K || rho * cfg->k > PROXIMITY_MAX_K)
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "rerank_factor * k = %u * %u exceeds %u", rho, cfg->k,
                 PROXIMITY_MAX_K);
-  if (cfg->reserved != 0) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "reserved must be 0");
+  if (cfg->lsh_bits > uint32_t(kLshMaxBits))
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "lsh_bits=%u exceeds %d", cfg->lsh_bits, kLshMaxBits);
+  const bool lsh = cfg->lsh_bits > 0 && cfg->capacity > 0;
+  if (lsh) {
+    if (!cfg->lsh_planes) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "lsh_planes is null but lsh_bits > 0");
+    if (cfg->capacity > uint32_t(kLshMaxBucket))
+      return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "capacity=%u per bucket exceeds %d", cfg->capacity, kLshMaxBucket);
+    if ((uint64_t(cfg->capacity) << cfg->lsh_bits) > PROXIMITY_MAX_CAPACITY)
+      return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "capacity << lsh_bits = %llu exceeds %u",
+                  (unsigned long long)(uint64_t(cfg->capacity) << cfg->lsh_bits), PROXIMITY_MAX_CAPACITY);
+  }
   if (cfg->max_batch == 0 || cfg->max_batch > PROXIMITY_MAX_BATCH)
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "max_batch=%u must be in 1..%u", cfg->max_batch,
                 PROXIMITY_MAX_BATCH);
@@ -432,6 +452,8 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   h->cfg = *cfg;
   h->cfg.rerank_factor = rho;
   h->K = int(rho * cfg->k);
+  h->lsh_bits = lsh ? int(cfg->lsh_bits) : 0;
+  h->slots = int(cfg->capacity) << h->lsh_bits;
   DeviceGuard guard(cfg->device);
   auto bail = [&](int code) {
     g_create_error = h->err;
@@ -447,7 +469,7 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   if (hipGetDeviceProperties(&prop, cfg->device) == hipSuccess && prop.multiProcessorCount > 0)
     h->n_cu = prop.multiProcessorCount;
 
-  const size_t c = cfg->capacity, B = cfg->max_batch, d = cfg->dim, k = size_t(h->K), N = cfg->n_docs;
+  const size_t c = size_t(h->slots), B = cfg->max_batch, d = cfg->dim, k = size_t(h->K), N = cfg->n_docs;
   const int kp = int(k) + kSlack;  // sized for the K = rerank_factor * k neighbours a search call asks for
   int rc;
 #define TRY_ALLOC(ptr, count, zero)                              \
@@ -479,16 +501,34 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   TRY_ALLOC(h->slot_prev, c, true);
   TRY_ALLOC(h->state, 1, true);
   h->ldD = long((c + B + 63) / 64 * 64);
-  TRY_ALLOC(h->D32, B * size_t(h->ldD), true);
-  TRY_ALLOC(h->cand_cnt, B, true);
-  TRY_ALLOC(h->cand_src, B * kCandCap, true);
-  TRY_ALLOC(h->cand_d, B * kCandCap, true);
+  if (!lsh) {  // the dense probe and its candidate lists belong to the flat cache
+    TRY_ALLOC(h->D32, B * size_t(h->ldD), true);
+    TRY_ALLOC(h->cand_cnt, B, true);
+    TRY_ALLOC(h->cand_src, B * kCandCap, true);
+    TRY_ALLOC(h->cand_d, B * kCandCap, true);
+  } else {
+    const size_t nb = size_t(1) << h->lsh_bits;
+    TRY_ALLOC(h->lsh_planes, size_t(h->lsh_bits) * d, false);
+    TRY_ALLOC(h->lsh_code, B, true);
+    TRY_ALLOC(h->lsh_sorted, B, true);
+    TRY_ALLOC(h->bkt_size, nb, true);
+    TRY_ALLOC(h->bkt_head, nb, false);
+    TRY_ALLOC(h->bkt_tail, nb, false);
+    if (hipMemcpy(h->lsh_planes, cfg->lsh_planes, size_t(h->lsh_bits) * d * sizeof(float), hipMemcpyDeviceToDevice) !=
+            hipSuccess ||
+        hipMemset(h->bkt_head, 0xff, nb * sizeof(int)) != hipSuccess ||
+        hipMemset(h->bkt_tail, 0xff, nb * sizeof(int)) != hipSuccess) {
+      h->err = "could not set up the bucketed cache";
+      return bail(PROXIMITY_ERR_HIP);
+    }
+    h->cfg.lsh_planes = h->lsh_planes;
+  }
   TRY_ALLOC(h->hit, B, true);
   TRY_ALLOC(h->src, B, true);
   TRY_ALLOC(h->row_slot, B, true);
   TRY_ALLOC(h->miss_list, B, true);
   TRY_ALLOC(h->miss_count, 1, true);
-  TRY_ALLOC(h->D64, size_t(kSmallRows) * (c > 0 ? c : 1), false);
+  TRY_ALLOC(h->D64, size_t(kSmallRows) * (c > 0 && !lsh ? c : 1), false);
 #undef TRY_ALLOC
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(resolver_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           int(kResolverLdsMax)) != hipSuccess) {
@@ -554,12 +594,13 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   h->last_stream = s;
 
-  const int c = int(h->cfg.capacity), dim = int(h->cfg.dim), kk = int(h->cfg.k), nn = int(n);
+  const int c = h->slots, dim = int(h->cfg.dim), kk = int(h->cfg.k), nn = int(n);
+  const bool lsh = h->lsh_bits > 0;
   const long long base_seq = (long long)h->next_seq;
   float* batch_rows = h->srcs + size_t(c) * dim;
 
   const int K = h->K;
-  if (nn <= kSmallRows && h->cfg.n_docs > 0) {
+  if (nn <= kSmallRows && h->cfg.n_docs > 0 && !lsh) {
     // A handful of rows: five launches in all.  Cache side (probe in float64; then resolver, key
     // insertion, hits on resident keys), streaming scan for the rows that missed, and
     // selection; then merge + float64 ranking + routing.  The rows are read from the caller's buffer.
@@ -580,6 +621,18 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   }
 
   HIP_TRY(h, hipMemcpyAsync(batch_rows, queries, size_t(n) * dim * sizeof(float), hipMemcpyDeviceToDevice, s));
+  if (lsh) {
+    // Section 3.2: codes, regrouping by code, one block per bucket that occurs, miss list in row order
+    const int b = int(h->cfg.capacity);
+    lsh_codes_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(batch_rows, nn, dim, h->lsh_planes, h->lsh_bits,
+                                                              h->lsh_code);
+    lsh_group_kernel<<<dim3(1), dim3(1024), 0, s>>>(h->lsh_code, nn, h->lsh_sorted);
+    lsh_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(
+        h->lsh_sorted, nn, b, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), batch_rows,
+        h->srcs, h->slot_seq, h->slot_next, h->slot_prev, h->bkt_size, h->bkt_head, h->bkt_tail, h->state, out_hit,
+        h->src, h->row_slot);
+    lsh_miss_list_kernel<<<dim3(1), dim3(1024), 0, s>>>(out_hit, nn, h->miss_list, h->miss_count, h->state);
+  } else {
   launch_row_norms<kDtypeF32>(h, batch_rows, nn, dim, h->srcnrm + c, s);
   int have_probe = 0;
   if (c > 0) {
@@ -614,9 +667,10 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
                                                  h->D32, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot,
                                                  h->miss_list, h->miss_count);
   }
+  }
   const void* X = h->cfg.n_docs > 0 ? h->cfg.corpus : nullptr;
   const int xdt = int(h->cfg.corpus_dtype);
-  post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, K, base_seq, h->srcs, h->srcnrm, h->slot_seq,
+  post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, K, lsh ? 0 : 1, base_seq, h->srcs, h->srcnrm, h->slot_seq,
                                                      out_hit, h->src, h->row_slot, h->val_ids, h->val_d, X, xdt,
                                                      out_ids, out_dists);
   rc = enqueue_scan(h, batch_rows, h->miss_list, h->miss_count, nn, K, K, h->res_ids, h->res_d, nullptr, s);
@@ -653,7 +707,7 @@ int proximity_cache_dump(const proximity_t* h, uint64_t* seq, float* keys, int64
   proximity* hh = const_cast<proximity*>(h);
   DeviceGuard guard(h->cfg.device);
   HIP_TRY(hh, hipStreamSynchronize(h->last_stream));
-  const size_t c = h->cfg.capacity, d = h->cfg.dim, k = size_t(h->K);  // K = rerank_factor * k ids per key
+  const size_t c = size_t(h->slots), d = h->cfg.dim, k = size_t(h->K);  // K = rerank_factor * k ids per key
   CacheState st;
   HIP_TRY(hh, hipMemcpy(&st, h->state, sizeof st, hipMemcpyDeviceToHost));
   std::vector<long long> sseq(c);
@@ -673,13 +727,20 @@ int proximity_cache_dump(const proximity_t* h, uint64_t* seq, float* keys, int64
     all_ids.resize(c * k);
     HIP_TRY(hh, hipMemcpy(all_ids.data(), h->val_ids, c * k * sizeof(int64_t), hipMemcpyDeviceToHost));
   }
-  uint32_t count = 0;
-  for (int t = st.head; t >= 0 && count < c; t = snext[size_t(t)]) {
-    if (seq) seq[count] = uint64_t(sseq[size_t(t)]);
-    if (keys) std::memcpy(keys + size_t(count) * d, all_keys.data() + size_t(t) * d, d * sizeof(float));
-    if (ids) std::memcpy(ids + size_t(count) * k, all_ids.data() + size_t(t) * k, k * sizeof(int64_t));
-    ++count;
+  // one eviction order (flat cache), or one per bucket, buckets in ascending code
+  std::vector<int> heads(1, st.head);
+  if (h->lsh_bits > 0) {
+    heads.resize(size_t(1) << h->lsh_bits);
+    HIP_TRY(hh, hipMemcpy(heads.data(), h->bkt_head, heads.size() * sizeof(int), hipMemcpyDeviceToHost));
   }
+  uint32_t count = 0;
+  for (int first : heads)
+    for (int t = first; t >= 0 && count < c; t = snext[size_t(t)]) {
+      if (seq) seq[count] = uint64_t(sseq[size_t(t)]);
+      if (keys) std::memcpy(keys + size_t(count) * d, all_keys.data() + size_t(t) * d, d * sizeof(float));
+      if (ids) std::memcpy(ids + size_t(count) * k, all_ids.data() + size_t(t) * k, k * sizeof(int64_t));
+      ++count;
+    }
   *n_live = count;
   return PROXIMITY_OK;
 }
@@ -691,6 +752,12 @@ int proximity_clear(proximity_t* h) {
   CacheState init{};
   init.head = init.tail = -1;
   HIP_TRY(h, hipMemcpy(h->state, &init, sizeof init, hipMemcpyHostToDevice));
+  if (h->lsh_bits > 0) {
+    const size_t nb = size_t(1) << h->lsh_bits;
+    HIP_TRY(h, hipMemset(h->bkt_size, 0, nb * sizeof(int)));
+    HIP_TRY(h, hipMemset(h->bkt_head, 0xff, nb * sizeof(int)));
+    HIP_TRY(h, hipMemset(h->bkt_tail, 0xff, nb * sizeof(int)));
+  }
   h->next_seq = 0;
   return PROXIMITY_OK;
 }

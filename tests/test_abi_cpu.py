@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol(binding):
 
 def test_abi_version_and_struct_layout(binding):
     assert binding.proximity_abi_version() == 2
-    assert C.sizeof(binding.ProximityConfig) == 56
+    assert C.sizeof(binding.ProximityConfig) == 64
     assert C.sizeof(binding.ProximityStats) == 128
     assert C.sizeof(binding.ProximityLaunch) == 16
     text = open(os.path.join(ROOT, "include", "proximity.h")).read()
@@ -47,7 +47,7 @@ def test_abi_version_and_struct_layout(binding):
 
 def make_cfg(b, **kw):
     vals = dict(struct_size=C.sizeof(b.ProximityConfig), dim=768, corpus=None, n_docs=0, corpus_dtype=0,
-                capacity=10, k=10, policy=0, max_batch=8, device=0, rerank_factor=1, reserved=0)
+                capacity=10, k=10, policy=0, max_batch=8, device=0, rerank_factor=1, lsh_bits=0, lsh_planes=None)
     vals.update(kw)
     return b.ProximityConfig(**vals)
 
@@ -56,7 +56,9 @@ def make_cfg(b, **kw):
     dict(struct_size=8), dict(dim=0), dict(dim=100), dict(dim=8192), dict(k=0), dict(k=1000),
     dict(max_batch=0), dict(max_batch=1 << 20), dict(capacity=(1 << 20) + 1), dict(n_docs=1 << 31),
     dict(n_docs=5, corpus=None), dict(corpus_dtype=7), dict(policy=2), dict(device=-1),
-    dict(k=100, rerank_factor=3), dict(rerank_factor=1 << 31), dict(reserved=1),
+    dict(k=100, rerank_factor=3), dict(rerank_factor=1 << 31), dict(lsh_bits=17, lsh_planes=4096),
+    dict(lsh_bits=4, lsh_planes=None), dict(lsh_bits=4, lsh_planes=4096, capacity=300),
+    dict(lsh_bits=16, lsh_planes=4096, capacity=32),
 ])
 def test_create_rejects_bad_config_before_any_gpu_work(binding, kw):
     b = binding

@@ -269,6 +269,89 @@ def test_reranking_bf16_corpus_and_no_corpus(B):
     px.close()
 
 
+# ---------------------------------------------------------------------------
+# Bucketed cache (Section 3.2)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("batch", [1, 6])
+def test_lsh_hand_worked_buckets(B, batch):
+    """The isolation example of the oracle's pins: one hyperplane, one entry per bucket, tau = 1.5."""
+    planes = np.zeros((1, 32), dtype=np.float32)
+    planes[0, 0] = 1.0
+    q = line_vectors([0.5, -0.5, 0.6, -10.0, -0.6, 0.4], dim=32)
+    corpus = line_vectors(range(-10, 10), dim=32)
+    px = B.Proximity(gpu_corpus(corpus), 32, 1, 2, po.POLICY_FIFO, 8, lsh_planes=torch.from_numpy(planes).to(DEV))
+    ids, _, hit = P.run_stream(px, q, 1.5, batch, DEV)
+    assert "".join("H" if h else "M" for h in hit) == "MMHMMH"
+    assert ids[0].tolist() == ids[2].tolist() == ids[5].tolist() == [10, 11]
+    seq, keys, _ = px.cache_dump(want_keys=True)
+    assert seq.tolist() == [4, 0] and (keys == q[[4, 0]]).all()
+    st = px.stats()
+    assert st["evictions"] == 2 and st["hits"] == 2 and st["size"] == 2 and st["queries"] == 6
+    px.close()
+
+
+_LSH_WANT = {}
+
+
+@pytest.mark.parametrize("batch", [1, 7, 64, 256])
+@pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
+def test_tiny_workload_bucketed(B, tiny, batch, policy):
+    w, corpus, q, _ = tiny
+    planes = W.lsh_planes(3, w.dim, 2)
+    if policy not in _LSH_WANT:
+        _LSH_WANT[policy] = po.lookup_stream_deferred(corpus, q, w.tau, 6, w.k, policy, planes=planes)
+    o_ids, o_d, o_hit, o_src, dec = _LSH_WANT[policy]
+    assert 300 < o_hit.sum() < 697 and dec.n_evictions > 100
+    px = B.Proximity(gpu_corpus(corpus), w.dim, 6, w.k, policy, 256, lsh_planes=torch.from_numpy(planes).to(DEV))
+    got = P.run_stream(px, q, w.tau, batch, DEV)
+    assert P.assert_stream_parity(got, (o_ids, o_d, o_hit, o_src), corpus, q, what=f"lsh b{batch}") == 0
+    seq, _, ids = px.cache_dump(want_ids=True)
+    assert seq.tolist() == dec.dump_seq().tolist()
+    assert (ids == o_ids[seq]).all()
+    st, os_ = px.stats(), dec.stats()
+    for key in ("queries", "hits", "misses", "inserts", "evictions", "size"):
+        assert st[key] == os_[key], key
+    px.close()
+
+
+def test_bucketed_with_reranking_and_clear(B, tiny):
+    w, corpus, q, _ = tiny
+    q = q[:400]
+    planes = W.lsh_planes(2, w.dim, 5)
+    want = po.lookup_stream_deferred(corpus, q, w.tau, 5, w.k, po.POLICY_LRU, planes=planes, rerank_factor=3)
+    px = B.Proximity(gpu_corpus(corpus), w.dim, 5, w.k, po.POLICY_LRU, 64, rerank_factor=3,
+                     lsh_planes=torch.from_numpy(planes).to(DEV))
+    for _ in range(2):          # the second pass starts from a cleared cache and must repeat the first
+        got = P.run_stream(px, q, w.tau, 64, DEV)
+        P.assert_stream_parity(got, want[:4], corpus, q, what="lsh rho=3", reranked=True)
+        seq, _, stored = px.cache_dump(want_ids=True)
+        assert seq.tolist() == want[4].dump_seq().tolist() and (stored == want[5][seq]).all()
+        px.clear()
+        assert px.stats()["size"] == 0 and len(px.cache_dump()[0]) == 0
+    px.close()
+
+
+def test_bucketed_probe_at_scale_without_corpus(B):
+    """1024 buckets of 20 entries, calls of 8192 rows: flags and cache contents against the oracle's decisions."""
+    dim, bits, b, tau = 128, 10, 20, 0.4
+    planes = W.lsh_planes(bits, dim, 7)
+    rng = np.random.default_rng(17)
+    fresh = W.unit_rows(rng.standard_normal((30000, dim)))
+    near = W.unit_rows(fresh[rng.integers(0, 30000, size=10960)] + 0.25 * W.unit_rows(rng.standard_normal((10960, dim))))
+    q = np.concatenate([fresh, near])[rng.permutation(40960)].astype(np.float32)
+    o_hit, _, dec = po.simulate_decisions(q, tau, b, po.POLICY_LRU, planes=planes)
+    assert 1000 < o_hit.sum() < 9000 and dec.n_evictions > 5000
+    px = B.Proximity(None, dim, b, 4, po.POLICY_LRU, 8192, device=DEV, lsh_planes=torch.from_numpy(planes).to(DEV))
+    _, _, hit = P.run_stream(px, q, tau, 8192, DEV)
+    assert (hit == o_hit).all()
+    seq, _, _ = px.cache_dump()
+    assert seq.tolist() == dec.dump_seq().tolist()
+    st, os_ = px.stats(), dec.stats()
+    for key in ("queries", "hits", "misses", "inserts", "evictions", "size"):
+        assert st[key] == os_[key], key
+    px.close()
+
+
 def test_tau_zero_and_tau_huge(B, tiny):
     w, corpus, q, _ = tiny
     q = q[:200]
