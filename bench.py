@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--rho", type=int, default=1,
                     help="re-ranking factor (Section 3.3.4): rho*k neighbours stored per key, hits re-ranked")
+    ap.add_argument("--lsh-bits", type=int, default=0,
+                    help="bucketed cache (Section 3.2): 2^L buckets; 0 = the flat cache")
+    ap.add_argument("--bucket-capacity", type=int, default=20, help="entries per bucket when --lsh-bits > 0")
     ap.add_argument("--n-docs", type=int, default=None, help="override corpus rows (debugging only)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -126,7 +129,11 @@ def probe_microbench(args, torch, np, W, Proximity, device):
     n_keys, dim, batch, tau = W.PROBE_KEYS, W.PROBE_DIM, W.PROBE_BATCH, W.PROBE_TAU
     steps = args.steps if args.steps is not None else 20
     warmup = args.warmup if args.warmup is not None else 2
-    px = Proximity(None, dim, n_keys, 1, W.POLICY_LRU, batch, device=device)
+    planes = None
+    if args.lsh_bits > 0:
+        planes = torch.from_numpy(W.lsh_planes(args.lsh_bits, dim, 0)).to(device)
+    px = Proximity(None, dim, args.bucket_capacity if planes is not None else n_keys, 1, W.POLICY_LRU, batch,
+                   device=device, lsh_planes=planes)
     keys = torch.from_numpy(W.probe_warm_keys(n_keys, dim, 0)).to(device)
     for b0 in range(0, n_keys, batch):
         px.search_batch(keys[b0:b0 + batch], tau)
@@ -146,6 +153,20 @@ def probe_microbench(args, torch, np, W, Proximity, device):
             hits += int(hit.sum().item())
     flops = 2.0 * batch * (n_keys + batch) * dim
     ms = total_ms / steps
+    if planes is not None:
+        # bucketed cache: no contraction; per row L inner products and at most b float64 distances
+        line = {"metric": "cache_probes_per_sec", "value": round(batch / (ms * 1e-3), 1), "unit": "queries/s",
+                "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+                "config": {"workload": f"probe, bucketed cache: {1 << args.lsh_bits} buckets x {args.bucket_capacity} "
+                                       f"entries x {dim} f32 warmed with {n_keys} keys, batches of {batch} (half "
+                                       f"perturbed resident keys, radius U(0,{W.PROBE_MAX_RADIUS}); half fresh), "
+                                       f"tau={tau}, LRU, no corpus",
+                           "hit_rate": round(hits / (steps * batch), 4), "resident_keys": px.stats()["size"]},
+                "roofline": None, "cpu_baseline": None}
+        print(json.dumps(line))
+        px.close()
+        return
     line = {"metric": "cache_probes_per_sec", "value": round(batch / (ms * 1e-3), 1), "unit": "queries/s",
             "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
@@ -212,7 +233,12 @@ def main():
     t_gen = time.perf_counter() - t_gen
     elem = 2 if w.corpus_dtype == W.DTYPE_BF16 else 4
 
-    px = Proximity(corpus_dev, w.dim, w.capacity, w.k, w.policy, max_batch, rerank_factor=args.rho)
+    planes = planes_host = None
+    if args.lsh_bits > 0:
+        planes_host = W.lsh_planes(args.lsh_bits, w.dim, w.seed)
+        planes = torch.from_numpy(planes_host).to(device)
+    capacity = args.bucket_capacity if planes is not None else w.capacity
+    px = Proximity(corpus_dev, w.dim, capacity, w.k, w.policy, max_batch, rerank_factor=args.rho, lsh_planes=planes)
     n_rows = len(queries)
     outs = (torch.empty((n_rows, w.k), dtype=torch.int64, device=device),
             torch.empty((n_rows, w.k), dtype=torch.float32, device=device),
@@ -243,8 +269,11 @@ def main():
         from oracle import proximity_oracle as po
         first = warmup * batch
         k_store = args.rho * w.k
-        orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy, rerank_factor=args.rho,
-                                 retrieve=lambda q: (np.full(k_store, -1, np.int64), np.full(k_store, np.inf)))
+        no_db = lambda q: (np.full(k_store, -1, np.int64), np.full(k_store, np.inf))
+        if planes_host is not None:
+            orc = po.LshCacheOracle(corpus, planes_host, capacity, w.k, w.policy, retrieve=no_db, rerank_factor=args.rho)
+        else:
+            orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy, rerank_factor=args.rho, retrieve=no_db)
         orc.lookup_stream(queries[:first], tau)            # decisions only: brings the cache to the timed region's state
         orc.retrieve = lambda q: po.exact_knn(corpus, q, k_store)
         n_s = min(args.cpu_sample, len(queries) - first)
@@ -265,7 +294,10 @@ def main():
                                f"{w.choice}({w.zipf_s}) stream of "
                                f"{w.n_stream} over {w.n_bases} bases (perturbation {w.radius}), capacity "
                                f"{w.capacity}, {'LRU' if w.policy else 'FIFO'}, k={w.k}",
-                   "tau": tau, "batch": batch, "rerank_factor": args.rho, "hit_rate": round(hit_rate, 4),
+                   "tau": tau, "batch": batch, "rerank_factor": args.rho,
+                   "cache": (f"bucketed: {1 << args.lsh_bits} buckets x {capacity}" if planes is not None
+                             else f"flat: {w.capacity}"),
+                   "hit_rate": round(hit_rate, 4),
                    "queries_timed": steps * batch, "setup_s": round(t_gen, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
     }

@@ -38,10 +38,30 @@ __device__ __forceinline__ float wave_sum(float v) {
   for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
   return v;
 }
+// v + (v moved across lanes by the data-parallel-primitive control CTRL); lanes the move does not
+// reach (outside ROW_MASK, or shifted in from beyond a row of 16) add zero.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_move_add(double v) {
+  const unsigned long long bits = (unsigned long long)__double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, int(unsigned(bits)), CTRL, ROW_MASK, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, int(unsigned(bits >> 32)), CTRL, ROW_MASK, 0xf, false);
+  return v + __longlong_as_double((long long)(((unsigned long long)unsigned(hi) << 32) | unsigned(lo)));
+}
+// Sum of a float64 over the wave, the same value in every lane.  The shuffle form costs twelve
+// trips through the LDS crossbar; this one stays in the vector unit: a running sum inside every
+// row of 16 lanes (shifts by 1, 2, 4, 8), then the row totals are handed on (lane 15 to the
+// next row for rows 1 and 3, lane 31 to rows 2 and 3), and lane 63 holds the total.
 __device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-  return v;
+  v = dpp_move_add<0x111, 0xf>(v);  // row_shr:1
+  v = dpp_move_add<0x112, 0xf>(v);  // row_shr:2
+  v = dpp_move_add<0x114, 0xf>(v);  // row_shr:4
+  v = dpp_move_add<0x118, 0xf>(v);  // row_shr:8
+  v = dpp_move_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+  v = dpp_move_add<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
+  const unsigned long long bits = (unsigned long long)__double_as_longlong(v);
+  const unsigned lo = unsigned(__builtin_amdgcn_readlane(int(unsigned(bits)), 63));
+  const unsigned hi = unsigned(__builtin_amdgcn_readlane(int(unsigned(bits >> 32)), 63));
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
 // Sum NV per-lane values across the 64 lanes of a wave with NV-1 + log2(64/NV)

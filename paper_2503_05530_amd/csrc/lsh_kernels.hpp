@@ -33,23 +33,31 @@ __global__ __launch_bounds__(256) void lsh_codes_kernel(const float* __restrict_
   if (row >= n) return;
   const float* q = Q + long(row) * dim;
   int c = 0;
-  for (int b = 0; b < n_bits; ++b) {
-    const float* r = planes + long(b) * dim;
-    double acc = 0.0;
-    for (int i = lane; i < dim; i += 64) acc += double(q[i]) * double(r[i]);
-    acc = wave_sum(acc);
-    if (acc >= 0.0) c |= 1 << b;
+  for (int b0 = 0; b0 < n_bits; b0 += 4) {  // four planes at a time, so that their loads overlap
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int i = lane; i < dim; i += 64) {
+      const double qv = double(q[i]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (b0 + u < n_bits) acc[u] += qv * double(planes[long(b0 + u) * dim + i]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (b0 + u < n_bits && wave_sum(acc[u]) >= 0.0) c |= 1 << (b0 + u);
   }
   if (lane == 0) code[row] = c;
 }
 
 // ---------------------------------------------------------------------------
 // Regroup the batch by code, rows of one code in row order: sorts (code, row) pairs.
-// One block of 1024 threads; n <= 2^13.  sorted[j] = (code << 13) | row.
+// One block of 1024 threads; n <= 2^13.  sorted[j] = (code << 13) | row; seg_start[g] is the
+// position in `sorted` where the g-th distinct code begins, *n_segs the number of distinct codes.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void lsh_group_kernel(const int* __restrict__ code, int n,
-                                                         uint32_t* __restrict__ sorted) {
+                                                         uint32_t* __restrict__ sorted, int* __restrict__ seg_start,
+                                                         int* __restrict__ n_segs) {
   __shared__ uint32_t keys[1 << kLshRowBits];
+  __shared__ int counts[1024];
   const int tid = threadIdx.x;
   const int P = next_pow2(n < 2 ? 2 : n);
   for (int i = tid; i < P; i += 1024) keys[i] = i < n ? (uint32_t(code[i]) << kLshRowBits) | uint32_t(i) : 0xffffffffu;
@@ -70,125 +78,212 @@ __global__ __launch_bounds__(1024) void lsh_group_kernel(const int* __restrict__
     }
   }
   for (int i = tid; i < n; i += 1024) sorted[i] = keys[i];
+  // positions where a new code begins, in order
+  constexpr int PER = (1 << kLshRowBits) / 1024;
+  int mine = 0;
+  for (int r = 0; r < PER; ++r) {
+    const int i = tid * PER + r;
+    if (i < n && (i == 0 || (keys[i] >> kLshRowBits) != (keys[i - 1] >> kLshRowBits))) ++mine;
+  }
+  counts[tid] = mine;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {  // inclusive scan
+    const int v = tid >= off ? counts[tid - off] : 0;
+    __syncthreads();
+    counts[tid] += v;
+    __syncthreads();
+  }
+  int pos = counts[tid] - mine;
+  for (int r = 0; r < PER; ++r) {
+    const int i = tid * PER + r;
+    if (i < n && (i == 0 || (keys[i] >> kLshRowBits) != (keys[i - 1] >> kLshRowBits))) seg_start[pos++] = i;
+  }
+  if (tid == 1023) *n_segs = counts[1023];
 }
 
 // ---------------------------------------------------------------------------
-// One block per position of the regrouped batch; the block at the first row of a code walks
-// that bucket's rows in order, the others return at once.
+// One block per distinct code of the regrouped batch (blocks beyond *n_segs return at once);
+// the block walks that bucket's rows in order.
 //
 // Per row: float64 distance to each live key of the bucket, nearest key (ties: smaller seq),
 // hit if within tau (LRU: the key moves to the back of the bucket's order); otherwise the row
 // takes the bucket's next free slot or evicts the front of its order, and its vector is written
 // into the slot.  Outputs per row as resolver_kernel: hit flag, answering source (slot, or
 // c_total + j when the key was stored by row j of this call), slot taken.
+//
+// The bucket's state lives in LDS while the block walks: inserting positions, the order as
+// local links, the current query, and -- when keys_in_lds -- the bucket's keys themselves
+// (b * dim floats), so that a row costs one fetch of its vector plus on-chip work.  Dynamic
+// LDS: (1 + (keys_in_lds ? b : 0)) * dim floats.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void lsh_resolve_kernel(
-    const uint32_t* __restrict__ sorted, int n, int b, int c_total, int dim, int policy_lru, long long base_seq,
-    double tau, const float* batch_rows, float* srcs, long long* slot_seq, int* slot_next,
+constexpr int kLshThreads = 1024;
+__global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
+    const uint32_t* __restrict__ sorted, const int* __restrict__ seg_start, const int* __restrict__ n_segs, int n,
+    int b, int c_total, int dim, int policy_lru, long long base_seq, double tau, int keys_in_lds,
+    const float* batch_rows, float* srcs, long long* slot_seq, int* slot_next,
     int* slot_prev, int* bkt_size, int* bkt_head, int* bkt_tail, CacheState* st, uint8_t* __restrict__ hit_out,
     int* __restrict__ src_out, int* __restrict__ row_slot) {
-  const int j0 = blockIdx.x;
-  if (j0 >= n) return;
-  const uint32_t first = sorted[j0];
-  const int code = int(first >> kLshRowBits);
-  if (j0 > 0 && int(sorted[j0 - 1] >> kLshRowBits) == code) return;
+  if (int(blockIdx.x) >= *n_segs) return;
+  const int j0 = seg_start[blockIdx.x];
+  const int code = int(sorted[j0] >> kLshRowBits);
 
-  __shared__ uint64_t keys[kLshMaxBucket];
+  extern __shared__ float lds_rows[];          // [dim] the current query, then [b][dim] keys if they fit
+  float* lq = lds_rows;
+  float* lkeys = lds_rows + dim;
   __shared__ double d64[kLshMaxBucket];
-  __shared__ int cid[kLshMaxBucket];
-  __shared__ int s_best;  // local index of the answering key, -1: miss
-  __shared__ int s_size;  // live keys of the bucket (read by every thread for the distances)
-  __shared__ int s_slot;  // slot the current row takes when it misses
-  const int tid = threadIdx.x, lane = tid & 63;
-  for (int s = tid; s < b; s += 256) keys[s] = pack_key(0.f, uint32_t(s));
+  __shared__ long long lseq[kLshMaxBucket];
+  __shared__ int lnext[kLshMaxBucket];         // the bucket's order, local slot numbers, -1 = none
+  __shared__ int lprev[kLshMaxBucket];
+  __shared__ int s_best;                       // local slot of the answering key, -1: miss
+  __shared__ int s_size;                       // live keys of the bucket
+  __shared__ int s_slot;                       // local slot the current row takes when it misses
+  const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
 
   const int slot0 = code * b;
   float* bucket_keys = srcs + long(slot0) * dim;
-  // the bucket's order is walked by thread 0 alone; head/tail are global slot ids
-  int head = 0, tail = 0;
+  const int size0 = bkt_size[code];
+  for (int s = tid; s < size0; s += kLshThreads) {
+    lseq[s] = slot_seq[slot0 + s];
+    const int nx = slot_next[slot0 + s], pv = slot_prev[slot0 + s];
+    lnext[s] = nx >= 0 ? nx - slot0 : -1;
+    lprev[s] = pv >= 0 ? pv - slot0 : -1;
+  }
+  if (keys_in_lds)
+    for (int x = tid; x < size0 * dim; x += kLshThreads) lkeys[x] = bucket_keys[x];
+  // the order is walked by thread 0 alone
+  int head = -1, tail = -1;
   int hits = 0, misses = 0, inserts = 0, evictions = 0, inbatch = 0;
   if (tid == 0) {
-    s_size = bkt_size[code];
-    head = bkt_head[code];
-    tail = bkt_tail[code];
+    s_size = size0;
+    const int h = bkt_head[code], tl = bkt_tail[code];
+    head = h >= 0 ? h - slot0 : -1;
+    tail = tl >= 0 ? tl - slot0 : -1;
+  }
+  // the row being resolved sits in LDS; the bucket's next row is fetched into registers meanwhile
+  constexpr int QR = 4096 / kLshThreads;  // values of a row per thread, at the largest dimension
+  constexpr uint32_t kNone = 0xffffffffu;
+  constexpr uint32_t kRowMask = (1u << kLshRowBits) - 1;
+  uint32_t e_cur = sorted[j0];
+  uint32_t e_nxt = j0 + 1 < n ? sorted[j0 + 1] : kNone;
+  float qreg[QR];
+#pragma unroll
+  for (int u = 0; u < QR; ++u) {
+    const int x = tid + u * kLshThreads;
+    qreg[u] = x < dim ? batch_rows[long(e_cur & kRowMask) * dim + x] : 0.f;
   }
   __syncthreads();
 
-  for (int j = j0; j < n; ++j) {
-    const uint32_t e = sorted[j];
-    if (int(e >> kLshRowBits) != code) break;
-    const int i = int(e & ((1u << kLshRowBits) - 1));
-    const float* q = batch_rows + long(i) * dim;
+  for (int j = j0;; ++j) {
+    const int i = int(e_cur & kRowMask);
+#pragma unroll
+    for (int u = 0; u < QR; ++u) {
+      const int x = tid + u * kLshThreads;
+      if (x < dim) lq[x] = qreg[u];
+    }
     const int size = s_size;
+    __syncthreads();
+    const bool more = e_nxt != kNone && int(e_nxt >> kLshRowBits) == code;
+    uint32_t e_nn = kNone;
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < QR; ++u) {
+        const int x = tid + u * kLshThreads;
+        if (x < dim) qreg[u] = batch_rows[long(e_nxt & kRowMask) * dim + x];
+      }
+      if (j + 2 < n) e_nn = sorted[j + 2];
+    }
 
-    block_candidate_distances<kDtypeF32, 4>(keys, size, q, bucket_keys, dim, d64, cid, tid);
+    for (int s = wib; s < size; s += kLshThreads / 64) {
+      const float* key = keys_in_lds ? lkeys + s * dim : bucket_keys + long(s) * dim;
+      double acc = 0.0;
+      for (int x = lane; x < dim; x += 64) {
+        const double diff = double(lq[x]) - double(key[x]);
+        acc += diff * diff;
+      }
+      acc = wave_sum(acc);
+      if (lane == 0) d64[s] = sqrt(acc);
+    }
     __syncthreads();
     if (tid < 64) {
       ResolverBest best{__longlong_as_double(0x7ff0000000000000ll), 0x7fffffffffffffffll, -1};
       for (int s = lane; s < size; s += 64) {
         const double d = d64[s];
-        if (d <= tau) best_take(best, d, slot_seq[slot0 + s], s);
+        if (d <= tau) best_take(best, d, lseq[s], s);
       }
       best_wave_reduce(best);
       if (lane == 0) {
         const int sb = best.src;
         s_best = sb;
         if (sb >= 0) {
-          const int t = slot0 + sb;
           ++hits;
-          const long long sq = slot_seq[t];
+          const long long sq = lseq[sb];
           if (sq >= base_seq) ++inbatch;
-          if (policy_lru && t != tail) {
-            const int p = slot_prev[t], nx = slot_next[t];  // nx >= 0 because t is not the tail
-            if (p >= 0) slot_next[p] = nx;
-            slot_prev[nx] = p;
-            slot_prev[t] = tail;
-            slot_next[t] = -1;
-            slot_next[tail] = t;
+          if (policy_lru && sb != tail) {
+            const int p = lprev[sb], nx = lnext[sb];  // nx >= 0 because sb is not the tail
+            if (p >= 0) lnext[p] = nx;
+            lprev[nx] = p;
+            lprev[sb] = tail;
+            lnext[sb] = -1;
+            lnext[tail] = sb;
             if (p < 0) head = nx;
-            tail = t;
+            tail = sb;
           }
           hit_out[i] = 1;
-          src_out[i] = sq >= base_seq ? c_total + int(sq - base_seq) : t;
+          src_out[i] = sq >= base_seq ? c_total + int(sq - base_seq) : slot0 + sb;
           row_slot[i] = -1;
         } else {
           ++misses;
           int t;
           if (size < b) {
-            t = slot0 + size;
+            t = size;
             s_size = size + 1;
           } else {
             t = head;
-            head = slot_next[t];
-            if (head >= 0) slot_prev[head] = -1;
+            head = lnext[t];
+            if (head >= 0) lprev[head] = -1;
             if (head < 0) tail = -1;
             ++evictions;
           }
-          slot_seq[t] = base_seq + i;
-          slot_prev[t] = tail;
-          slot_next[t] = -1;
-          if (tail >= 0) slot_next[tail] = t;
+          lseq[t] = base_seq + i;
+          lprev[t] = tail;
+          lnext[t] = -1;
+          if (tail >= 0) lnext[tail] = t;
           if (tail < 0) head = t;
           tail = t;
           ++inserts;
           hit_out[i] = 0;
           src_out[i] = -1;
-          row_slot[i] = t;
+          row_slot[i] = slot0 + t;
           s_slot = t;
         }
       }
     }
     __syncthreads();
     if (s_best < 0) {  // the new key goes into its slot at once: later rows of the bucket compare against it
-      float* dst = srcs + long(s_slot) * dim;
-      for (int x = tid; x < dim; x += 256) dst[x] = q[x];
+      const int t = s_slot;
+      float* dst = bucket_keys + long(t) * dim;
+      for (int x = tid; x < dim; x += kLshThreads) {
+        const float v = lq[x];
+        dst[x] = v;
+        if (keys_in_lds) lkeys[t * dim + x] = v;
+      }
     }
-    __syncthreads();  // the seq and the new key are visible to the whole block for the next row
+    __syncthreads();  // the new key is in place, and lq may be overwritten by the next row
+    if (!more) break;
+    e_cur = e_nxt;
+    e_nxt = e_nn;
+  }
+
+  const int size1 = s_size;
+  for (int s = tid; s < size1; s += kLshThreads) {
+    slot_seq[slot0 + s] = lseq[s];
+    slot_next[slot0 + s] = lnext[s] >= 0 ? slot0 + lnext[s] : -1;
+    slot_prev[slot0 + s] = lprev[s] >= 0 ? slot0 + lprev[s] : -1;
   }
   if (tid == 0) {
-    bkt_size[code] = s_size;
-    bkt_head[code] = head;
-    bkt_tail[code] = tail;
+    bkt_size[code] = size1;
+    bkt_head[code] = head >= 0 ? slot0 + head : -1;
+    bkt_tail[code] = tail >= 0 ? slot0 + tail : -1;
     atomicAdd(&st->size, inserts - evictions);
     atomicAdd(&st->hits, (unsigned long long)hits);
     atomicAdd(&st->misses, (unsigned long long)misses);

@@ -45,6 +45,7 @@ constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan
 constexpr size_t kResolverLdsMax = 147 * 1024;  // dynamic LDS the LDS-state resolver may ask for
 static_assert(kResolverLdsMax + kResolverStaticLds <= 160 * 1024 - 256, "the resolver block must fit the LDS of one CU");
 constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32 tiles use the split-column kernel
+constexpr size_t kLshLdsMax = 144 * 1024;  // dynamic LDS the bucket resolver may ask for (query + bucket keys)
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
 static_assert(sizeof(proximity_config) == 64, "proximity_config layout is part of the ABI");
@@ -76,6 +77,8 @@ struct proximity {
   float* lsh_planes = nullptr; // [lsh_bits][dim], the library's own copy
   int* lsh_code = nullptr;     // [max_batch] code of each batch row
   uint32_t* lsh_sorted = nullptr;  // [max_batch] (code, row) pairs grouped by code
+  int* lsh_seg_start = nullptr;    // [max_batch] where each distinct code of the batch begins in lsh_sorted
+  int* lsh_n_segs = nullptr;       // number of distinct codes in the batch
   int* bkt_size = nullptr;     // per bucket: live keys, front and back of its eviction order (-1: empty)
   int* bkt_head = nullptr;
   int* bkt_tail = nullptr;
@@ -511,6 +514,8 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     TRY_ALLOC(h->lsh_planes, size_t(h->lsh_bits) * d, false);
     TRY_ALLOC(h->lsh_code, B, true);
     TRY_ALLOC(h->lsh_sorted, B, true);
+    TRY_ALLOC(h->lsh_seg_start, B, true);
+    TRY_ALLOC(h->lsh_n_segs, 1, true);
     TRY_ALLOC(h->bkt_size, nb, true);
     TRY_ALLOC(h->bkt_head, nb, false);
     TRY_ALLOC(h->bkt_tail, nb, false);
@@ -533,6 +538,11 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(resolver_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           int(kResolverLdsMax)) != hipSuccess) {
     h->err = "could not raise the dynamic LDS limit of the resolver";
+    return bail(PROXIMITY_ERR_HIP);
+  }
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(lsh_resolve_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          int(kLshLdsMax)) != hipSuccess) {
+    h->err = "could not raise the dynamic LDS limit of the bucket resolver";
     return bail(PROXIMITY_ERR_HIP);
   }
   CacheState init{};
@@ -626,9 +636,14 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     const int b = int(h->cfg.capacity);
     lsh_codes_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(batch_rows, nn, dim, h->lsh_planes, h->lsh_bits,
                                                               h->lsh_code);
-    lsh_group_kernel<<<dim3(1), dim3(1024), 0, s>>>(h->lsh_code, nn, h->lsh_sorted);
-    lsh_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(
-        h->lsh_sorted, nn, b, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), batch_rows,
+    lsh_group_kernel<<<dim3(1), dim3(1024), 0, s>>>(h->lsh_code, nn, h->lsh_sorted, h->lsh_seg_start, h->lsh_n_segs);
+    const int max_segs = nn < (1 << h->lsh_bits) ? nn : (1 << h->lsh_bits);  // distinct codes a batch can have
+    // the bucket's keys stay in LDS while its block walks, when b * dim floats fit
+    const size_t row_bytes = size_t(dim) * sizeof(float);
+    const int keys_in_lds = (size_t(b) + 1) * row_bytes <= kLshLdsMax ? 1 : 0;
+    lsh_resolve_kernel<<<dim3(max_segs), dim3(kLshThreads), (keys_in_lds ? size_t(b) + 1 : 1) * row_bytes, s>>>(
+        h->lsh_sorted, h->lsh_seg_start, h->lsh_n_segs, nn, b, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), keys_in_lds,
+        batch_rows,
         h->srcs, h->slot_seq, h->slot_next, h->slot_prev, h->bkt_size, h->bkt_head, h->bkt_tail, h->state, out_hit,
         h->src, h->row_slot);
     lsh_miss_list_kernel<<<dim3(1), dim3(1024), 0, s>>>(out_hit, nn, h->miss_list, h->miss_count, h->state);
