@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=24, help="queries the oracle is timed on")
+    ap.add_argument("--recall-sweep", action="store_true",
+                    help="hit rate and database k-recall (Section 4) over tau, flat and bucketed cache, then exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for HBM byte counters)")
     return ap.parse_args()
@@ -122,6 +124,50 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
                 "frac": round(gbs / HBM_PEAK_GBS, 4), **common}
     return {"bound": "mfma", "achieved": round(tflops, 2), "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(tflops / F32_MFMA_PEAK_TFLOPS, 4), **common}
+
+
+def recall_sweep(args, torch, np, W, Proximity, device):
+    """Hit rate and database k-recall as Section 4 defines it: the fraction of the k documents the cache
+    hands out that are among the k the index returns for the same query.  The index's own answers come from
+    the library's plain search (proximity_knn_batch); the overlap is counted with tensor operations here,
+    outside the method."""
+    w = W.WORKLOADS[args.workload]
+    batch = 64 if args.batch is None else args.batch
+    n_q = (args.steps if args.steps is not None else 200) * batch
+    corpus_dev = torch.from_numpy(W.corpus_for(w, args.n_docs)).to(device)
+    q_dev = torch.from_numpy(W.stream_for(w, n_q)).to(device)
+    truth = torch.empty((n_q, w.k), dtype=torch.int64, device=device)
+    plain = Proximity(corpus_dev, w.dim, 0, w.k, w.policy, batch)
+    for r0 in range(0, n_q, batch):
+        plain.knn_batch(q_dev[r0:r0 + batch], out_ids=truth[r0:r0 + batch])
+    plain.close()
+    rows = []
+    bits = args.lsh_bits if args.lsh_bits > 0 else 4
+    planes = torch.from_numpy(W.lsh_planes(bits, w.dim, w.seed)).to(device)
+    caches = (("flat", w.capacity, None), (f"bucketed {1 << bits}x{args.bucket_capacity}", args.bucket_capacity, planes))
+    for name, cap, pl in caches:
+        for rho in sorted({1, args.rho}):
+            px = Proximity(corpus_dev, w.dim, cap, w.k, w.policy, batch, rerank_factor=rho, lsh_planes=pl)
+            for tau in (w.taus or (0.0, 0.1, 0.25, 0.5, 1.0)):
+                px.clear()
+                ids = torch.empty((n_q, w.k), dtype=torch.int64, device=device)
+                hit = torch.empty((n_q,), dtype=torch.uint8, device=device)
+                torch.cuda.synchronize(device)
+                t0 = time.perf_counter()
+                for r0 in range(0, n_q, batch):
+                    px.search_batch(q_dev[r0:r0 + batch], tau, out_ids=ids[r0:r0 + batch], out_hit=hit[r0:r0 + batch],
+                                    want_dists=False)
+                torch.cuda.synchronize(device)
+                dt = time.perf_counter() - t0
+                same = (ids[:, :, None] == truth[:, None, :]).any(dim=2).float().mean(dim=1)   # per query
+                hits = hit.bool()
+                rows.append({"cache": name, "rerank_factor": rho, "tau": tau, "hit_rate": round(float(hits.float().mean()), 4),
+                             "k_recall": round(float(same.mean()), 4),
+                             "k_recall_on_hits": round(float(same[hits].mean()), 4) if bool(hits.any()) else None,
+                             "queries_per_s": round(n_q / dt, 1)})
+            px.close()
+    print(json.dumps({"metric": "database_k_recall_sweep", "unit": "fraction", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": w.name, "queries": n_q, "batch": batch, "k": w.k}, "rows": rows}))
 
 
 def probe_microbench(args, torch, np, W, Proximity, device):
@@ -207,6 +253,8 @@ def main():
         return
     if args.workload == "probe":
         return probe_microbench(args, torch, np, W, Proximity, device)
+    if args.recall_sweep:
+        return recall_sweep(args, torch, np, W, Proximity, device)
     w = W.WORKLOADS[args.workload]
     tau = w.tau if args.tau is None else args.tau
     batch = w.batch if args.batch is None else args.batch

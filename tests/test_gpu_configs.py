@@ -121,6 +121,25 @@ def test_mid_workload_with_reranking(B, mid, batch):
     px.close()
 
 
+@pytest.mark.parametrize("batch", [1, 64])
+def test_mid_workload_bucketed(B, mid, batch):
+    """The bucketed cache (Section 3.2) at the mid workload's size: 16 buckets of 20 entries."""
+    w, corpus, corpus_dev, q, knn_ids, knn_d, _ = mid
+    tau, bits, b = 0.25, 4, 20
+    planes = W.lsh_planes(bits, w.dim, w.seed)
+    if "dec" not in _MID_LSH:
+        _MID_LSH["dec"] = po.simulate_decisions(q, tau, b, w.policy, planes=planes)
+    decisions = _MID_LSH["dec"]
+    assert 2000 < decisions[0].sum() < 5000 and decisions[2].n_evictions > 500
+    px = B.Proximity(corpus_dev, w.dim, b, w.k, w.policy, 64, lsh_planes=torch.from_numpy(planes).to(DEV))
+    got = P.run_stream(px, q, tau, batch, DEV)
+    excused, n = check_against_decisions(got, decisions, q, px, MID_WINDOW, knn_ids, knn_d, corpus,
+                                         P.DIST_RTOL_F32, f"mid bucketed batch={batch}")
+    assert excused == 0 and n > 500
+    px.close()
+
+
+_MID_LSH = {}
 _MID_RERANK = {}
 
 
