@@ -1,0 +1,98 @@
+"""Seeded random configurations, GPU against the oracle: every switch of the interface drawn at random
+(dimension, k, capacity, policy, corpus type and size, re-ranking factor, bucketed or flat cache, tolerance,
+how the stream is cut into calls), on streams that mix rewordings at several radii, exact repeats and fresh
+vectors, so that distances fall on both sides of the tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import proximity_oracle as po
+from paper_2503_05530_amd import workloads as W
+
+import parity as P
+
+pytestmark = pytest.mark.gpu
+DEV = torch.device("cuda:0")
+
+
+def draw_case(seed):
+    rng = np.random.default_rng([seed, 99])
+    dim = int(rng.choice([32, 64, 96, 128, 384, 768]))
+    k = int(rng.choice([1, 3, 10, 17, 32]))
+    rho = int(rng.choice([1, 1, 2, 4]))
+    n_docs = int(rng.choice([0, 5, 700, 3000, 20000]))
+    bf16 = bool(rng.random() < 0.25) and n_docs > 0
+    lsh_bits = int(rng.choice([0, 0, 1, 3, 5]))
+    capacity = int(rng.choice([0, 1, 2, 7, 40])) if lsh_bits == 0 else int(rng.choice([1, 2, 5]))
+    policy = int(rng.choice([po.POLICY_FIFO, po.POLICY_LRU]))
+    n_bases = int(rng.choice([3, 12, 60]))
+    n = int(rng.choice([150, 400]))
+    tau = float(rng.choice([0.0, 0.05, 0.2, 0.45, 1e9]))
+    bases = W.unit_rows(rng.standard_normal((n_bases, dim)))
+    idx = rng.integers(0, n_bases, size=n)
+    radius = rng.choice([0.0, 0.03, 0.15, 0.3, 0.6], size=n)
+    q = W.unit_rows(bases[idx] + radius[:, None] * W.unit_rows(rng.standard_normal((n, dim)))).astype(np.float32)
+    repeats = rng.random(n) < 0.15                       # exact repeats of an earlier row
+    for t in np.flatnonzero(repeats):
+        if t > 0:
+            q[t] = q[rng.integers(0, t)]
+    cuts, r0 = [], 0
+    while r0 < n:
+        step = int(rng.choice([1, 2, 4, 5, 9, 33, 64, 200]))
+        cuts.append((r0, min(n, r0 + step)))
+        r0 += step
+    return dict(dim=dim, k=k, rho=rho, n_docs=n_docs, bf16=bf16, lsh_bits=lsh_bits, capacity=capacity, policy=policy,
+                tau=tau, q=q, cuts=cuts, seed=seed)
+
+
+@pytest.mark.parametrize("seed", range(80))
+def test_random_configuration(seed):
+    import paper_2503_05530_amd.binding as B
+    c = draw_case(seed)
+    dim, k, rho, q = c["dim"], c["k"], c["rho"], c["q"]
+    corpus = corpus_dev = None
+    if c["n_docs"] > 0:
+        x32 = W.corpus_f32(c["n_docs"], dim, seed)
+        if c["bf16"]:
+            corpus = W.bf16_bits_to_f32(W.f32_to_bf16_bits(x32))
+            corpus_dev = torch.from_numpy(x32).to(DEV).to(torch.bfloat16)
+        else:
+            corpus, corpus_dev = x32, torch.from_numpy(x32).to(DEV)
+    planes = W.lsh_planes(c["lsh_bits"], dim, seed) if c["lsh_bits"] and c["capacity"] else None
+    what = {key: v for key, v in c.items() if key not in ("q", "cuts")}
+
+    if corpus is None:
+        hit, src, dec = po.simulate_decisions(q, c["tau"], c["capacity"], c["policy"], planes=planes)
+        want = None
+    else:
+        want = po.lookup_stream_deferred(corpus, q, c["tau"], c["capacity"], k, c["policy"], rerank_factor=rho,
+                                         planes=planes)
+        hit, src, dec = want[2], want[3], want[4]
+
+    px = B.Proximity(corpus_dev, dim, c["capacity"], k, c["policy"], 256, device=DEV, rerank_factor=rho,
+                     lsh_planes=None if planes is None else torch.from_numpy(planes).to(DEV))
+    ids, dists, flags = [], [], []
+    for r0, r1 in c["cuts"]:
+        i, d, h = px.search_batch(torch.from_numpy(q[r0:r1]).to(DEV), c["tau"])
+        ids.append(i); dists.append(d); flags.append(h)
+    ids, dists, flags = (torch.cat(x).cpu().numpy() for x in (ids, dists, flags))
+    assert (flags == hit).all(), f"{what}: flags differ first at {np.flatnonzero(flags != hit)[:5]}"
+    if want is None:
+        assert (ids == -1).all() and np.isinf(dists).all()
+    else:
+        P.assert_stream_parity((ids, dists, flags), want[:4], corpus, q,
+                               dist_rtol=P.DIST_RTOL_BF16 if c["bf16"] else P.DIST_RTOL_F32, what=str(what),
+                               reranked=rho > 1)
+    seq, _, stored = px.cache_dump(want_ids=True)
+    assert seq.tolist() == dec.dump_seq().tolist(), what
+    if want is not None and len(seq):
+        if rho > 1:
+            want_stored = want[5][seq]
+            if c["n_docs"] >= rho * k + 8:          # away from padding, stored lists must agree outright
+                assert (stored == want_stored).all(), what
+        else:
+            assert (stored == ids[seq]).all(), what
+    st, os_ = px.stats(), dec.stats()
+    for key in ("queries", "hits", "misses", "inserts", "evictions", "size"):
+        assert st[key] == os_[key], (what, key)
+    px.close()
