@@ -184,19 +184,35 @@ def probe_microbench(args, torch, np, W, Proximity, device):
     for b0 in range(0, n_keys, batch):
         px.search_batch(keys[b0:b0 + batch], tau)
     mix = W.ProbeMix(dim, 0)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    total_ms, hits = 0.0, 0
+    # Pass 1 (untimed) draws the batches: each is drawn against the keys resident when it arrives, so the
+    # library's own cache is read back between calls.  Pass 2 clears the cache, warms it the same way and
+    # replays the recorded batches back to back: the same states recur, and the timed calls are not
+    # separated by host work (an idle GPU drops its clocks and the short kernels of a call would be timed slow).
+    batches = []
     for step in range(warmup + steps):
-        _, resident, _ = px.cache_dump(want_keys=True)     # the batch is drawn against the keys resident now
+        _, resident, _ = px.cache_dump(want_keys=True)
         q = torch.from_numpy(mix.batch(resident, batch)).to(device)
-        torch.cuda.synchronize(device)
-        ev0.record()
-        _, _, hit = px.search_batch(q, tau)
-        ev1.record()
-        torch.cuda.synchronize(device)
-        if step >= warmup:
-            total_ms += ev0.elapsed_time(ev1)
-            hits += int(hit.sum().item())
+        px.search_batch(q, tau)
+        batches.append(q)
+    sizes_1 = px.stats()
+    px.clear()
+    for b0 in range(0, n_keys, batch):
+        px.search_batch(keys[b0:b0 + batch], tau)
+    out_ids = torch.empty((batch, 1), dtype=torch.int64, device=device)
+    out_hit = torch.empty((warmup + steps, batch), dtype=torch.uint8, device=device)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for step in range(warmup):
+        px.search_batch(batches[step], tau, out_ids=out_ids, out_hit=out_hit[step], want_dists=False)
+    torch.cuda.synchronize(device)
+    ev0.record()
+    for step in range(warmup, warmup + steps):
+        px.search_batch(batches[step], tau, out_ids=out_ids, out_hit=out_hit[step], want_dists=False)
+    ev1.record()
+    torch.cuda.synchronize(device)
+    total_ms = ev0.elapsed_time(ev1)
+    hits = int(out_hit[warmup:].sum().item())
+    sizes_2 = px.stats()
+    assert all(sizes_1[key] == sizes_2[key] for key in ("hits", "misses", "evictions", "size")), "replay diverged"
     flops = 2.0 * batch * (n_keys + batch) * dim
     ms = total_ms / steps
     if planes is not None:

@@ -22,30 +22,50 @@ constexpr int kLshMaxBucket = 256;   // keys per bucket the resolver's LDS array
 constexpr int kLshRowBits = 13;      // batch rows are numbered below 2^13 (the largest batch)
 
 // ---------------------------------------------------------------------------
-// Hash codes.  One wave per row: bit i of code[row] is 1 exactly when q . r_i >= 0, with the
-// inner product accumulated in float64 (the sign is the decision here).
+// Hash codes.  One wave per four rows: bit i of code[row] is 1 exactly when q . r_i >= 0, with the
+// inner product accumulated in float64 (the sign is the decision here).  The normals are read
+// once per four rows and four of them are in flight together with the four rows' values.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void lsh_codes_kernel(const float* __restrict__ Q, int n, int dim,
                                                         const float* __restrict__ planes, int n_bits,
                                                         int* __restrict__ code) {
+  constexpr int R = 4;  // rows per wave
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= n) return;
-  const float* q = Q + long(row) * dim;
-  int c = 0;
-  for (int b0 = 0; b0 < n_bits; b0 += 4) {  // four planes at a time, so that their loads overlap
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int i = lane; i < dim; i += 64) {
-      const double qv = double(q[i]);
+  const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * R;
+  if (row0 >= n) return;
+  const float* q[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) q[r] = Q + long(row0 + r < n ? row0 + r : n - 1) * dim;
+  int c[R] = {0, 0, 0, 0};
+  for (int b0 = 0; b0 < n_bits; b0 += 4) {
+    double acc[4][R];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int r = 0; r < R; ++r) acc[u][r] = 0.0;
+    for (int x = lane; x < dim; x += 64) {
+      float qv[R], pv[4];
+#pragma unroll
+      for (int r = 0; r < R; ++r) qv[r] = q[r][x];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) pv[u] = b0 + u < n_bits ? planes[long(b0 + u) * dim + x] : 0.f;
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        if (b0 + u < n_bits) acc[u] += qv * double(planes[long(b0 + u) * dim + i]);
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[u][r] += double(qv[r]) * double(pv[u]);
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-      if (b0 + u < n_bits && wave_sum(acc[u]) >= 0.0) c |= 1 << (b0 + u);
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        if (b0 + u < n_bits && wave_sum(acc[u][r]) >= 0.0) c[r] |= 1 << (b0 + u);
   }
-  if (lane == 0) code[row] = c;
+  if (lane < R && row0 + lane < n) {
+    int mine = c[0];
+#pragma unroll
+    for (int r = 1; r < R; ++r) mine = lane == r ? c[r] : mine;
+    code[row0 + lane] = mine;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -138,6 +158,14 @@ __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
   __shared__ int s_size;                       // live keys of the bucket
   __shared__ int s_slot;                       // local slot the current row takes when it misses
   const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  // Inside the row loop only LDS traffic has to be ordered between the waves when the keys live in
+  // LDS; a full __syncthreads() would also wait for the next row's vector, which is fetched ahead on purpose.
+  auto row_barrier = [&]() {
+    if (keys_in_lds)
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else
+      __syncthreads();
+  };
 
   const int slot0 = code * b;
   float* bucket_keys = srcs + long(slot0) * dim;
@@ -181,7 +209,7 @@ __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
       if (x < dim) lq[x] = qreg[u];
     }
     const int size = s_size;
-    __syncthreads();
+    row_barrier();
     const bool more = e_nxt != kNone && int(e_nxt >> kLshRowBits) == code;
     uint32_t e_nn = kNone;
     if (more) {
@@ -203,7 +231,7 @@ __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
       acc = wave_sum(acc);
       if (lane == 0) d64[s] = sqrt(acc);
     }
-    __syncthreads();
+    row_barrier();
     if (tid < 64) {
       ResolverBest best{__longlong_as_double(0x7ff0000000000000ll), 0x7fffffffffffffffll, -1};
       for (int s = lane; s < size; s += 64) {
@@ -258,7 +286,7 @@ __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
         }
       }
     }
-    __syncthreads();
+    row_barrier();
     if (s_best < 0) {  // the new key goes into its slot at once: later rows of the bucket compare against it
       const int t = s_slot;
       float* dst = bucket_keys + long(t) * dim;
@@ -268,12 +296,13 @@ __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
         if (keys_in_lds) lkeys[t * dim + x] = v;
       }
     }
-    __syncthreads();  // the new key is in place, and lq may be overwritten by the next row
+    row_barrier();  // the new key is in place, and lq may be overwritten by the next row
     if (!more) break;
     e_cur = e_nxt;
     e_nxt = e_nn;
   }
 
+  __syncthreads();
   const int size1 = s_size;
   for (int s = tid; s < size1; s += kLshThreads) {
     slot_seq[slot0 + s] = lseq[s];

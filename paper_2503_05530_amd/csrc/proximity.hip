@@ -634,7 +634,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   if (lsh) {
     // Section 3.2: codes, regrouping by code, one block per bucket that occurs, miss list in row order
     const int b = int(h->cfg.capacity);
-    lsh_codes_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(batch_rows, nn, dim, h->lsh_planes, h->lsh_bits,
+    lsh_codes_kernel<<<dim3((nn + 15) / 16), dim3(256), 0, s>>>(batch_rows, nn, dim, h->lsh_planes, h->lsh_bits,
                                                               h->lsh_code);
     lsh_group_kernel<<<dim3(1), dim3(1024), 0, s>>>(h->lsh_code, nn, h->lsh_sorted, h->lsh_seg_start, h->lsh_n_segs);
     const int max_segs = nn < (1 << h->lsh_bits) ? nn : (1 << h->lsh_bits);  // distinct codes a batch can have
