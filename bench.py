@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 F32_MFMA_PEAK_TFLOPS = 157.3   # MI355X dense float32 matrix, published
+BF16_MFMA_PEAK_TFLOPS = 2500.0 # MI355X dense bfloat16 matrix, published
 
 
 def parse_args():
@@ -106,9 +107,16 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
     avg_q = sum(q for _, q in busy) / len(busy)
     gbs = bytes_per_launch / (avg_ms * 1e-3) / 1e9
     tflops = sum(2.0 * q * n_docs * dim for _, q in busy) / (sum(ms for ms, _ in busy) * 1e-3) / 1e12
-    ridge_q = F32_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) * elem_bytes / 2   # queries per launch at the ridge
+    # a bfloat16 corpus is scanned on the bfloat16 matrix cores with the queries split into three bfloat16
+    # terms: three multiply-adds of that type per term of the inner product
+    bf16x3 = elem_bytes == 2 and dim >= 64 and batch > 4
+    mfma_peak = BF16_MFMA_PEAK_TFLOPS if bf16x3 else F32_MFMA_PEAK_TFLOPS
+    per_term = 3.0 if bf16x3 else 1.0
+    ridge_q = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9) * elem_bytes / (2 * per_term)  # queries per launch at the ridge
     if batch <= 4:
         kernel = "scores_stream_kernel"
+    elif bf16x3:
+        kernel = "scan_bf16x3_kernel"
     else:
         kernel = "scan_mfma_dma_kernel" if elem_bytes == 4 and dim >= 64 else "scan_mfma_topk_kernel"
     tile = 0 if batch <= 4 else (32 if avg_q <= 32 else 64 if avg_q <= 64 else 128)
@@ -117,13 +125,15 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
               "traffic_counters": counted, "kernel": kernel,
               "launches_timed": len(busy), "avg_launch_ms": round(avg_ms, 5),
               "queries_per_launch_avg": round(avg_q, 3), "achieved_GBps": round(gbs, 1),
-              "achieved_TFLOPs": round(tflops, 2), "algorithmic_bytes_per_launch": bytes_per_launch,
-              "algorithmic_flops_per_launch_avg": 2.0 * avg_q * n_docs * dim}
+              "achieved_TFLOPs": round(tflops * per_term, 2), "algorithmic_bytes_per_launch": bytes_per_launch,
+              "algorithmic_flops_per_launch_avg": 2.0 * per_term * avg_q * n_docs * dim,
+              "float32_equivalent_TFLOPs": round(tflops, 2)}
     if avg_q < ridge_q:
         return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gbs / HBM_PEAK_GBS, 4), **common}
-    return {"bound": "mfma", "achieved": round(tflops, 2), "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(tflops / F32_MFMA_PEAK_TFLOPS, 4), **common}
+    return {"bound": "mfma", "achieved": round(tflops * per_term, 2), "peak": mfma_peak, "unit": "TFLOP/s",
+            "frac": round(tflops * per_term / mfma_peak, 4),
+            "mfma_dtype": "bf16 x3 split, f32 accumulate" if bf16x3 else "f32", **common}
 
 
 def recall_sweep(args, torch, np, W, Proximity, device):
@@ -349,11 +359,25 @@ def main():
                          f"replay of rows 0..{first - 1}; {int((o_hit == 0).sum())} misses, "
                          f"{cdt:.1f} s, float64 numpy (single-threaded element-wise code)",
                "host_cpus": os.cpu_count()}
+        # the two pieces on their own, oracle code as it stands: one cache probe (distances to c keys and the
+        # nearest) at two cache sizes, and one database call (all distances and the ranking) on this corpus
+        parts = {}
+        for c_keys in (300, 10000):
+            keys64 = po.as_f64_rows(corpus[:c_keys])
+            t0 = time.perf_counter()
+            for t in range(20):
+                po.l2_distances(queries[t], keys64).argmin()
+            parts[f"probe_us_c{c_keys}"] = round((time.perf_counter() - t0) / 20 * 1e6, 1)
+        t0 = time.perf_counter()
+        po.exact_knn(corpus, queries[0], w.k)
+        parts[f"scan_s_{n_docs}_docs"] = round(time.perf_counter() - t0, 3)
+        cpu["parts"] = parts
 
     line = {
         "metric": "retrieval_queries_per_sec", "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(1e3 * dt / steps, 5), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if (elem == 2 and w.dim >= 64 and batch > 4) else "f32",
+        "data": "synthetic",
         "config": {"workload": f"{w.name}: corpus {n_docs}x{w.dim} {'bf16' if elem == 2 else 'f32'} unit Gaussian, "
                                f"{w.choice}({w.zipf_s}) stream of "
                                f"{w.n_stream} over {w.n_bases} bases (perturbation {w.radius}), capacity "

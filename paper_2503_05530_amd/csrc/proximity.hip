@@ -26,6 +26,7 @@
 #include "cache_kernels.hpp"
 #include "lsh_kernels.hpp"
 #include "mfma_kernels.hpp"
+#include "bf16x3_kernels.hpp"
 #include "resolver_lds.hpp"
 #include "scan_kernels.hpp"
 #include "select_kernels.hpp"
@@ -95,6 +96,7 @@ struct proximity {
   uint64_t* pairs[2] = {nullptr, nullptr};
   long pairs_elems = 0;
   uint64_t* topk_buf = nullptr;  // batched scan: [query tiles][scan blocks][tile queries][kTopkCap]
+  uint16_t* qplanes = nullptr;   // bfloat16 corpus: the three bfloat16 planes of a call's queries, [3][max_batch][dim]
   int scan_blocks = 1;           // blocks that share the corpus in the batched scan
   int64_t* res_ids = nullptr;
   float* res_d = nullptr;
@@ -254,6 +256,29 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
   const int dim = int(h->cfg.dim);
   const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
   const bool dma = !bf16 && dim >= 64;  // the global->LDS pipeline needs float32 rows and two slabs per tile
+  if (bf16 && dim >= 64) {
+    // bfloat16 rows: three-term split of the queries on the bfloat16 matrix cores (planes written by the
+    // caller); the tile shape for up to 64 queries, and the one for more
+    const long plane_stride = long(h->cfg.max_batch) * dim;
+    const uint16_t* X16 = static_cast<const uint16_t*>(h->cfg.corpus);
+    const bool known = m_count_ptr == nullptr;
+#define PROX_SCAN16(TM, LO, HI)                                                                                 \
+  do {                                                                                                          \
+    const dim3 grid(G, (span + TM - 1) / TM);                                                                   \
+    if (dump_all)                                                                                               \
+      scan_bf16x3_kernel<TM, true><<<grid, dim3(TM * 4), 0, s>>>(X16, h->xnrm, n_rows, dim, h->qplanes,        \
+                                                                  plane_stride, m_count_ptr, m_limit, base, LO, \
+                                                                  HI, kp, seed, h->topk_buf, out);              \
+    else                                                                                                        \
+      scan_bf16x3_kernel<TM, false><<<grid, dim3(TM * 4), 0, s>>>(X16, h->xnrm, n_rows, dim, h->qplanes,       \
+                                                                   plane_stride, m_count_ptr, m_limit, base,    \
+                                                                   LO, HI, kp, seed, h->topk_buf, out);         \
+  } while (0)
+    if (!known || m_limit <= 64) PROX_SCAN16(64, 0, 64);
+    if (m_limit > 64) PROX_SCAN16(128, 64, 0x7fffffff);
+#undef PROX_SCAN16
+    return;
+  }
 #define PROX_SCAN(TM, TN, LO, HI)                                                                              \
   do {                                                                                                         \
     const dim3 grid(G, (span + TM - 1) / TM);                                                                  \
@@ -351,10 +376,13 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     // valid bound for the whole corpus and lets the full scan drop almost every row at once
     // instead of learning a bound block by block.  Then the full scan, then the merge.
     const uint64_t* seed = nullptr;
+    if (bf16 && dim >= 64)
+      split_bf16x3_kernel<<<dim3(m_limit), dim3(256), 0, s>>>(Qbase, qlist, m_count_ptr, m_limit, dim, h->qplanes,
+                                                               long(h->cfg.max_batch) * dim);
     if (N >= 8L * kSeedRows) {
       const int gs = kSeedRows / 128;
-      // float32 rows: the head's scores are written out whole and merged; otherwise per-block lists
-      const bool dump_seed = !bf16 && dim >= 64;
+      // the head's scores are written out whole and merged; rows of 32 columns only: per-block lists
+      const bool dump_seed = dim >= 64;
       for (int base = 0; base < m_limit; base += kScanPassQueries) {
         const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
         launch_batched_scan(h, kSeedRows, gs, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, nullptr,
@@ -489,6 +517,7 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     if (size_t(kSeedRows + kp - 1) / kp > lists) lists = size_t(kSeedRows + kp - 1) / kp;  // dumped head scores
     const size_t pass_q = (B < size_t(kScanPassQueries) ? B : size_t(kScanPassQueries)) + 127;
     TRY_ALLOC(h->topk_buf, size_t(h->scan_blocks) * pass_q * kTopkCap, false);
+    if (cfg->corpus_dtype == PROXIMITY_DTYPE_BF16) TRY_ALLOC(h->qplanes, 3 * B * d, true);
   }
   h->pairs_elems = long(B * lists * kp);
   TRY_ALLOC(h->pairs[0], size_t(h->pairs_elems), false);
