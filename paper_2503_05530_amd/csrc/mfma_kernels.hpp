@@ -338,8 +338,9 @@ __device__ __forceinline__ float f4_get(const float4& v, int e) {
 //  * a ring of three stages: while slab s is multiplied, slabs s+1 and s+2 are
 //    in flight, and one barrier per slab suffices (it both publishes slab s and
 //    retires the stage that slab s+2 will overwrite);
-//  * a stage is (TN + TM) x 128 bytes = 24 KiB at most, so two blocks fit a CU
-//    and hide each other's barriers.
+//  * a stage is (TN + TM) x 128 bytes = 24 KiB, so two blocks fit a CU and hide each
+//    other's barriers (TM = 96: 28 KiB, one block per CU; still quicker than padding
+//    65..96 queries to the 128-query shape).
 // The compaction scratch is the stage that was consumed last, which stays free
 // until the next slab's loads are issued.
 // DUMP = true turns the selection off: every score is written as a key to
@@ -357,7 +358,7 @@ __device__ __forceinline__ void lds_dma16_once(const float* gptr, float* lds_wav
 }
 
 template <int TM, bool DUMP>
-__global__ __launch_bounds__(256, 2) void scan_mfma_dma_kernel(
+__global__ __launch_bounds__(256, TM == 96 ? 1 : 2) void scan_mfma_dma_kernel(
     const float* __restrict__ X, const float* __restrict__ xnrm, long n_rows, int dim,
     const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
     int m_limit, int m_base, int m_lo, int m_hi, int kp, const uint64_t* __restrict__ seed,

@@ -302,7 +302,12 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
   const bool known = m_count_ptr == nullptr;  // then M = m_limit and only its own shape is launched
   if (!known || m_limit <= 32) PROX_SCAN(32, 256, 0, 32);
   if (m_limit > 32 && (!known || m_limit <= 64)) PROX_SCAN(64, 256, 32, 64);
-  if (m_limit > 64) PROX_SCAN(128, 128, 64, 0x7fffffff);
+  if (dma) {  // 96 queries: three accumulator blocks per wave, one block per CU (84 KiB ring)
+    if (m_limit > 64 && (!known || m_limit <= 96)) PROX_SCAN(96, 128, 64, 96);
+    if (m_limit > 96) PROX_SCAN(128, 128, 96, 0x7fffffff);
+  } else if (m_limit > 64) {
+    PROX_SCAN(128, 128, 64, 0x7fffffff);
+  }
 #undef PROX_SCAN
 }
 

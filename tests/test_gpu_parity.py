@@ -35,7 +35,7 @@ def gpu_corpus(x: np.ndarray, bf16=False):
     (700, 64, 7, 2), (70000, 768, 10, 13), (3, 32, 5, 2), (8191, 1024, 16, 4), (300, 4096, 3, 8),
     # more than 8 queries: matrix-core scan, one tile shape per range of query counts
     (50000, 768, 10, 9), (50000, 768, 10, 40), (50011, 768, 32, 100), (30000, 768, 10, 300),
-    (1000, 64, 7, 20), (200, 32, 100, 70), (131, 96, 5, 129),
+    (1000, 64, 7, 20), (200, 32, 100, 70), (131, 96, 5, 129), (40000, 768, 10, 80), (40000, 128, 32, 96),
 ])
 def test_knn_matches_oracle_f32(B, n_docs, dim, k, nq):
     corpus = W.corpus_f32(n_docs, dim, 3)
