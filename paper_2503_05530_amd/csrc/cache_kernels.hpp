@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256) void probe_candidates_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Order-preserving resolver: lines 2-9 of Algorithm 1 for rows 0..n-1 in order,
+// Order-preserving resolver: Algorithm 1 after the distances (nearest key, tolerance test,
+// eviction, insertion) for rows 0..n-1 in order,
 // given every row's candidate sources.  One wave walks the rows; the only
 // sequential state is which sources are live and the eviction order (a doubly
 // linked list over slots: FIFO appends on insert, LRU also moves a slot to the

@@ -5,8 +5,8 @@
 // Slots are laid out bucket by bucket: bucket g owns slots g*b .. g*b+b-1 and fills them in
 // index order, so its live slots are always the first `size[g]`.  Buckets do not interact, so a
 // batch is regrouped by code (keeping row order inside a code) and every bucket that occurs is
-// walked by its own block, rows in order, exactly as lines 2-9 of Algorithm 1 prescribe for one
-// cache; different buckets run side by side.  A bucket holds a few dozen keys, so the block
+// walked by its own block, rows in order, exactly as Algorithm 1 prescribes for one cache (nearest
+// key, tolerance test, eviction, insertion); different buckets run side by side.  A bucket holds a few dozen keys, so the block
 // computes the distances to all of them directly in float64 (direct-difference form) and there is
 // no pre-filter.  A key is written into its slot at once (the block owns the bucket), so later
 // rows of the batch simply find it there; its value arrives after the scan, which is why a hit on

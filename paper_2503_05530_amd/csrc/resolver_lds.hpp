@@ -1,4 +1,5 @@
-// The order-preserving resolver (lines 2-9 of Algorithm 1, rows in order) with its
+// The order-preserving resolver (Algorithm 1 after the distances: nearest key, tolerance test,
+// eviction, insertion; rows in order) with its
 // sequential state in LDS.  Same inputs, outputs and decisions as resolver_kernel.
 //
 // Walking thousands of rows one after the other, every dependent access to global
