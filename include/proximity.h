@@ -64,8 +64,8 @@ enum { PROXIMITY_POLICY_FIFO = 0, PROXIMITY_POLICY_LRU = 1 };
 typedef struct proximity proximity_t;
 
 /*
- * Parameters fixed for the life of an instance (Algorithm 1 "stored state";
- * Section 3.1: k is "picked at the start"; Section 3.3.1: capacity c;
+ * Parameters fixed for the life of an instance (the state Algorithm 1 keeps
+ * between queries; Section 3.1: k is chosen once; Section 3.3.1: capacity c;
  * Section 3.3.2: eviction policy).
  */
 typedef struct proximity_config {

@@ -38,7 +38,7 @@ lists order equal distances by document index and are padded with -1 / +inf
 when the index holds fewer than k vectors; capacity 0 disables caching; with
 rho > 1 a hit ranks by (distance to the current query, document index) and
 reports those distances, and rho is a whole number; an inner product of
-exactly zero gives hash bit 1 (the paper's ">= 0"), bit i of the code has
+exactly zero gives hash bit 1 (the hash formula of Section 3.2 includes zero), bit i of the code has
 weight 2^i, and L = 0 means a single bucket.
 
 Parity status: every function here is pinned by tests that do not re-use its
