@@ -148,10 +148,9 @@ __global__ __launch_bounds__(TM * 4, TM == 128 ? 1 : 2) void scan_bf16x3_kernel(
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       const float* g = reinterpret_cast<const float*>(src[i] + islab * kSlabBf16);
-      if (is_x[i])
-        lds_dma16_once(g, base + i * 256);  // corpus rows: streamed once
-      else
-        lds_dma16(g, base + i * 256);       // query planes: re-read by every block
+      // A slab takes 64 bytes of a row, half a cache line: the other half is wanted by the next slab,
+      // so corpus rows are not marked read-once here (that would drop the line in between and fetch it twice).
+      lds_dma16(g, base + i * 256);
     }
     ++is;
     if (++islab == n_slabs) {
