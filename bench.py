@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--cpu-sample", type=int, default=24, help="queries the oracle is timed on")
     ap.add_argument("--recall-sweep", action="store_true",
                     help="hit rate and database k-recall (Section 4) over tau, flat and bucketed cache, then exit")
+    ap.add_argument("--probe-scaling", action="store_true",
+                    help="cache lookup time against the number of cached keys, flat and bucketed (Section 4.4), then exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for HBM byte counters)")
     return ap.parse_args()
@@ -183,6 +185,41 @@ def recall_sweep(args, torch, np, W, Proximity, device):
                       "config": {"workload": w.name, "queries": n_q, "batch": batch, "k": w.k}, "rows": rows}))
 
 
+def probe_scaling(args, torch, np, W, Proximity, device):
+    """Lookup time of the cache alone (no corpus) as the number of cached keys grows: the flat cache compares
+    a query with every key, the bucketed one with one bucket of 20 (Section 3.2's cost argument, Section 4.4's
+    measurement).  Per size: fill the cache with fresh unit vectors, then time calls of 1 and of 1 024 fresh
+    queries at a tolerance nothing meets (every row is compared, misses, and replaces a key)."""
+    dim, tau = W.PROBE_DIM, 0.05
+    rows = []
+    g = torch.Generator(device=device)
+    g.manual_seed(1234)
+    fresh = lambda n: torch.nn.functional.normalize(torch.randn(n, dim, device=device, generator=g), dim=1)
+    for n_keys in (320, 1280, 5120, 20480, 81920):
+        bits = max(1, (n_keys // 20 - 1).bit_length())            # buckets of 20: 2^bits * 20 >= n_keys
+        planes = torch.from_numpy(W.lsh_planes(bits, dim, 0)).to(device)
+        for name, px in (("flat", Proximity(None, dim, n_keys, 1, W.POLICY_LRU, 1024, device=device)),
+                         (f"bucketed 2^{bits} x 20", Proximity(None, dim, 20, 1, W.POLICY_LRU, 1024, device=device,
+                                                                lsh_planes=planes))):
+            for b0 in range(0, 4 * n_keys, 1024):                  # four times the capacity: buckets fill up too
+                px.search_batch(fresh(1024), tau)
+            entry = {"cache": name, "capacity": n_keys, "resident": px.stats()["size"]}
+            for batch, calls in ((1, 300), (1024, 20)):
+                qs = [fresh(batch) for _ in range(calls)]
+                out_ids = torch.empty((batch, 1), dtype=torch.int64, device=device)
+                out_hit = torch.empty((batch,), dtype=torch.uint8, device=device)
+                torch.cuda.synchronize(device)
+                t0 = time.perf_counter()
+                for q in qs:
+                    px.search_batch(q, tau, out_ids=out_ids, out_hit=out_hit, want_dists=False)
+                torch.cuda.synchronize(device)
+                entry[f"us_per_query_batch{batch}"] = round((time.perf_counter() - t0) / (calls * batch) * 1e6, 3)
+            rows.append(entry)
+            px.close()
+    print(json.dumps({"metric": "cache_lookup_time_vs_capacity", "unit": "us per query", "n_gpus": 1,
+                      "data": "synthetic", "config": {"dim": dim, "tau": tau, "policy": "LRU"}, "rows": rows}))
+
+
 def probe_microbench(args, torch, np, W, Proximity, device):
     """Cache probe alone: 10 000 resident keys, batches of 4 096 queries, no corpus behind the cache."""
     n_keys, dim, batch, tau = W.PROBE_KEYS, W.PROBE_DIM, W.PROBE_BATCH, W.PROBE_TAU
@@ -280,6 +317,8 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4,
                           "copies": 5}))
         return
+    if args.probe_scaling:
+        return probe_scaling(args, torch, np, W, Proximity, device)
     if args.workload == "probe":
         return probe_microbench(args, torch, np, W, Proximity, device)
     if args.recall_sweep:
