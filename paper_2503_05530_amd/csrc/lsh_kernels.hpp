@@ -323,6 +323,143 @@ __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Calls with a handful of rows (n <= kSmallRows): the whole cache side of the bucketed cache in
+// one launch of one block.  Rows in order; per row the code (one wave per hyperplane), the
+// float64 distances to the keys of its bucket, the decision and the update of that bucket, all
+// in device memory (the block is alone, a barrier orders its own writes and reads).  Rows that
+// hit a key stored before the call are answered from the stored lists at the end, as
+// probe_resolve_small_kernel does; hits on rows of the same call and misses are routed by the
+// selection kernel.  Rows are read from the caller's buffer.  b <= kLshMaxBucket.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void lsh_small_kernel(
+    const float* __restrict__ queries, int n, int b, int c_total, int dim, int k, int K, int n_bits,
+    const float* __restrict__ planes, int policy_lru, long long base_seq, double tau, float* srcs,
+    long long* slot_seq, int* slot_next, int* slot_prev, int* bkt_size, int* bkt_head, int* bkt_tail, CacheState* st,
+    const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, const void* __restrict__ X,
+    int corpus_dtype, uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
+    int* __restrict__ miss_count, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
+  __shared__ uint64_t keys[kLshMaxBucket];
+  __shared__ double d64[kLshMaxBucket];
+  __shared__ int cid[kLshMaxBucket];
+  __shared__ int s_bits[kLshMaxBits];
+  __shared__ int s_best, s_slot;
+  const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  for (int s = tid; s < b; s += 1024) keys[s] = pack_key(0.f, uint32_t(s));
+  int hits = 0, misses = 0, inserts = 0, evictions = 0, inbatch = 0, M = 0;  // kept by thread 0
+
+  for (int i = 0; i < n; ++i) {
+    const float* q = queries + long(i) * dim;
+    // code: wave w takes hyperplane w
+    if (wib < n_bits) {
+      double acc = 0.0;
+      for (int x = lane; x < dim; x += 64) acc += double(q[x]) * double(planes[long(wib) * dim + x]);
+      acc = wave_sum(acc);
+      if (lane == 0) s_bits[wib] = acc >= 0.0 ? 1 << wib : 0;
+    }
+    __syncthreads();
+    int code = 0;
+    for (int w = 0; w < n_bits; ++w) code |= s_bits[w];
+    const int slot0 = code * b;
+    float* bucket_keys = srcs + long(slot0) * dim;
+    const int size = bkt_size[code];
+    block_candidate_distances<kDtypeF32, 16>(keys, size, q, bucket_keys, dim, d64, cid, tid);
+    __syncthreads();
+    if (tid < 64) {
+      ResolverBest best{__longlong_as_double(0x7ff0000000000000ll), 0x7fffffffffffffffll, -1};
+      for (int s = lane; s < size; s += 64) {
+        const double d = d64[s];
+        if (d <= tau) best_take(best, d, slot_seq[slot0 + s], s);
+      }
+      best_wave_reduce(best);
+      if (lane == 0) {
+        int head = bkt_head[code], tail = bkt_tail[code];
+        const int sb = best.src;
+        s_best = sb;
+        if (sb >= 0) {
+          const int t = slot0 + sb;
+          ++hits;
+          const long long sq = slot_seq[t];
+          if (sq >= base_seq) ++inbatch;
+          if (policy_lru && t != tail) {
+            const int p = slot_prev[t], nx = slot_next[t];  // nx >= 0 because t is not the tail
+            if (p >= 0) slot_next[p] = nx;
+            slot_prev[nx] = p;
+            slot_prev[t] = tail;
+            slot_next[t] = -1;
+            slot_next[tail] = t;
+            if (p < 0) head = nx;
+            tail = t;
+          }
+          hit_out[i] = 1;
+          src_out[i] = sq >= base_seq ? c_total + int(sq - base_seq) : t;
+          row_slot[i] = -1;
+        } else {
+          ++misses;
+          int t;
+          if (size < b) {
+            t = slot0 + size;
+            bkt_size[code] = size + 1;
+          } else {
+            t = head;
+            head = slot_next[t];
+            if (head >= 0) slot_prev[head] = -1;
+            if (head < 0) tail = -1;
+            ++evictions;
+          }
+          slot_seq[t] = base_seq + i;
+          slot_prev[t] = tail;
+          slot_next[t] = -1;
+          if (tail >= 0) slot_next[tail] = t;
+          if (tail < 0) head = t;
+          tail = t;
+          ++inserts;
+          hit_out[i] = 0;
+          src_out[i] = -1;
+          row_slot[i] = t;
+          miss_list[M++] = i;
+          s_slot = t;
+        }
+        bkt_head[code] = head;
+        bkt_tail[code] = tail;
+      }
+    }
+    __syncthreads();
+    if (s_best < 0) {
+      float* dst = srcs + long(s_slot) * dim;
+      for (int x = tid; x < dim; x += 1024) dst[x] = q[x];
+    }
+    __syncthreads();  // this row's key, links and counts are in place for the next row
+  }
+  if (tid == 0) {
+    st->size += inserts - evictions;
+    st->queries += (unsigned long long)n;
+    st->hits += (unsigned long long)hits;
+    st->misses += (unsigned long long)misses;
+    st->inserts += (unsigned long long)inserts;
+    st->evictions += (unsigned long long)evictions;
+    st->inbatch_hits += (unsigned long long)inbatch;
+    *miss_count = M;
+  }
+  // hits on keys stored before the call: the stored list, or (re-ranking factor above 1) the stored
+  // documents nearest to the row's own query
+  for (int i = 0; i < n; ++i) {
+    if (!hit_out[i]) continue;
+    const int s = src_out[i];
+    if (s >= c_total) continue;
+    if (K == k || X == nullptr) {
+      for (int e = tid; e < k; e += 1024) {
+        out_ids[long(i) * k + e] = val_ids[long(s) * K + e];
+        if (out_d) out_d[long(i) * k + e] = val_d[long(s) * K + e];
+      }
+    } else {
+      __syncthreads();
+      block_rerank_stored_any<1024>(corpus_dtype, val_ids + long(s) * K, K, k, queries + long(i) * dim, X, dim,
+                                    out_ids + long(i) * k, out_d ? out_d + long(i) * k : nullptr, keys, d64, cid, tid);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // The rows that missed, in row order, and their number.  One block of 1024 threads, n <= 2^13.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void lsh_miss_list_kernel(const uint8_t* __restrict__ hit, int n,

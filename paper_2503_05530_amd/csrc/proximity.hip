@@ -664,6 +664,22 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     return check_launch(h, "proximity_search_batch");
   }
 
+  if (lsh && nn <= kSmallRows && h->cfg.n_docs > 0) {
+    // A handful of rows on the bucketed cache: the cache side in one launch, then the same scan,
+    // selection and routing launches as for the flat cache.
+    lsh_small_kernel<<<dim3(1), dim3(1024), 0, s>>>(
+        queries, nn, int(h->cfg.capacity), c, dim, kk, K, h->lsh_bits, h->lsh_planes,
+        h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->srcs, h->slot_seq, h->slot_next,
+        h->slot_prev, h->bkt_size, h->bkt_head, h->bkt_tail, h->state, h->val_ids, h->val_d, h->cfg.corpus,
+        int(h->cfg.corpus_dtype), out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
+    const SmallRouting rt{out_hit, h->src, h->row_slot, h->slot_seq, h->val_ids, h->val_d, base_seq, nn, c};
+    rc = enqueue_scan(h, queries, h->miss_list, h->miss_count, nn, K, kk, out_ids, out_dists, &rt, s);
+    if (rc != PROXIMITY_OK) return rc;
+    h->next_seq += n;
+    if (h->prof_on) ++h->prof_call;
+    return check_launch(h, "proximity_search_batch");
+  }
+
   HIP_TRY(h, hipMemcpyAsync(batch_rows, queries, size_t(n) * dim * sizeof(float), hipMemcpyDeviceToDevice, s));
   if (lsh) {
     // Section 3.2: codes, regrouping by code, one block per bucket that occurs, miss list in row order
