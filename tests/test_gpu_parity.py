@@ -331,6 +331,32 @@ def test_bucketed_with_reranking_and_clear(B, tiny):
     px.close()
 
 
+@pytest.mark.parametrize("dim,bits,b,batch", [
+    (64, 16, 4, 512),       # the most hyperplanes
+    (64, 1, 256, 300),      # the largest bucket
+    (1024, 2, 64, 128),     # a bucket whose keys do not fit on chip: distances read from device memory
+    (4096, 1, 3, 4),        # the largest dimension, calls of four rows
+])
+def test_bucketed_limits(B, dim, bits, b, batch):
+    rng = np.random.default_rng(dim + bits)
+    planes = W.lsh_planes(bits, dim, 3)
+    n_bases = 150 if (b << bits) >= 100 else 8          # a cache of six entries wants a small working set
+    base = W.unit_rows(rng.standard_normal((n_bases, dim)))
+    idx = rng.integers(0, n_bases, size=1500)
+    q = W.unit_rows(base[idx] + rng.choice([0.0, 0.1, 0.4], size=1500)[:, None]
+                    * W.unit_rows(rng.standard_normal((1500, dim)))).astype(np.float32)
+    corpus = W.corpus_f32(300, dim, 5)
+    want = po.lookup_stream_deferred(corpus, q, 0.3, b, 2, po.POLICY_LRU, planes=planes)
+    assert 100 < want[2].sum() < 1400
+    px = B.Proximity(gpu_corpus(corpus), dim, b, 2, po.POLICY_LRU, 512, lsh_planes=torch.from_numpy(planes).to(DEV))
+    got = P.run_stream(px, q, 0.3, batch, DEV)
+    P.assert_stream_parity(got, want[:4], corpus, q, what=f"bucketed {dim}/{bits}/{b}")
+    seq, _, _ = px.cache_dump()
+    assert seq.tolist() == want[4].dump_seq().tolist()
+    assert px.stats()["evictions"] == want[4].n_evictions
+    px.close()
+
+
 def test_bucketed_probe_at_scale_without_corpus(B):
     """1024 buckets of 20 entries, calls of 8192 rows: flags and cache contents against the oracle's decisions."""
     dim, bits, b, tau = 128, 10, 20, 0.4
