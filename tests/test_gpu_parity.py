@@ -471,3 +471,29 @@ def test_same_batch_three_times_is_bit_identical(B, tiny):
     for o in outs[1:]:
         for a, b in zip(outs[0], o):
             assert (a == b).all()
+
+
+def test_two_instances_interleaved(B, tiny):
+    """Two handles alive at once, calls alternating between them: no state is shared."""
+    w, corpus, q, want = tiny
+    q = q[:384]
+    planes = W.lsh_planes(2, w.dim, 9)
+    want_b = po.lookup_stream_deferred(corpus, q, w.tau, 4, w.k, po.POLICY_FIFO, planes=planes, rerank_factor=2)
+    corpus_dev = gpu_corpus(corpus)
+    a = B.Proximity(corpus_dev, w.dim, w.capacity, w.k, po.POLICY_LRU, 64)
+    b = B.Proximity(corpus_dev, w.dim, 4, w.k, po.POLICY_FIFO, 64, rerank_factor=2,
+                    lsh_planes=torch.from_numpy(planes).to(DEV))
+    outs_a, outs_b = [], []
+    for r0 in range(0, len(q), 48):
+        rows = torch.from_numpy(q[r0:r0 + 48]).to(DEV)
+        outs_a.append(a.search_batch(rows, w.tau))
+        outs_b.append(b.search_batch(rows, w.tau))
+        outs_b.append(b.search_batch(rows[:0], w.tau))          # an empty call in between changes nothing
+    cat = lambda outs, j: torch.cat([o[j] for o in outs]).cpu().numpy()
+    o_ids, o_d, o_hit, o_src, _ = want[po.POLICY_LRU]
+    P.assert_stream_parity((cat(outs_a, 0), cat(outs_a, 1), cat(outs_a, 2)),
+                           (o_ids[:384], o_d[:384], o_hit[:384], o_src[:384]), corpus, q, what="instance a")
+    P.assert_stream_parity((cat(outs_b, 0), cat(outs_b, 1), cat(outs_b, 2)), want_b[:4], corpus, q,
+                           what="instance b", reranked=True)
+    a.close()
+    b.close()
