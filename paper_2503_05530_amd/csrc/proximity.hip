@@ -719,9 +719,8 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
                                                            h->cand_d);
   }
   // the sequential resolver: with its state in LDS whenever that fits
-  const size_t lds_state = (size_t(3) * c + nn) * sizeof(int);
-  if (have_probe && lds_state <= kResolverLdsMax) {
-    resolver_lds_kernel<<<dim3(1), dim3(256), lds_state, s>>>(
+  if (have_probe && resolver_lds_fits(size_t(c), size_t(nn), kResolverLdsMax)) {
+    resolver_lds_kernel<<<dim3(1), dim3(kResolverThreads), resolver_lds_bytes(size_t(c), size_t(nn)), s>>>(
         nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state, h->slot_seq,
         h->slot_next, h->slot_prev, h->cand_cnt, h->cand_src, h->cand_d, kCandCap, h->D32, h->ldD, h->srcs, h->srcnrm,
         out_hit, h->src, h->row_slot, h->miss_list, h->miss_count);

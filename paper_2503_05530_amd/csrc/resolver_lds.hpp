@@ -2,24 +2,42 @@
 // eviction, insertion; rows in order) with its
 // sequential state in LDS.  Same inputs, outputs and decisions as resolver_kernel.
 //
-// Walking thousands of rows one after the other, every dependent access to global
-// memory costs a microsecond.  Here the block copies the eviction order (next/prev
-// per slot) into LDS, keeps "which row of this batch overwrote slot t" (-1: none)
-// and "which slot row j took" (-1: none) there as well, lets its first wave walk
-// the rows, and writes the state back at the end.
+// Walking thousands of rows one after the other, every dependent memory access is
+// on the critical path: a microsecond in global memory, some sixty nanoseconds in
+// LDS.  This kernel therefore keeps the eviction order in a form whose updates need
+// no dependent reads at all:
+//
+//   * The order is a queue of slot numbers in LDS, oldest use first.  Every use of a
+//     slot (its insertion; under LRU also every hit on it, Section 3.3.2) appends the
+//     slot to the queue and notes the position in qpos[slot].  An entry is current
+//     iff qpos[queue[j]] == j; older entries of a slot that was used again are stale
+//     and skipped.  The next victim is the first current entry, which is exactly the
+//     least recently used (FIFO: first inserted) slot.
+//   * The walking wave holds the next 64 queue entries in registers (one per lane)
+//     with a mask of those still current.  A hit clears the bit of the slot it
+//     touched with one compare; an eviction takes the lowest set bit.  The window is
+//     refilled 64 entries at a time, so a miss costs no LDS round trip either.
+//
+// The linked list in global memory stays the representation between calls.  At entry
+// the block turns it into the queue by list ranking (pointer jumping, log2(size)
+// rounds over packed (next, distance-to-tail) words); at exit it compacts the current
+// queue entries and writes the links back.
+//
+// Besides the order the LDS state holds "which row of this batch overwrote slot t"
+// (-1: none), "which slot row j took" and "which source answered row j" (none: 0xffff),
+// all 16 bits wide.  The walk itself issues no access to global memory on its usual
+// paths (a store would be waited for at the next loop merge, a microsecond each
+// time); flags, sources and the list of missing rows are written out at the end.
 //
 // Rows are taken in chunks of 64.  While the first wave resolves chunk k, the other
-// three waves stage chunk k+1: every row's candidate count and its first
+// waves stage chunk k+1: every row's candidate count and its first
 // kStageCands candidates go to LDS, so that the walk touches global memory only
 // for rows with longer lists.  Three row kinds get a short path:
 //   * runs of consecutive rows without any candidate all miss; their victims are the
-//     next slots along the eviction order, which keep their relative order when they
-//     are appended again, so a run costs one pointer chase plus a constant number of
-//     link updates, and the per-row bookkeeping is done by one lane per row;
+//     next current window entries, one lane each does the bookkeeping of one row;
 //   * one candidate: liveness and threshold test on registers and LDS;
 //   * up to kStageCands candidates: one lane per candidate; the usual outcome (none
 //     or exactly one live candidate within tau) needs no reduction.
-// Needs (3c + n) * 4 bytes of dynamic LDS on top of the static staging buffers.
 #pragma once
 
 #include "cache_kernels.hpp"
@@ -27,6 +45,8 @@
 namespace prox {
 
 constexpr int kStageCands = 8;
+constexpr int kResolverThreads = 1024;
+constexpr int kRankPerThread = 20;  // list-ranking results one thread carries over the buffer switch
 
 struct ResolverChunk {
   int cnt[64];
@@ -34,22 +54,56 @@ struct ResolverChunk {
   double d[64][kStageCands];
 };
 
-constexpr size_t kResolverStaticLds = 2 * sizeof(ResolverChunk);
+constexpr size_t kResolverStaticLds = 2 * sizeof(ResolverChunk) + 256;
 
-__global__ __launch_bounds__(256) void resolver_lds_kernel(
+// Dynamic LDS of the kernel: queue [c + n], qpos [c], row-of-slot [c], slot-of-row [n], source-of-row [n],
+// 16 bits each; the list ranking at entry uses the same memory as two buffers of c packed words.
+inline size_t resolver_lds_bytes(size_t c, size_t n) {
+  const size_t state = 2 * (c + n) + 2 * c + 2 * c + 2 * n + 2 * n;
+  const size_t rank = 8 * c;
+  return ((state > rank ? state : rank) + 15) & ~size_t(15);
+}
+// Can the kernel hold this cache and batch?  (16-bit positions; ranking results per thread.)
+inline bool resolver_lds_fits(size_t c, size_t n, size_t lds_max) {
+  return c >= 1 && c + n <= 65534 && c <= size_t(kResolverThreads) * kRankPerThread &&
+         resolver_lds_bytes(c, n) <= lds_max;
+}
+
+// Exclusive prefix sum of one int per thread over the block (all threads call it; `wave_total`
+// holds one int per wave and may be reused after the next barrier).
+__device__ __forceinline__ int block_exclusive_sum(int mine, int* wave_total, int lane, int wib) {
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += o;
+  }
+  __syncthreads();  // earlier readers of wave_total are done
+  if (lane == 63) wave_total[wib] = incl;
+  __syncthreads();
+  int at = incl - mine;
+  for (int w = 0; w < wib; ++w) at += wave_total[w];
+  return at;
+}
+
+__global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
     int n, int c, int dim, int policy_lru, long long base_seq, double tau, CacheState* __restrict__ st,
     long long* slot_seq, int* slot_next, int* slot_prev, const int* __restrict__ cand_cnt,
     const int* __restrict__ cand_src, const double* __restrict__ cand_d, int cap, const float* __restrict__ D32,
     long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm, uint8_t* __restrict__ hit_out,
     int* __restrict__ src_out, int* __restrict__ row_slot, int* __restrict__ miss_list,
     int* __restrict__ miss_count) {
-  extern __shared__ int lds_state[];
+  extern __shared__ int lds_raw[];
   __shared__ ResolverChunk chunk[2];
-  int* lnext = lds_state;          // [c]
-  int* lprev = lds_state + c;      // [c]
-  int* lrow = lds_state + 2 * c;   // [c]  row of this batch that overwrote the slot, -1 if none
-  int* lslot = lds_state + 3 * c;  // [n]  slot taken by a row that missed, -1 otherwise
-  const int tid = threadIdx.x, lane = tid & 63;
+  __shared__ int wave_total[kResolverThreads / 64];
+  unsigned short* queue = reinterpret_cast<unsigned short*>(lds_raw);  // [c + n]
+  unsigned short* qpos = queue + (c + n);                              // [c]
+  short* lrow = reinterpret_cast<short*>(qpos + c);                    // [c]
+  unsigned short* lslot = reinterpret_cast<unsigned short*>(lrow + c); // [n]
+  unsigned short* lsrc = lslot + n;                                    // [n]
+  constexpr unsigned kNone = 0xffffu;
+  const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  constexpr int NT = kResolverThreads;
 
   auto stage_chunk = [&](int i0, ResolverChunk& ch, int t, int nt) {
     for (int e = t; e < 64 * kStageCands; e += nt) {
@@ -64,129 +118,202 @@ __global__ __launch_bounds__(256) void resolver_lds_kernel(
     }
   };
 
-  for (int s = tid; s < c; s += 256) {
-    lnext[s] = slot_next[s];
-    lprev[s] = slot_prev[s];
-    lrow[s] = -1;
+  // ---- the eviction order: linked list -> queue (position = size - 1 - distance to the tail) ----
+  const int size0 = st->size;
+  {
+    unsigned* from = reinterpret_cast<unsigned*>(lds_raw);  // packed: next slot << 16 | distance to the tail so far
+    unsigned* to = from + c;
+    for (int s = tid; s < size0; s += NT) {
+      const int nx = slot_next[s];
+      from[s] = nx < 0 ? (kNone << 16) : (unsigned(nx) << 16 | 1u);
+    }
+    __syncthreads();
+    for (int span = 1; span < size0; span <<= 1) {
+      for (int s = tid; s < size0; s += NT) {
+        unsigned a = from[s];
+        const unsigned nx = a >> 16;
+        if (nx != kNone) {
+          const unsigned b = from[nx];
+          a = (b & 0xffff0000u) | ((a & 0xffffu) + (b & 0xffffu));
+        }
+        to[s] = a;
+      }
+      __syncthreads();
+      unsigned* t = from;
+      from = to;
+      to = t;
+    }
+    int dist[kRankPerThread];
+#pragma unroll
+    for (int j = 0; j < kRankPerThread; ++j) {
+      const int s = tid + NT * j;
+      dist[j] = s < size0 ? int(from[s] & 0xffffu) : 0;
+    }
+    __syncthreads();  // the ranking buffers are dead from here on; the state arrays take their place
+#pragma unroll
+    for (int j = 0; j < kRankPerThread; ++j) {
+      const int s = tid + NT * j;
+      if (s < size0) {
+        const int pos = size0 - 1 - dist[j];
+        queue[pos] = (unsigned short)s;
+        qpos[s] = (unsigned short)pos;
+      }
+    }
   }
-  for (int i = tid; i < n; i += 256) lslot[i] = -1;
-  stage_chunk(0, chunk[0], tid, 256);
+  for (int s = tid; s < c; s += NT) lrow[s] = -1;
+  for (int i = tid; i < n; i += NT) lslot[i] = (unsigned short)kNone;
+  stage_chunk(0, chunk[0], tid, NT);
   __syncthreads();
 
-  int size = st->size, head = st->head, tail = st->tail;  // walked by the first wave only
-  unsigned long long hits = 0, misses = 0, inserts = 0, evictions = 0, inbatch = 0, dense = 0;
+  // walked by the first wave only
+  int size = size0;
+  int qnext = 0, qtail = size0; // queue positions: next one the window has not seen, end
+  int wslot = int(kNone);       // window: this lane's queue entry
+  unsigned long long wmask = 0; //         lanes whose entry is still current and not taken
+  // counters of this call; every miss inserts, so misses and insertions both equal M
+  int hits = 0, evictions = 0, inbatch = 0, dense = 0;
   int M = 0;
   const double kInf = __longlong_as_double(0x7ff0000000000000ll);
   const int n_chunks = (n + 63) / 64;
 
+  auto window_load = [&]() {
+    const int pos = qnext + lane;
+    int sl = int(kNone);
+    bool cur = false;
+    if (pos < qtail) {
+      sl = queue[pos];
+      cur = qpos[sl] == pos;
+    }
+    wslot = sl;
+    wmask = __ballot(cur);
+    qnext = qnext + 64 < qtail ? qnext + 64 : qtail;
+  };
+  // slot t was used just now: it goes to the back of the order
+  auto touch = [&](int t) {
+    if (lane == 0) {
+      queue[qtail] = (unsigned short)t;
+      qpos[t] = (unsigned short)qtail;
+    }
+    ++qtail;
+    wmask &= ~__ballot(wslot == t);  // an entry of t in the window is stale now
+  };
+  auto is_live = [&](int s) -> bool {
+    if (s < c) return lrow[s] < 0;
+    const unsigned t = lslot[s - c];
+    return t != kNone && lrow[t] == s - c;
+  };
+  // The walking wave's control flow depends only on values every lane holds alike.  Values read
+  // from LDS at a common address are such values, but the compiler cannot know; passing them
+  // through readfirstlane keeps the loop state in scalar registers and the branches scalar.
+  auto uniform = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+  auto is_live_uniform = [&](int s) -> bool {
+    if (s < c) return uniform(lrow[s]) < 0;
+    const int t = uniform(lslot[s - c]);
+    return t != int(kNone) && uniform(lrow[t]) == s - c;
+  };
+
+  // a run of m consecutive rows from row i on that all miss
+  auto miss_run = [&](int i, int m) {
+    int done = 0;
+    if (size < c) {
+      // free slots are taken in index order
+      done = m < c - size ? m : c - size;
+      if (lane < done) {
+        const int t = size + lane;
+        lrow[t] = short(i + lane);
+        lslot[i + lane] = (unsigned short)t;
+        queue[qtail + lane] = (unsigned short)t;
+        qpos[t] = (unsigned short)(qtail + lane);
+      }
+      qtail += done;
+      size += done;
+    }
+    // the other victims are the next current entries of the order; window lane number `rank` among
+    // the current ones serves row i + done + rank
+    while (done < m) {
+      while (wmask == 0 && qnext < qtail) window_load();
+      const int avail = __popcll(wmask);
+      if (avail == 0) break;  // no live key: cannot happen with size == c >= 1
+      const int g = m - done < avail ? m - done : avail;
+      const int rank = __builtin_amdgcn_mbcnt_hi(unsigned(wmask >> 32), __builtin_amdgcn_mbcnt_lo(unsigned(wmask), 0u));
+      const bool chosen = ((wmask >> lane) & 1ull) && rank < g;
+      if (chosen) {
+        const int t = wslot, row = i + done + rank;
+        lrow[t] = short(row);
+        lslot[row] = (unsigned short)t;
+        queue[qtail + rank] = (unsigned short)t;
+        qpos[t] = (unsigned short)(qtail + rank);
+      }
+      wmask &= ~__ballot(chosen);
+      qtail += g;
+      done += g;
+      evictions += g;
+    }
+    M += m;
+  };
+  // row i hits on source s
+  auto hit_row = [&](int s) {
+    ++hits;
+    if (s >= c) ++inbatch;
+    if (policy_lru) touch(s < c ? s : uniform(lslot[s - c]));  // also when it is at the back already
+  };
+
   for (int ck = 0; ck < n_chunks; ++ck) {
     const int i0 = ck * 64;
     if (tid >= 64) {
-      if (ck + 1 < n_chunks) stage_chunk(i0 + 64, chunk[(ck + 1) & 1], tid - 64, 192);
+      if (ck + 1 < n_chunks) stage_chunk(i0 + 64, chunk[(ck + 1) & 1], tid - 64, NT - 64);
     } else {
       const ResolverChunk& ch = chunk[ck & 1];
       const int rows = n - i0 < 64 ? n - i0 : 64;
       const int my_cnt = ch.cnt[lane];
       int my_s0 = -1;
-      double my_d0 = kInf;
-      if (my_cnt >= 1 && my_cnt <= cap) {
+      bool my_within = false;
+      if (my_cnt == 1) {
         my_s0 = ch.src[lane][0];
-        my_d0 = ch.d[lane][0];
+        my_within = ch.d[lane][0] <= tau;
       }
-      const unsigned long long zero_mask = __ballot(my_cnt == 0);
-      int my_hit = 0, my_src = -1;
+      // rows that miss whatever the state: no candidate, or a single one beyond tau
+      const unsigned long long miss_mask = __ballot(my_cnt == 0 || (my_cnt == 1 && !my_within));
+      // rows with one candidate within tau: a hit iff that source is live
+      const unsigned long long one_mask = __ballot(my_cnt == 1 && my_within);
+      int my_src = int(kNone);
       int r = 0;
       while (r < rows) {
-        const int i = i0 + r;
-        // r is wave-uniform: readlane moves the staged values without another trip through LDS
-        const int cnt = __builtin_amdgcn_readlane(my_cnt, r);
-        if (cnt == 0) {
-          // a run of rows without candidates: all miss
-          const unsigned long long rest = ~(zero_mask >> r);
-          int m = rest ? __ffsll((long long)rest) - 1 : 64;
-          if (size < c) {
-            // free slots are taken in index order
-            m = m < c - size ? m : c - size;
-            if (lane < m) {
-              const int t = size + lane;
-              lrow[t] = i + lane;
-              lprev[t] = lane == 0 ? tail : t - 1;
-              lnext[t] = lane == m - 1 ? -1 : t + 1;
-              lslot[i + lane] = t;
-              miss_list[M + lane] = i + lane;
-            }
-            if (tail >= 0) {
-              if (lane == 0) lnext[tail] = size;
-            } else {
-              head = size;
-            }
-            tail = size + m - 1;
-            size += m;
-            inserts += m;
-          } else {
-            // victims are the first m slots of the eviction order; appended again in the same
-            // order they keep the links among themselves
-            m = m < c ? m : c;
-            int my_t = -1, cur = head;
-            for (int j = 0; j < m; ++j) {
-              if (lane == j) my_t = cur;
-              cur = lnext[cur];
-            }
-            if (lane < m) {
-              lrow[my_t] = i + lane;
-              lslot[i + lane] = my_t;
-              miss_list[M + lane] = i + lane;
-            }
-            if (m < c) {  // otherwise the whole order was replaced by itself
-              const int t_last = __builtin_amdgcn_readlane(my_t, m - 1);
-              if (lane == 0) {
-                lprev[cur] = -1;
-                lnext[tail] = head;
-                lprev[head] = tail;
-                lnext[t_last] = -1;
-              }
-              head = cur;
-              tail = t_last;
-            }
-            evictions += m;
-            inserts += m;
+        // ---- the short loop: runs of sure misses and single-candidate rows ----
+        while (r < rows) {
+          const unsigned long long mm = miss_mask >> r;
+          if (mm & 1ull) {
+            const unsigned long long rest = ~mm;  // rows past the end are in neither mask: a run ends there
+            const int m = rest ? __ffsll((long long)rest) - 1 : 64;
+            miss_run(i0 + r, m);
+            r += m;
+            continue;
           }
-          misses += m;
-          M += m;
-          r += m;
-          continue;
-        }
-
-        int best_src = -1;
-        if (cnt == 1) {
+          if (!((one_mask >> r) & 1ull)) break;
+          // r is wave-uniform: readlane moves the staged value without another trip through LDS
           const int s = __builtin_amdgcn_readlane(my_s0, r);
-          const long long dbits = __double_as_longlong(my_d0);
-          const unsigned dlo = unsigned(__builtin_amdgcn_readlane(int(dbits & 0xffffffffll), r));
-          const unsigned dhi = unsigned(__builtin_amdgcn_readlane(int(dbits >> 32), r));
-          const double d = __longlong_as_double((long long)((unsigned long long)dhi << 32 | dlo));
-          bool live;
-          if (s < c) {
-            live = lrow[s] < 0;
+          if (is_live_uniform(s)) {
+            hit_row(s);
+            if (lane == r) my_src = s;
           } else {
-            const int t = lslot[s - c];
-            live = t >= 0 && lrow[t] == s - c;
+            miss_run(i0 + r, 1);
           }
-          if (live && d <= tau) best_src = s;
-        } else if (cnt <= cap) {
-          // several candidates, one lane each: from LDS when the staged part holds them all
+          ++r;
+        }
+        if (r >= rows) break;
+
+        // ---- a row with several candidates ----
+        const int i = i0 + r;
+        const int cnt = __builtin_amdgcn_readlane(my_cnt, r);
+        int best_src = -1;
+        if (cnt <= cap) {
+          // one lane each: from LDS when the staged part holds them all
           const bool staged = cnt <= kStageCands;
           // candidate p of this row: is it live and within tau?
           auto within = [&](int p, int& s, double& d) {
             s = staged ? ch.src[r][p] : cand_src[long(i) * cap + p];
             d = staged ? ch.d[r][p] : cand_d[long(i) * cap + p];
-            bool live;
-            if (s < c) {
-              live = lrow[s] < 0;
-            } else {
-              const int t = lslot[s - c];
-              live = t >= 0 && lrow[t] == s - c;
-            }
-            return live && d <= tau;
+            return is_live(s) && d <= tau;
           };
           int my_ok_s = -1, total = 0;
           for (int p0 = 0; p0 < cnt; p0 += 64) {
@@ -252,81 +379,80 @@ __global__ __launch_bounds__(256) void resolver_lds_kernel(
           }
           best_src = best.src;
         }
-
+        best_src = uniform(best_src);
         if (best_src >= 0) {
-          ++hits;
-          if (best_src >= c) ++inbatch;
-          const int t = best_src < c ? best_src : lslot[best_src - c];
-          if (policy_lru && t != tail) {
-            const int p = lprev[t], nx = lnext[t];  // nx >= 0 because t is not the tail
-            if (lane == 0) {
-              if (p >= 0) lnext[p] = nx;
-              lprev[nx] = p;
-              lprev[t] = tail;
-              lnext[t] = -1;
-              lnext[tail] = t;
-            }
-            if (p < 0) head = nx;
-            tail = t;
-          }
-          if (lane == r) {
-            my_hit = 1;
-            my_src = best_src;
-          }
+          hit_row(best_src);
+          if (lane == r) my_src = best_src;
         } else {
-          ++misses;
-          int t;
-          if (size < c) {
-            t = size++;
-          } else {
-            t = head;
-            head = lnext[t];
-            if (lane == 0 && head >= 0) lprev[head] = -1;
-            if (head < 0) tail = -1;
-            ++evictions;
-          }
-          if (lane == 0) {
-            lrow[t] = i;
-            lprev[t] = tail;
-            lnext[t] = -1;
-            if (tail >= 0) lnext[tail] = t;
-            lslot[i] = t;
-            miss_list[M] = i;
-          }
-          if (tail < 0) head = t;
-          tail = t;
-          ++inserts;
-          ++M;
+          miss_run(i, 1);
         }
         ++r;
       }
-      if (lane < rows) {
-        hit_out[i0 + lane] = uint8_t(my_hit);
-        src_out[i0 + lane] = my_src;
-      }
+      if (lane < rows) lsrc[i0 + lane] = (unsigned short)my_src;
     }
     __syncthreads();
   }
 
+  // the walking wave hands the scalars the whole block needs through LDS
+  __shared__ int walk_out[2];
   if (tid == 0) {
-    st->size = size;
-    st->head = head;
-    st->tail = tail;
+    walk_out[0] = size;
+    walk_out[1] = qtail;
     st->queries += (unsigned long long)n;
-    st->hits += hits;
-    st->misses += misses;
-    st->inserts += inserts;
-    st->evictions += evictions;
-    st->inbatch_hits += inbatch;
-    st->dense_resolves += dense;
+    st->hits += (unsigned long long)hits;
+    st->misses += (unsigned long long)M;
+    st->inserts += (unsigned long long)M;
+    st->evictions += (unsigned long long)evictions;
+    st->inbatch_hits += (unsigned long long)inbatch;
+    st->dense_resolves += (unsigned long long)dense;
     *miss_count = M;
   }
-  for (int s = tid; s < c; s += 256) {
-    slot_next[s] = lnext[s];
-    slot_prev[s] = lprev[s];
+  __syncthreads();
+  const int size_end = walk_out[0], q_end = walk_out[1];
+  for (int s = tid; s < c; s += NT)
     if (lrow[s] >= 0) slot_seq[s] = base_seq + lrow[s];
+  for (int i = tid; i < n; i += NT) {
+    const unsigned t = lslot[i], src = lsrc[i];
+    row_slot[i] = t == kNone ? -1 : int(t);
+    hit_out[i] = uint8_t(src != kNone);
+    src_out[i] = src == kNone ? -1 : int(src);
   }
-  for (int i = tid; i < n; i += 256) row_slot[i] = lslot[i];
+  // the rows that missed, in row order: exactly those that took a slot
+  {
+    const int per = (n + NT - 1) / NT;
+    const int a0 = tid * per < n ? tid * per : n;
+    const int a1 = a0 + per < n ? a0 + per : n;
+    int mine = 0;
+    for (int i = a0; i < a1; ++i) mine += lslot[i] != kNone ? 1 : 0;
+    int at = block_exclusive_sum(mine, wave_total, lane, wib);
+    for (int i = a0; i < a1; ++i)
+      if (lslot[i] != kNone) miss_list[at++] = i;
+  }
+  __syncthreads();  // lrow is free now: it takes the compacted order
+
+  // ---- queue -> linked list: the current entries, in queue order ----
+  unsigned short* order = reinterpret_cast<unsigned short*>(lrow);  // [size_end]
+  const int per = (q_end + NT - 1) / NT;
+  const int j0 = tid * per < q_end ? tid * per : q_end;
+  const int j1 = j0 + per < q_end ? j0 + per : q_end;
+  int mine = 0;
+  for (int j = j0; j < j1; ++j) mine += qpos[queue[j]] == j ? 1 : 0;
+  int at = block_exclusive_sum(mine, wave_total, lane, wib);
+  for (int j = j0; j < j1; ++j) {
+    const unsigned short s = queue[j];
+    if (qpos[s] == j) order[at++] = s;
+  }
+  __syncthreads();
+  for (int p = tid; p < size_end; p += NT) {
+    const int s = order[p];
+    slot_next[s] = p + 1 < size_end ? int(order[p + 1]) : -1;
+    slot_prev[s] = p > 0 ? int(order[p - 1]) : -1;
+  }
+  if (tid == 0) {
+    st->size = size_end;
+    st->head = size_end > 0 ? int(order[0]) : -1;
+    st->tail = size_end > 0 ? int(order[size_end - 1]) : -1;
+  }
 }
 
 }  // namespace prox

@@ -169,19 +169,21 @@ def test_one_call_of_the_largest_batch(B):
     px.close()
 
 
+@pytest.mark.parametrize("cap", [13000, 21000])
 @pytest.mark.parametrize("policy", [po.POLICY_FIFO, po.POLICY_LRU])
-def test_cache_too_large_for_on_chip_state(B, policy):
-    """13 000 keys: the eviction order no longer fits on chip and the resolver works from device memory."""
+def test_cache_at_and_beyond_on_chip_state(B, policy, cap):
+    """13 000 keys: near the largest eviction order the resolver holds on chip; 21 000: it no longer
+    fits and the resolver works from device memory."""
     # The literal oracle needs minutes at this cache size.  At tau = 0 a query hits exactly when the
     # same vector is resident, so Algorithm 1 is a textbook FIFO/LRU cache keyed by vector identity
     # (test_oracle_pins shows the oracle equal to that model); the model is the expectation here, and
     # the oracle itself is compared on a prefix.
     from collections import OrderedDict
-    dim, cap = 32, 13000
+    dim = 32
     rng = np.random.default_rng(31)
-    vecs = W.unit_rows(rng.standard_normal((13600, dim))).astype(np.float32)
-    which = np.concatenate([np.arange(13300), rng.integers(0, 13300, size=700), np.arange(13300, 13600),
-                            rng.integers(0, 13600, size=700)])
+    vecs = W.unit_rows(rng.standard_normal((cap + 600, dim))).astype(np.float32)
+    which = np.concatenate([np.arange(cap + 300), rng.integers(0, cap + 300, size=700),
+                            np.arange(cap + 300, cap + 600), rng.integers(0, cap + 600, size=700)])
     q = vecs[which]
     model, want_hit, evictions = OrderedDict(), [], 0
     for t, key in enumerate(which.tolist()):
