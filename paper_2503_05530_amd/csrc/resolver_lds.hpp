@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
   };
 
   // ---- the eviction order: linked list -> queue (position = size - 1 - distance to the tail) ----
-  const int size0 = st->size;
+  const int size0 = __builtin_amdgcn_readfirstlane(st->size);
   {
     unsigned* from = reinterpret_cast<unsigned*>(lds_raw);  // packed: next slot << 16 | distance to the tail so far
     unsigned* to = from + c;
@@ -260,7 +260,9 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
 
   for (int ck = 0; ck < n_chunks; ++ck) {
     const int i0 = ck * 64;
-    if (tid >= 64) {
+    // (the wave number as a scalar: the compiler then sees that whole waves take one side, and
+    // the walk's state does not pass through the join of a divergent branch)
+    if (__builtin_amdgcn_readfirstlane(wib) != 0) {
       if (ck + 1 < n_chunks) stage_chunk(i0 + 64, chunk[(ck + 1) & 1], tid - 64, NT - 64);
     } else {
       const ResolverChunk& ch = chunk[ck & 1];
