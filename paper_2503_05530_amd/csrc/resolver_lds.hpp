@@ -32,12 +32,17 @@
 // Rows are taken in chunks of 64.  While the first wave resolves chunk k, the other
 // waves stage chunk k+1: every row's candidate count and its first
 // kStageCands candidates go to LDS, so that the walk touches global memory only
-// for rows with longer lists.  Three row kinds get a short path:
-//   * runs of consecutive rows without any candidate all miss; their victims are the
-//     next current window entries, one lane each does the bookkeeping of one row;
-//   * one candidate: liveness and threshold test on registers and LDS;
-//   * up to kStageCands candidates: one lane per candidate; the usual outcome (none
-//     or exactly one live candidate within tau) needs no reduction.
+// for rows with longer lists.  A short loop handles the two common row kinds:
+//   * runs of consecutive rows that miss whatever the state (no candidate, or a
+//     single one beyond tau): their victims are the next current window entries,
+//     one lane each does the bookkeeping of one row;
+//   * one candidate within tau: a hit iff that source is live (one or two LDS reads).
+// Rows with several candidates leave the short loop: one lane per candidate; the
+// usual outcome (none or exactly one live candidate within tau) needs no reduction.
+//
+// One wave issues at most one instruction every four cycles, so after the memory
+// waits are gone the instruction count per row is what is left to pay for; the loop
+// state is kept in scalar registers for that reason (see the notes at `uniform`).
 #pragma once
 
 #include "cache_kernels.hpp"
@@ -327,7 +332,7 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
           }
           if (total == 1) {
             // the usual outcome: nothing to compare
-            best_src = __shfl(my_ok_s, __ffsll((long long)__ballot(my_ok_s >= 0)) - 1, kWave);
+            best_src = __builtin_amdgcn_readlane(my_ok_s, __ffsll((long long)__ballot(my_ok_s >= 0)) - 1);
           } else if (total >= 2) {
             // nearest wins, equal distances go to the older key: a key untouched in this batch still
             // carries its own seq, a row of this batch has base_seq + row
