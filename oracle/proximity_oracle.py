@@ -29,6 +29,10 @@ What it follows
   hands the first k to the caller, and a hit orders the stored rho * k documents
   by their distance to the *current* query (``rerank_stored``) and hands out the
   k nearest.  rho = 1 is the plain procedure: nothing is re-ranked.
+* ``metric`` selects the distance function d of Section 2.2 (Euclidean, inner
+  product or cosine, fixed when the index is built): ``metric_distances`` is what
+  the database ranks by and reports, ``key_distances`` is what the cache compares
+  with tau (Section 3.1 compares query and key with the database's distance).
 
 Readings where the paper is silent (each listed in the design notes):
 the hit test is ``<=``; an empty cache misses; equal nearest distances pick
@@ -39,7 +43,11 @@ when the index holds fewer than k vectors; capacity 0 disables caching; with
 rho > 1 a hit ranks by (distance to the current query, document index) and
 reports those distances, and rho is a whole number; an inner product of
 exactly zero gives hash bit 1 (the hash formula of Section 3.2 includes zero), bit i of the code has
-weight 2^i, and L = 0 means a single bucket.
+weight 2^i, and L = 0 means a single bucket; the cosine distance is 1 - cos; the
+inner-product "distance" is the negated inner product (larger product = closer),
+and because that is no distance between two queries (a query is not nearest to
+itself under it) the cache of an inner-product index compares query and key by
+Euclidean distance.
 
 Parity status: every function here is pinned by tests that do not re-use its
 own formula (hand-worked eviction streams, reduction to textbook exact-match
@@ -55,6 +63,9 @@ import numpy as np
 
 POLICY_FIFO = 0
 POLICY_LRU = 1
+METRIC_L2 = 0
+METRIC_IP = 1
+METRIC_COSINE = 2
 
 
 def as_f64_rows(a) -> np.ndarray:
@@ -68,8 +79,28 @@ def l2_distances(q: np.ndarray, rows: np.ndarray) -> np.ndarray:
     return np.sqrt(np.sum(diff * diff, axis=1))
 
 
+def metric_distances(q: np.ndarray, rows: np.ndarray, metric: int = METRIC_L2) -> np.ndarray:
+    """Distance from q to every row under the index's distance function (Section 2.2), float64:
+    Euclidean; negated inner product; or cosine distance 1 - q.x / (|q| |x|)."""
+    if metric == METRIC_L2:
+        return l2_distances(q, rows)
+    q64, x = as_f64_rows(q), as_f64_rows(rows)
+    dots = np.sum(x * q64[None, :], axis=1)
+    if metric == METRIC_IP:
+        return -dots
+    if metric == METRIC_COSINE:
+        return 1.0 - dots / (np.sqrt(np.sum(x * x, axis=1)) * np.sqrt(np.sum(q64 * q64)))
+    raise ValueError("metric must be L2 (0), inner product (1) or cosine (2)")
+
+
+def key_distances(q: np.ndarray, keys: np.ndarray, metric: int = METRIC_L2) -> np.ndarray:
+    """Distance between a query and cached keys, the quantity compared with tau: the index's own
+    distance, except for an inner-product index, whose cache falls back to Euclidean distance."""
+    return metric_distances(q, keys, METRIC_L2 if metric == METRIC_IP else metric)
+
+
 def exact_knn(corpus: np.ndarray, q: np.ndarray, k: int,
-              chunk_rows: int = 1 << 18) -> Tuple[np.ndarray, np.ndarray]:
+              chunk_rows: int = 1 << 18, metric: int = METRIC_L2) -> Tuple[np.ndarray, np.ndarray]:
     """Ranked k nearest corpus rows of q (Section 2.2): ids int64[k], dists float64[k].
 
     Rows are independent, so distances are evaluated a block of rows at a time
@@ -80,7 +111,7 @@ def exact_knn(corpus: np.ndarray, q: np.ndarray, k: int,
     d = np.empty(n, dtype=np.float64)
     for r0 in range(0, n, chunk_rows):
         r1 = min(n, r0 + chunk_rows)
-        d[r0:r1] = l2_distances(q, corpus[r0:r1])
+        d[r0:r1] = metric_distances(q, corpus[r0:r1], metric)
     order = np.argsort(d, kind="stable")[:k]
     ids = np.full(k, -1, dtype=np.int64)
     dists = np.full(k, np.inf, dtype=np.float64)
@@ -89,14 +120,15 @@ def exact_knn(corpus: np.ndarray, q: np.ndarray, k: int,
     return ids, dists
 
 
-def rerank_stored(corpus: np.ndarray, q: np.ndarray, stored_ids: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+def rerank_stored(corpus: np.ndarray, q: np.ndarray, stored_ids: np.ndarray, k: int,
+                  metric: int = METRIC_L2) -> Tuple[np.ndarray, np.ndarray]:
     """Section 3.3.4, the hit side: of the documents stored with the matched key, the k
     nearest to the current query, ranked; ids int64[k], dists float64[k] (padded -1 / +inf)."""
     valid = np.asarray([i for i in np.asarray(stored_ids).tolist() if i >= 0], dtype=np.int64)
     ids = np.full(k, -1, dtype=np.int64)
     dists = np.full(k, np.inf, dtype=np.float64)
     if len(valid):
-        d = l2_distances(q, corpus[valid])
+        d = metric_distances(q, corpus[valid], metric)
         order = sorted(range(len(valid)), key=lambda j: (d[j], int(valid[j])))[:k]
         ids[: len(order)] = valid[order]
         dists[: len(order)] = d[order]
@@ -120,7 +152,7 @@ class FlatCacheOracle:
     """
 
     def __init__(self, corpus: Optional[np.ndarray], capacity: int, k: int, policy: int,
-                 retrieve: Optional[Callable] = None, rerank_factor: int = 1):
+                 retrieve: Optional[Callable] = None, rerank_factor: int = 1, metric: int = METRIC_L2):
         if policy not in (POLICY_FIFO, POLICY_LRU):
             raise ValueError("policy must be FIFO (0) or LRU (1)")
         if int(rerank_factor) != rerank_factor or rerank_factor < 1:
@@ -131,7 +163,9 @@ class FlatCacheOracle:
         self.rho = int(rerank_factor)
         self.k_store = self.rho * self.k          # neighbours asked of the database and kept per key
         self.policy = int(policy)
-        self.retrieve = retrieve if retrieve is not None else (lambda q: exact_knn(corpus, q, self.k_store))
+        self.metric = int(metric)
+        self.retrieve = retrieve if retrieve is not None else (
+            lambda q: exact_knn(corpus, q, self.k_store, metric=self.metric))
         self.entries: List[_Entry] = []
         self.n_queries = 0
         self.n_hits = 0
@@ -159,7 +193,7 @@ class FlatCacheOracle:
         best = -1
         if self.entries:
             keys = np.stack([e.key for e in self.entries])
-            dists = l2_distances(q64, keys)
+            dists = key_distances(q64, keys, self.metric)
             min_dist = dists.min()
             # nearest key; among equal distances the oldest insertion
             cands = [i for i in range(len(self.entries)) if dists[i] == min_dist]
@@ -171,7 +205,7 @@ class FlatCacheOracle:
                     self.entries.append(self.entries.pop(best))
                 if self.rho == 1:
                     return e.ids.copy(), e.dists.copy(), True, e.seq
-                r_ids, r_d = rerank_stored(self.corpus, q64, e.ids, self.k)
+                r_ids, r_d = rerank_stored(self.corpus, q64, e.ids, self.k, self.metric)
                 return r_ids, r_d, True, e.seq
 
         ids, nd = self.retrieve(q64)
@@ -240,8 +274,8 @@ class LshCacheOracle:
     """
 
     def __init__(self, corpus: Optional[np.ndarray], planes, bucket_capacity: int, k: int, policy: int,
-                 retrieve: Optional[Callable] = None, rerank_factor: int = 1):
-        self.corpus, self.planes = corpus, np.asarray(planes, dtype=np.float64)
+                 retrieve: Optional[Callable] = None, rerank_factor: int = 1, metric: int = METRIC_L2):
+        self.corpus, self.planes, self.metric = corpus, np.asarray(planes, dtype=np.float64), int(metric)
         self.bucket_capacity, self.k, self.policy, self.rho = int(bucket_capacity), int(k), int(policy), int(rerank_factor)
         self.k_store = self.rho * self.k
         self.retrieve = retrieve
@@ -251,7 +285,7 @@ class LshCacheOracle:
     def _bucket(self, code: int) -> FlatCacheOracle:
         if code not in self.buckets:
             self.buckets[code] = FlatCacheOracle(self.corpus, self.bucket_capacity, self.k, self.policy,
-                                                 retrieve=self.retrieve, rerank_factor=self.rho)
+                                                 retrieve=self.retrieve, rerank_factor=self.rho, metric=self.metric)
         return self.buckets[code]
 
     def lookup(self, q, tau: float):
@@ -304,24 +338,27 @@ class LshCacheOracle:
 # ---------------------------------------------------------------------------
 
 def simulate_decisions(queries, tau: float, capacity: int, policy: int,
-                       oracle: Optional[FlatCacheOracle] = None, planes=None):
+                       oracle: Optional[FlatCacheOracle] = None, planes=None, metric: int = METRIC_L2):
     """Replay Algorithm 1's control flow only.  Returns (hit[n], source_seq[n], oracle).
     With ``planes`` the cache is the bucketed one and ``capacity`` is per bucket."""
     k_dummy = 1
     no_db = lambda q: (np.full(k_dummy, -1, np.int64), np.full(k_dummy, np.inf))
     if oracle is None and planes is not None:
-        oracle = LshCacheOracle(None, planes, capacity, k_dummy, policy, retrieve=no_db)
+        oracle = LshCacheOracle(None, planes, capacity, k_dummy, policy, retrieve=no_db, metric=metric)
     if oracle is None:
         oracle = FlatCacheOracle(None, capacity, k_dummy, policy,
                                  retrieve=lambda q: (np.full(k_dummy, -1, np.int64),
-                                                     np.full(k_dummy, np.inf)))
+                                                     np.full(k_dummy, np.inf)), metric=metric)
     _, _, hit, src = oracle.lookup_stream(queries, tau)
     return hit, src, oracle
 
 
 def batched_exact_knn(corpus: np.ndarray, queries: np.ndarray, k: int,
-                      chunk_rows: int = 1 << 16) -> Tuple[np.ndarray, np.ndarray]:
+                      chunk_rows: int = 1 << 16, metric: int = METRIC_L2) -> Tuple[np.ndarray, np.ndarray]:
     """Ranked exact k-NN for several queries at once, float64.
+
+    (Described for the Euclidean distance.  The other two rank by the same matrix product:
+    -q.x, or -q.x / |x| for cosine, whose order per query is that of the cosine distance.)
 
     Squared distances come from the identity |q-x|^2 = |q|^2 + |x|^2 - 2 q.x with
     a float64 matrix product per block of corpus rows; each block keeps its k
@@ -336,7 +373,12 @@ def batched_exact_knn(corpus: np.ndarray, queries: np.ndarray, k: int,
     for r0 in range(0, n, chunk_rows):
         r1 = min(n, r0 + chunk_rows)
         x = as_f64_rows(corpus[r0:r1])
-        d2 = qn[:, None] + np.sum(x * x, axis=1)[None, :] - 2.0 * (q64 @ x.T)
+        if metric == METRIC_L2:
+            d2 = qn[:, None] + np.sum(x * x, axis=1)[None, :] - 2.0 * (q64 @ x.T)
+        elif metric == METRIC_IP:
+            d2 = -(q64 @ x.T)
+        else:
+            d2 = -(q64 @ x.T) / np.sqrt(np.sum(x * x, axis=1))[None, :]
         kk = min(k, r1 - r0)
         kth = np.partition(d2, kk - 1, axis=1)[:, kk - 1]
         for i in range(m):
@@ -354,19 +396,19 @@ def batched_exact_knn(corpus: np.ndarray, queries: np.ndarray, k: int,
         best = cand_id[i][order]
         ids[i, : len(best)] = best
         if len(best):
-            dists[i, : len(best)] = l2_distances(q64[i], corpus[best])
+            dists[i, : len(best)] = metric_distances(q64[i], corpus[best], metric)
     return ids, dists
 
 
 def lookup_stream_deferred(corpus, queries, tau: float, capacity: int, k: int, policy: int,
-                           knn_chunk: int = 256, rerank_factor: int = 1, planes=None):
+                           knn_chunk: int = 256, rerank_factor: int = 1, planes=None, metric: int = METRIC_L2):
     """Outputs of ``FlatCacheOracle.lookup_stream`` computed decisions-first.
 
     Returns ids[n,k], dists[n,k], hit[n], source_seq[n], decision_oracle; with
     ``rerank_factor`` > 1 a sixth item, stored_ids[n, rerank_factor*k]: what each query that
     missed stored with its key.
     """
-    hit, src, dec = simulate_decisions(queries, tau, capacity, policy, planes=planes)
+    hit, src, dec = simulate_decisions(queries, tau, capacity, policy, planes=planes, metric=metric)
     n = len(queries)
     k_store = int(rerank_factor) * k
     miss_rows = np.flatnonzero(hit == 0)
@@ -374,7 +416,7 @@ def lookup_stream_deferred(corpus, queries, tau: float, capacity: int, k: int, p
     stored_d = np.full((n, k_store), np.inf, dtype=np.float64)
     for c0 in range(0, len(miss_rows), knn_chunk):
         rows = miss_rows[c0:c0 + knn_chunk]
-        i_, d_ = batched_exact_knn(corpus, np.asarray(queries)[rows], k_store)
+        i_, d_ = batched_exact_knn(corpus, np.asarray(queries)[rows], k_store, metric=metric)
         stored_ids[rows], stored_d[rows] = i_, d_
     ids = stored_ids[:, :k].copy()
     dists = stored_d[:, :k].copy()
@@ -384,7 +426,7 @@ def lookup_stream_deferred(corpus, queries, tau: float, capacity: int, k: int, p
         dists[hit_rows] = dists[src[hit_rows]]
         return ids, dists, hit, src, dec
     for t in hit_rows:
-        ids[t], dists[t] = rerank_stored(corpus, as_f64_rows(queries[t]), stored_ids[src[t]], k)
+        ids[t], dists[t] = rerank_stored(corpus, as_f64_rows(queries[t]), stored_ids[src[t]], k, metric)
     return ids, dists, hit, src, dec, stored_ids
 
 

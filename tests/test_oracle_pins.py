@@ -461,6 +461,130 @@ def test_lsh_zero_tolerance_is_a_set_associative_cache(policy):
 
 
 # ---------------------------------------------------------------------------
+# Other distance functions (Section 2.2: Euclidean, inner product or cosine)
+# ---------------------------------------------------------------------------
+def scaled_corpus(n, dim, seed):
+    """Rows of very different lengths, so that the three distance functions rank differently."""
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((n, dim)) * rng.uniform(0.2, 5.0, size=(n, 1))).astype(np.float32)
+
+
+def test_metric_distances_by_hand():
+    q = np.array([1.0, 0.0])
+    rows = np.array([[2.0, 0.0], [0.0, 3.0], [-1.0, 0.0], [1.0, 1.0]])
+    np.testing.assert_allclose(po.metric_distances(q, rows, po.METRIC_COSINE),
+                               [0.0, 1.0, 2.0, 1.0 - 1.0 / math.sqrt(2.0)], atol=1e-15)
+    np.testing.assert_allclose(po.metric_distances(q, rows, po.METRIC_IP), [-2.0, 0.0, 1.0, -1.0], atol=0)
+    np.testing.assert_allclose(po.metric_distances(q, rows, po.METRIC_L2),
+                               [1.0, math.sqrt(10.0), 2.0, 1.0], atol=1e-15)
+    # ranked lists: cosine and inner product agree here, Euclidean does not
+    assert po.exact_knn(rows, q, 4, metric=po.METRIC_COSINE)[0].tolist() == [0, 3, 1, 2]
+    assert po.exact_knn(rows, q, 4, metric=po.METRIC_IP)[0].tolist() == [0, 3, 1, 2]
+    assert po.exact_knn(rows, q, 4, metric=po.METRIC_L2)[0].tolist() == [0, 3, 2, 1]
+    # the cache of an inner-product index compares by Euclidean distance
+    np.testing.assert_allclose(po.key_distances(q, rows, po.METRIC_IP), po.l2_distances(q, rows), atol=0)
+    np.testing.assert_allclose(po.key_distances(q, rows, po.METRIC_COSINE),
+                               po.metric_distances(q, rows, po.METRIC_COSINE), atol=0)
+
+
+def test_metric_knn_matches_pure_python_loops():
+    corpus = scaled_corpus(41, 6, 2)
+    q = np.random.default_rng(3).standard_normal(6).astype(np.float32)
+    cos, ip = [], []
+    for j in range(41):
+        dot = xx = qq = 0.0
+        for i in range(6):
+            dot += float(q[i]) * float(corpus[j, i])
+            xx += float(corpus[j, i]) ** 2
+            qq += float(q[i]) ** 2
+        cos.append((1.0 - dot / (math.sqrt(xx) * math.sqrt(qq)), j))
+        ip.append((-dot, j))
+    for metric, ref in ((po.METRIC_COSINE, sorted(cos)), (po.METRIC_IP, sorted(ip))):
+        ids, dists = po.exact_knn(corpus, q, 9, metric=metric)
+        assert ids.tolist() == [j for _, j in ref[:9]]
+        np.testing.assert_allclose(dists, [v for v, _ in ref[:9]], rtol=1e-13, atol=1e-15)
+
+
+def test_metric_knn_matches_library_neighbours():
+    from scipy.spatial.distance import cdist
+    from sklearn.neighbors import NearestNeighbors
+
+    corpus = scaled_corpus(600, 20, 4).astype(np.float64)
+    queries = np.random.default_rng(5).standard_normal((5, 20)) * 3.0
+    nn = NearestNeighbors(n_neighbors=8, algorithm="brute", metric="cosine").fit(corpus)
+    lib_d, lib_i = nn.kneighbors(queries)
+    full = cdist(queries, corpus, metric="cosine")
+    for r in range(5):
+        ids, dists = po.exact_knn(corpus, queries[r], 8, metric=po.METRIC_COSINE)
+        assert ids.tolist() == lib_i[r].tolist()
+        np.testing.assert_allclose(dists, lib_d[r], rtol=1e-9, atol=1e-12)
+        np.testing.assert_allclose(dists, np.sort(full[r])[:8], rtol=1e-9, atol=1e-12)
+        ids, dists = po.exact_knn(corpus, queries[r], 8, metric=po.METRIC_IP)
+        prod = corpus @ queries[r]
+        assert ids.tolist() == np.argsort(-prod, kind="stable")[:8].tolist()
+        np.testing.assert_allclose(dists, -np.sort(prod)[::-1][:8], rtol=1e-12)
+    b_ids, b_d = po.batched_exact_knn(corpus, queries, 8, chunk_rows=128, metric=po.METRIC_COSINE)
+    assert b_ids.tolist() == lib_i.tolist()
+    np.testing.assert_allclose(b_d, lib_d, rtol=1e-9, atol=1e-12)
+    b_ids, _ = po.batched_exact_knn(corpus, queries, 8, chunk_rows=128, metric=po.METRIC_IP)
+    assert b_ids.tolist() == [np.argsort(-(corpus @ queries[r]), kind="stable")[:8].tolist() for r in range(5)]
+
+
+def test_cosine_properties():
+    """Cosine distance ignores lengths, and on unit vectors it is half the squared Euclidean distance."""
+    corpus = scaled_corpus(300, 16, 6).astype(np.float64)
+    q = np.random.default_rng(7).standard_normal(16)
+    d = po.metric_distances(q, corpus, po.METRIC_COSINE)
+    scale = np.random.default_rng(8).uniform(0.1, 9.0, size=(300, 1))
+    np.testing.assert_allclose(po.metric_distances(4.5 * q, corpus * scale, po.METRIC_COSINE), d, rtol=0, atol=1e-14)
+    unit = corpus / np.linalg.norm(corpus, axis=1, keepdims=True)
+    qu = q / np.linalg.norm(q)
+    np.testing.assert_allclose(d, po.l2_distances(qu, unit) ** 2 / 2.0, rtol=0, atol=1e-14)
+    assert (d >= -1e-15).all() and (d <= 2.0 + 1e-15).all()
+    # on unit vectors all three distance functions rank alike
+    want = po.exact_knn(unit, qu, 15)[0].tolist()
+    assert po.exact_knn(unit, qu, 15, metric=po.METRIC_COSINE)[0].tolist() == want
+    assert po.exact_knn(unit, qu, 15, metric=po.METRIC_IP)[0].tolist() == want
+
+
+def test_cache_under_other_metrics_hand_worked():
+    """(1,0), (5,0), (0,1), (0,2), (3,3) with tau = 0.1 and room for every key: the second and fourth
+    query point the same way as the one before them, so the cosine cache hits on both although they
+    are far away; the Euclidean cache, and with it the cache of an inner-product index, hits on neither."""
+    qs = np.array([[1, 0], [5, 0], [0, 1], [0, 2], [3, 3]], dtype=np.float32)
+    qs = np.concatenate([qs, np.zeros((5, 2), np.float32)], axis=1)
+    corpus = scaled_corpus(50, 4, 9)
+    for metric, flags in ((po.METRIC_COSINE, "MHMHM"), (po.METRIC_L2, "MMMMM"), (po.METRIC_IP, "MMMMM")):
+        o = po.FlatCacheOracle(corpus, 8, 3, po.POLICY_LRU, metric=metric)
+        ids, dists, hit, src = o.lookup_stream(qs, 0.1)
+        assert "".join("H" if h else "M" for h in hit) == flags
+        for t in range(5):
+            own_ids, own_d = po.exact_knn(corpus, qs[src[t]], 3, metric=metric)
+            assert ids[t].tolist() == own_ids.tolist()
+            np.testing.assert_allclose(dists[t], own_d, rtol=0, atol=0)
+    # the hit at position 1 returns what (1,0) stored; under cosine that is also (5,0)'s own answer
+    o = po.FlatCacheOracle(corpus, 8, 3, po.POLICY_LRU, metric=po.METRIC_COSINE)
+    ids, _, _, _ = o.lookup_stream(qs, 0.1)
+    assert ids[1].tolist() == po.exact_knn(corpus, qs[1], 3, metric=po.METRIC_COSINE)[0].tolist()
+
+
+@pytest.mark.parametrize("metric", [po.METRIC_IP, po.METRIC_COSINE])
+def test_metric_deferred_form_equals_literal_form(metric):
+    w = W.WORKLOADS["tiny"]
+    corpus = scaled_corpus(3000, w.dim, 10)
+    q = W.stream_for(w, 260) * np.random.default_rng(11).uniform(0.5, 2.0, size=(260, 1)).astype(np.float32)
+    tau = 0.25 if metric == po.METRIC_IP else 0.012
+    lit = po.FlatCacheOracle(corpus, 20, 5, po.POLICY_LRU, rerank_factor=2, metric=metric)
+    l_ids, l_d, l_hit, l_src = lit.lookup_stream(q, tau)
+    d_ids, d_d, d_hit, d_src, dec, _ = po.lookup_stream_deferred(corpus, q, tau, 20, 5, po.POLICY_LRU,
+                                                                rerank_factor=2, metric=metric)
+    assert 20 < l_hit.sum() < 240
+    assert (l_hit == d_hit).all() and (l_src == d_src).all() and (l_ids == d_ids).all()
+    np.testing.assert_allclose(l_d, d_d, rtol=1e-12, atol=1e-14)
+    assert dec.dump_seq().tolist() == lit.dump_seq().tolist()
+
+
+# ---------------------------------------------------------------------------
 # Input generators (recipe checks, not method arithmetic)
 # ---------------------------------------------------------------------------
 def test_generator_recipe_is_stable():
