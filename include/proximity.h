@@ -40,7 +40,7 @@
 extern "C" {
 #endif
 
-#define PROXIMITY_ABI_VERSION 2u
+#define PROXIMITY_ABI_VERSION 3u
 
 enum {
   PROXIMITY_OK = 0,
@@ -54,6 +54,15 @@ enum {
 
 enum { PROXIMITY_DTYPE_F32 = 0, PROXIMITY_DTYPE_BF16 = 1 };
 enum { PROXIMITY_POLICY_FIFO = 0, PROXIMITY_POLICY_LRU = 1 };
+/* The index's distance function (Section 2.2: Euclidean, inner product or cosine, fixed when
+ * the index is built).  Smaller is closer in all three:
+ *   L2      sqrt(sum (q_i - x_i)^2)
+ *   IP      -(q . x)             (the ranked list is by descending inner product)
+ *   COSINE  1 - q.x / (|q| |x|)  (vectors of length zero are not validated)
+ * The cache compares a query with its keys by the same function (Section 3.1), except under
+ * IP: the negated inner product is no distance between two queries (a query is not nearest
+ * to itself), so the cache of an inner-product index compares by Euclidean distance. */
+enum { PROXIMITY_METRIC_L2 = 0, PROXIMITY_METRIC_IP = 1, PROXIMITY_METRIC_COSINE = 2 };
 
 /* Limits checked by proximity_create(). */
 #define PROXIMITY_MAX_K 240u
@@ -97,6 +106,10 @@ typedef struct proximity_config {
                              the origin; bit i of a query's code is 1 exactly when its inner
                              product with row i is >= 0 (evaluated in float64).  Copied at
                              creation; NULL when lsh_bits is 0                               */
+  uint32_t metric;        /* PROXIMITY_METRIC_*: ranks the documents, is the unit of tau and of
+                             every reported distance.  Under COSINE the instance keeps its keys
+                             scaled to unit length (proximity_cache_dump returns them so)    */
+  uint32_t reserved0;     /* must be 0                                                        */
 } proximity_config;
 
 /* Counters since creation or the last proximity_clear(). */
@@ -133,7 +146,7 @@ uint32_t proximity_abi_version(void);
  * (capacity x dim float32 keys, capacity x rerank_factor*k values) and all
  * workspaces, sized for max_batch.  *out receives the handle.  Blocks until the norms are done.
  * Errors: INVALID_ARG (null, bad struct_size, dim/k/max_batch/capacity/n_docs/
- * rerank_factor*k/lsh_bits outside the limits, unknown dtype/policy, lsh_planes
+ * rerank_factor*k/lsh_bits outside the limits, unknown dtype/policy/metric, lsh_planes
  * null with lsh_bits > 0, corpus null with n_docs > 0), OOM,
  * HIP.  On error *out is set to NULL.
  */
@@ -149,15 +162,17 @@ void proximity_destroy(proximity_t* h);
  *   queries    DEVICE [n][dim] float32
  *   n          1..max_batch (0 is accepted and does nothing)
  *   k          must equal cfg.k
- *   tau        tolerance as Euclidean (not squared) distance; finite, >= 0.
+ *   tau        tolerance in the units of the instance's distance function between query
+ *              and key (Euclidean, not squared, under L2 and IP; cosine distance under
+ *              COSINE); finite, >= 0.
  *              A key at distance exactly tau is a hit.  May differ between calls.
  *   out_ids    DEVICE [n][k] int64: ranked document indices (ascending distance,
  *              equal distances by ascending index; -1 padding when n_docs < k).
  *              On a hit: the list stored with the matched key, unchanged
  *              (rerank_factor 1), or the k of the stored documents nearest to
  *              this query (rerank_factor > 1, Section 3.3.4).
- *   out_dists  DEVICE [n][k] float32 or NULL: Euclidean distances that go with
- *              out_ids (+inf padding).  On a hit with rerank_factor 1 these are
+ *   out_dists  DEVICE [n][k] float32 or NULL: the distances (by the instance's distance
+ *              function) that go with out_ids (+inf padding).  On a hit with rerank_factor 1 these are
  *              the stored distances to the matched key, not to the query; with
  *              rerank_factor > 1 they are distances to the query.
  *   out_hit    DEVICE [n] uint8: 1 = answered from the cache, 0 = index searched

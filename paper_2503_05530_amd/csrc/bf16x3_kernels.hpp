@@ -58,7 +58,7 @@ __global__ __launch_bounds__(TM * 4, TM == 128 ? 1 : 2) void scan_bf16x3_kernel(
     const uint16_t* __restrict__ X, const float* __restrict__ xnrm, long n_rows, int dim,
     const uint16_t* __restrict__ Qplanes, long plane_stride, const int* __restrict__ m_count_ptr,
     int m_limit, int m_base, int m_lo, int m_hi, int kp, const uint64_t* __restrict__ seed,
-    uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out) {
+    uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out, int cosine) {
   constexpr int NW = TM / 16;                   // waves per block
   constexpr int NT = NW * 64;                   // threads per block
   constexpr int TN = 32 * NW;                   // corpus rows per tile (32 per wave)
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(TM * 4, TM == 128 ? 1 : 2) void scan_bf16x3_kernel(
 #pragma unroll
         for (int j = 0; j < CB; ++j) {
           const int q = m0 + qb0 + 32 * j + r32;
-          if (q < M && row0 + lr < n_rows) out[long(q) * n_rows + row0 + lr] = pack_key(nr - 2.f * acc[j][e], uint32_t(row0 + lr));
+          if (q < M && row0 + lr < n_rows) out[long(q) * n_rows + row0 + lr] = pack_key(row_score(nr, acc[j][e], cosine), uint32_t(row0 + lr));
           acc[j][e] = 0.f;
         }
       }
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(TM * 4, TM == 128 ? 1 : 2) void scan_bf16x3_kernel(
       const bool row_ok = row0 + lr < n_rows;
 #pragma unroll
       for (int j = 0; j < CB; ++j) {
-        const float sc = nr - 2.f * acc[j][e];
+        const float sc = row_score(nr, acc[j][e], cosine);
         acc[j][e] = sc;
         pass[j] |= (sc <= T[j] && row_ok) ? (1u << e) : 0u;
       }

@@ -292,13 +292,13 @@ __global__ __launch_bounds__(64) void resolver_kernel(
 //     stored list now, before any list is overwritten: the list itself (K == k), or
 //     with a re-ranking factor above 1 (K = rho * k stored per key, Section 3.3.4) the
 //     k stored documents nearest to the row's own query.
-// X / corpus_dtype: the corpus, read only for re-ranking.
+// X / corpus_kind: the corpus with its element type and distance function (see corpus_kind), read only for re-ranking.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void post_resolve_kernel(
     int n, int c, int dim, int k, int K, int copy_keys, long long base_seq, float* srcs, float* srcnrm,
     const long long* __restrict__ slot_seq, const uint8_t* __restrict__ hit, const int* __restrict__ src,
     const int* __restrict__ row_slot, const int64_t* __restrict__ val_ids, const float* __restrict__ val_d,
-    const void* __restrict__ X, int corpus_dtype, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
+    const void* __restrict__ X, int corpus_kind, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   const int i = blockIdx.x;
   if (i >= n) return;
   if (hit[i]) {
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(256) void post_resolve_kernel(
         __shared__ int cid[256];
         const float* q = srcs + long(c + i) * dim;
         float* od = out_d ? out_d + long(i) * k : nullptr;
-        block_rerank_stored_any<256>(corpus_dtype, val_ids + long(s) * K, K, k, q, X, dim, out_ids + long(i) * k, od,
+        block_rerank_stored_any<256>(corpus_kind, val_ids + long(s) * K, K, k, q, X, dim, out_ids + long(i) * k, od,
                                      keys, d64, cid, threadIdx.x);
       }
     }
@@ -347,7 +347,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, int 
                                                        const int64_t* __restrict__ res_ids,
                                                        const float* __restrict__ res_d, int64_t* val_ids,
                                                        float* val_d, const float* __restrict__ batch_rows, int dim,
-                                                       const void* __restrict__ X, int corpus_dtype,
+                                                       const void* __restrict__ X, int corpus_kind,
                                                        int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   const int i = blockIdx.x;
   if (i >= n) return;
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, int 
       __shared__ int cid[256];
       const float* q = batch_rows + long(i) * dim;
       float* od = out_d ? out_d + long(i) * k : nullptr;
-      block_rerank_stored_any<256>(corpus_dtype, res_ids + long(from) * K, K, k, q, X, dim, out_ids + long(i) * k, od,
+      block_rerank_stored_any<256>(corpus_kind, res_ids + long(from) * K, K, k, q, X, dim, out_ids + long(i) * k, od,
                                    keys, d64, cid, threadIdx.x);
     }
     return;
@@ -408,7 +408,7 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
     const float* __restrict__ queries, int n, int c, int dim, int k, int K, int policy_lru, long long base_seq,
     double tau, CacheState* st, long long* slot_seq, int* slot_next, int* slot_prev, float* srcs, float* srcnrm,
     const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, const void* __restrict__ X,
-    int corpus_dtype, double* D64, int phase,
+    int corpus_kind, double* D64, int phase,
     uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
     int* __restrict__ miss_count, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
           }
         } else {
           // re-ranking factor above 1 (Section 3.3.4): the stored documents nearest to this row's query
-          block_rerank_stored_any<1024>(corpus_dtype, val_ids + long(s) * K, K, k, queries + long(i) * dim, X, dim,
+          block_rerank_stored_any<1024>(corpus_kind, val_ids + long(s) * K, K, k, queries + long(i) * dim, X, dim,
                                         out_ids + long(i) * k, out_d ? out_d + long(i) * k : nullptr, rr_keys, rr_d,
                                         rr_id, tid);
           __syncthreads();  // the LDS arrays serve the next row

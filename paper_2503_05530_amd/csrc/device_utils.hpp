@@ -169,4 +169,15 @@ __device__ __forceinline__ int next_pow2(int v) {
   return p;
 }
 
+// Score of a corpus row from its inner product with the query; smaller is closer, and per query
+// the order of the scores is the order of the distances (Section 2.2's three distance functions):
+//   Euclidean:      |x|^2 - 2 q.x    (row_term = |x|^2; the query's own |q|^2 is the same for every row)
+//   inner product:  -2 q.x           (row_term = 0)
+//   cosine:         -2 q.x / |x|     (row_term = 1/|x|, `cosine` set)
+__device__ __forceinline__ float row_score(float row_term, float dot, int cosine) {
+  const float mul = cosine ? -2.f * row_term : -2.f;
+  const float add = cosine ? 0.f : row_term;
+  return fmaf(dot, mul, add);
+}
+
 }  // namespace prox

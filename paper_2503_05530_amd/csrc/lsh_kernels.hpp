@@ -336,7 +336,7 @@ __global__ __launch_bounds__(1024) void lsh_small_kernel(
     const float* __restrict__ planes, int policy_lru, long long base_seq, double tau, float* srcs,
     long long* slot_seq, int* slot_next, int* slot_prev, int* bkt_size, int* bkt_head, int* bkt_tail, CacheState* st,
     const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, const void* __restrict__ X,
-    int corpus_dtype, uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
+    int corpus_kind, uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
     int* __restrict__ miss_count, int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
   __shared__ uint64_t keys[kLshMaxBucket];
   __shared__ double d64[kLshMaxBucket];
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(1024) void lsh_small_kernel(
     const int slot0 = code * b;
     float* bucket_keys = srcs + long(slot0) * dim;
     const int size = bkt_size[code];
-    block_candidate_distances<kDtypeF32, 16>(keys, size, q, bucket_keys, dim, d64, cid, tid);
+    block_candidate_distances<kDtypeF32, 16>(keys, size, q, bucket_keys, dim, d64, cid, tid, kMetricL2);
     __syncthreads();
     if (tid < 64) {
       ResolverBest best{__longlong_as_double(0x7ff0000000000000ll), 0x7fffffffffffffffll, -1};
@@ -453,7 +453,7 @@ __global__ __launch_bounds__(1024) void lsh_small_kernel(
       }
     } else {
       __syncthreads();
-      block_rerank_stored_any<1024>(corpus_dtype, val_ids + long(s) * K, K, k, queries + long(i) * dim, X, dim,
+      block_rerank_stored_any<1024>(corpus_kind, val_ids + long(s) * K, K, k, queries + long(i) * dim, X, dim,
                                     out_ids + long(i) * k, out_d ? out_d + long(i) * k : nullptr, keys, d64, cid, tid);
     }
   }

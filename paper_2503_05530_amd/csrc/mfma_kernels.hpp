@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_topk_kernel(
     const void* __restrict__ X, const float* __restrict__ xnrm, long n_rows, int dim,
     const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
     int m_limit, int m_base, int m_lo, int m_hi, int kp, const uint64_t* __restrict__ seed,
-    uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out) {
+    uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out, int cosine) {
   constexpr int WR = TM >= 128 ? 2 : 4;        // waves along corpus rows
   constexpr int WC = 4 / WR;                   // waves along queries
   constexpr int RB = TN / WR / 32;             // 32-row blocks per wave
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256, 2) void scan_mfma_topk_kernel(
 #pragma unroll
         for (int j = 0; j < CB; ++j) {
           const int q = b_row0 + 32 * j + (lane & 31);
-          const float sc = nr - 2.f * acc[i][j][e];
+          const float sc = row_score(nr, acc[i][j][e], cosine);
           if (sc <= T[j] && row < n_rows && m0 + q < M) {
             const int pos = atomicAdd(&count[q], 1);
             my_buf[long(q) * kTopkCap + pos] = pack_key(sc, uint32_t(row));
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(256, TM == 96 ? 1 : 2) void scan_mfma_dma_kernel(
     const float* __restrict__ X, const float* __restrict__ xnrm, long n_rows, int dim,
     const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
     int m_limit, int m_base, int m_lo, int m_hi, int kp, const uint64_t* __restrict__ seed,
-    uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out) {
+    uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out, int cosine) {
   constexpr int TN = TM >= 128 ? 64 : 128;      // corpus rows per tile
   constexpr int WR = TN / 32;                   // waves along corpus rows (32 rows each)
   constexpr int WC = 4 / WR;                    // waves along queries
@@ -503,7 +503,7 @@ __global__ __launch_bounds__(256, TM == 96 ? 1 : 2) void scan_mfma_dma_kernel(
 #pragma unroll
         for (int j = 0; j < CB; ++j) {
           const int q = m0 + qb0 + 32 * j + r32;
-          if (q < M && row0 + lr < n_rows) out[long(q) * n_rows + row0 + lr] = pack_key(nr - 2.f * acc[j][e], uint32_t(row0 + lr));
+          if (q < M && row0 + lr < n_rows) out[long(q) * n_rows + row0 + lr] = pack_key(row_score(nr, acc[j][e], cosine), uint32_t(row0 + lr));
           acc[j][e] = 0.f;
         }
       }
@@ -523,7 +523,7 @@ __global__ __launch_bounds__(256, TM == 96 ? 1 : 2) void scan_mfma_dma_kernel(
       const bool row_ok = row0 + lr < n_rows;
 #pragma unroll
       for (int j = 0; j < CB; ++j) {
-        const float sc = nr - 2.f * acc[j][e];
+        const float sc = row_score(nr, acc[j][e], cosine);
         acc[j][e] = sc;
         pass[j] |= (sc <= T[j] && row_ok) ? (1u << e) : 0u;
       }

@@ -49,7 +49,7 @@ constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32
 constexpr size_t kLshLdsMax = 144 * 1024;  // dynamic LDS the bucket resolver may ask for (query + bucket keys)
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
 
-static_assert(sizeof(proximity_config) == 64, "proximity_config layout is part of the ABI");
+static_assert(sizeof(proximity_config) == 72, "proximity_config layout is part of the ABI");
 static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is part of the ABI");
 static_assert(sizeof(proximity_launch_t) == 16, "proximity_launch_t layout is part of the ABI");
 
@@ -188,7 +188,7 @@ int stream_group(int dim, int n) {
 template <int DT, int MQ, bool ONCE>
 void launch_scores_stream_mq(const proximity* h, const void* X, const float* xnrm, long n_rows, int dim,
                              const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
-                             int m_begin, float* S, long ldS, hipStream_t s) {
+                             int m_begin, float* S, long ldS, int cosine, hipStream_t s) {
   const long n_blocks64 = (n_rows + 63) / 64;
   long grid = (n_blocks64 + 3) / 4;
   const long cap = long(h->n_cu) * 8;
@@ -198,7 +198,7 @@ void launch_scores_stream_mq(const proximity* h, const void* X, const float* xnr
 #define PROX_STREAM_CASE(D)                                                                              \
   case D:                                                                                                \
     scores_stream_kernel<D, MQ, DT, ONCE><<<g, b, 0, s>>>(X, xnrm, 0, n_rows, Qbase, qlist, m_count_ptr,      \
-                                                    m_limit, m_begin, S, ldS);                          \
+                                                    m_limit, m_begin, S, ldS, cosine);                  \
     return;
   switch (dim) {
     PROX_STREAM_CASE(768)
@@ -212,25 +212,25 @@ void launch_scores_stream_mq(const proximity* h, const void* X, const float* xnr
   if (ggrid > cap) ggrid = cap;
   if (ggrid < 1) ggrid = 1;
   scores_stream_generic_kernel<MQ, DT><<<dim3((unsigned)ggrid), b, size_t(MQ) * dim * sizeof(float), s>>>(
-      X, xnrm, 0, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS);
+      X, xnrm, 0, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, cosine);
 }
 
 template <int DT, bool ONCE>
 void launch_scores_stream(const proximity* h, int mq, const void* X, const float* xnrm, long n_rows, int dim,
                           const float* Qbase, const int* qlist, const int* m_count_ptr, int m_limit,
-                          int m_begin, float* S, long ldS, hipStream_t s) {
+                          int m_begin, float* S, long ldS, int cosine, hipStream_t s) {
   switch (mq) {
     case 1:
-      launch_scores_stream_mq<DT, 1, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      launch_scores_stream_mq<DT, 1, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, cosine, s);
       break;
     case 2:
-      launch_scores_stream_mq<DT, 2, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      launch_scores_stream_mq<DT, 2, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, cosine, s);
       break;
     case 4:
-      launch_scores_stream_mq<DT, 4, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      launch_scores_stream_mq<DT, 4, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, cosine, s);
       break;
     default:
-      launch_scores_stream_mq<DT, 8, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, s);
+      launch_scores_stream_mq<DT, 8, ONCE>(h, X, xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, m_begin, S, ldS, cosine, s);
       break;
   }
 }
@@ -254,6 +254,7 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
                          const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
                          uint64_t* out, bool dump_all, hipStream_t s) {
   const int dim = int(h->cfg.dim);
+  const int cosine = h->cfg.metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
   const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
   const bool dma = !bf16 && dim >= 64;  // the global->LDS pipeline needs float32 rows and two slabs per tile
   if (bf16 && dim >= 64) {
@@ -268,11 +269,11 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
     if (dump_all)                                                                                               \
       scan_bf16x3_kernel<TM, true><<<grid, dim3(TM * 4), 0, s>>>(X16, h->xnrm, n_rows, dim, h->qplanes,        \
                                                                   plane_stride, m_count_ptr, m_limit, base, LO, \
-                                                                  HI, kp, seed, h->topk_buf, out);              \
+                                                                  HI, kp, seed, h->topk_buf, out, cosine);      \
     else                                                                                                        \
       scan_bf16x3_kernel<TM, false><<<grid, dim3(TM * 4), 0, s>>>(X16, h->xnrm, n_rows, dim, h->qplanes,       \
                                                                    plane_stride, m_count_ptr, m_limit, base,    \
-                                                                   LO, HI, kp, seed, h->topk_buf, out);         \
+                                                                   LO, HI, kp, seed, h->topk_buf, out, cosine); \
   } while (0)
     if (!known || m_limit <= 64) PROX_SCAN16(64, 0, 64);
     if (m_limit > 64) PROX_SCAN16(128, 64, 0x7fffffff);
@@ -285,19 +286,19 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
     if (dma && dump_all)                                                                                       \
       scan_mfma_dma_kernel<TM, true><<<grid, dim3(256), 0, s>>>(                                               \
           static_cast<const float*>(h->cfg.corpus), h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit,  \
-          base, LO, HI, kp, seed, h->topk_buf, out);                                                           \
+          base, LO, HI, kp, seed, h->topk_buf, out, cosine);                                                   \
     else if (dma)                                                                                              \
       scan_mfma_dma_kernel<TM, false><<<grid, dim3(256), 0, s>>>(                                              \
           static_cast<const float*>(h->cfg.corpus), h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit,  \
-          base, LO, HI, kp, seed, h->topk_buf, out);                                                           \
+          base, LO, HI, kp, seed, h->topk_buf, out, cosine);                                                   \
     else if (bf16)                                                                                             \
       scan_mfma_topk_kernel<TM, TN, kDtypeBF16><<<grid, dim3(256), 0, s>>>(                                    \
           h->cfg.corpus, h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, seed,     \
-          h->topk_buf, out);                                                                                   \
+          h->topk_buf, out, cosine);                                                                           \
     else                                                                                                       \
       scan_mfma_topk_kernel<TM, TN, kDtypeF32><<<grid, dim3(256), 0, s>>>(                                     \
           h->cfg.corpus, h->xnrm, n_rows, dim, Qbase, qlist, m_count_ptr, m_limit, base, LO, HI, kp, seed,     \
-          h->topk_buf, out);                                                                                   \
+          h->topk_buf, out, cosine);                                                                           \
   } while (0)
   const bool known = m_count_ptr == nullptr;  // then M = m_limit and only its own shape is launched
   if (!known || m_limit <= 32) PROX_SCAN(32, 256, 0, 32);
@@ -341,6 +342,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   }
   const int kp = k + kSlack;
   const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
+  const int metric = int(h->cfg.metric), cosine = metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
   int cur = 0;
   if (m_limit <= kStreamMaxQueries) {
     const int mq = stream_group(dim, m_limit);
@@ -349,10 +351,10 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       prof_begin(h, s);
       if (bf16)
         launch_scores_stream<kDtypeBF16, true>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
-                                         m0, h->S, h->ldS, s);
+                                         m0, h->S, h->ldS, cosine, s);
       else
         launch_scores_stream<kDtypeF32, true>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
-                                        m0, h->S, h->ldS, s);
+                                        m0, h->S, h->ldS, cosine, s);
       prof_end(h, s, m0, mq);
       if (small_routing) {
         // a handful of queries: selection, float64 ranking and routing in one launch;
@@ -362,11 +364,11 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
           if (bf16)
             select_finish_small_kernel<kDtypeBF16, kSelE><<<grid, dim3(kSelThreads), 0, s>>>(
                 h->S, h->ldS, N, kp, k, k_out, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
-                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d);
+                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d, metric);
           else
             select_finish_small_kernel<kDtypeF32, kSelE><<<grid, dim3(kSelThreads), 0, s>>>(
                 h->S, h->ldS, N, kp, k, k_out, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
-                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d);
+                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d, metric);
         }
       } else {
         select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
@@ -409,10 +411,10 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   }
   if (bf16)
     rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
-                                                                     qlist, m_count_ptr, m_limit, res_ids, res_d);
+                                                                     qlist, m_count_ptr, m_limit, res_ids, res_d, metric);
   else
     rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
-                                                                    qlist, m_count_ptr, m_limit, res_ids, res_d);
+                                                                    qlist, m_count_ptr, m_limit, res_ids, res_d, metric);
   return PROXIMITY_OK;
 }
 
@@ -477,6 +479,9 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown corpus_dtype %u", cfg->corpus_dtype);
   if (cfg->policy != PROXIMITY_POLICY_FIFO && cfg->policy != PROXIMITY_POLICY_LRU)
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown policy %u", cfg->policy);
+  if (cfg->metric > PROXIMITY_METRIC_COSINE)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown metric %u", cfg->metric);
+  if (cfg->reserved0 != 0) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "reserved0 must be 0");
   if (cfg->device < 0) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "device=%d is negative", cfg->device);
 
   int n_dev = 0;
@@ -590,6 +595,11 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
       launch_row_norms<kDtypeBF16>(h, cfg->corpus, long(N), int(d), h->xnrm, nullptr);
     else
       launch_row_norms<kDtypeF32>(h, cfg->corpus, long(N), int(d), h->xnrm, nullptr);
+    if (cfg->metric != PROXIMITY_METRIC_L2) {
+      long g = (long(N) + 255) / 256;
+      if (g > long(h->n_cu) * 8) g = long(h->n_cu) * 8;
+      row_terms_kernel<<<dim3((unsigned)g), dim3(256)>>>(h->xnrm, long(N), cfg->metric == PROXIMITY_METRIC_COSINE ? 1 : 0);
+    }
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -642,6 +652,20 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   const bool lsh = h->lsh_bits > 0;
   const long long base_seq = (long long)h->next_seq;
   float* batch_rows = h->srcs + size_t(c) * dim;
+  const int xkind = corpus_kind(int(h->cfg.corpus_dtype), int(h->cfg.metric));
+  // The cache compares query and key.  Euclidean index, and inner-product index (whose cache falls
+  // back to the Euclidean distance): as given.  Cosine index: the rows are scaled to unit length
+  // first (so are the keys they become); between unit vectors the cosine distance is half the
+  // squared Euclidean distance, so "cosine distance <= tau" is "Euclidean distance <= sqrt(2 tau)"
+  // and the whole cache side runs unchanged on the scaled rows.
+  double tau_key = double(tau);
+  bool rows_in_place = false;
+  if (h->cfg.metric == PROXIMITY_METRIC_COSINE) {
+    unit_rows_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(queries, nn, dim, batch_rows);
+    queries = batch_rows;
+    rows_in_place = true;
+    tau_key = std::sqrt(2.0 * double(tau));
+  }
 
   const int K = h->K;
   if (nn <= kSmallRows && h->cfg.n_docs > 0 && !lsh) {
@@ -651,9 +675,9 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     const int grid = c > 0 ? ((c + 15) / 16 < h->n_cu ? (c + 15) / 16 : h->n_cu) : 1;
     for (int phase = 1; phase <= 2; ++phase) {
       probe_resolve_small_kernel<<<dim3(phase == 2 ? 1 : grid), dim3(1024), 0, s>>>(
-          queries, nn, c, dim, kk, K, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state,
+          queries, nn, c, dim, kk, K, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, h->state,
           h->slot_seq, h->slot_next, h->slot_prev, h->srcs, h->srcnrm, h->val_ids, h->val_d, h->cfg.corpus,
-          int(h->cfg.corpus_dtype), h->D64, phase, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids,
+          xkind, h->D64, phase, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids,
           out_dists);
     }
     const SmallRouting rt{out_hit, h->src, h->row_slot, h->slot_seq, h->val_ids, h->val_d, base_seq, nn, c};
@@ -669,9 +693,9 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     // selection and routing launches as for the flat cache.
     lsh_small_kernel<<<dim3(1), dim3(1024), 0, s>>>(
         queries, nn, int(h->cfg.capacity), c, dim, kk, K, h->lsh_bits, h->lsh_planes,
-        h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->srcs, h->slot_seq, h->slot_next,
+        h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, h->srcs, h->slot_seq, h->slot_next,
         h->slot_prev, h->bkt_size, h->bkt_head, h->bkt_tail, h->state, h->val_ids, h->val_d, h->cfg.corpus,
-        int(h->cfg.corpus_dtype), out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
+        xkind, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
     const SmallRouting rt{out_hit, h->src, h->row_slot, h->slot_seq, h->val_ids, h->val_d, base_seq, nn, c};
     rc = enqueue_scan(h, queries, h->miss_list, h->miss_count, nn, K, kk, out_ids, out_dists, &rt, s);
     if (rc != PROXIMITY_OK) return rc;
@@ -680,7 +704,8 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     return check_launch(h, "proximity_search_batch");
   }
 
-  HIP_TRY(h, hipMemcpyAsync(batch_rows, queries, size_t(n) * dim * sizeof(float), hipMemcpyDeviceToDevice, s));
+  if (!rows_in_place)
+    HIP_TRY(h, hipMemcpyAsync(batch_rows, queries, size_t(n) * dim * sizeof(float), hipMemcpyDeviceToDevice, s));
   if (lsh) {
     // Section 3.2: codes, regrouping by code, one block per bucket that occurs, miss list in row order
     const int b = int(h->cfg.capacity);
@@ -692,7 +717,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     const size_t row_bytes = size_t(dim) * sizeof(float);
     const int keys_in_lds = (size_t(b) + 1) * row_bytes <= kLshLdsMax ? 1 : 0;
     lsh_resolve_kernel<<<dim3(max_segs), dim3(kLshThreads), (keys_in_lds ? size_t(b) + 1 : 1) * row_bytes, s>>>(
-        h->lsh_sorted, h->lsh_seg_start, h->lsh_n_segs, nn, b, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), keys_in_lds,
+        h->lsh_sorted, h->lsh_seg_start, h->lsh_n_segs, nn, b, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, keys_in_lds,
         batch_rows,
         h->srcs, h->slot_seq, h->slot_next, h->slot_prev, h->bkt_size, h->bkt_head, h->bkt_tail, h->state, out_hit,
         h->src, h->row_slot);
@@ -706,7 +731,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
       const int mq = stream_group(dim, nn);
       for (int m0 = 0; m0 < nn; m0 += mq)
         launch_scores_stream<kDtypeF32, false>(h, mq, h->srcs, h->srcnrm, long(c) + nn, dim, batch_rows, nullptr, nullptr,
-                                        nn, m0, h->D32 + size_t(m0) * h->ldD, h->ldD, s);
+                                        nn, m0, h->D32 + size_t(m0) * h->ldD, h->ldD, 0, s);
     } else if (long((c + nn + 31) / 32) * ((nn + 31) / 32) <= kProbeSmallBlocks) {
       probe_mfma_small_kernel<<<dim3((c + nn + 31) / 32, (nn + 31) / 32), dim3(256), 0, s>>>(
           h->srcs, h->srcnrm, c + nn, batch_rows, nn, dim, h->D32, h->ldD);
@@ -715,25 +740,25 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
           h->srcs, h->srcnrm, c + nn, batch_rows, nn, dim, h->D32, h->ldD);
     }
     probe_candidates_kernel<<<dim3(nn), dim3(256), 0, s>>>(h->D32, h->ldD, h->srcs, h->srcnrm, dim, c, nn, h->state,
-                                                           double(tau), kCandCap, h->cand_cnt, h->cand_src,
+                                                           tau_key, kCandCap, h->cand_cnt, h->cand_src,
                                                            h->cand_d);
   }
   // the sequential resolver: with its state in LDS whenever that fits
   if (have_probe && resolver_lds_fits(size_t(c), size_t(nn), kResolverLdsMax)) {
     resolver_lds_kernel<<<dim3(1), dim3(kResolverThreads), resolver_lds_bytes(size_t(c), size_t(nn)), s>>>(
-        nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, double(tau), h->state, h->slot_seq,
+        nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, h->state, h->slot_seq,
         h->slot_next, h->slot_prev, h->cand_cnt, h->cand_src, h->cand_d, kCandCap, h->D32, h->ldD, h->srcs, h->srcnrm,
         out_hit, h->src, h->row_slot, h->miss_list, h->miss_count);
   } else {
     resolver_kernel<<<dim3(1), dim3(64), 0, s>>>(nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq,
-                                                 double(tau), h->state, h->slot_seq, h->slot_next, h->slot_prev,
+                                                 tau_key, h->state, h->slot_seq, h->slot_next, h->slot_prev,
                                                  have_probe ? h->cand_cnt : nullptr, h->cand_src, h->cand_d, kCandCap,
                                                  h->D32, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot,
                                                  h->miss_list, h->miss_count);
   }
   }
   const void* X = h->cfg.n_docs > 0 ? h->cfg.corpus : nullptr;
-  const int xdt = int(h->cfg.corpus_dtype);
+  const int xdt = xkind;
   post_resolve_kernel<<<dim3(nn), dim3(256), 0, s>>>(nn, c, dim, kk, K, lsh ? 0 : 1, base_seq, h->srcs, h->srcnrm, h->slot_seq,
                                                      out_hit, h->src, h->row_slot, h->val_ids, h->val_d, X, xdt,
                                                      out_ids, out_dists);

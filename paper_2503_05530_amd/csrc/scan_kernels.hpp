@@ -114,7 +114,7 @@ template <int DIM, int MQ, int DT, bool ONCE>
 __global__ __launch_bounds__(256) void scores_stream_kernel(
     const void* __restrict__ X, const float* __restrict__ xnrm, long row_begin, long n_rows,
     const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
-    int m_limit, int m_begin, float* __restrict__ S, long ldS) {
+    int m_limit, int m_begin, float* __restrict__ S, long ldS, int cosine) {
   constexpr int COLS = RowChunk<DT>::kCols;       // columns per lane per segment
   constexpr int SEG = 64 * COLS;                  // columns per wave-wide load
   constexpr int NSEG = (DIM + SEG - 1) / SEG;     // segments per row
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(256) void scores_stream_kernel(
       const float nr = xnrm[row_begin + row];
 #pragma unroll
       for (int m = 0; m < MQ; ++m)
-        if (m < m_here) S[long(m) * ldS + row] = nr - 2.f * stage[wib][m][lane];
+        if (m < m_here) S[long(m) * ldS + row] = row_score(nr, stage[wib][m][lane], cosine);
     }
   }
 }
@@ -205,7 +205,7 @@ template <int MQ, int DT>
 __global__ __launch_bounds__(256) void scores_stream_generic_kernel(
     const void* __restrict__ X, const float* __restrict__ xnrm, long row_begin, long n_rows, int dim,
     const float* __restrict__ Qbase, const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
-    int m_limit, int m_begin, float* __restrict__ S, long ldS) {
+    int m_limit, int m_begin, float* __restrict__ S, long ldS, int cosine) {
   constexpr int COLS = RowChunk<DT>::kCols;
   constexpr int SEG = 64 * COLS;
   extern __shared__ float qs[];  // [MQ][dim]
@@ -244,9 +244,31 @@ __global__ __launch_bounds__(256) void scores_stream_generic_kernel(
       const float nr = xnrm[row_begin + row];
 #pragma unroll
       for (int m = 0; m < MQ; ++m)
-        if (m < m_here) S[long(m) * ldS + row] = nr - 2.f * acc[m];
+        if (m < m_here) S[long(m) * ldS + row] = row_score(nr, acc[m], cosine);
     }
   }
+}
+
+// The per-row term of row_score for the distance functions other than Euclidean, made in place
+// from the squared lengths: inner product 0, cosine 1/|x|.
+__global__ __launch_bounds__(256) void row_terms_kernel(float* __restrict__ nrm, long n_rows, int cosine) {
+  const long stride = long(gridDim.x) * 256;
+  for (long r = long(blockIdx.x) * 256 + threadIdx.x; r < n_rows; r += stride)
+    nrm[r] = cosine ? 1.f / sqrtf(nrm[r]) : 0.f;
+}
+
+// Rows scaled to unit length (float64 sum of squares, one rounding per element): what a cosine
+// index's cache works on.  One wave per row.
+__global__ __launch_bounds__(256) void unit_rows_kernel(const float* __restrict__ in, int n_rows, int dim,
+                                                        float* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows) return;
+  const float* src = in + long(row) * dim;
+  double acc = 0.0;
+  for (int i = lane; i < dim; i += 64) acc += double(src[i]) * double(src[i]);
+  const double scale = 1.0 / sqrt(wave_sum(acc));
+  for (int i = lane; i < dim; i += 64) out[long(row) * dim + i] = float(double(src[i]) * scale);
 }
 
 }  // namespace prox

@@ -86,14 +86,23 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const void* __restr
 }
 
 
-// Float64 Euclidean distance (direct-difference form) from query q to each of the kp candidate
-// rows named by `keys`, by the NW waves of a block; four candidates per wave are in flight at
-// once so that their row fetches overlap.  d64[c] / cid[c] receive distance and id of candidate
+// The distance functions of Section 2.2, as numbered at the C boundary.
+constexpr int kMetricL2 = 0, kMetricIP = 1, kMetricCosine = 2;
+// How kernels that only pass the corpus through are told what it is: element type in the low
+// four bits, distance function above them.
+__host__ __device__ constexpr int corpus_kind(int dtype, int metric) { return dtype | (metric << 4); }
+__host__ __device__ constexpr int kind_dtype(int kind) { return kind & 15; }
+__host__ __device__ constexpr int kind_metric(int kind) { return kind >> 4; }
+
+// Float64 distance from query q to each of the kp candidate rows named by `keys`, by the NW waves
+// of a block; four candidates per wave are in flight at once so that their row fetches overlap.
+// Euclidean: direct-difference form, sqrt(sum (q_i - x_i)^2); inner product: -(q.x); cosine:
+// 1 - q.x / (|q| |x|), all sums in float64.  d64[c] / cid[c] receive distance and id of candidate
 // c (padding candidates: +inf and INT_MAX).  The caller synchronises afterwards.
 template <int DT, int NW>
 __device__ __forceinline__ void block_candidate_distances(const uint64_t* keys, int kp, const float* __restrict__ q,
                                                           const void* __restrict__ X, int dim, double* d64, int* cid,
-                                                          int tid) {
+                                                          int tid, int metric = kMetricL2) {
   using Elem = typename std::conditional<DT == kDtypeF32, float, uint16_t>::type;
   const int lane = tid & 63, wib = tid >> 6;
   constexpr int G = 4;
@@ -107,6 +116,39 @@ __device__ __forceinline__ void block_candidate_distances(const uint64_t* keys, 
       id[g] = c < kp ? key_id(keys[c]) : -1;
       row[g] = static_cast<const Elem*>(X) + long(id[g] >= 0 ? id[g] : 0) * dim;
       acc[g] = 0.0;
+    }
+    if (metric != kMetricL2) {
+      // inner product, and for cosine the two squared lengths as well
+      double xx[G], qq = 0.0;
+#pragma unroll
+      for (int g = 0; g < G; ++g) xx[g] = 0.0;
+      for (int i = lane; i < dim; i += 64) {
+        const double qv = double(q[i]);
+        qq += qv * qv;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          double xv;
+          if (DT == kDtypeF32)
+            xv = double(reinterpret_cast<const float*>(row[g])[i]);
+          else
+            xv = double(bf16_to_float(reinterpret_cast<const uint16_t*>(row[g])[i]));
+          acc[g] += qv * xv;
+          xx[g] += xv * xv;
+        }
+      }
+      qq = wave_sum(qq);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const int c = c0 + g * NW;
+        const double dot = wave_sum(acc[g]);
+        const double len2 = wave_sum(xx[g]);
+        if (lane == 0 && c < kp) {
+          const double d = metric == kMetricIP ? -dot : 1.0 - dot / (sqrt(len2) * sqrt(qq));
+          d64[c] = id[g] >= 0 ? d : __longlong_as_double(0x7ff0000000000000ll);
+          cid[c] = id[g] >= 0 ? id[g] : 0x7fffffff;
+        }
+      }
+      continue;
     }
     for (int i = lane; i < dim; i += 64) {
       const double qv = double(q[i]);
@@ -166,27 +208,28 @@ template <int DT, int NT>
 __device__ __forceinline__ void block_rerank_stored(const int64_t* __restrict__ stored, int K, int k,
                                                     const float* __restrict__ q, const void* __restrict__ X, int dim,
                                                     int64_t* __restrict__ out_ids, float* __restrict__ out_d,
-                                                    uint64_t* keys, double* d64, int* cid, int tid) {
+                                                    uint64_t* keys, double* d64, int* cid, int tid,
+                                                    int metric = kMetricL2) {
   for (int e = tid; e < K; e += NT) {
     const int64_t id = stored[e];
     keys[e] = id >= 0 ? pack_key(0.f, uint32_t(id)) : kPadKey;
   }
   __syncthreads();
-  block_candidate_distances<DT, NT / 64>(keys, K, q, X, dim, d64, cid, tid);
+  block_candidate_distances<DT, NT / 64>(keys, K, q, X, dim, d64, cid, tid, metric);
   __syncthreads();
   block_write_ranked(d64, cid, K, k, out_ids, out_d, tid, NT);
 }
-// the same with the corpus type chosen at run time
+// the same with the corpus type and the distance function chosen at run time (see corpus_kind)
 template <int NT>
-__device__ __forceinline__ void block_rerank_stored_any(int corpus_dtype, const int64_t* __restrict__ stored, int K,
+__device__ __forceinline__ void block_rerank_stored_any(int kind, const int64_t* __restrict__ stored, int K,
                                                         int k, const float* __restrict__ q,
                                                         const void* __restrict__ X, int dim,
                                                         int64_t* __restrict__ out_ids, float* __restrict__ out_d,
                                                         uint64_t* keys, double* d64, int* cid, int tid) {
-  if (corpus_dtype == kDtypeBF16)
-    block_rerank_stored<kDtypeBF16, NT>(stored, K, k, q, X, dim, out_ids, out_d, keys, d64, cid, tid);
+  if (kind_dtype(kind) == kDtypeBF16)
+    block_rerank_stored<kDtypeBF16, NT>(stored, K, k, q, X, dim, out_ids, out_d, keys, d64, cid, tid, kind_metric(kind));
   else
-    block_rerank_stored<kDtypeF32, NT>(stored, K, k, q, X, dim, out_ids, out_d, keys, d64, cid, tid);
+    block_rerank_stored<kDtypeF32, NT>(stored, K, k, q, X, dim, out_ids, out_d, keys, d64, cid, tid, kind_metric(kind));
 }
 
 // Final ranking in float64.  One block of 16 waves per query: for each of the kp
@@ -202,7 +245,7 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
                                                          const int* __restrict__ qlist,
                                                          const int* __restrict__ m_count_ptr, int m_limit,
                                                          int64_t* __restrict__ res_ids,
-                                                         float* __restrict__ res_dists) {
+                                                         float* __restrict__ res_dists, int metric) {
   const int m = blockIdx.x;
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   if (m >= m_total) return;
@@ -213,7 +256,7 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
   __shared__ double d64[256];
   __shared__ int ids[256];
 
-  block_candidate_distances<DT, kRerankThreads / 64>(cand + long(m) * kp, kp, q, X, dim, d64, ids, threadIdx.x);
+  block_candidate_distances<DT, kRerankThreads / 64>(cand + long(m) * kp, kp, q, X, dim, d64, ids, threadIdx.x, metric);
   __syncthreads();
   block_write_ranked(d64, ids, kp, k, res_ids + long(qrow) * k, res_dists + long(qrow) * k, threadIdx.x,
                      kRerankThreads);
@@ -303,7 +346,7 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
     const float* __restrict__ S, long ldS, long len, int kp, int k, int k_out, uint64_t* __restrict__ lists,
     int n_seg, int phase, const void* __restrict__ X, int dim, const float* __restrict__ Qbase,
     const int* __restrict__ qlist, const int* __restrict__ m_count_ptr, int m_limit, int m_begin, SmallRouting rt,
-    int64_t* __restrict__ out_ids, float* __restrict__ out_d) {
+    int64_t* __restrict__ out_ids, float* __restrict__ out_d, int metric) {
   constexpr int SEG = E * kSelThreads;
   const int q = m_begin + blockIdx.y;   // position in the miss list; S rows are relative to m_begin
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
@@ -360,7 +403,7 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
   // ---- float64 ranking of the kp survivors (as rerank_f64_kernel) ----
   const int qrow = qlist ? qlist[q] : q;
   const float* qv = Qbase + long(qrow) * dim;
-  block_candidate_distances<DT, kSelThreads / 64>(list, kp, qv, X, dim, d64, cid, tid);
+  block_candidate_distances<DT, kSelThreads / 64>(list, kp, qv, X, dim, d64, cid, tid, metric);
   __syncthreads();
   for (int c = tid; c < kp; c += kSelThreads) {
     const double d = d64[c];
@@ -403,7 +446,7 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
           __syncthreads();
           block_rerank_stored<DT, kSelThreads>(fin_ids, k, k_out, Qbase + long(i) * dim, X, dim,
                                                out_ids + long(i) * k_out, out_d ? out_d + long(i) * k_out : nullptr,
-                                               list, d64, cid, tid);
+                                               list, d64, cid, tid, metric);
         }
       }
   }

@@ -24,7 +24,8 @@ def run_stream(px, queries: np.ndarray, tau: float, batch: int, device):
     return cat(ids), cat(dists), cat(hit)
 
 
-def assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref_queries, dist_rtol=DIST_RTOL_F32, what=""):
+def assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref_queries, dist_rtol=DIST_RTOL_F32, what="",
+                       metric=po.METRIC_L2):
     """Row-wise comparison of ranked lists.
 
     `ref_queries[t]` is the vector the distances of row t refer to (the query
@@ -32,8 +33,11 @@ def assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref_queries, dist_rto
     differ from the oracle only by swapping or substituting documents whose
     float64 distances agree with the oracle's, position by position, to
     ID_TIE_RTOL.  Returned distances must be within dist_rtol.
-    Returns the number of rows that needed the tie allowance.
+    Returns the number of rows that needed the tie allowance.  `metric`: the index's distance
+    function; inner products and cosine distances can be close to zero, so for them the two
+    comparisons also allow 1e-6 absolute.
     """
+    atol = 0 if metric == po.METRIC_L2 else 1e-6
     assert ids.shape == o_ids.shape, what
     excused = 0
     bad_rows = np.flatnonzero((ids != o_ids).any(axis=1))
@@ -42,17 +46,18 @@ def assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref_queries, dist_rto
         valid = ids[t] >= 0
         assert (valid == (o_ids[t] >= 0)).all(), f"{what} row {t}: padding differs"
         assert len(set(ids[t][valid].tolist())) == valid.sum(), f"{what} row {t}: duplicate ids"
-        d_true = po.l2_distances(ref_queries[t], corpus[ids[t][valid]])
-        np.testing.assert_allclose(d_true, o_dists[t][valid], rtol=ID_TIE_RTOL, atol=0,
+        d_true = po.metric_distances(ref_queries[t], corpus[ids[t][valid]], metric)
+        np.testing.assert_allclose(d_true, o_dists[t][valid], rtol=ID_TIE_RTOL, atol=atol * ID_TIE_RTOL,
                                    err_msg=f"{what} row {t}: ids differ beyond near-ties")
         excused += 1
     fin = np.isfinite(o_dists)
     assert (np.isfinite(dists) == fin).all(), what
-    np.testing.assert_allclose(dists[fin], o_dists[fin], rtol=dist_rtol, atol=0, err_msg=what)
+    np.testing.assert_allclose(dists[fin], o_dists[fin], rtol=dist_rtol, atol=atol, err_msg=what)
     return excused
 
 
-def assert_stream_parity(gpu, oracle_out, corpus, queries, dist_rtol=DIST_RTOL_F32, what="", reranked=False):
+def assert_stream_parity(gpu, oracle_out, corpus, queries, dist_rtol=DIST_RTOL_F32, what="", reranked=False,
+                         metric=po.METRIC_L2):
     """`reranked`: the instance re-ranks on a hit (re-ranking factor above 1), so every row's
     distances refer to its own query; otherwise a hit row's distances refer to the matched key."""
     ids, dists, hit = gpu
@@ -61,4 +66,4 @@ def assert_stream_parity(gpu, oracle_out, corpus, queries, dist_rtol=DIST_RTOL_F
     mism = np.flatnonzero(hit != o_hit)
     assert len(mism) == 0, f"{what}: hit/miss flags differ first at row {mism[:5]}"
     ref = np.asarray(queries) if reranked else np.asarray(queries)[o_src]
-    return assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref, dist_rtol, what)
+    return assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref, dist_rtol, what, metric)

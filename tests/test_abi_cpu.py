@@ -34,8 +34,8 @@ def test_library_exports_every_declared_symbol(binding):
 
 
 def test_abi_version_and_struct_layout(binding):
-    assert binding.proximity_abi_version() == 2
-    assert C.sizeof(binding.ProximityConfig) == 64
+    assert binding.proximity_abi_version() == 3
+    assert C.sizeof(binding.ProximityConfig) == 72
     assert C.sizeof(binding.ProximityStats) == 128
     assert C.sizeof(binding.ProximityLaunch) == 16
     text = open(os.path.join(ROOT, "include", "proximity.h")).read()
@@ -43,11 +43,14 @@ def test_abi_version_and_struct_layout(binding):
               re.finditer(r"#define PROXIMITY_MAX_(\w+)\s+(\(?[0-9u <]+\)?)", text)}
     assert limits == {"K": binding.MAX_K, "DIM": binding.MAX_DIM, "BATCH": binding.MAX_BATCH,
                       "CAPACITY": binding.MAX_CAPACITY}
+    metrics = re.search(r"PROXIMITY_METRIC_L2 = (\d), PROXIMITY_METRIC_IP = (\d), PROXIMITY_METRIC_COSINE = (\d)", text)
+    assert [int(v) for v in metrics.groups()] == [binding.METRIC_L2, binding.METRIC_IP, binding.METRIC_COSINE]
 
 
 def make_cfg(b, **kw):
     vals = dict(struct_size=C.sizeof(b.ProximityConfig), dim=768, corpus=None, n_docs=0, corpus_dtype=0,
-                capacity=10, k=10, policy=0, max_batch=8, device=0, rerank_factor=1, lsh_bits=0, lsh_planes=None)
+                capacity=10, k=10, policy=0, max_batch=8, device=0, rerank_factor=1, lsh_bits=0, lsh_planes=None,
+                metric=0, reserved0=0)
     vals.update(kw)
     return b.ProximityConfig(**vals)
 
@@ -58,7 +61,7 @@ def make_cfg(b, **kw):
     dict(n_docs=5, corpus=None), dict(corpus_dtype=7), dict(policy=2), dict(device=-1),
     dict(k=100, rerank_factor=3), dict(rerank_factor=1 << 31), dict(lsh_bits=17, lsh_planes=4096),
     dict(lsh_bits=4, lsh_planes=None), dict(lsh_bits=4, lsh_planes=4096, capacity=300),
-    dict(lsh_bits=16, lsh_planes=4096, capacity=32),
+    dict(lsh_bits=16, lsh_planes=4096, capacity=32), dict(metric=3), dict(reserved0=1),
 ])
 def test_create_rejects_bad_config_before_any_gpu_work(binding, kw):
     b = binding

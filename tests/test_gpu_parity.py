@@ -210,6 +210,100 @@ def test_cache_at_and_beyond_on_chip_state(B, policy, cap):
 
 
 # ---------------------------------------------------------------------------
+# Inner-product and cosine indexes (Section 2.2's other distance functions)
+# ---------------------------------------------------------------------------
+def lengths(n, lo, hi, seed):
+    return np.random.default_rng(seed).uniform(lo, hi, size=(n, 1)).astype(np.float32)
+
+
+@pytest.mark.parametrize("metric", [po.METRIC_IP, po.METRIC_COSINE])
+@pytest.mark.parametrize("n_docs,dim,k,nq,bf16", [
+    (5000, 768, 10, 1, False), (9001, 768, 32, 4, False), (50000, 768, 10, 40, False), (30011, 384, 100, 70, False),
+    (40000, 768, 10, 100, False), (700, 32, 7, 20, False), (20000, 384, 100, 6, True), (20000, 384, 100, 128, True),
+])
+def test_knn_other_metrics(B, metric, n_docs, dim, k, nq, bf16):
+    """Rows of very different lengths: the three distance functions rank differently."""
+    x32 = W.corpus_f32(n_docs, dim, 3) * lengths(n_docs, 0.3, 3.0, 4)
+    t = gpu_corpus(x32, bf16)
+    corpus = W.bf16_bits_to_f32(W.f32_to_bf16_bits(x32)) if bf16 else x32
+    q = (W.unit_rows(np.random.default_rng(5).standard_normal((nq, dim))) * lengths(nq, 0.5, 2.0, 6)).astype(np.float32)
+    px = B.Proximity(t, dim, 0, k, B.POLICY_FIFO, nq, metric=metric)
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    o_ids, o_d = po.batched_exact_knn(corpus, q, k, metric=metric)
+    l2_ids, _ = po.batched_exact_knn(corpus, q, k)
+    assert (o_ids != l2_ids).any()
+    P.assert_lists_match(ids.cpu().numpy(), dists.cpu().numpy(), o_ids, o_d, corpus, q,
+                         dist_rtol=P.DIST_RTOL_BF16 if bf16 else P.DIST_RTOL_F32, what=f"knn metric {metric}",
+                         metric=metric)
+    px.close()
+
+
+@pytest.mark.parametrize("batch", [1, 7, 64, 256])
+@pytest.mark.parametrize("metric,policy", [(po.METRIC_IP, po.POLICY_LRU), (po.METRIC_COSINE, po.POLICY_FIFO),
+                                           (po.METRIC_COSINE, po.POLICY_LRU)])
+def test_tiny_workload_other_metrics(B, tiny, batch, metric, policy):
+    w, corpus, q, _ = tiny
+    xc = corpus * lengths(len(corpus), 0.3, 3.0, 21)
+    if metric == po.METRIC_COSINE:
+        # queries of all lengths; two of the same base are about 0.14^2 / 2 apart in cosine distance
+        qs, tau = (q * lengths(len(q), 0.5, 2.0, 22)).astype(np.float32), 0.02
+    else:
+        qs, tau = q, w.tau          # the cache of an inner-product index compares by Euclidean distance
+    want = po.lookup_stream_deferred(xc, qs, tau, w.capacity, w.k, policy, rerank_factor=2, metric=metric)
+    o_ids, o_d, o_hit, o_src, dec, stored = want
+    assert 500 < o_hit.sum() < 900
+    px = B.Proximity(gpu_corpus(xc), w.dim, w.capacity, w.k, policy, 256, rerank_factor=2, metric=metric)
+    got = P.run_stream(px, qs, tau, batch, DEV)
+    excused = P.assert_stream_parity(got, (o_ids, o_d, o_hit, o_src), xc, qs, what=f"metric {metric} b{batch}",
+                                     reranked=True, metric=metric)
+    assert excused == 0
+    seq, keys, ids = px.cache_dump(want_keys=True, want_ids=True)
+    assert seq.tolist() == dec.dump_seq().tolist()
+    assert (ids == stored[seq]).all()
+    if metric == po.METRIC_COSINE:   # keys are kept at unit length
+        np.testing.assert_allclose(keys, qs[seq] / np.linalg.norm(qs[seq].astype(np.float64), axis=1, keepdims=True),
+                                   rtol=0, atol=1e-7)
+    st = px.stats()
+    assert st["hits"] == int(o_hit.sum()) and st["evictions"] == dec.n_evictions
+    px.close()
+
+
+def test_cache_under_other_metrics_hand_worked(B):
+    """The stream of the oracle's pin of the same name: only the cosine cache hits."""
+    qs = np.zeros((5, 32), np.float32)
+    qs[:, :2] = [[1, 0], [5, 0], [0, 1], [0, 2], [3, 3]]
+    corpus = W.corpus_f32(500, 32, 9) * lengths(500, 0.3, 3.0, 10)
+    for metric, flags in ((po.METRIC_COSINE, "MHMHM"), (po.METRIC_L2, "MMMMM"), (po.METRIC_IP, "MMMMM")):
+        o = po.FlatCacheOracle(corpus, 8, 3, po.POLICY_LRU, metric=metric)
+        want = o.lookup_stream(qs, 0.1)
+        assert "".join("H" if h else "M" for h in want[2]) == flags
+        for batch in (1, 5):
+            px = B.Proximity(gpu_corpus(corpus), 32, 8, 3, po.POLICY_LRU, 8, metric=metric)
+            got = P.run_stream(px, qs, 0.1, batch, DEV)
+            P.assert_stream_parity(got, want, corpus, qs, what=f"hand-worked metric {metric}", metric=metric)
+            px.close()
+
+
+@pytest.mark.parametrize("metric", [po.METRIC_IP, po.METRIC_COSINE])
+def test_bucketed_cache_other_metrics(B, tiny, metric):
+    w, corpus, q, _ = tiny
+    xc = corpus * lengths(len(corpus), 0.3, 3.0, 21)
+    qs = (q * lengths(len(q), 0.5, 2.0, 22)).astype(np.float32) if metric == po.METRIC_COSINE else q
+    tau = 0.02 if metric == po.METRIC_COSINE else w.tau
+    planes = W.lsh_planes(3, w.dim, 5)
+    want = po.lookup_stream_deferred(xc, qs, tau, 8, w.k, po.POLICY_LRU, planes=planes, metric=metric)
+    assert 300 < want[2].sum() < 900
+    for batch in (1, 100):
+        px = B.Proximity(gpu_corpus(xc), w.dim, 8, w.k, po.POLICY_LRU, 128,
+                         lsh_planes=torch.from_numpy(planes).to(DEV), metric=metric)
+        got = P.run_stream(px, qs, tau, batch, DEV)
+        P.assert_stream_parity(got, want[:4], xc, qs, what=f"bucketed metric {metric} b{batch}", metric=metric)
+        seq, _, _ = px.cache_dump()
+        assert seq.tolist() == want[4].dump_seq().tolist()
+        px.close()
+
+
+# ---------------------------------------------------------------------------
 # Re-ranking factor (Section 3.3.4)
 # ---------------------------------------------------------------------------
 _RERANK_WANT = {}   # oracle outputs per policy, computed once
