@@ -38,6 +38,9 @@ def parse_args():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--rho", type=int, default=1,
                     help="re-ranking factor (Section 3.3.4): rho*k neighbours stored per key, hits re-ranked")
+    ap.add_argument("--metric", default="l2", choices=["l2", "ip", "cosine"],
+                    help="the index's distance function (Section 2.2).  The workloads' tolerances are Euclidean; "
+                         "for cosine the run uses tau^2/2, the cosine distance of unit vectors that far apart")
     ap.add_argument("--lsh-bits", type=int, default=0,
                     help="bucketed cache (Section 3.2): 2^L buckets; 0 = the flat cache")
     ap.add_argument("--bucket-capacity", type=int, default=20, help="entries per bucket when --lsh-bits > 0")
@@ -354,7 +357,11 @@ def main():
         planes_host = W.lsh_planes(args.lsh_bits, w.dim, w.seed)
         planes = torch.from_numpy(planes_host).to(device)
     capacity = args.bucket_capacity if planes is not None else w.capacity
-    px = Proximity(corpus_dev, w.dim, capacity, w.k, w.policy, max_batch, rerank_factor=args.rho, lsh_planes=planes)
+    metric = {"l2": 0, "ip": 1, "cosine": 2}[args.metric]
+    if metric == 2:
+        tau = tau * tau / 2.0
+    px = Proximity(corpus_dev, w.dim, capacity, w.k, w.policy, max_batch, rerank_factor=args.rho, lsh_planes=planes,
+                   metric=metric)
     n_rows = len(queries)
     outs = (torch.empty((n_rows, w.k), dtype=torch.int64, device=device),
             torch.empty((n_rows, w.k), dtype=torch.float32, device=device),
@@ -372,8 +379,9 @@ def main():
     sweep = []
     if not args.no_sweep and args.workload == "mid":
         for s_tau, s_batch, s_warm, s_steps in ((0.0, 1, 100, 2000), (0.25, 64, 30, 300), (0.0, 64, 10, 200)):
-            s_dt, s_hit = timed_run(torch, px, q_dev, s_tau, s_batch, s_warm, s_steps, outs, device)
-            s_busy = profiled_scan(torch, px, q_dev, s_tau, s_batch, s_warm + s_steps, min(s_steps, 200), outs,
+            run_tau = s_tau * s_tau / 2.0 if metric == 2 else s_tau
+            s_dt, s_hit = timed_run(torch, px, q_dev, run_tau, s_batch, s_warm, s_steps, outs, device)
+            s_busy = profiled_scan(torch, px, q_dev, run_tau, s_batch, s_warm + s_steps, min(s_steps, 200), outs,
                                    device)
             sweep.append({"tau": s_tau, "batch": s_batch, "steps": s_steps, "warmup": s_warm,
                           "queries_per_s": round(s_steps * s_batch / s_dt, 1), "hit_rate": round(s_hit, 4),
@@ -387,11 +395,13 @@ def main():
         k_store = args.rho * w.k
         no_db = lambda q: (np.full(k_store, -1, np.int64), np.full(k_store, np.inf))
         if planes_host is not None:
-            orc = po.LshCacheOracle(corpus, planes_host, capacity, w.k, w.policy, retrieve=no_db, rerank_factor=args.rho)
+            orc = po.LshCacheOracle(corpus, planes_host, capacity, w.k, w.policy, retrieve=no_db,
+                                    rerank_factor=args.rho, metric=metric)
         else:
-            orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy, rerank_factor=args.rho, retrieve=no_db)
+            orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy, rerank_factor=args.rho, retrieve=no_db,
+                                     metric=metric)
         orc.lookup_stream(queries[:first], tau)            # decisions only: brings the cache to the timed region's state
-        orc.retrieve = lambda q: po.exact_knn(corpus, q, k_store)
+        orc.retrieve = lambda q: po.exact_knn(corpus, q, k_store, metric=metric)
         n_s = min(args.cpu_sample, len(queries) - first)
         t0 = time.perf_counter()
         o_ids, o_d, o_hit, _ = orc.lookup_stream(queries[first:first + n_s], tau)
@@ -424,7 +434,7 @@ def main():
                                f"{w.choice}({w.zipf_s}) stream of "
                                f"{w.n_stream} over {w.n_bases} bases (perturbation {w.radius}), capacity "
                                f"{w.capacity}, {'LRU' if w.policy else 'FIFO'}, k={w.k}",
-                   "tau": tau, "batch": batch, "rerank_factor": args.rho,
+                   "tau": tau, "batch": batch, "rerank_factor": args.rho, "distance": args.metric,
                    "cache": (f"bucketed: {1 << args.lsh_bits} buckets x {capacity}" if planes is not None
                              else f"flat: {w.capacity}"),
                    "hit_rate": round(hit_rate, 4),
