@@ -107,8 +107,12 @@ typedef struct proximity_config {
                              product with row i is >= 0 (evaluated in float64).  Copied at
                              creation; NULL when lsh_bits is 0                               */
   uint32_t metric;        /* PROXIMITY_METRIC_*: ranks the documents, is the unit of tau and of
-                             every reported distance.  Under COSINE the instance keeps its keys
-                             scaled to unit length (proximity_cache_dump returns them so)    */
+                             every reported distance.  Under COSINE the instance scales each
+                             query to unit length in float32 before the cache sees it, keeps
+                             its keys so (proximity_cache_dump returns them so), and decides
+                             "cosine distance <= tau" as "Euclidean distance between the unit
+                             vectors <= sqrt(2 tau)"; tau = 0 thus matches a key exactly when
+                             the two unit-length float32 vectors are identical               */
   uint32_t reserved0;     /* must be 0                                                        */
 } proximity_config;
 

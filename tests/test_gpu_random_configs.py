@@ -1,7 +1,10 @@
 """Seeded random configurations, GPU against the oracle: every switch of the interface drawn at random
 (dimension, k, capacity, policy, corpus type and size, re-ranking factor, bucketed or flat cache, tolerance,
 how the stream is cut into calls), on streams that mix rewordings at several radii, exact repeats and fresh
-vectors, so that distances fall on both sides of the tolerance."""
+vectors, so that distances fall on both sides of the tolerance.  Seeds 0..79 use the Euclidean index, seeds
+from 80 on alternate between the inner-product and the cosine index on corpora whose rows have lengths
+0.3..3 (for cosine the queries get lengths 0.5..2 as well, and the tolerance becomes tau^2 / 2, the cosine
+distance of unit vectors tau apart)."""
 import numpy as np
 import pytest
 import torch
@@ -41,18 +44,26 @@ def draw_case(seed):
         step = int(rng.choice([1, 2, 4, 5, 9, 33, 64, 200]))
         cuts.append((r0, min(n, r0 + step)))
         r0 += step
+    metric = po.METRIC_L2 if seed < 80 else (po.METRIC_IP if seed % 2 == 0 else po.METRIC_COSINE)
+    if metric == po.METRIC_COSINE:
+        q = (q * rng.uniform(0.5, 2.0, size=(n, 1))).astype(np.float32)
+        # a repeat is now the same direction at another length.  Exactly zero is not a usable tolerance here:
+        # in float64 the cosine distance of a vector to its own multiple is a few 1e-16 either side of zero
+        tau = min(1e9, max(tau * tau / 2.0, 1e-12))
     return dict(dim=dim, k=k, rho=rho, n_docs=n_docs, bf16=bf16, lsh_bits=lsh_bits, capacity=capacity, policy=policy,
-                tau=tau, q=q, cuts=cuts, seed=seed)
+                tau=tau, q=q, cuts=cuts, seed=seed, metric=metric)
 
 
-@pytest.mark.parametrize("seed", range(80))
+@pytest.mark.parametrize("seed", range(120))
 def test_random_configuration(seed):
     import paper_2503_05530_amd.binding as B
     c = draw_case(seed)
-    dim, k, rho, q = c["dim"], c["k"], c["rho"], c["q"]
+    dim, k, rho, q, metric = c["dim"], c["k"], c["rho"], c["q"], c["metric"]
     corpus = corpus_dev = None
     if c["n_docs"] > 0:
         x32 = W.corpus_f32(c["n_docs"], dim, seed)
+        if metric != po.METRIC_L2:
+            x32 = x32 * np.random.default_rng([seed, 98]).uniform(0.3, 3.0, size=(c["n_docs"], 1)).astype(np.float32)
         if c["bf16"]:
             corpus = W.bf16_bits_to_f32(W.f32_to_bf16_bits(x32))
             corpus_dev = torch.from_numpy(x32).to(DEV).to(torch.bfloat16)
@@ -62,15 +73,15 @@ def test_random_configuration(seed):
     what = {key: v for key, v in c.items() if key not in ("q", "cuts")}
 
     if corpus is None:
-        hit, src, dec = po.simulate_decisions(q, c["tau"], c["capacity"], c["policy"], planes=planes)
+        hit, src, dec = po.simulate_decisions(q, c["tau"], c["capacity"], c["policy"], planes=planes, metric=metric)
         want = None
     else:
         want = po.lookup_stream_deferred(corpus, q, c["tau"], c["capacity"], k, c["policy"], rerank_factor=rho,
-                                         planes=planes)
+                                         planes=planes, metric=metric)
         hit, src, dec = want[2], want[3], want[4]
 
     px = B.Proximity(corpus_dev, dim, c["capacity"], k, c["policy"], 256, device=DEV, rerank_factor=rho,
-                     lsh_planes=None if planes is None else torch.from_numpy(planes).to(DEV))
+                     lsh_planes=None if planes is None else torch.from_numpy(planes).to(DEV), metric=metric)
     ids, dists, flags = [], [], []
     for r0, r1 in c["cuts"]:
         i, d, h = px.search_batch(torch.from_numpy(q[r0:r1]).to(DEV), c["tau"])
@@ -82,7 +93,7 @@ def test_random_configuration(seed):
     else:
         P.assert_stream_parity((ids, dists, flags), want[:4], corpus, q,
                                dist_rtol=P.DIST_RTOL_BF16 if c["bf16"] else P.DIST_RTOL_F32, what=str(what),
-                               reranked=rho > 1)
+                               reranked=rho > 1, metric=metric)
     seq, _, stored = px.cache_dump(want_ids=True)
     assert seq.tolist() == dec.dump_seq().tolist(), what
     if want is not None and len(seq):
