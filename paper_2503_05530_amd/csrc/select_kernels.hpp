@@ -105,70 +105,87 @@ __device__ __forceinline__ void block_candidate_distances(const uint64_t* keys, 
                                                           int tid, int metric = kMetricL2) {
   using Elem = typename std::conditional<DT == kDtypeF32, float, uint16_t>::type;
   const int lane = tid & 63, wib = tid >> 6;
-  constexpr int G = 4;
+  // Candidates in flight per wave: enough that the usual k + 8 candidates of a query take one round
+  // (four waves: 8 each; sixteen waves: 4 each).
+  constexpr int G = NW >= 16 ? 4 : 8;
+  constexpr int V = DT == kDtypeF32 ? 4 : 8;  // elements per 16-byte load
+  const int n_vec = dim / V;                  // dim is a multiple of 32
+  // element e of a 16-byte piece of a row / of the matching piece(s) of the query, as float64
+  auto row_elem = [](const uint4& t, int e) -> double {
+    const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+    if (DT == kDtypeF32) return double(__uint_as_float(w[e & 3]));
+    const uint32_t pair = w[(e >> 1) & 3];
+    return double(__uint_as_float((e & 1) ? (pair & 0xffff0000u) : (pair << 16)));
+  };
+  auto query_elem = [](const float4 (&t)[V / 4], int e) -> double {
+    const float4& f = t[e >> 2];
+    return double((e & 3) == 0 ? f.x : (e & 3) == 1 ? f.y : (e & 3) == 2 ? f.z : f.w);
+  };
   for (int c0 = wib; c0 < kp; c0 += NW * G) {
     int id[G];
-    const Elem* row[G];
-    double acc[G];
+    const uint4* row[G];
+    double acc[G], xx[G], qq = 0.0;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const int c = c0 + g * NW;
       id[g] = c < kp ? key_id(keys[c]) : -1;
-      row[g] = static_cast<const Elem*>(X) + long(id[g] >= 0 ? id[g] : 0) * dim;
+      row[g] = reinterpret_cast<const uint4*>(static_cast<const Elem*>(X) + long(id[g] >= 0 ? id[g] : 0) * dim);
       acc[g] = 0.0;
+      xx[g] = 0.0;
     }
-    if (metric != kMetricL2) {
-      // inner product, and for cosine the two squared lengths as well
-      double xx[G], qq = 0.0;
+    // Rows are fetched 16 bytes per lane, two steps of all G rows issued before anything is used, so
+    // that a row of 768 floats costs two memory round trips.
+    for (int iv0 = lane; iv0 < n_vec; iv0 += 128) {
+      uint4 raw[2][G];
+      float4 qraw[2][V / 4];
+      const bool two = iv0 + 64 < n_vec;
 #pragma unroll
-      for (int g = 0; g < G; ++g) xx[g] = 0.0;
-      for (int i = lane; i < dim; i += 64) {
-        const double qv = double(q[i]);
-        qq += qv * qv;
+      for (int st = 0; st < 2; ++st) {
+        if (st == 1 && !two) break;
+        const int iv = iv0 + 64 * st;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-          double xv;
-          if (DT == kDtypeF32)
-            xv = double(reinterpret_cast<const float*>(row[g])[i]);
-          else
-            xv = double(bf16_to_float(reinterpret_cast<const uint16_t*>(row[g])[i]));
-          acc[g] += qv * xv;
-          xx[g] += xv * xv;
+        for (int h = 0; h < V / 4; ++h) qraw[st][h] = reinterpret_cast<const float4*>(q)[iv * (V / 4) + h];
+#pragma unroll
+        for (int g = 0; g < G; ++g) raw[st][g] = row[g][iv];
+      }
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        if (st == 1 && !two) break;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const double qv = query_elem(qraw[st], e);
+          if (metric != kMetricL2) qq += qv * qv;
+#pragma unroll
+          for (int g = 0; g < G; ++g) {
+            const double xv = row_elem(raw[st][g], e);
+            if (metric == kMetricL2) {
+              const double diff = qv - xv;
+              acc[g] += diff * diff;
+            } else {
+              // inner product, and for cosine the two squared lengths as well
+              acc[g] += qv * xv;
+              xx[g] += xv * xv;
+            }
+          }
         }
       }
-      qq = wave_sum(qq);
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const int c = c0 + g * NW;
-        const double dot = wave_sum(acc[g]);
-        const double len2 = wave_sum(xx[g]);
-        if (lane == 0 && c < kp) {
-          const double d = metric == kMetricIP ? -dot : 1.0 - dot / (sqrt(len2) * sqrt(qq));
-          d64[c] = id[g] >= 0 ? d : __longlong_as_double(0x7ff0000000000000ll);
-          cid[c] = id[g] >= 0 ? id[g] : 0x7fffffff;
-        }
-      }
-      continue;
     }
-    for (int i = lane; i < dim; i += 64) {
-      const double qv = double(q[i]);
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        double xv;
-        if (DT == kDtypeF32)
-          xv = double(reinterpret_cast<const float*>(row[g])[i]);
-        else
-          xv = double(bf16_to_float(reinterpret_cast<const uint16_t*>(row[g])[i]));
-        const double diff = qv - xv;
-        acc[g] += diff * diff;
-      }
-    }
+    if (metric != kMetricL2) qq = wave_sum(qq);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const int c = c0 + g * NW;
+      if (c0 + g * NW >= kp && g > 0) break;  // wave-uniform: nothing left in this round
       const double total = wave_sum(acc[g]);
+      double d;
+      if (metric == kMetricL2) {
+        d = sqrt(total);
+      } else if (metric == kMetricIP) {
+        d = -total;
+      } else {
+        d = 1.0 - total / (sqrt(wave_sum(xx[g])) * sqrt(qq));
+      }
       if (lane == 0 && c < kp) {
-        d64[c] = id[g] >= 0 ? sqrt(total) : __longlong_as_double(0x7ff0000000000000ll);
+        d64[c] = id[g] >= 0 ? d : __longlong_as_double(0x7ff0000000000000ll);
         cid[c] = id[g] >= 0 ? id[g] : 0x7fffffff;
       }
     }
@@ -301,19 +318,34 @@ struct SmallRouting {
 // kp smallest of `len` keys in global memory -> sorted list[0..kp) in LDS, by one block of 256.
 __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ in, long len, int kp, uint64_t* list,
                                                    int list_cap, uint64_t* mins, int* count, int tid) {
+  // both passes read eight keys per thread at a time, all loads issued before the first is used
+  constexpr int U = 8;
   uint64_t tmin = ~0ull;
-  for (long j = tid; j < len; j += kSelThreads) {
-    const uint64_t kv = in[j];
-    tmin = kv < tmin ? kv : tmin;
+  for (long j0 = tid; j0 < len; j0 += long(U) * kSelThreads) {
+    uint64_t kv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long j = j0 + long(u) * kSelThreads;
+      kv[u] = j < len ? in[j] : ~0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) tmin = kv[u] < tmin ? kv[u] : tmin;
   }
   if (tid == 0) *count = 0;
   const uint64_t bound = block_bound_for_kp<kSelThreads / 64>(tmin, kp, mins, tid);
-  for (long j = tid; j < len; j += kSelThreads) {
-    const uint64_t kv = in[j];
-    if (kv <= bound) {
-      const int pos = atomicAdd(count, 1);
-      if (pos < list_cap) list[pos] = kv;
+  for (long j0 = tid; j0 < len; j0 += long(U) * kSelThreads) {
+    uint64_t kv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long j = j0 + long(u) * kSelThreads;
+      kv[u] = j < len ? in[j] : ~0ull;
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (kv[u] <= bound && j0 + long(u) * kSelThreads < len) {
+        const int pos = atomicAdd(count, 1);
+        if (pos < list_cap) list[pos] = kv[u];
+      }
   }
   __syncthreads();
   const int cnt = *count;
