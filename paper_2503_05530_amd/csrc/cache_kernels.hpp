@@ -28,10 +28,27 @@ struct CacheState {
 // The one routine every float64 decision in this file goes through.
 __device__ __forceinline__ double wave_dist64(const float* __restrict__ a, const float* __restrict__ b, int dim,
                                               int lane) {
+  // 16 bytes per lane and two steps in flight (rows are 128-byte aligned: dim is a multiple of 32)
+  const float4* a4 = reinterpret_cast<const float4*>(a);
+  const float4* b4 = reinterpret_cast<const float4*>(b);
+  const int n_vec = dim / 4;
   double acc = 0.0;
-  for (int i = lane; i < dim; i += 64) {
-    const double diff = double(a[i]) - double(b[i]);
-    acc += diff * diff;
+  for (int iv = lane; iv < n_vec; iv += 128) {
+    const bool two = iv + 64 < n_vec;
+    const float4 x0 = a4[iv], y0 = b4[iv];
+    float4 x1 = x0, y1 = y0;
+    if (two) {
+      x1 = a4[iv + 64];
+      y1 = b4[iv + 64];
+    }
+    const double dx = double(x0.x) - double(y0.x), dy = double(x0.y) - double(y0.y);
+    const double dz = double(x0.z) - double(y0.z), dw = double(x0.w) - double(y0.w);
+    acc += dx * dx + dy * dy + dz * dz + dw * dw;
+    if (two) {
+      const double ex = double(x1.x) - double(y1.x), ey = double(x1.y) - double(y1.y);
+      const double ez = double(x1.z) - double(y1.z), ew = double(x1.w) - double(y1.w);
+      acc += ex * ex + ey * ey + ez * ez + ew * ew;
+    }
   }
   return sqrt(wave_sum(acc));
 }
@@ -420,23 +437,42 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
   __shared__ long long red_seq[NW];
   __shared__ int red_src[NW];
   __shared__ double pair_d[kSmallRows];
+  // the decisions of this call, kept on chip for the routing below (reading them back from global
+  // memory would put two more round trips on the path of every call)
+  __shared__ int dec_hit[kSmallRows], dec_src[kSmallRows], dec_slot[kSmallRows];
 
   const int size0 = st->size;
   // phase 1
   if (phase != 2)
   for (int s = blockIdx.x * NW + wib; s < size0; s += gridDim.x * NW) {
-    const float* key = srcs + long(s) * dim;
+    // 16 bytes per lane, two steps of the key and of every row issued before anything is used
+    const float4* key = reinterpret_cast<const float4*>(srcs + long(s) * dim);
+    const int n_vec = dim / 4;
     double acc[kSmallRows];
 #pragma unroll
     for (int i = 0; i < kSmallRows; ++i) acc[i] = 0.0;
-    for (int e = lane; e < dim; e += 64) {
-      const double kv = double(key[e]);
+    for (int iv0 = lane; iv0 < n_vec; iv0 += 128) {
+      const bool two = iv0 + 64 < n_vec;
+      float4 kv[2], qv[2][kSmallRows];
 #pragma unroll
-      for (int i = 0; i < kSmallRows; ++i)
-        if (i < n) {
-          const double diff = double(queries[long(i) * dim + e]) - kv;
-          acc[i] += diff * diff;
-        }
+      for (int st = 0; st < 2; ++st) {
+        if (st == 1 && !two) break;
+        kv[st] = key[iv0 + 64 * st];
+#pragma unroll
+        for (int i = 0; i < kSmallRows; ++i)
+          if (i < n) qv[st][i] = reinterpret_cast<const float4*>(queries + long(i) * dim)[iv0 + 64 * st];
+      }
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        if (st == 1 && !two) break;
+#pragma unroll
+        for (int i = 0; i < kSmallRows; ++i)
+          if (i < n) {
+            const double dx = double(qv[st][i].x) - double(kv[st].x), dy = double(qv[st][i].y) - double(kv[st].y);
+            const double dz = double(qv[st][i].z) - double(kv[st].z), dw = double(qv[st][i].w) - double(kv[st].w);
+            acc[i] += dx * dx + dy * dy + dz * dz + dw * dw;
+          }
+      }
     }
 #pragma unroll
     for (int i = 0; i < kSmallRows; ++i)
@@ -462,13 +498,12 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
     ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
     for (int s = tid; s < size0; s += 1024) {
       const long long seq = slot_seq[s];
-      if (seq < base_seq) {   // still the key it held when the call began
-        const double d = D64[long(i) * c + s];
-        if (d <= tau) best_take(best, d, seq, s);
-      }
+      const double d = D64[long(i) * c + s];  // (read whether or not it is needed: the two loads overlap)
+      // seq < base_seq: still the key it held when the call began
+      if (seq < base_seq && d <= tau) best_take(best, d, seq, s);
     }
     if (tid < i) {
-      const int t = row_slot[tid];
+      const int t = dec_slot[tid];
       const long long seq = base_seq + tid;
       if (t >= 0 && slot_seq[t] == seq && pair_d[tid] <= tau) best_take(best, pair_d[tid], seq, c + tid);
     }
@@ -486,7 +521,10 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
       if (b.src >= 0) {
         ++hits;
         if (b.src >= c) ++inbatch;
-        const int t = b.src < c ? b.src : row_slot[b.src - c];
+        const int t = b.src < c ? b.src : dec_slot[b.src - c];
+        dec_hit[i] = 1;
+        dec_src[i] = b.src;
+        dec_slot[i] = -1;
         if (policy_lru && t != tail) {
           const int p = slot_prev[t], nx = slot_next[t];
           if (p >= 0) slot_next[p] = nx; else head = nx;
@@ -518,6 +556,9 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
           tail = t;
           ++inserts;
         }
+        dec_hit[i] = 0;
+        dec_src[i] = -1;
+        dec_slot[i] = t;
         hit_out[i] = 0;
         src_out[i] = -1;
         row_slot[i] = t;
@@ -541,8 +582,8 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
   __syncthreads();
   // keys of rows that missed and still own their slot; hits on keys resident before the call
   for (int i = 0; i < n; ++i) {
-    if (hit_out[i]) {
-      const int s = src_out[i];
+    if (dec_hit[i]) {
+      const int s = dec_src[i];
       if (s < c) {
         if (K == k) {
           for (int e = tid; e < k; e += 1024) {
@@ -558,7 +599,7 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
         }
       }
     } else {
-      const int t = row_slot[i];
+      const int t = dec_slot[i];
       if (t >= 0 && slot_seq[t] == base_seq + i) {
         float sq = 0.f;
         for (int e = tid; e < dim; e += 1024) {
