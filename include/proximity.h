@@ -80,8 +80,8 @@ typedef struct proximity proximity_t;
 typedef struct proximity_config {
   uint32_t struct_size;   /* sizeof(proximity_config), for ABI checking                       */
   uint32_t dim;           /* embedding dimension d; multiple of 32, <= PROXIMITY_MAX_DIM     */
-  const void* corpus;     /* DEVICE [n_docs][dim], float32 or bfloat16; BORROWED: it must
-                             stay allocated and unchanged until proximity_destroy()          */
+  const void* corpus;     /* DEVICE [n_docs][dim], float32 or bfloat16, 16-byte aligned; BORROWED:
+                             it must stay allocated and unchanged until proximity_destroy()  */
   uint64_t n_docs;        /* < 2^31.  0 is allowed: misses then return ids -1 / dists +inf
                              (for runs that time the cache probe alone)                      */
   uint32_t corpus_dtype;  /* PROXIMITY_DTYPE_*.  Queries and cache keys are always float32   */
@@ -150,7 +150,7 @@ uint32_t proximity_abi_version(void);
  * (capacity x dim float32 keys, capacity x rerank_factor*k values) and all
  * workspaces, sized for max_batch.  *out receives the handle.  Blocks until the norms are done.
  * Errors: INVALID_ARG (null, bad struct_size, dim/k/max_batch/capacity/n_docs/
- * rerank_factor*k/lsh_bits outside the limits, unknown dtype/policy/metric, lsh_planes
+ * rerank_factor*k/lsh_bits outside the limits, unknown dtype/policy/metric, misaligned corpus, lsh_planes
  * null with lsh_bits > 0, corpus null with n_docs > 0), OOM,
  * HIP.  On error *out is set to NULL.
  */
@@ -163,7 +163,7 @@ void proximity_destroy(proximity_t* h);
  * The lookup procedure of Algorithm 1 for n queries, with the semantics of
  * processing rows 0..n-1 one after the other (and calls in call order).
  *
- *   queries    DEVICE [n][dim] float32
+ *   queries    DEVICE [n][dim] float32, 16-byte aligned (as the corpus must be)
  *   n          1..max_batch (0 is accepted and does nothing)
  *   k          must equal cfg.k
  *   tau        tolerance in the units of the instance's distance function between query

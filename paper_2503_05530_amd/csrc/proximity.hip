@@ -430,6 +430,8 @@ int validate_call(proximity* h, const float* queries, uint32_t n, uint32_t k, in
   if (n > h->cfg.max_batch)
     return fail(h, PROXIMITY_ERR_BATCH_TOO_LARGE, "n=%u exceeds max_batch=%u", n, h->cfg.max_batch);
   if (n > 0 && (!queries || !out_ids)) return fail(h, PROXIMITY_ERR_INVALID_ARG, "queries or out_ids is null");
+  if (reinterpret_cast<uintptr_t>(queries) % 16 != 0)
+    return fail(h, PROXIMITY_ERR_INVALID_ARG, "queries must be 16-byte aligned (rows are read 16 bytes at a time)");
   return PROXIMITY_OK;
 }
 
@@ -479,6 +481,8 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown corpus_dtype %u", cfg->corpus_dtype);
   if (cfg->policy != PROXIMITY_POLICY_FIFO && cfg->policy != PROXIMITY_POLICY_LRU)
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown policy %u", cfg->policy);
+  if (reinterpret_cast<uintptr_t>(cfg->corpus) % 16 != 0)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "corpus must be 16-byte aligned (rows are read 16 bytes at a time)");
   if (cfg->metric > PROXIMITY_METRIC_COSINE)
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown metric %u", cfg->metric);
   if (cfg->reserved0 != 0) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "reserved0 must be 0");

@@ -62,6 +62,7 @@ def make_cfg(b, **kw):
     dict(k=100, rerank_factor=3), dict(rerank_factor=1 << 31), dict(lsh_bits=17, lsh_planes=4096),
     dict(lsh_bits=4, lsh_planes=None), dict(lsh_bits=4, lsh_planes=4096, capacity=300),
     dict(lsh_bits=16, lsh_planes=4096, capacity=32), dict(metric=3), dict(reserved0=1),
+    dict(n_docs=5, corpus=4096 + 4),
 ])
 def test_create_rejects_bad_config_before_any_gpu_work(binding, kw):
     b = binding

@@ -552,6 +552,10 @@ def test_call_errors_leave_state_untouched(B, tiny):
     assert lib.proximity_search_batch(h, None, 8, w.k, 0.1, ids.data_ptr(), None, hit.data_ptr(), None) == B.ERR_INVALID_ARG
     assert lib.proximity_search_batch(h, qd.data_ptr(), 8, w.k, 0.1, ids.data_ptr(), None, None, None) == B.ERR_INVALID_ARG
     assert "out_hit" in B.last_error(h)
+    # a pointer into the middle of a row: rows are read 16 bytes at a time, so it is turned away, not followed
+    assert lib.proximity_search_batch(h, qd.data_ptr() + 4, 7, w.k, 0.1, ids.data_ptr(), None, hit.data_ptr(), None) == B.ERR_INVALID_ARG
+    assert "aligned" in B.last_error(h)
+    assert lib.proximity_knn_batch(h, qd.data_ptr() + 8, 7, w.k, ids.data_ptr(), None, None) == B.ERR_INVALID_ARG
     assert px.stats()["queries"] == 0
     assert lib.proximity_search_batch(h, qd.data_ptr(), 0, w.k, 0.1, None, None, None, None) == B.OK
     px.close()
