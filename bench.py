@@ -298,6 +298,16 @@ def probe_microbench(args, torch, np, W, Proximity, device):
     px.close()
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -410,7 +420,7 @@ def main():
                "sample": f"stream rows {first}..{first + n_s - 1} of the same workload after a decisions-only "
                          f"replay of rows 0..{first - 1}; {int((o_hit == 0).sum())} misses, "
                          f"{cdt:.1f} s, float64 numpy (single-threaded element-wise code)",
-               "host_cpus": os.cpu_count()}
+               "host_cpus": os.cpu_count(), "cpu_model": cpu_model()}
         # the two pieces on their own, oracle code as it stands: one cache probe (distances to c keys and the
         # nearest) at two cache sizes, and one database call (all distances and the ranking) on this corpus
         parts = {}
