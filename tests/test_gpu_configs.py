@@ -26,7 +26,8 @@ def B():
     return b
 
 
-def check_against_decisions(got, decisions, queries, px, knn_window, knn_ids, knn_d, corpus_rows, dist_rtol, what):
+def check_against_decisions(got, decisions, queries, px, knn_window, knn_ids, knn_d, corpus_rows, dist_rtol, what,
+                            metric=po.METRIC_L2):
     """Flags for all rows; ids/dists for rows answered by a query inside the k-NN window."""
     ids, dists, hit = got
     o_hit, o_src, dec = decisions
@@ -39,7 +40,7 @@ def check_against_decisions(got, decisions, queries, px, knn_window, knn_ids, kn
     rows = np.flatnonzero(o_src < knn_window)
     assert len(rows) > 0
     excused = P.assert_lists_match(ids[rows], dists[rows], knn_ids[o_src[rows]], knn_d[o_src[rows]],
-                                   corpus_rows, np.asarray(queries)[o_src[rows]], dist_rtol, what)
+                                   corpus_rows, np.asarray(queries)[o_src[rows]], dist_rtol, what, metric)
     seq, _, dump_ids = px.cache_dump(want_ids=True)
     assert seq.tolist() == dec.dump_seq().tolist(), f"{what}: cache contents differ"
     assert (dump_ids == ids[seq]).all(), f"{what}: stored lists differ from the lists returned at insertion"
@@ -84,6 +85,26 @@ def test_mid_workload(B, mid, tau, batch):
     else:
         assert decisions[tau][0].sum() == 0
     px.close()
+
+
+@pytest.mark.parametrize("metric", [po.METRIC_IP, po.METRIC_COSINE])
+def test_mid_workload_other_metrics(B, mid, metric):
+    """The mid workload on an inner-product and on a cosine index (Section 2.2), calls of 1 and of 64 rows.
+    Rows and queries have unit length up to float32 rounding, so the tolerance that separates rewordings
+    from other queries is tau = 0.25 as a Euclidean distance (inner-product index) and tau^2 / 2 as a cosine
+    distance."""
+    w, corpus, corpus_dev, q, _, _, _ = mid
+    tau = 0.25 if metric == po.METRIC_IP else 0.25 * 0.25 / 2.0
+    knn_ids, knn_d = po.batched_exact_knn(corpus, q[:MID_WINDOW], w.k, chunk_rows=1 << 17, metric=metric)
+    decisions = po.simulate_decisions(q, tau, w.capacity, w.policy, metric=metric)
+    assert 3000 < decisions[0].sum() < 4000
+    for batch in (1, 64):
+        px = B.Proximity(corpus_dev, w.dim, w.capacity, w.k, w.policy, 64, metric=metric)
+        got = P.run_stream(px, q, tau, batch, DEV)
+        excused, n = check_against_decisions(got, decisions, q, px, MID_WINDOW, knn_ids, knn_d, corpus,
+                                             P.DIST_RTOL_F32, f"mid metric={metric} batch={batch}", metric=metric)
+        assert excused == 0
+        px.close()
 
 
 @pytest.mark.parametrize("batch", [1, 64])
