@@ -315,15 +315,19 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
 // Merge per-query lists of `len` keys in pairs[cur] down to one sorted list of kp keys per
 // query, ping-ponging between the two key buffers.  Returns the index of the buffer that
 // holds the result.
+// Merge levels over per-query lists of `len` keys (sorted runs of kp) until at most stop_len keys are
+// left per query (stop_len = kp: one list).  *len_out receives what is left.
 int enqueue_merge_levels(proximity* h, int cur, long len, int kp, const int* m_count_ptr, int m_limit,
-                         hipStream_t s) {
-  while (len > kp) {
+                         hipStream_t s, long stop_len, long* len_out = nullptr) {
+  if (stop_len < kp) stop_len = kp;
+  while (len > stop_len) {
     const int g = int((len + kSelSeg - 1) / kSelSeg);
     select_kernel<false, kSelE><<<dim3(g, m_limit), dim3(kSelThreads), 0, s>>>(
         h->pairs[cur], len, len, 0, kp, h->pairs[cur ^ 1], g, m_count_ptr, m_limit, 0);
     cur ^= 1;
     len = long(g) * kp;
   }
+  if (len_out) *len_out = len;
   return cur;
 }
 
@@ -344,6 +348,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
   const int metric = int(h->cfg.metric), cosine = metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
   int cur = 0;
+  long left = kp;  // keys per query handed to the ranking kernel
   if (m_limit <= kStreamMaxQueries) {
     const int mq = stream_group(dim, m_limit);
     const int g1 = int((N + kSelSeg - 1) / kSelSeg);
@@ -361,12 +366,13 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
         // res_ids / res_d are then the caller's output rows
         for (int phase = 1; phase <= 2; ++phase) {
           const dim3 grid(phase == 2 ? 1 : g1, mq);
+          // (four waves for both phases: with sixteen the second phase, one block per query, was slower)
           if (bf16)
-            select_finish_small_kernel<kDtypeBF16, kSelE><<<grid, dim3(kSelThreads), 0, s>>>(
+            select_finish_small_kernel<kDtypeBF16, kSelE, kSelThreads><<<grid, dim3(kSelThreads), 0, s>>>(
                 h->S, h->ldS, N, kp, k, k_out, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
                 m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d, metric);
           else
-            select_finish_small_kernel<kDtypeF32, kSelE><<<grid, dim3(kSelThreads), 0, s>>>(
+            select_finish_small_kernel<kDtypeF32, kSelE, kSelThreads><<<grid, dim3(kSelThreads), 0, s>>>(
                 h->S, h->ldS, N, kp, k, k_out, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
                 m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d, metric);
         }
@@ -376,7 +382,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       }
     }
     if (small_routing) return PROXIMITY_OK;
-    cur = enqueue_merge_levels(h, 0, long(g1) * kp, kp, m_count_ptr, m_limit, s);
+    cur = enqueue_merge_levels(h, 0, long(g1) * kp, kp, m_count_ptr, m_limit, s, kRerankMergeKeys, &left);
   } else {
     // Batched scan on the matrix cores, in two steps.  First the head of the corpus
     // (kSeedRows rows) is scanned and merged on its own: its kp-th best score per query is a
@@ -395,7 +401,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
         launch_batched_scan(h, kSeedRows, gs, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, nullptr,
                             h->pairs[0], dump_seed, s);
       }
-      cur = enqueue_merge_levels(h, 0, dump_seed ? long(kSeedRows) : long(gs) * kp, kp, m_count_ptr, m_limit, s);
+      cur = enqueue_merge_levels(h, 0, dump_seed ? long(kSeedRows) : long(gs) * kp, kp, m_count_ptr, m_limit, s, kp);
       seed = h->pairs[cur];
       cur ^= 1;  // the full scan writes into the other buffer
     }
@@ -407,13 +413,15 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
                           s);
       prof_end(h, s, base, span);
     }
-    cur = enqueue_merge_levels(h, cur, long(G) * kp, kp, m_count_ptr, m_limit, s);
+    // the last merge level happens inside the ranking kernel
+    cur = enqueue_merge_levels(h, cur, long(G) * kp, kp, m_count_ptr, m_limit, s, kRerankMergeKeys, &left);
   }
+  const int n_lists = int(left / kp);
   if (bf16)
-    rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
+    rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase,
                                                                      qlist, m_count_ptr, m_limit, res_ids, res_d, metric);
   else
-    rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], kp, k, h->cfg.corpus, dim, Qbase,
+    rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase,
                                                                     qlist, m_count_ptr, m_limit, res_ids, res_d, metric);
   return PROXIMITY_OK;
 }

@@ -249,36 +249,6 @@ __device__ __forceinline__ void block_rerank_stored_any(int kind, const int64_t*
     block_rerank_stored<kDtypeF32, NT>(stored, K, k, q, X, dim, out_ids, out_d, keys, d64, cid, tid, kind_metric(kind));
 }
 
-// Final ranking in float64.  One block of 16 waves per query: for each of the kp
-// float32 candidates recompute the Euclidean distance to the query in direct-difference
-// form in float64 (one wave per candidate row, rows fetched concurrently), rank the candidates by
-// (distance, id) and write the first k ids and distances to row `qrow` of the
-// result arrays.  Padding candidates (id -1) get distance +inf and id -1.
-constexpr int kRerankThreads = 1024;
-template <int DT>
-__global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64_t* __restrict__ cand, int kp, int k,
-                                                         const void* __restrict__ X, int dim,
-                                                         const float* __restrict__ Qbase,
-                                                         const int* __restrict__ qlist,
-                                                         const int* __restrict__ m_count_ptr, int m_limit,
-                                                         int64_t* __restrict__ res_ids,
-                                                         float* __restrict__ res_dists, int metric) {
-  const int m = blockIdx.x;
-  const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
-  if (m >= m_total) return;
-  const int qrow = qlist ? qlist[m] : m;
-  const float* q = Qbase + long(qrow) * dim;
-  const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-
-  __shared__ double d64[256];
-  __shared__ int ids[256];
-
-  block_candidate_distances<DT, kRerankThreads / 64>(cand + long(m) * kp, kp, q, X, dim, d64, ids, threadIdx.x, metric);
-  __syncthreads();
-  block_write_ranked(d64, ids, kp, k, res_ids + long(qrow) * k, res_dists + long(qrow) * k, threadIdx.x,
-                     kRerankThreads);
-}
-
 // Fills result rows of the listed queries with "no document" (used when the
 // instance has no corpus): ids -1, distances +inf.
 __global__ void fill_empty_results_kernel(const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
@@ -315,34 +285,36 @@ struct SmallRouting {
   int n, c;
 };
 
-// kp smallest of `len` keys in global memory -> sorted list[0..kp) in LDS, by one block of 256.
+// kp smallest of `len` keys in global memory -> sorted list[0..kp) in LDS, by one block of NT threads
+// (mins: NT / 64 entries at least; list: list_cap >= 64 entries).
+template <int NT>
 __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ in, long len, int kp, uint64_t* list,
                                                    int list_cap, uint64_t* mins, int* count, int tid) {
   // both passes read eight keys per thread at a time, all loads issued before the first is used
   constexpr int U = 8;
   uint64_t tmin = ~0ull;
-  for (long j0 = tid; j0 < len; j0 += long(U) * kSelThreads) {
+  for (long j0 = tid; j0 < len; j0 += long(U) * NT) {
     uint64_t kv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const long j = j0 + long(u) * kSelThreads;
+      const long j = j0 + long(u) * NT;
       kv[u] = j < len ? in[j] : ~0ull;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) tmin = kv[u] < tmin ? kv[u] : tmin;
   }
   if (tid == 0) *count = 0;
-  const uint64_t bound = block_bound_for_kp<kSelThreads / 64>(tmin, kp, mins, tid);
-  for (long j0 = tid; j0 < len; j0 += long(U) * kSelThreads) {
+  const uint64_t bound = block_bound_for_kp<NT / 64>(tmin, kp, mins, tid);
+  for (long j0 = tid; j0 < len; j0 += long(U) * NT) {
     uint64_t kv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const long j = j0 + long(u) * kSelThreads;
+      const long j = j0 + long(u) * NT;
       kv[u] = j < len ? in[j] : ~0ull;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      if (kv[u] <= bound && j0 + long(u) * kSelThreads < len) {
+      if (kv[u] <= bound && j0 + long(u) * NT < len) {
         const int pos = atomicAdd(count, 1);
         if (pos < list_cap) list[pos] = kv[u];
       }
@@ -351,42 +323,84 @@ __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ 
   const int cnt = *count;
   if (cnt <= list_cap) {
     const int P = next_pow2(cnt > kp ? cnt : kp);
-    for (int i = cnt + tid; i < (P < 64 ? 64 : P); i += kSelThreads) list[i] = kPadKey;
+    for (int i = cnt + tid; i < (P < 64 ? 64 : P); i += NT) list[i] = kPadKey;
     __syncthreads();
     if (P <= 64)
       block_sort_upto64(list, tid);
     else
-      block_bitonic_sort(list, P, tid, kSelThreads);
+      block_bitonic_sort(list, P, tid, NT);
     return;
   }
   // exact ties made the survivor set larger than the list: keep a running best-kp list and
   // fold the input in, half a list at a time
   const int chunk = list_cap / 2;
-  for (int i = tid; i < kp; i += kSelThreads) list[i] = kPadKey;
+  for (int i = tid; i < kp; i += NT) list[i] = kPadKey;
   __syncthreads();
   for (long c0 = 0; c0 < len; c0 += chunk) {
-    for (int i = tid; i < chunk; i += kSelThreads) list[kp + i] = c0 + i < len ? in[c0 + i] : kPadKey;
+    for (int i = tid; i < chunk; i += NT) list[kp + i] = c0 + i < len ? in[c0 + i] : kPadKey;
     const int P = next_pow2(kp + chunk);
-    for (int i = kp + chunk + tid; i < P; i += kSelThreads) list[i] = kPadKey;
+    for (int i = kp + chunk + tid; i < P; i += NT) list[i] = kPadKey;
     __syncthreads();
-    block_bitonic_sort(list, P, tid, kSelThreads);
+    block_bitonic_sort(list, P, tid, NT);
   }
 }
 
-template <int DT, int E>
-__global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
+// Final ranking in float64.  One block of 16 waves per query.  The query's float32 candidates arrive
+// as n_lists sorted lists of kp keys each (what the last merge level would have read); the block
+// first cuts them to the kp best (n_lists = 1: nothing to do), then recomputes for each of those the
+// distance to the query in float64 (direct-difference form for the Euclidean distance; one wave per
+// candidate row, rows fetched concurrently), ranks them by
+// (distance, id) and writes the first k ids and distances to row `qrow` of the
+// result arrays.  Padding candidates (id -1) get distance +inf and id -1.
+constexpr int kRerankThreads = 1024;
+constexpr int kRerankMergeKeys = 2048;  // n_lists * kp may not exceed this
+template <int DT>
+__global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64_t* __restrict__ cand, int n_lists,
+                                                         int kp, int k,
+                                                         const void* __restrict__ X, int dim,
+                                                         const float* __restrict__ Qbase,
+                                                         const int* __restrict__ qlist,
+                                                         const int* __restrict__ m_count_ptr, int m_limit,
+                                                         int64_t* __restrict__ res_ids,
+                                                         float* __restrict__ res_dists, int metric) {
+  const int m = blockIdx.x;
+  const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
+  if (m >= m_total) return;
+  const int qrow = qlist ? qlist[m] : m;
+  const float* q = Qbase + long(qrow) * dim;
+
+  __shared__ double d64[256];
+  __shared__ int ids[256];
+  __shared__ uint64_t list[kRerankMergeKeys];
+  __shared__ uint64_t mins[kRerankThreads / 64];
+  __shared__ int count;
+
+  const uint64_t* mine = cand + long(m) * n_lists * kp;
+  if (n_lists > 1) {
+    block_topk_of_keys<kRerankThreads>(mine, long(n_lists) * kp, kp, list, kRerankMergeKeys, mins, &count, threadIdx.x);
+    __syncthreads();
+    mine = list;
+  }
+  block_candidate_distances<DT, kRerankThreads / 64>(mine, kp, q, X, dim, d64, ids, threadIdx.x, metric);
+  __syncthreads();
+  block_write_ranked(d64, ids, kp, k, res_ids + long(qrow) * k, res_dists + long(qrow) * k, threadIdx.x,
+                     kRerankThreads);
+}
+
+template <int DT, int E, int NT>
+__global__ __launch_bounds__(NT) void select_finish_small_kernel(
     const float* __restrict__ S, long ldS, long len, int kp, int k, int k_out, uint64_t* __restrict__ lists,
     int n_seg, int phase, const void* __restrict__ X, int dim, const float* __restrict__ Qbase,
     const int* __restrict__ qlist, const int* __restrict__ m_count_ptr, int m_limit, int m_begin, SmallRouting rt,
     int64_t* __restrict__ out_ids, float* __restrict__ out_d, int metric) {
-  constexpr int SEG = E * kSelThreads;
+  constexpr int SEG = E * NT;
   const int q = m_begin + blockIdx.y;   // position in the miss list; S rows are relative to m_begin
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   if (q >= m_total) return;
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
 
   __shared__ uint64_t list[SEG];
-  __shared__ uint64_t mins[kSelThreads];
+  __shared__ uint64_t mins[NT];
   __shared__ int count;
   __shared__ double d64[256];
   __shared__ int cid[256];
@@ -400,44 +414,44 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
   uint64_t tmin = ~0ull;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    const long j = seg0 + e * kSelThreads + tid;
+    const long j = seg0 + e * NT + tid;
     uint64_t kv = ~0ull;
     if (j < len) kv = pack_key(S[long(blockIdx.y) * ldS + j], uint32_t(j));
     key[e] = kv;
     tmin = kv < tmin ? kv : tmin;
   }
   if (tid == 0) count = 0;
-  const uint64_t bound = block_bound_for_kp<kSelThreads / 64>(tmin, kp, mins, tid);
+  const uint64_t bound = block_bound_for_kp<NT / 64>(tmin, kp, mins, tid);
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    const long j = seg0 + e * kSelThreads + tid;
+    const long j = seg0 + e * NT + tid;
     if (j < len && key[e] <= bound) list[atomicAdd(&count, 1)] = key[e];
   }
   __syncthreads();
   {
     const int cnt = count;
     const int P = next_pow2(cnt > kp ? cnt : kp);
-    for (int i = cnt + tid; i < (P < 64 ? 64 : P); i += kSelThreads) list[i] = kPadKey;
+    for (int i = cnt + tid; i < (P < 64 ? 64 : P); i += NT) list[i] = kPadKey;
     __syncthreads();
     if (P <= 64)
       block_sort_upto64(list, tid);
     else
-      block_bitonic_sort(list, P, tid, kSelThreads);
+      block_bitonic_sort(list, P, tid, NT);
     uint64_t* o = lists + (long(q) * n_seg + g) * kp;
-    for (int i = tid; i < kp; i += kSelThreads) o[i] = list[i];
+    for (int i = tid; i < kp; i += NT) o[i] = list[i];
   }
   }
   if (phase == 1) return;
 
   // ---- merge all segments' lists ----
-  block_topk_of_keys(lists + long(q) * n_seg * kp, long(n_seg) * kp, kp, list, SEG, mins, &count, tid);
+  block_topk_of_keys<NT>(lists + long(q) * n_seg * kp, long(n_seg) * kp, kp, list, SEG, mins, &count, tid);
 
   // ---- float64 ranking of the kp survivors (as rerank_f64_kernel) ----
   const int qrow = qlist ? qlist[q] : q;
   const float* qv = Qbase + long(qrow) * dim;
-  block_candidate_distances<DT, kSelThreads / 64>(list, kp, qv, X, dim, d64, cid, tid, metric);
+  block_candidate_distances<DT, NT / 64>(list, kp, qv, X, dim, d64, cid, tid, metric);
   __syncthreads();
-  for (int c = tid; c < kp; c += kSelThreads) {
+  for (int c = tid; c < kp; c += NT) {
     const double d = d64[c];
     const int id = cid[c];
     int rank = 0;
@@ -455,28 +469,28 @@ __global__ __launch_bounds__(kSelThreads) void select_finish_small_kernel(
 
   // ---- routing (as finalize_kernel): k ranked entries are this query's result; the caller gets
   // the first k_out, the cache slot all k (k > k_out with a re-ranking factor, Section 3.3.4) ----
-  for (int e = tid; e < k_out; e += kSelThreads) {
+  for (int e = tid; e < k_out; e += NT) {
     out_ids[long(qrow) * k_out + e] = fin_ids[e];
     if (out_d) out_d[long(qrow) * k_out + e] = fin_d[e];
   }
   if (rt.hit) {
     const int t = rt.row_slot[qrow];
     if (t >= 0 && rt.slot_seq[t] == rt.base_seq + qrow)
-      for (int e = tid; e < k; e += kSelThreads) {
+      for (int e = tid; e < k; e += NT) {
         rt.val_ids[long(t) * k + e] = fin_ids[e];
         rt.val_d[long(t) * k + e] = fin_d[e];
       }
     for (int i = qrow + 1; i < rt.n; ++i)
       if (rt.hit[i] && rt.src[i] == rt.c + qrow) {
         if (k == k_out) {
-          for (int e = tid; e < k; e += kSelThreads) {
+          for (int e = tid; e < k; e += NT) {
             out_ids[long(i) * k + e] = fin_ids[e];
             if (out_d) out_d[long(i) * k + e] = fin_d[e];
           }
         } else {
           // a later row of the call hit this one: the stored documents nearest to that row's query
           __syncthreads();
-          block_rerank_stored<DT, kSelThreads>(fin_ids, k, k_out, Qbase + long(i) * dim, X, dim,
+          block_rerank_stored<DT, NT>(fin_ids, k, k_out, Qbase + long(i) * dim, X, dim,
                                                out_ids + long(i) * k_out, out_d ? out_d + long(i) * k_out : nullptr,
                                                list, d64, cid, tid, metric);
         }
