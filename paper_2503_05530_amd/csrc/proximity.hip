@@ -716,7 +716,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     return check_launch(h, "proximity_search_batch");
   }
 
-  if (!rows_in_place)
+  if (!rows_in_place && lsh)
     HIP_TRY(h, hipMemcpyAsync(batch_rows, queries, size_t(n) * dim * sizeof(float), hipMemcpyDeviceToDevice, s));
   if (lsh) {
     // Section 3.2: codes, regrouping by code, one block per bucket that occurs, miss list in row order
@@ -735,7 +735,10 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
         h->src, h->row_slot);
     lsh_miss_list_kernel<<<dim3(1), dim3(1024), 0, s>>>(out_hit, nn, h->miss_list, h->miss_count, h->state);
   } else {
-  launch_row_norms<kDtypeF32>(h, batch_rows, nn, dim, h->srcnrm + c, s);
+  if (rows_in_place)
+    launch_row_norms<kDtypeF32>(h, batch_rows, nn, dim, h->srcnrm + c, s);
+  else  // the rows into the batch buffer and their norms, in one launch
+    copy_rows_norms_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(queries, nn, dim, batch_rows, h->srcnrm + c);
   int have_probe = 0;
   if (c > 0) {
     have_probe = 1;

@@ -249,6 +249,25 @@ __global__ __launch_bounds__(256) void scores_stream_generic_kernel(
   }
 }
 
+// A call's rows copied into the instance's batch buffer together with their squared norms
+// (row_norms_kernel's arithmetic), in one launch.  One wave per row.
+__global__ __launch_bounds__(256) void copy_rows_norms_kernel(const float* __restrict__ in, int n_rows, int dim,
+                                                              float* __restrict__ out, float* __restrict__ nrm) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n_rows) return;
+  const float4* src = reinterpret_cast<const float4*>(in + long(row) * dim);
+  float4* dst = reinterpret_cast<float4*>(out + long(row) * dim);
+  float acc = 0.f;
+  for (int c = lane; c < dim / 4; c += 64) {
+    const float4 v = src[c];
+    dst[c] = v;
+    acc += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) nrm[row] = acc;
+}
+
 // The per-row term of row_score for the distance functions other than Euclidean, made in place
 // from the squared lengths: inner product 0, cosine 1/|x|.
 __global__ __launch_bounds__(256) void row_terms_kernel(float* __restrict__ nrm, long n_rows, int cosine) {
