@@ -45,6 +45,8 @@
 // state is kept in scalar registers for that reason (see the notes at `uniform`).
 #pragma once
 
+#include <type_traits>
+
 #include "cache_kernels.hpp"
 
 namespace prox {
@@ -314,38 +316,51 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
         const int cnt = __builtin_amdgcn_readlane(my_cnt, r);
         int best_src = -1;
         if (cnt <= cap) {
-          // one lane each: from LDS when the staged part holds them all
-          const bool staged = cnt <= kStageCands;
-          // candidate p of this row: is it live and within tau?
-          auto within = [&](int p, int& s, double& d) {
-            s = staged ? ch.src[r][p] : cand_src[long(i) * cap + p];
-            d = staged ? ch.d[r][p] : cand_d[long(i) * cap + p];
-            return is_live(s) && d <= tau;
-          };
-          int my_ok_s = -1, total = 0;
-          for (int p0 = 0; p0 < cnt; p0 += 64) {
-            int s;
-            double d;
-            const bool ok = p0 + lane < cnt && within(p0 + lane, s, d);
-            if (ok) my_ok_s = s;
-            total += __popcll(__ballot(ok));
-          }
-          if (total == 1) {
-            // the usual outcome: nothing to compare
-            best_src = __builtin_amdgcn_readlane(my_ok_s, __ffsll((long long)__ballot(my_ok_s >= 0)) - 1);
-          } else if (total >= 2) {
-            // nearest wins, equal distances go to the older key: a key untouched in this batch still
-            // carries its own seq, a row of this batch has base_seq + row
-            ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
+          // One lane per candidate.  The staged part of the list is read from LDS; longer lists come
+          // from global memory.  (Two instances of the code rather than one that picks the address:
+          // a load whose address may be in either memory goes through the slower generic path.)
+          auto decide = [&](auto staged_tag) {
+            constexpr bool kStaged = decltype(staged_tag)::value;
+            // candidate p of this row: is it live and within tau?
+            auto within = [&](int p, int& s, double& d) {
+              if (kStaged) {
+                s = ch.src[r][p];
+                d = ch.d[r][p];
+              } else {
+                s = cand_src[long(i) * cap + p];
+                d = cand_d[long(i) * cap + p];
+              }
+              return is_live(s) && d <= tau;
+            };
+            int my_ok_s = -1, total = 0;
             for (int p0 = 0; p0 < cnt; p0 += 64) {
               int s;
               double d;
-              if (p0 + lane < cnt && within(p0 + lane, s, d))
-                best_take(best, d, s < c ? slot_seq[s] : base_seq + (s - c), s);
+              const bool ok = p0 + lane < cnt && within(p0 + lane, s, d);
+              if (ok) my_ok_s = s;
+              total += __popcll(__ballot(ok));
             }
-            best_wave_reduce(best);
-            best_src = best.src;
-          }
+            if (total == 1) {
+              // the usual outcome: nothing to compare
+              best_src = __builtin_amdgcn_readlane(my_ok_s, __ffsll((long long)__ballot(my_ok_s >= 0)) - 1);
+            } else if (total >= 2) {
+              // nearest wins, equal distances go to the older key: a key untouched in this batch still
+              // carries its own seq, a row of this batch has base_seq + row
+              ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
+              for (int p0 = 0; p0 < cnt; p0 += 64) {
+                int s;
+                double d;
+                if (p0 + lane < cnt && within(p0 + lane, s, d))
+                  best_take(best, d, s < c ? slot_seq[s] : base_seq + (s - c), s);
+              }
+              best_wave_reduce(best);
+              best_src = best.src;
+            }
+          };
+          if (cnt <= kStageCands)
+            decide(std::true_type{});
+          else
+            decide(std::false_type{});
         } else {
           ++dense;
           ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
