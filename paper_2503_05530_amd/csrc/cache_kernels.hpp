@@ -496,11 +496,13 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
     }
     __syncthreads();
     ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
-    for (int s = tid; s < size0; s += 1024) {
+    for (int s = tid; s < c; s += 1024) {
+      // (both read whether or not they are needed, and over all c slots rather than the size0 in use:
+      // the loads then wait neither for each other nor for the cache state to arrive)
       const long long seq = slot_seq[s];
-      const double d = D64[long(i) * c + s];  // (read whether or not it is needed: the two loads overlap)
+      const double d = D64[long(i) * c + s];
       // seq < base_seq: still the key it held when the call began
-      if (seq < base_seq && d <= tau) best_take(best, d, seq, s);
+      if (s < size0 && seq < base_seq && d <= tau) best_take(best, d, seq, s);
     }
     if (tid < i) {
       const int t = dec_slot[tid];
@@ -579,7 +581,8 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
     st->inbatch_hits += inbatch;
     *miss_count = M;
   }
-  __syncthreads();
+  // (no barrier: what follows reads only the decisions in LDS and the slot state of the row loop,
+  // both behind that loop's last barrier, so it overlaps with the first thread's bookkeeping)
   // keys of rows that missed and still own their slot; hits on keys resident before the call
   for (int i = 0; i < n; ++i) {
     if (dec_hit[i]) {
