@@ -99,7 +99,7 @@ COUNTER_TRAFFIC = {
     ("scores_stream_kernel", 0, 1_000_000, 768, 4):
         {"fetch_bytes": 1_501_992 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scores_stream_mid_b1.md"},
     ("scan_mfma_dma_kernel", 64, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_504_666 * 2048, "write_bytes": 7_040 * 1024, "source": "profiles/scan_mfma_mid_b64.md"},
+        {"fetch_bytes": 1_504_671 * 2048, "write_bytes": 7_040 * 1024, "source": "profiles/scan_mfma_mid_b64.md"},
     ("scan_bf16x3_kernel", 128, 8_000_000, 384, 2):
         {"fetch_bytes": 3_116_246 * 2048, "write_bytes": 233_673 * 1024,
          "source": "profiles/scan_bf16x3_lowreuse_b128.md"},
