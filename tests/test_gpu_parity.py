@@ -209,6 +209,53 @@ def test_cache_at_and_beyond_on_chip_state(B, policy, cap):
     assert hit[:600].tolist() == o_hit.tolist()
 
 
+@pytest.mark.parametrize("trial", range(16))
+def test_exact_match_model_at_many_sizes(B, trial):
+    """tau = 0 on streams with heavily repeated vectors: Algorithm 1 is then a textbook FIFO/LRU cache keyed
+    by vector identity (test_oracle_pins shows the oracle equal to that model), which is cheap enough to check
+    capacities from 1 to beyond the on-chip limit, calls of up to 8 192 rows cut at random, tens of thousands
+    of rows, hits on rows of the same call, and long eviction sequences."""
+    from collections import OrderedDict
+    rng = np.random.default_rng([trial, 4242])
+    dim = 32
+    cap = int(rng.choice([1, 2, 7, 63, 64, 65, 300, 1000, 4097, 10000, 16000, 18700, 19000]))
+    policy = int(rng.integers(0, 2))
+    max_batch = int(rng.choice([64, 512, 4096, 8192]))
+    n_vec = int(cap * rng.choice([0.5, 1.2, 3.0])) + 5
+    n = int(rng.choice([3000, 12000, 30000]))
+    vecs = W.unit_rows(rng.standard_normal((n_vec, dim))).astype(np.float32)
+    which = np.minimum((rng.pareto(1.0, size=n) * n_vec / 20).astype(np.int64), n_vec - 1)
+    q = vecs[which]
+    model, want_hit, evictions = OrderedDict(), [], 0
+    for t, key in enumerate(which.tolist()):
+        if key in model:
+            want_hit.append(1)
+            if policy == po.POLICY_LRU:
+                model.move_to_end(key)
+        else:
+            want_hit.append(0)
+            if len(model) >= cap:
+                model.popitem(last=False)
+                evictions += 1
+            model[key] = t
+    px = B.Proximity(None, dim, cap, 3, policy, max_batch, device=DEV)
+    flags, r0 = [], 0
+    while r0 < n:
+        step = int(rng.integers(1, max_batch + 1))
+        _, _, h = px.search_batch(torch.from_numpy(q[r0:r0 + step]).to(DEV), 0.0)
+        flags.append(h)
+        r0 += step
+    hit = torch.cat(flags).cpu().numpy()
+    what = f"cap {cap} policy {policy} max_batch {max_batch} rows {n}"
+    assert hit.tolist() == want_hit, what
+    seq, _, _ = px.cache_dump()
+    assert seq.tolist() == list(model.values()), what
+    assert px.stats()["evictions"] == evictions and px.stats()["hits"] == sum(want_hit), what
+    px.close()
+    o_hit, _, _ = po.simulate_decisions(q[:300], 0.0, cap, policy)
+    assert hit[:300].tolist() == o_hit.tolist()
+
+
 # ---------------------------------------------------------------------------
 # Inner-product and cosine indexes (Section 2.2's other distance functions)
 # ---------------------------------------------------------------------------
