@@ -107,3 +107,45 @@ def test_random_configuration(seed):
     for key in ("queries", "hits", "misses", "inserts", "evictions", "size"):
         assert st[key] == os_[key], (what, key)
     px.close()
+
+
+@pytest.mark.parametrize("trial", range(12))
+def test_random_stream_at_larger_capacity(trial):
+    """Cache decisions alone (no corpus) on longer streams against larger caches than the cases above:
+    capacities 100 to 5 000, 2 000 to 6 000 rows cut into calls of up to 4 096, skewed reuse of the bases and
+    radii on both sides of the tolerance, so that long candidate lists, the full-row fallback, hits on rows of
+    the same call and thousands of evictions all occur; Euclidean and cosine."""
+    import paper_2503_05530_amd.binding as B
+    rng = np.random.default_rng([trial, 777])
+    dim = int(rng.choice([32, 64, 128]))
+    cap = int(rng.choice([100, 500, 2000, 5000]))
+    policy = int(rng.integers(0, 2))
+    metric = int(rng.choice([po.METRIC_L2, po.METRIC_L2, po.METRIC_COSINE]))
+    max_batch = int(rng.choice([64, 1024, 4096]))
+    n = int(rng.choice([2000, 6000]))
+    n_bases = int(cap * rng.choice([0.3, 1.0, 2.5])) + 3
+    tau = float(rng.choice([0.1, 0.3, 0.5]))
+    bases = W.unit_rows(rng.standard_normal((n_bases, dim)))
+    idx = np.minimum((rng.pareto(1.2, size=n) * n_bases / 10).astype(np.int64), n_bases - 1)
+    radius = rng.choice([0.0, 0.05, 0.2, 0.35, 0.6], size=n)
+    q = W.unit_rows(bases[idx] + radius[:, None] * W.unit_rows(rng.standard_normal((n, dim)))).astype(np.float32)
+    if metric == po.METRIC_COSINE:
+        q = (q * rng.uniform(0.5, 2.0, size=(n, 1))).astype(np.float32)
+        tau = tau * tau / 2.0
+    o_hit, _, dec = po.simulate_decisions(q, tau, cap, policy, metric=metric)
+    px = B.Proximity(None, dim, cap, 3, policy, max_batch, device=DEV, metric=metric)
+    flags, r0 = [], 0
+    while r0 < n:
+        step = int(rng.integers(1, max_batch + 1))
+        _, _, h = px.search_batch(torch.from_numpy(q[r0:r0 + step]).to(DEV), tau)
+        flags.append(h)
+        r0 += step
+    hit = torch.cat(flags).cpu().numpy()
+    what = f"dim {dim} cap {cap} policy {policy} metric {metric} max_batch {max_batch} rows {n} tau {tau}"
+    assert (hit == o_hit).all(), f"{what}: flags differ first at {np.flatnonzero(hit != o_hit)[:5]}"
+    seq, _, _ = px.cache_dump()
+    assert seq.tolist() == dec.dump_seq().tolist(), what
+    st, os_ = px.stats(), dec.stats()
+    for key in ("queries", "hits", "misses", "inserts", "evictions", "size"):
+        assert st[key] == os_[key], (what, key)
+    px.close()
