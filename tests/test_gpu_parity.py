@@ -65,6 +65,33 @@ def test_knn_matches_oracle_bf16(B, nq):
     px.close()
 
 
+@pytest.mark.parametrize("trial", range(30))
+def test_knn_random_shapes(B, trial):
+    """The index search alone at shapes drawn at random: dimensions from 32 to 2 048, corpus sizes around
+    every threshold of the launch logic (tile and segment sizes, the head pass), k from 1 to the largest, query
+    counts around every tile-shape boundary, both corpus types, all three distance functions."""
+    rng = np.random.default_rng([trial, 99])
+    dim = int(rng.choice([32, 64, 96, 128, 160, 256, 384, 512, 768, 1024, 2048]))
+    n_docs = int(rng.choice([1, 7, 63, 129, 1000, 4095, 16383, 16384 * 8 - 1, 16384 * 8, 140001]))
+    n_docs = min(n_docs, 60_000_000 // dim)
+    k = int(rng.choice([1, 5, 10, 32, 100, B.MAX_K]))
+    nq = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 31, 32, 33, 64, 65, 96, 97, 128, 129, 200]))
+    bf16 = bool(rng.random() < 0.3)
+    metric = int(rng.choice([po.METRIC_L2, po.METRIC_L2, po.METRIC_IP, po.METRIC_COSINE]))
+    x32 = W.corpus_f32(n_docs, dim, trial)
+    if metric != po.METRIC_L2:
+        x32 = (x32 * rng.uniform(0.3, 3.0, size=(n_docs, 1))).astype(np.float32)
+    corpus = W.bf16_bits_to_f32(W.f32_to_bf16_bits(x32)) if bf16 else x32
+    q = (W.unit_rows(rng.standard_normal((nq, dim))) * rng.uniform(0.5, 2.0, size=(nq, 1))).astype(np.float32)
+    px = B.Proximity(gpu_corpus(x32, bf16), dim, 0, k, B.POLICY_FIFO, nq, metric=metric)
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    o_ids, o_d = po.batched_exact_knn(corpus, q, k, metric=metric)
+    P.assert_lists_match(ids.cpu().numpy(), dists.cpu().numpy(), o_ids, o_d, corpus, q,
+                         dist_rtol=P.DIST_RTOL_BF16 if bf16 else P.DIST_RTOL_F32,
+                         what=f"n_docs {n_docs} dim {dim} k {k} nq {nq} bf16 {bf16} metric {metric}", metric=metric)
+    px.close()
+
+
 @pytest.mark.parametrize("nq", [1, 4, 70])
 def test_knn_at_the_largest_k(B, nq):
     n_docs, dim, k = 40000, 768, B.MAX_K
