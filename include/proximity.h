@@ -4,11 +4,14 @@
  * The library implements the per-query retrieval step of an approximate
  * key-value cache placed in front of a vector index (Algorithm 1, Section 3.1):
  * each query embedding is compared with every cached query key (Euclidean
- * distance); if the nearest key lies within the tolerance tau the cached list of
+ * distance unless the instance is created with another PROXIMITY_METRIC_*);
+ * if the nearest key lies within the tolerance tau the cached list of
  * document indices is returned, otherwise the index is searched exactly for the
  * k nearest documents (the nearest-neighbour search of Section 2.2), the oldest
  * (FIFO) or least recently used (LRU) entry is evicted when the cache already
  * holds c entries (Section 3.3.2), and the query with its result is stored.
+ * Options fixed at creation: the re-ranking factor of Section 3.3.4
+ * (rerank_factor) and the bucketed cache of Section 3.2 (lsh_bits, lsh_planes).
  *
  * Queries are an ordered stream (Section 3.1 processes one query at a time).
  * A call may hand over many rows; the result is exactly what processing the
