@@ -397,7 +397,7 @@ __global__ __launch_bounds__(NT) void select_finish_small_kernel(
   const int q = m_begin + blockIdx.y;   // position in the miss list; S rows are relative to m_begin
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   if (q >= m_total) return;
-  const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
+  const int g = blockIdx.x, tid = threadIdx.x;
 
   __shared__ uint64_t list[SEG];
   __shared__ uint64_t mins[NT];
