@@ -433,6 +433,11 @@ def main():
         t0 = time.perf_counter()
         po.exact_knn(corpus, queries[0], w.k)
         parts[f"scan_s_{n_docs}_docs"] = round(time.perf_counter() - t0, 3)
+        # the oracle's batched form (float64 matrix product per block of rows, multi-threaded BLAS) on 64 queries:
+        # the fastest the oracle's own code answers misses on this host
+        t0 = time.perf_counter()
+        po.batched_exact_knn(corpus, queries[:64], w.k, metric=metric)
+        parts["batched_scan_s_64_queries_all_cores"] = round(time.perf_counter() - t0, 3)
         cpu["parts"] = parts
 
     line = {
