@@ -52,7 +52,9 @@ Euclidean distance.
 Parity status: every function here is pinned by tests that do not re-use its
 own formula (hand-worked eviction streams, reduction to textbook exact-match
 FIFO/LRU caches, brute-force loops, library nearest-neighbour routines, closed
-forms for tau = 0 and tau = infinity).  Document ids at full corpus scale have
+forms for tau = 0 and tau = infinity), the block-streamed search
+``exact_knn_over_chunks`` included (literal search and a library routine, on uneven
+blocks with duplicated rows).  Document ids at full corpus scale have
 no independent pin beyond those small cases ("parity unpinned" at that scale).
 """
 from __future__ import annotations

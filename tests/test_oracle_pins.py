@@ -156,6 +156,60 @@ def test_batched_knn_equals_literal_knn_including_ties():
     assert b_ids[0, :3].tolist() == [3, 100, 650]
 
 
+def uneven_blocks(corpus, sizes):
+    """(first_row, rows) blocks of the given sizes, in row order, covering the corpus."""
+    r0 = 0
+    for s in sizes:
+        yield r0, corpus[r0:r0 + s]
+        r0 += s
+    assert r0 == len(corpus)
+
+
+def test_knn_over_chunks_equals_literal_knn_on_uneven_blocks_with_ties():
+    """The streamed form (Section 2.2's search over a corpus that arrives block by block) against the literal
+    brute force: duplicated rows spread over several blocks, blocks smaller than k, a one-row last block, a
+    query sitting on a duplicated row, and k larger than the corpus."""
+    rng = np.random.default_rng(11)
+    corpus = rng.standard_normal((331, 12)).astype(np.float32)
+    for j in (40, 41, 97, 205, 330):           # five copies of row 7, the last one alone in the last block
+        corpus[j] = corpus[7]
+    corpus[300] = corpus[299]                   # a pair of equal rows inside one block
+    queries = rng.standard_normal((7, 12)).astype(np.float32)
+    queries[0] = corpus[7]                      # distance 0 to six identical rows
+    queries[1] = corpus[299]
+    sizes = [3, 5, 33, 1, 57, 100, 2, 64, 60, 5, 1]       # several blocks hold fewer than k rows
+    for k in (1, 4, 9, 40):
+        c_ids, c_d = po.exact_knn_over_chunks(uneven_blocks(corpus, sizes), queries, k)
+        for r in range(len(queries)):
+            ids, d = po.exact_knn(corpus, queries[r], k)
+            assert c_ids[r].tolist() == ids.tolist(), (k, r)
+            np.testing.assert_allclose(c_d[r], d, rtol=1e-13, atol=1e-15)
+    c_ids, _ = po.exact_knn_over_chunks(uneven_blocks(corpus, sizes), queries, 9)
+    assert c_ids[0, :6].tolist() == [7, 40, 41, 97, 205, 330]      # equal distances rank by index across blocks
+    assert c_ids[1, :2].tolist() == [299, 300]
+    # k larger than the corpus: every row ranked, then padding
+    small = corpus[:6]
+    c_ids, c_d = po.exact_knn_over_chunks(uneven_blocks(small, [2, 3, 1]), queries[:2], 9)
+    for r in range(2):
+        ids, d = po.exact_knn(small, queries[r], 9)
+        assert c_ids[r].tolist() == ids.tolist() and c_ids[r, 6:].tolist() == [-1, -1, -1]
+        assert np.isinf(c_d[r, 6:]).all()
+        np.testing.assert_allclose(c_d[r, :6], d[:6], rtol=1e-13)
+
+
+def test_knn_over_chunks_matches_library_neighbours():
+    from sklearn.neighbors import NearestNeighbors
+
+    rng = np.random.default_rng(12)
+    corpus = rng.standard_normal((900, 20))
+    queries = rng.standard_normal((5, 20))
+    nn = NearestNeighbors(n_neighbors=13, algorithm="brute", metric="euclidean").fit(corpus)
+    lib_d, lib_i = nn.kneighbors(queries)
+    c_ids, c_d = po.exact_knn_over_chunks(uneven_blocks(corpus, [7, 300, 1, 292, 300]), queries, 13)
+    assert (c_ids == lib_i).all()
+    np.testing.assert_allclose(c_d, lib_d, rtol=1e-10)
+
+
 # ---------------------------------------------------------------------------
 # Extreme tolerances and counters
 # ---------------------------------------------------------------------------
