@@ -83,7 +83,13 @@ def l2_distances(q: np.ndarray, rows: np.ndarray) -> np.ndarray:
 
 def metric_distances(q: np.ndarray, rows: np.ndarray, metric: int = METRIC_L2) -> np.ndarray:
     """Distance from q to every row under the index's distance function (Section 2.2), float64:
-    Euclidean; negated inner product; or cosine distance 1 - q.x / (|q| |x|)."""
+    Euclidean; negated inner product; or cosine distance 1 - q.x / (|q| |x|).
+
+    The cosine form is evaluated as 1 - q.x / sqrt((q.q) (x.x)) with the three sums taken the same way, so that
+    a row bit-identical to q is at distance exactly 0 (the three sums are then one number s, and
+    sqrt(s * s) == s in binary floating point; sqrt(s) * sqrt(s) can differ from s in the last place).
+    Section 3.3.3 reads a tolerance of 0 as exact matching: an identical query must be a hit at tau = 0.
+    """
     if metric == METRIC_L2:
         return l2_distances(q, rows)
     q64, x = as_f64_rows(q), as_f64_rows(rows)
@@ -91,7 +97,8 @@ def metric_distances(q: np.ndarray, rows: np.ndarray, metric: int = METRIC_L2) -
     if metric == METRIC_IP:
         return -dots
     if metric == METRIC_COSINE:
-        return 1.0 - dots / (np.sqrt(np.sum(x * x, axis=1)) * np.sqrt(np.sum(q64 * q64)))
+        qq = np.sum(q64[None, :] * q64[None, :], axis=1)[0]
+        return 1.0 - dots / np.sqrt(np.sum(x * x, axis=1) * qq)
     raise ValueError("metric must be L2 (0), inner product (1) or cosine (2)")
 
 

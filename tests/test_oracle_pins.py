@@ -601,6 +601,30 @@ def test_cosine_properties():
     assert po.exact_knn(unit, qu, 15, metric=po.METRIC_IP)[0].tolist() == want
 
 
+def test_cosine_distance_of_identical_vectors_is_exactly_zero():
+    """Section 3.3.3: a tolerance of 0 is exact matching, so a vector must be at distance exactly 0 from a
+    bit-identical copy of itself (and, the formula being free of lengths, from its multiples by powers of two,
+    which scale every term exactly) -- for every vector, not just for lucky roundings."""
+    rng = np.random.default_rng(31)
+    for dim in (4, 33, 384, 768):
+        v = (rng.standard_normal((400, dim)) * rng.uniform(1e-3, 1e3, size=(400, 1))).astype(np.float32)
+        for r in range(0, 400, 7):
+            d = po.metric_distances(v[r], v[r:r + 1], po.METRIC_COSINE)
+            assert d[0] == 0.0
+            assert po.metric_distances(v[r], 4.0 * v[r:r + 1], po.METRIC_COSINE)[0] == 0.0
+            assert po.metric_distances(0.5 * v[r], v[r:r + 1], po.METRIC_COSINE)[0] == 0.0
+        # and nothing else is at zero: the nearest other row is clearly away
+        d = po.metric_distances(v[0], v[1:], po.METRIC_COSINE)
+        assert d.min() > 1e-3
+    # an exact-match cache under cosine: repeats hit at tau = 0, whatever their power-of-two length
+    vocab = rng.standard_normal((30, 24)).astype(np.float32)
+    which = rng.integers(0, 30, size=500)
+    q = vocab[which] * rng.choice([0.5, 1.0, 2.0, 8.0], size=(500, 1)).astype(np.float32)
+    for policy in (po.POLICY_FIFO, po.POLICY_LRU):
+        hit, _, _ = po.simulate_decisions(q, 0.0, 7, policy, metric=po.METRIC_COSINE)
+        assert hit.tolist() == textbook_cache_flags(which.tolist(), 7, policy)
+
+
 def test_cache_under_other_metrics_hand_worked():
     """(1,0), (5,0), (0,1), (0,2), (3,3) with tau = 0.1 and room for every key: the second and fourth
     query point the same way as the one before them, so the cosine cache hits on both although they
