@@ -27,7 +27,10 @@
  *     C++ exception or abort crosses this boundary.  Argument errors are found
  *     before any GPU work is enqueued and leave the handle unchanged; the text
  *     of the last error is available from proximity_last_error().
- *   - A handle is an ordered stream consumer and is not thread-safe.
+ *   - A handle is an ordered stream consumer and is not thread-safe.  Its workspaces are shared by all
+ *     of its calls, so at any time the calls of one handle must be in flight on ONE stream only: before
+ *     passing a different stream than the previous call did, wait for that call (hipStreamSynchronize,
+ *     or an event the new stream waits on).  Calls that overlap on two streams race.
  *   - The library allocates all of its device memory in proximity_create().
  *     proximity_search_batch() and proximity_knn_batch() allocate nothing and
  *     never wait for the device: the number of misses is consumed on the
@@ -43,7 +46,7 @@
 extern "C" {
 #endif
 
-#define PROXIMITY_ABI_VERSION 3u
+#define PROXIMITY_ABI_VERSION 4u
 
 enum {
   PROXIMITY_OK = 0,
@@ -110,12 +113,11 @@ typedef struct proximity_config {
                              product with row i is >= 0 (evaluated in float64).  Copied at
                              creation; NULL when lsh_bits is 0                               */
   uint32_t metric;        /* PROXIMITY_METRIC_*: ranks the documents, is the unit of tau and of
-                             every reported distance.  Under COSINE the instance scales each
-                             query to unit length in float32 before the cache sees it, keeps
-                             its keys so (proximity_cache_dump returns them so), and decides
-                             "cosine distance <= tau" as "Euclidean distance between the unit
-                             vectors <= sqrt(2 tau)"; tau = 0 thus matches a key exactly when
-                             the two unit-length float32 vectors are identical               */
+                             every reported distance.  Keys are the queries as the caller gave
+                             them under every metric (proximity_cache_dump returns them so);
+                             query-key distances are evaluated in float64, the cosine one as
+                             1 - q.k / sqrt((q.q)(k.k)), which is exactly 0 for a key identical
+                             to the query, so tau = 0 is an exact-match cache here too          */
   uint32_t reserved0;     /* must be 0                                                        */
 } proximity_config;
 
@@ -129,7 +131,15 @@ typedef struct proximity_stats_t {
   uint64_t size;           /* keys resident now, <= capacity                                 */
   uint64_t inbatch_hits;   /* hits on a key stored by an earlier row of the same call        */
   uint64_t dense_resolves; /* rows whose nearest key was found by the full-row fallback      */
-  uint64_t reserved[8];
+  uint64_t slack_exhausted;  /* index searches (since creation or the last clear, proximity_knn_batch
+                                included) whose float32 candidate list of k + 8 rows could not be
+                                proven to hold the k nearest under the float32 error bound, and were
+                                ranked again from every row within that bound of the k-th          */
+  uint64_t slack_unresolved; /* of those, searches that stayed with the float64 ranking of their
+                                k + 8 candidates because the second ranking had no room: more than
+                                2048 rows within the bound of the k-th (thousands of identical
+                                documents).  0 means every list returned so far is provably exact  */
+  uint64_t reserved[6];
 } proximity_stats_t;
 
 /*
@@ -146,6 +156,20 @@ typedef struct proximity_launch_t {
 } proximity_launch_t;
 
 uint32_t proximity_abi_version(void);
+
+/*
+ * How far the float32 score by which the index search pre-ranks a row can lie from the row's exact score
+ * (host arithmetic, no GPU work).  The search ranks by float32 scores -- |x|^2 - 2 q.x (L2), -2 q.x (IP),
+ * -2 q.x / |x| (COSINE) -- keeps the k + 8 best and ranks those by float64 distance (Section 2.2 asks for
+ * the exact ranked list).  With E this bound, W the worst kept float32 score and t the k-th smallest exact
+ * score among the kept rows, W - E > t proves that no other row belongs to the k nearest; a search for
+ * which it fails is ranked again from all rows scoring at most t + E (counted in slack_exhausted).
+ *   E = g (X^2 + 2 |q| X)   L2          g = (3 dim + 16) 2^-24: every product and partial sum of a dim-term
+ *   E = g 2 |q| X           IP              inner product rounds once (three products per term when a
+ *   E = g 4 |q|             COSINE          bfloat16 corpus is searched with the query split in three)
+ * |q| = query_length, X = max_row_length (the longest corpus row).  NaN for a bad argument.
+ */
+double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_length, double max_row_length);
 
 /*
  * Create an instance on cfg->device: computes the squared norm of every corpus

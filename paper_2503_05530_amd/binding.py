@@ -20,7 +20,7 @@ ERR_INVALID_ARG, ERR_K_MISMATCH, ERR_BATCH_TOO_LARGE, ERR_BAD_TAU, ERR_HIP, ERR_
 DTYPE_F32, DTYPE_BF16 = 0, 1
 POLICY_FIFO, POLICY_LRU = 0, 1
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
-ABI_VERSION = 3
+ABI_VERSION = 4
 MAX_K, MAX_DIM, MAX_BATCH, MAX_CAPACITY = 240, 4096, 8192, 1 << 20   # PROXIMITY_MAX_* of the header
 
 
@@ -34,7 +34,8 @@ class ProximityConfig(C.Structure):
 
 class ProximityStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("queries", "hits", "misses", "inserts", "evictions", "size",
-                                          "inbatch_hits", "dense_resolves")] + [("reserved", C.c_uint64 * 8)]
+                                          "inbatch_hits", "dense_resolves", "slack_exhausted",
+                                          "slack_unresolved")] + [("reserved", C.c_uint64 * 6)]
 
 
 class ProximityLaunch(C.Structure):
@@ -51,6 +52,8 @@ lib = C.CDLL(LIB_PATH)
 _H = C.c_void_p
 lib.proximity_abi_version.restype = C.c_uint32
 lib.proximity_abi_version.argtypes = []
+lib.proximity_score_error_bound.restype = C.c_double
+lib.proximity_score_error_bound.argtypes = [C.c_uint32, C.c_uint32, C.c_double, C.c_double]
 lib.proximity_last_error.restype = C.c_char_p
 lib.proximity_last_error.argtypes = [_H]
 lib.proximity_create.restype = C.c_int
@@ -73,7 +76,7 @@ lib.proximity_profile_start.argtypes = [_H]
 lib.proximity_profile_stop.restype = C.c_int
 lib.proximity_profile_stop.argtypes = [_H, C.POINTER(ProximityLaunch), C.c_uint32, C.POINTER(C.c_uint32)]
 
-EXPORTED = ("proximity_abi_version", "proximity_last_error", "proximity_create", "proximity_destroy",
+EXPORTED = ("proximity_abi_version", "proximity_score_error_bound", "proximity_last_error", "proximity_create", "proximity_destroy",
             "proximity_search_batch", "proximity_knn_batch", "proximity_stats", "proximity_cache_dump",
             "proximity_clear", "proximity_profile_start", "proximity_profile_stop")
 

@@ -24,15 +24,19 @@ struct CacheState {
   unsigned long long queries, hits, misses, inserts, evictions, inbatch_hits, dense_resolves, pad2;
 };
 
-// Euclidean distance in float64, direct-difference form, computed by one wave.
-// The one routine every float64 decision in this file goes through.
-__device__ __forceinline__ double wave_dist64(const float* __restrict__ a, const float* __restrict__ b, int dim,
-                                              int lane) {
+// Distance between a query and a key in float64, computed by one wave: the one routine every float64
+// decision in this file goes through.  cosine == 0: Euclidean, direct-difference form,
+// sqrt(sum (a_i - b_i)^2).  cosine == 1: 1 - a.b / sqrt((a.a)(b.b)); the three sums run over the same
+// elements in the same order, so a vector against a bit-identical copy of itself gives exactly 0
+// (a.b, a.a and b.b are then the same number s, and sqrt(s*s) == s in binary floating point), which is
+// what makes a tolerance of zero an exact-match cache under this distance too (Section 3.3.3).
+__device__ __forceinline__ double wave_keydist64(const float* __restrict__ a, const float* __restrict__ b, int dim,
+                                                 int lane, int cosine) {
   // 16 bytes per lane and two steps in flight (rows are 128-byte aligned: dim is a multiple of 32)
   const float4* a4 = reinterpret_cast<const float4*>(a);
   const float4* b4 = reinterpret_cast<const float4*>(b);
   const int n_vec = dim / 4;
-  double acc = 0.0;
+  double acc = 0.0, aa = 0.0, bb = 0.0;
   for (int iv = lane; iv < n_vec; iv += 128) {
     const bool two = iv + 64 < n_vec;
     const float4 x0 = a4[iv], y0 = b4[iv];
@@ -41,24 +45,46 @@ __device__ __forceinline__ double wave_dist64(const float* __restrict__ a, const
       x1 = a4[iv + 64];
       y1 = b4[iv + 64];
     }
-    const double dx = double(x0.x) - double(y0.x), dy = double(x0.y) - double(y0.y);
-    const double dz = double(x0.z) - double(y0.z), dw = double(x0.w) - double(y0.w);
-    acc += dx * dx + dy * dy + dz * dz + dw * dw;
-    if (two) {
-      const double ex = double(x1.x) - double(y1.x), ey = double(x1.y) - double(y1.y);
-      const double ez = double(x1.z) - double(y1.z), ew = double(x1.w) - double(y1.w);
-      acc += ex * ex + ey * ey + ez * ez + ew * ew;
+    const float xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+    const float ys[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (e >= 4 && !two) break;
+      const double x = double(xs[e]), y = double(ys[e]);
+      if (cosine) {
+        acc += x * y;
+        aa += x * x;
+        bb += y * y;
+      } else {
+        const double df = x - y;
+        acc += df * df;
+      }
     }
   }
+  if (cosine) return 1.0 - wave_sum(acc) / sqrt(wave_sum(aa) * wave_sum(bb));
   return sqrt(wave_sum(acc));
 }
 
-// Float32 pre-filter bound for "distance <= tau".  The float32 probe value
-// d2 = (|s|^2 - 2 q.s) + |q|^2 carries an absolute error far below
-// 1e-5 * (|q|^2 + |s|^2); anything that could be within tau in exact arithmetic
-// passes this bound and is then decided in float64.
-__device__ __forceinline__ float prefilter_bound(double tau, float qn, float sn) {
-  const double b = tau * tau * (1.0 + 1e-3) + 1e-4 * (double(qn) + double(sn));
+// The float32 probe value of a source, from the probe's score  score = |s|^2 - 2 q.s  and the two squared
+// lengths: the squared Euclidean distance, or (cosine) the cosine distance 1 - q.s / (|q| |s|).
+__device__ __forceinline__ float probe_value(float score, float qn, float sn, int cosine) {
+  if (cosine) return 1.f - 0.5f * (sn - score) / sqrtf(qn * sn);
+  return score + qn;
+}
+
+// Float32 pre-filter bound for "distance <= tau" on probe_value.  The float32 inner product behind the
+// probe value carries an absolute error of at most (dim + 8) * 2^-24 * |q| |s| (every product and every
+// partial sum rounds once), so the squared distance is off by at most twice that plus the roundings of
+// the two squared lengths, i.e. by less than `rel` * (|q|^2 + |s|^2), and the cosine distance by less
+// than `rel`; anything that could be within tau in exact arithmetic passes the bound and is then decided
+// in float64.  (The factor 1 + 1e-3 covers the float32 rounding of tau^2 itself.)
+__device__ __forceinline__ float prefilter_rel(int dim) { return 2.5f * float(dim + 8) * 5.9604645e-8f; }
+__device__ __forceinline__ float dense_slack(float qn, float sn_max, int dim, int cosine) {
+  return 2.f * (cosine ? prefilter_rel(dim) + 1e-6f : prefilter_rel(dim) * (qn + sn_max));
+}
+__device__ __forceinline__ float prefilter_bound(double tau, float qn, float sn, int dim, int cosine) {
+  const double rel = double(prefilter_rel(dim));
+  const double b = cosine ? tau * (1.0 + 1e-3) + rel + 1e-6 : tau * tau * (1.0 + 1e-3) + rel * (double(qn) + double(sn));
   return b > 3.0e38 ? 3.0e38f : float(b);
 }
 
@@ -73,8 +99,8 @@ __device__ __forceinline__ float prefilter_bound(double tau, float qn, float sn)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void probe_candidates_kernel(
     const float* __restrict__ D32, long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm,
-    int dim, int c, int n, const CacheState* __restrict__ st, double tau, int cap, int* __restrict__ cand_cnt,
-    int* __restrict__ cand_src, double* __restrict__ cand_d) {
+    int dim, int c, int n, const CacheState* __restrict__ st, double tau, int cosine, int cap,
+    int* __restrict__ cand_cnt, int* __restrict__ cand_src, double* __restrict__ cand_d) {
   const int i = blockIdx.x;
   if (i >= n) return;
   __shared__ int count;
@@ -85,14 +111,16 @@ __global__ __launch_bounds__(256) void probe_candidates_kernel(
   const float qn = srcnrm[c + i];
   const float* row = D32 + long(i) * ldD;
   for (int s = threadIdx.x; s < size0; s += blockDim.x) {
-    if (row[s] + qn <= prefilter_bound(tau, qn, srcnrm[s])) {
+    const float sn = srcnrm[s];
+    if (probe_value(row[s], qn, sn, cosine) <= prefilter_bound(tau, qn, sn, dim, cosine)) {
       const int pos = atomicAdd(&count, 1);
       if (pos < cap) list[pos] = s;
     }
   }
   for (int j = threadIdx.x; j < i; j += blockDim.x) {
     const int s = c + j;
-    if (row[s] + qn <= prefilter_bound(tau, qn, srcnrm[s])) {
+    const float sn = srcnrm[s];
+    if (probe_value(row[s], qn, sn, cosine) <= prefilter_bound(tau, qn, sn, dim, cosine)) {
       const int pos = atomicAdd(&count, 1);
       if (pos < cap) list[pos] = s;
     }
@@ -105,7 +133,7 @@ __global__ __launch_bounds__(256) void probe_candidates_kernel(
   const int m = cnt < cap ? cnt : cap;
   for (int p = wib; p < m; p += 4) {
     const int s = list[p];
-    const double d = wave_dist64(q, srcs + long(s) * dim, dim, lane);
+    const double d = wave_keydist64(q, srcs + long(s) * dim, dim, lane, cosine);
     if (lane == 0) {
       cand_src[long(i) * cap + p] = s;
       cand_d[long(i) * cap + p] = d;
@@ -156,7 +184,7 @@ __device__ __forceinline__ void best_wave_reduce(ResolverBest& b) {
 }
 
 __global__ __launch_bounds__(64) void resolver_kernel(
-    int n, int c, int dim, int policy_lru, long long base_seq, double tau, CacheState* __restrict__ st,
+    int n, int c, int dim, int policy_lru, long long base_seq, double tau, int cosine, CacheState* __restrict__ st,
     long long* slot_seq, int* slot_next, int* slot_prev, const int* __restrict__ cand_cnt,
     const int* __restrict__ cand_src, const double* __restrict__ cand_d, int cap, const float* __restrict__ D32,
     long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm, uint8_t* __restrict__ hit_out,
@@ -198,7 +226,7 @@ __global__ __launch_bounds__(64) void resolver_kernel(
       for (int t = lane; t < size; t += 64) {
         const long long sq = slot_seq[t];
         const int s = sq >= base_seq ? c + int(sq - base_seq) : t;
-        mn = fminf(mn, row[s] + qn);
+        mn = fminf(mn, probe_value(row[s], qn, srcnrm[s], cosine));
         snmax = fmaxf(snmax, srcnrm[s]);
       }
 #pragma unroll
@@ -206,8 +234,9 @@ __global__ __launch_bounds__(64) void resolver_kernel(
         mn = fminf(mn, __shfl_xor(mn, m, kWave));
         snmax = fmaxf(snmax, __shfl_xor(snmax, m, kWave));
       }
-      const float slack = 2e-4f * (qn + snmax);
-      if (mn <= prefilter_bound(tau, qn, snmax) + slack) {
+      // twice the error bound of a probe value: a source beyond minimum + slack cannot be the nearest
+      const float slack = dense_slack(qn, snmax, dim, cosine);
+      if (mn <= prefilter_bound(tau, qn, snmax, dim, cosine) + slack) {
         const float near = mn + slack;
         for (int t0 = 0; t0 < size; t0 += 64) {
           const int t = t0 + lane;
@@ -217,7 +246,7 @@ __global__ __launch_bounds__(64) void resolver_kernel(
           if (t < size) {
             sq = slot_seq[t];
             s = sq >= base_seq ? c + int(sq - base_seq) : t;
-            is_near = row[s] + qn <= near;
+            is_near = probe_value(row[s], qn, srcnrm[s], cosine) <= near;
           }
           unsigned long long mask = __ballot(is_near);
           while (mask) {
@@ -225,7 +254,7 @@ __global__ __launch_bounds__(64) void resolver_kernel(
             mask &= mask - 1;
             const int sb = __shfl(s, b, kWave);
             const long long sqb = __shfl(sq, b, kWave);
-            const double d = wave_dist64(srcs + long(c + i) * dim, srcs + long(sb) * dim, dim, lane);
+            const double d = wave_keydist64(srcs + long(c + i) * dim, srcs + long(sb) * dim, dim, lane, cosine);
             if (d <= tau) best_take(best, d, sqb, sb);
           }
         }
@@ -407,8 +436,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, int c, int k, int 
 // Calls with a handful of rows (n <= kSmallRows): the whole cache side in two launches of
 // this kernel.
 //
-// phase == 1, a grid of blocks: Euclidean distance from every row of the call to every
-// resident key, directly in float64 (direct-difference form, one wave per key):
+// phase == 1, a grid of blocks: distance (Euclidean, or cosine when `cosine` is set) from every row of
+// the call to every resident key, directly in float64 (one wave per key):
 // with so few rows there is nothing to pre-filter.  D64[i * c + s].
 // phase == 2, one block: rows in order, exactly as resolver_kernel does -- nearest live
 // source within tau (ties: smaller seq) is a hit, otherwise evict/insert -- with distances
@@ -423,7 +452,8 @@ constexpr int kSmallRows = 4;
 
 __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
     const float* __restrict__ queries, int n, int c, int dim, int k, int K, int policy_lru, long long base_seq,
-    double tau, CacheState* st, long long* slot_seq, int* slot_next, int* slot_prev, float* srcs, float* srcnrm,
+    double tau, int cosine, CacheState* st, long long* slot_seq, int* slot_next, int* slot_prev, float* srcs,
+    float* srcnrm,
     const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, const void* __restrict__ X,
     int corpus_kind, double* D64, int phase,
     uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
@@ -448,9 +478,9 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
     // 16 bytes per lane, two steps of the key and of every row issued before anything is used
     const float4* key = reinterpret_cast<const float4*>(srcs + long(s) * dim);
     const int n_vec = dim / 4;
-    double acc[kSmallRows];
+    double acc[kSmallRows], qq[kSmallRows], kk = 0.0;   // cosine: inner products and the squared lengths
 #pragma unroll
-    for (int i = 0; i < kSmallRows; ++i) acc[i] = 0.0;
+    for (int i = 0; i < kSmallRows; ++i) acc[i] = qq[i] = 0.0;
     for (int iv0 = lane; iv0 < n_vec; iv0 += 128) {
       const bool two = iv0 + 64 < n_vec;
       float4 kv[2], qv[2][kSmallRows];
@@ -465,19 +495,30 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
 #pragma unroll
       for (int st = 0; st < 2; ++st) {
         if (st == 1 && !two) break;
+        const double kx = double(kv[st].x), ky = double(kv[st].y), kz = double(kv[st].z), kw = double(kv[st].w);
+        if (cosine) kk += kx * kx + ky * ky + kz * kz + kw * kw;
 #pragma unroll
         for (int i = 0; i < kSmallRows; ++i)
           if (i < n) {
-            const double dx = double(qv[st][i].x) - double(kv[st].x), dy = double(qv[st][i].y) - double(kv[st].y);
-            const double dz = double(qv[st][i].z) - double(kv[st].z), dw = double(qv[st][i].w) - double(kv[st].w);
-            acc[i] += dx * dx + dy * dy + dz * dz + dw * dw;
+            const double qx = double(qv[st][i].x), qy = double(qv[st][i].y), qz = double(qv[st][i].z),
+                         qw = double(qv[st][i].w);
+            if (cosine) {
+              // (each sum takes its four products in the same order, so identical vectors give identical sums)
+              acc[i] += qx * kx + qy * ky + qz * kz + qw * kw;
+              qq[i] += qx * qx + qy * qy + qz * qz + qw * qw;
+            } else {
+              const double dx = qx - kx, dy = qy - ky, dz = qz - kz, dw = qw - kw;
+              acc[i] += dx * dx + dy * dy + dz * dz + dw * dw;
+            }
           }
       }
     }
+    if (cosine) kk = wave_sum(kk);
 #pragma unroll
     for (int i = 0; i < kSmallRows; ++i)
       if (i < n) {
-        const double d = sqrt(wave_sum(acc[i]));
+        const double total = wave_sum(acc[i]);
+        const double d = cosine ? 1.0 - total / sqrt(wave_sum(qq[i]) * kk) : sqrt(total);
         if (lane == 0) D64[long(i) * c + s] = d;
       }
   }
@@ -491,7 +532,7 @@ __global__ __launch_bounds__(1024) void probe_resolve_small_kernel(
   for (int i = 0; i < n; ++i) {
     // distances to earlier rows of this call (at most three), one wave each
     if (wib < i) {
-      const double d = wave_dist64(queries + long(i) * dim, queries + long(wib) * dim, dim, lane);
+      const double d = wave_keydist64(queries + long(i) * dim, queries + long(wib) * dim, dim, lane, cosine);
       if (lane == 0) pair_d[wib] = d;
     }
     __syncthreads();

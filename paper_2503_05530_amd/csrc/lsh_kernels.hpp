@@ -125,7 +125,7 @@ __global__ __launch_bounds__(1024) void lsh_group_kernel(const int* __restrict__
 // One block per distinct code of the regrouped batch (blocks beyond *n_segs return at once);
 // the block walks that bucket's rows in order.
 //
-// Per row: float64 distance to each live key of the bucket, nearest key (ties: smaller seq),
+// Per row: float64 distance (Euclidean, or cosine when `cosine` is set) to each live key of the bucket, nearest key (ties: smaller seq),
 // hit if within tau (LRU: the key moves to the back of the bucket's order); otherwise the row
 // takes the bucket's next free slot or evicts the front of its order, and its vector is written
 // into the slot.  Outputs per row as resolver_kernel: hit flag, answering source (slot, or
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(1024) void lsh_group_kernel(const int* __restrict__
 constexpr int kLshThreads = 1024;
 __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
     const uint32_t* __restrict__ sorted, const int* __restrict__ seg_start, const int* __restrict__ n_segs, int n,
-    int b, int c_total, int dim, int policy_lru, long long base_seq, double tau, int keys_in_lds,
+    int b, int c_total, int dim, int policy_lru, long long base_seq, double tau, int cosine, int keys_in_lds,
     const float* batch_rows, float* srcs, long long* slot_seq, int* slot_next,
     int* slot_prev, int* bkt_size, int* bkt_head, int* bkt_tail, CacheState* st, uint8_t* __restrict__ hit_out,
     int* __restrict__ src_out, int* __restrict__ row_slot) {
@@ -223,13 +223,23 @@ __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
 
     for (int s = wib; s < size; s += kLshThreads / 64) {
       const float* key = keys_in_lds ? lkeys + s * dim : bucket_keys + long(s) * dim;
-      double acc = 0.0;
+      // Euclidean: direct-difference form; cosine: 1 - q.k / sqrt((q.q)(k.k)), the three sums over the same
+      // elements in the same order (so a key equal to the query is at distance exactly 0)
+      double acc = 0.0, qq = 0.0, kk = 0.0;
       for (int x = lane; x < dim; x += 64) {
-        const double diff = double(lq[x]) - double(key[x]);
-        acc += diff * diff;
+        const double qv = double(lq[x]), kv = double(key[x]);
+        if (cosine) {
+          acc += qv * kv;
+          qq += qv * qv;
+          kk += kv * kv;
+        } else {
+          const double diff = qv - kv;
+          acc += diff * diff;
+        }
       }
       acc = wave_sum(acc);
-      if (lane == 0) d64[s] = sqrt(acc);
+      if (cosine) acc = 1.0 - acc / sqrt(wave_sum(qq) * wave_sum(kk));
+      if (lane == 0) d64[s] = cosine ? acc : sqrt(acc);
     }
     row_barrier();
     if (tid < 64) {
@@ -333,7 +343,7 @@ __global__ __launch_bounds__(kLshThreads) void lsh_resolve_kernel(
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void lsh_small_kernel(
     const float* __restrict__ queries, int n, int b, int c_total, int dim, int k, int K, int n_bits,
-    const float* __restrict__ planes, int policy_lru, long long base_seq, double tau, float* srcs,
+    const float* __restrict__ planes, int policy_lru, long long base_seq, double tau, int cosine, float* srcs,
     long long* slot_seq, int* slot_next, int* slot_prev, int* bkt_size, int* bkt_head, int* bkt_tail, CacheState* st,
     const int64_t* __restrict__ val_ids, const float* __restrict__ val_d, const void* __restrict__ X,
     int corpus_kind, uint8_t* hit_out, int* src_out, int* row_slot, int* __restrict__ miss_list,
@@ -362,7 +372,8 @@ __global__ __launch_bounds__(1024) void lsh_small_kernel(
     const int slot0 = code * b;
     float* bucket_keys = srcs + long(slot0) * dim;
     const int size = bkt_size[code];
-    block_candidate_distances<kDtypeF32, 16>(keys, size, q, bucket_keys, dim, d64, cid, tid, kMetricL2);
+    block_candidate_distances<kDtypeF32, 16>(keys, size, q, bucket_keys, dim, d64, cid, tid,
+                                             cosine ? kMetricCosine : kMetricL2);
     __syncthreads();
     if (tid < 64) {
       ResolverBest best{__longlong_as_double(0x7ff0000000000000ll), 0x7fffffffffffffffll, -1};

@@ -30,6 +30,7 @@
 #include "resolver_lds.hpp"
 #include "scan_kernels.hpp"
 #include "select_kernels.hpp"
+#include "slack_kernels.hpp"
 
 using namespace prox;
 
@@ -100,6 +101,8 @@ struct proximity {
   int scan_blocks = 1;           // blocks that share the corpus in the batched scan
   int64_t* res_ids = nullptr;
   float* res_d = nullptr;
+  SlackState* slack = nullptr;   // is the float32 candidate list long enough? (select_kernels.hpp)
+  RedoBuffers redo{};            // queries noted for the second ranking of the batched scan, and their rows
 
   // cache side
   float* srcs = nullptr;     // [capacity + max_batch][dim]: slot keys, then the current batch
@@ -370,11 +373,11 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
           if (bf16)
             select_finish_small_kernel<kDtypeBF16, kSelE, kSelThreads><<<grid, dim3(kSelThreads), 0, s>>>(
                 h->S, h->ldS, N, kp, k, k_out, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
-                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d, metric);
+                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d, metric, h->slack);
           else
             select_finish_small_kernel<kDtypeF32, kSelE, kSelThreads><<<grid, dim3(kSelThreads), 0, s>>>(
                 h->S, h->ldS, N, kp, k, k_out, h->pairs[0], g1, phase, h->cfg.corpus, dim, Qbase, qlist,
-                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d, metric);
+                m_count_ptr, m_limit, m0, *small_routing, res_ids, res_d, metric, h->slack);
         }
       } else {
         select_kernel<true, kSelE><<<dim3(g1, mq), dim3(kSelThreads), 0, s>>>(
@@ -417,12 +420,27 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     cur = enqueue_merge_levels(h, cur, long(G) * kp, kp, m_count_ptr, m_limit, s, kRerankMergeKeys, &left);
   }
   const int n_lists = int(left / kp);
-  if (bf16)
-    rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase,
-                                                                     qlist, m_count_ptr, m_limit, res_ids, res_d, metric);
-  else
-    rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase,
-                                                                    qlist, m_count_ptr, m_limit, res_ids, res_d, metric);
+  // float64 ranking of the candidates, then -- for queries whose list could not be proven long enough, which
+  // the ranking notes on the device -- a second ranking from a rescan; its two launches return at once otherwise
+  long rg = (N + 3) / 4;
+  if (rg > long(h->n_cu) * 8) rg = long(h->n_cu) * 8;
+  if (bf16) {
+    rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
+        h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr, m_limit, res_ids, res_d, metric,
+        h->slack, h->redo);
+    redo_collect_kernel<kDtypeBF16><<<dim3((unsigned)rg), dim3(256), 0, s>>>(h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist,
+                                                                             h->slack, h->redo, cosine);
+    redo_rank_kernel<kDtypeBF16><<<dim3(m_limit), dim3(1024), 0, s>>>(h->cfg.corpus, dim, Qbase, qlist, h->slack,
+                                                                      h->redo, k, res_ids, res_d, metric);
+  } else {
+    rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
+        h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr, m_limit, res_ids, res_d, metric,
+        h->slack, h->redo);
+    redo_collect_kernel<kDtypeF32><<<dim3((unsigned)rg), dim3(256), 0, s>>>(h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist,
+                                                                            h->slack, h->redo, cosine);
+    redo_rank_kernel<kDtypeF32><<<dim3(m_limit), dim3(1024), 0, s>>>(h->cfg.corpus, dim, Qbase, qlist, h->slack,
+                                                                     h->redo, k, res_ids, res_d, metric);
+  }
   return PROXIMITY_OK;
 }
 
@@ -448,6 +466,12 @@ int validate_call(proximity* h, const float* queries, uint32_t n, uint32_t k, in
 extern "C" {
 
 uint32_t proximity_abi_version(void) { return PROXIMITY_ABI_VERSION; }
+
+double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_length, double max_row_length) {
+  if (metric > PROXIMITY_METRIC_COSINE || dim == 0 || !(query_length >= 0.0) || !(max_row_length >= 0.0))
+    return std::nan("");
+  return score_error_bound(int(metric), int(dim), query_length, max_row_length);
+}
 
 const char* proximity_last_error(const proximity_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
 
@@ -546,6 +570,13 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   TRY_ALLOC(h->pairs[1], size_t(h->pairs_elems), false);
   TRY_ALLOC(h->res_ids, B * k, true);
   TRY_ALLOC(h->res_d, B * k, true);
+  TRY_ALLOC(h->slack, 1, true);
+  if (N > 0) {
+    TRY_ALLOC(h->redo.list, B, true);
+    TRY_ALLOC(h->redo.thr, B, true);
+    TRY_ALLOC(h->redo.cnt, B, true);
+    TRY_ALLOC(h->redo.wide, B * size_t(kWideCap), false);
+  }
   TRY_ALLOC(h->srcs, (c + B) * d, true);
   TRY_ALLOC(h->srcnrm, c + B, true);
   TRY_ALLOC(h->val_ids, c * k, true);
@@ -607,6 +638,11 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
       launch_row_norms<kDtypeBF16>(h, cfg->corpus, long(N), int(d), h->xnrm, nullptr);
     else
       launch_row_norms<kDtypeF32>(h, cfg->corpus, long(N), int(d), h->xnrm, nullptr);
+    {  // the largest row length, for the error bound of the float32 scores
+      long g = (long(N) + 255) / 256;
+      if (g > long(h->n_cu) * 8) g = long(h->n_cu) * 8;
+      max_norm_kernel<<<dim3((unsigned)g), dim3(256)>>>(h->xnrm, long(N), h->slack);
+    }
     if (cfg->metric != PROXIMITY_METRIC_L2) {
       long g = (long(N) + 255) / 256;
       if (g > long(h->n_cu) * 8) g = long(h->n_cu) * 8;
@@ -665,19 +701,12 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   const long long base_seq = (long long)h->next_seq;
   float* batch_rows = h->srcs + size_t(c) * dim;
   const int xkind = corpus_kind(int(h->cfg.corpus_dtype), int(h->cfg.metric));
-  // The cache compares query and key.  Euclidean index, and inner-product index (whose cache falls
-  // back to the Euclidean distance): as given.  Cosine index: the rows are scaled to unit length
-  // first (so are the keys they become); between unit vectors the cosine distance is half the
-  // squared Euclidean distance, so "cosine distance <= tau" is "Euclidean distance <= sqrt(2 tau)"
-  // and the whole cache side runs unchanged on the scaled rows.
-  double tau_key = double(tau);
-  bool rows_in_place = false;
-  if (h->cfg.metric == PROXIMITY_METRIC_COSINE) {
-    unit_rows_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(queries, nn, dim, batch_rows);
-    queries = batch_rows;
-    rows_in_place = true;
-    tau_key = std::sqrt(2.0 * double(tau));
-  }
+  // The cache compares query and key by the index's own distance (Section 3.1), in float64 on the vectors as
+  // the caller gave them: Euclidean for the Euclidean index and for the inner-product index (whose negated
+  // inner product is no distance between two queries), cosine distance for the cosine index.  tau is in
+  // that distance's units.
+  const double tau_key = double(tau);
+  const int cos_keys = h->cfg.metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
 
   const int K = h->K;
   if (nn <= kSmallRows && h->cfg.n_docs > 0 && !lsh) {
@@ -687,8 +716,8 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     const int grid = c > 0 ? ((c + 15) / 16 < h->n_cu ? (c + 15) / 16 : h->n_cu) : 1;
     for (int phase = 1; phase <= 2; ++phase) {
       probe_resolve_small_kernel<<<dim3(phase == 2 ? 1 : grid), dim3(1024), 0, s>>>(
-          queries, nn, c, dim, kk, K, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, h->state,
-          h->slot_seq, h->slot_next, h->slot_prev, h->srcs, h->srcnrm, h->val_ids, h->val_d, h->cfg.corpus,
+          queries, nn, c, dim, kk, K, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, cos_keys,
+          h->state, h->slot_seq, h->slot_next, h->slot_prev, h->srcs, h->srcnrm, h->val_ids, h->val_d, h->cfg.corpus,
           xkind, h->D64, phase, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids,
           out_dists);
     }
@@ -705,7 +734,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     // selection and routing launches as for the flat cache.
     lsh_small_kernel<<<dim3(1), dim3(1024), 0, s>>>(
         queries, nn, int(h->cfg.capacity), c, dim, kk, K, h->lsh_bits, h->lsh_planes,
-        h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, h->srcs, h->slot_seq, h->slot_next,
+        h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, cos_keys, h->srcs, h->slot_seq, h->slot_next,
         h->slot_prev, h->bkt_size, h->bkt_head, h->bkt_tail, h->state, h->val_ids, h->val_d, h->cfg.corpus,
         xkind, out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, out_ids, out_dists);
     const SmallRouting rt{out_hit, h->src, h->row_slot, h->slot_seq, h->val_ids, h->val_d, base_seq, nn, c};
@@ -716,7 +745,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     return check_launch(h, "proximity_search_batch");
   }
 
-  if (!rows_in_place && lsh)
+  if (lsh)
     HIP_TRY(h, hipMemcpyAsync(batch_rows, queries, size_t(n) * dim * sizeof(float), hipMemcpyDeviceToDevice, s));
   if (lsh) {
     // Section 3.2: codes, regrouping by code, one block per bucket that occurs, miss list in row order
@@ -729,16 +758,14 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     const size_t row_bytes = size_t(dim) * sizeof(float);
     const int keys_in_lds = (size_t(b) + 1) * row_bytes <= kLshLdsMax ? 1 : 0;
     lsh_resolve_kernel<<<dim3(max_segs), dim3(kLshThreads), (keys_in_lds ? size_t(b) + 1 : 1) * row_bytes, s>>>(
-        h->lsh_sorted, h->lsh_seg_start, h->lsh_n_segs, nn, b, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, keys_in_lds,
+        h->lsh_sorted, h->lsh_seg_start, h->lsh_n_segs, nn, b, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, cos_keys, keys_in_lds,
         batch_rows,
         h->srcs, h->slot_seq, h->slot_next, h->slot_prev, h->bkt_size, h->bkt_head, h->bkt_tail, h->state, out_hit,
         h->src, h->row_slot);
     lsh_miss_list_kernel<<<dim3(1), dim3(1024), 0, s>>>(out_hit, nn, h->miss_list, h->miss_count, h->state);
   } else {
-  if (rows_in_place)
-    launch_row_norms<kDtypeF32>(h, batch_rows, nn, dim, h->srcnrm + c, s);
-  else  // the rows into the batch buffer and their norms, in one launch
-    copy_rows_norms_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(queries, nn, dim, batch_rows, h->srcnrm + c);
+  // the rows into the batch buffer and their norms, in one launch
+  copy_rows_norms_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(queries, nn, dim, batch_rows, h->srcnrm + c);
   int have_probe = 0;
   if (c > 0) {
     have_probe = 1;
@@ -755,7 +782,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
           h->srcs, h->srcnrm, c + nn, batch_rows, nn, dim, h->D32, h->ldD);
     }
     probe_candidates_kernel<<<dim3(nn), dim3(256), 0, s>>>(h->D32, h->ldD, h->srcs, h->srcnrm, dim, c, nn, h->state,
-                                                           tau_key, kCandCap, h->cand_cnt, h->cand_src,
+                                                           tau_key, cos_keys, kCandCap, h->cand_cnt, h->cand_src,
                                                            h->cand_d);
   }
   // the sequential resolver: with its state in LDS whenever that fits
@@ -764,12 +791,12 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   const bool few_rows = long(nn) * 600 < long(c);
   if (have_probe && !few_rows && resolver_lds_fits(size_t(c), size_t(nn), kResolverLdsMax)) {
     resolver_lds_kernel<<<dim3(1), dim3(kResolverThreads), resolver_lds_bytes(size_t(c), size_t(nn)), s>>>(
-        nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, h->state, h->slot_seq,
+        nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, cos_keys, h->state, h->slot_seq,
         h->slot_next, h->slot_prev, h->cand_cnt, h->cand_src, h->cand_d, kCandCap, h->D32, h->ldD, h->srcs, h->srcnrm,
         out_hit, h->src, h->row_slot, h->miss_list, h->miss_count);
   } else {
     resolver_kernel<<<dim3(1), dim3(64), 0, s>>>(nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq,
-                                                 tau_key, h->state, h->slot_seq, h->slot_next, h->slot_prev,
+                                                 tau_key, cos_keys, h->state, h->slot_seq, h->slot_next, h->slot_prev,
                                                  have_probe ? h->cand_cnt : nullptr, h->cand_src, h->cand_d, kCandCap,
                                                  h->D32, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot,
                                                  h->miss_list, h->miss_count);
@@ -806,6 +833,10 @@ int proximity_stats(const proximity_t* h, proximity_stats_t* out) {
   out->size = uint64_t(st.size);
   out->inbatch_hits = st.inbatch_hits;
   out->dense_resolves = st.dense_resolves;
+  SlackState sl;
+  HIP_TRY(hh, hipMemcpy(&sl, h->slack, sizeof sl, hipMemcpyDeviceToHost));
+  out->slack_exhausted = sl.exhausted;
+  out->slack_unresolved = sl.unresolved;
   return PROXIMITY_OK;
 }
 
@@ -865,6 +896,7 @@ int proximity_clear(proximity_t* h) {
     HIP_TRY(h, hipMemset(h->bkt_head, 0xff, nb * sizeof(int)));
     HIP_TRY(h, hipMemset(h->bkt_tail, 0xff, nb * sizeof(int)));
   }
+  HIP_TRY(h, hipMemset(&h->slack->exhausted, 0, 2 * sizeof(unsigned long long)));
   h->next_seq = 0;
   return PROXIMITY_OK;
 }

@@ -94,7 +94,7 @@ __device__ __forceinline__ int block_exclusive_sum(int mine, int* wave_total, in
 }
 
 __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
-    int n, int c, int dim, int policy_lru, long long base_seq, double tau, CacheState* __restrict__ st,
+    int n, int c, int dim, int policy_lru, long long base_seq, double tau, int cosine, CacheState* __restrict__ st,
     long long* slot_seq, int* slot_next, int* slot_prev, const int* __restrict__ cand_cnt,
     const int* __restrict__ cand_src, const double* __restrict__ cand_d, int cap, const float* __restrict__ D32,
     long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm, uint8_t* __restrict__ hit_out,
@@ -369,7 +369,7 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
           float mn = 3.4e38f, snmax = 0.f;
           for (int t = lane; t < size; t += 64) {
             const int s = lrow[t] >= 0 ? c + lrow[t] : t;
-            mn = fminf(mn, row[s] + qn);
+            mn = fminf(mn, probe_value(row[s], qn, srcnrm[s], cosine));
             snmax = fmaxf(snmax, srcnrm[s]);
           }
 #pragma unroll
@@ -377,8 +377,8 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
             mn = fminf(mn, __shfl_xor(mn, mm, kWave));
             snmax = fmaxf(snmax, __shfl_xor(snmax, mm, kWave));
           }
-          const float slack = 2e-4f * (qn + snmax);
-          if (mn <= prefilter_bound(tau, qn, snmax) + slack) {
+          const float slack = dense_slack(qn, snmax, dim, cosine);
+          if (mn <= prefilter_bound(tau, qn, snmax, dim, cosine) + slack) {
             const float near = mn + slack;
             for (int t0 = 0; t0 < size; t0 += 64) {
               const int t = t0 + lane;
@@ -386,7 +386,7 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
               bool is_near = false;
               if (t < size) {
                 s = lrow[t] >= 0 ? c + lrow[t] : t;
-                is_near = row[s] + qn <= near;
+                is_near = probe_value(row[s], qn, srcnrm[s], cosine) <= near;
               }
               unsigned long long mask = __ballot(is_near);
               while (mask) {
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
                 mask &= mask - 1;
                 const int sb = __shfl(s, b, kWave);
                 const long long sqb = sb < c ? slot_seq[sb] : base_seq + (sb - c);
-                const double d = wave_dist64(srcs + long(c + i) * dim, srcs + long(sb) * dim, dim, lane);
+                const double d = wave_keydist64(srcs + long(c + i) * dim, srcs + long(sb) * dim, dim, lane, cosine);
                 if (d <= tau) best_take(best, d, sqb, sb);
               }
             }

@@ -276,18 +276,4 @@ __global__ __launch_bounds__(256) void row_terms_kernel(float* __restrict__ nrm,
     nrm[r] = cosine ? 1.f / sqrtf(nrm[r]) : 0.f;
 }
 
-// Rows scaled to unit length (float64 sum of squares, one rounding per element): what a cosine
-// index's cache works on.  One wave per row.
-__global__ __launch_bounds__(256) void unit_rows_kernel(const float* __restrict__ in, int n_rows, int dim,
-                                                        float* __restrict__ out) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= n_rows) return;
-  const float* src = in + long(row) * dim;
-  double acc = 0.0;
-  for (int i = lane; i < dim; i += 64) acc += double(src[i]) * double(src[i]);
-  const double scale = 1.0 / sqrt(wave_sum(acc));
-  for (int i = lane; i < dim; i += 64) out[long(row) * dim + i] = float(double(src[i]) * scale);
-}
-
 }  // namespace prox

@@ -97,7 +97,7 @@ __host__ __device__ constexpr int kind_metric(int kind) { return kind >> 4; }
 // Float64 distance from query q to each of the kp candidate rows named by `keys`, by the NW waves
 // of a block; four candidates per wave are in flight at once so that their row fetches overlap.
 // Euclidean: direct-difference form, sqrt(sum (q_i - x_i)^2); inner product: -(q.x); cosine:
-// 1 - q.x / (|q| |x|), all sums in float64.  d64[c] / cid[c] receive distance and id of candidate
+// 1 - q.x / sqrt((q.q)(x.x)), all sums in float64.  d64[c] / cid[c] receive distance and id of candidate
 // c (padding candidates: +inf and INT_MAX).  The caller synchronises afterwards.
 template <int DT, int NW>
 __device__ __forceinline__ void block_candidate_distances(const uint64_t* keys, int kp, const float* __restrict__ q,
@@ -182,7 +182,7 @@ __device__ __forceinline__ void block_candidate_distances(const uint64_t* keys, 
       } else if (metric == kMetricIP) {
         d = -total;
       } else {
-        d = 1.0 - total / (sqrt(wave_sum(xx[g])) * sqrt(qq));
+        d = 1.0 - total / sqrt(wave_sum(xx[g]) * qq);  // (one root over the product: exactly 0 for a row equal to q)
       }
       if (lane == 0 && c < kp) {
         d64[c] = id[g] >= 0 ? d : __longlong_as_double(0x7ff0000000000000ll);
@@ -194,9 +194,10 @@ __device__ __forceinline__ void block_candidate_distances(const uint64_t* keys, 
 
 // Ranks n (distance, id) pairs held in LDS by (distance, id) and writes the first k ids and
 // distances (id INT_MAX stands for "no document": id -1, distance +inf).  out_d may be null.
+// kth (LDS, may be null) receives the distance of rank k-1 when n >= k.
 __device__ __forceinline__ void block_write_ranked(const double* d64, const int* ids, int n, int k,
                                                    int64_t* __restrict__ out_ids, float* __restrict__ out_d, int tid,
-                                                   int nthreads) {
+                                                   int nthreads, double* kth = nullptr) {
   for (int c = tid; c < n; c += nthreads) {
     const double d = d64[c];
     const int id = ids[c];
@@ -210,6 +211,7 @@ __device__ __forceinline__ void block_write_ranked(const double* d64, const int*
       out_ids[rank] = id == 0x7fffffff ? -1ll : int64_t(id);
       if (out_d) out_d[rank] = float(d);
     }
+    if (kth && rank == k - 1) *kth = d;
   }
   for (int r = n + tid; r < k; r += nthreads) {  // fewer entries than k: pad
     out_ids[r] = -1ll;
@@ -249,8 +251,134 @@ __device__ __forceinline__ void block_rerank_stored_any(int kind, const int64_t*
     block_rerank_stored<kDtypeF32, NT>(stored, K, k, q, X, dim, out_ids, out_d, keys, d64, cid, tid, kind_metric(kind));
 }
 
+// ---------------------------------------------------------------------------
+// Is the float32 candidate list long enough?
+//
+// The scan ranks rows by float32 scores and hands the kp = k + slack best to the float64 ranking.  The
+// answer is the exact ranked list of Section 2.2 only if no row outside the list belongs to the true k
+// nearest.  A float32 score differs from the exact score of its row by at most E (below), every row
+// outside the list has a float32 score of at least W, the list's worst, and the k-th smallest exact score
+// inside the list, t_k, bounds the true k-th smallest from above.  So  W - E > t_k  proves the list
+// sufficient.  Where the proof fails (many rows within rounding error of the k-th, e.g. duplicated
+// documents) the query is ranked again from every row whose float32 score is at most t_k + E -- a set that
+// provably holds the true k nearest -- and counted in `exhausted`; if that set outgrows its buffer
+// (kWideCap rows) the query keeps the float64 ranking of its kp candidates and is counted in `unresolved`.
+//
+// E: a float32 inner product of dim terms, summed in any order, is within g |q| |x| of the exact one with
+// g = (terms + 2) 2^-24 (each product and each partial sum rounds once; the three-term bfloat16 split has
+// 3 dim exact products and a remainder below 2^-24 |q| per element); the squared length of a row carries
+// the same relative error; the final multiply-add rounds once more.  With X the largest row length:
+//   Euclidean      score = |x|^2 - 2 q.x          E = g (X^2 + 2 |q| X)
+//   inner product  score = -2 q.x                 E = g 2 |q| X
+//   cosine         score = -2 q.x / |x|           E = g 4 |q|     (the reciprocal length rounds as well)
+// ---------------------------------------------------------------------------
+constexpr int kWideCap = 2048;   // rows the second ranking of a query can hold
+
+struct SlackState {
+  unsigned xmax2_bits;      // largest squared row length of the corpus, as float bits (non-negative floats order as unsigned)
+  int redo_count;           // queries of the current call whose list could not be proven sufficient
+  int redo_ticket;          // blocks of the second ranking that have finished
+  int pad;
+  unsigned long long exhausted, unresolved;
+};
+// The queries noted for the second ranking of the batched scan, one entry per row a call can carry.
+struct RedoBuffers {
+  int* list;        // [max_batch] their positions in the call's miss list
+  float* thr;       // [max_batch] t_k + E of each, rounded up
+  int* cnt;         // [max_batch] rows collected for each; zero between calls
+  uint64_t* wide;   // [max_batch][kWideCap] the collected rows as packed (score, row) keys
+};
+
+__host__ __device__ inline double score_error_bound(int metric, int dim, double q_len, double x_max) {
+  const double g = (3.0 * double(dim) + 16.0) * 5.9604644775390625e-08;
+  if (metric == kMetricL2) return g * (x_max * x_max + 2.0 * q_len * x_max);
+  if (metric == kMetricIP) return g * 2.0 * q_len * x_max;
+  return g * 4.0 * q_len;
+}
+// the exact score that goes with a float64 distance (qq = |q|^2)
+__device__ __forceinline__ double score_of_distance(int metric, double d, double qq) {
+  if (metric == kMetricL2) return d * d - qq;
+  if (metric == kMetricIP) return 2.0 * d;
+  return 2.0 * (d - 1.0) * sqrt(qq);
+}
+
+// Block-uniform verdict on a sorted list of kp float32 candidates whose k-th smallest float64 distance is
+// kth_d: true when the list provably holds the k nearest rows.  *thr receives t_k + E (rounded up), the
+// score bound of the second ranking.  `red` is 2 doubles of LDS.  Ends with a barrier.
+__device__ __forceinline__ bool block_list_sufficient(const uint64_t* keys, int kp, double kth_d,
+                                                      const float* __restrict__ q, int dim, int metric,
+                                                      const SlackState* __restrict__ slack, double* red, float* thr,
+                                                      int tid) {
+  if (tid < 64) {
+    double qq = 0.0;
+    for (int x = tid; x < dim; x += 64) qq += double(q[x]) * double(q[x]);
+    qq = wave_sum(qq);
+    if (tid == 0) {
+      const uint64_t worst = keys[kp - 1];
+      bool ok = true;
+      float t = __uint_as_float(0x7f800000u);
+      if (key_id(worst) >= 0) {   // a padding entry means every row of the corpus is in the list
+        const double x_max = sqrt(double(__uint_as_float(slack->xmax2_bits)));
+        const double e = score_error_bound(metric, dim, sqrt(qq), x_max) * (1.0 + 1e-6);
+        const double t_k = score_of_distance(metric, kth_d, qq);
+        ok = double(key_score(worst)) - e > t_k;
+        t = __double2float_ru(t_k + e);
+      }
+      red[0] = ok ? 1.0 : 0.0;
+      *thr = t;
+    }
+  }
+  __syncthreads();
+  return red[0] != 0.0;
+}
+
+// The second ranking: exact k nearest among n candidate rows named by `keys` (LDS, any order, ids >= 0), by
+// float64 distance and index, 256 candidates at a time against a running best list.  Work arrays in LDS:
+// d64 / cid [256] for a chunk, best_d / best_id [2][256].  Result: ids (or -1) and distances of rank 0..k-1
+// through `emit(rank, id, distance)`.  All threads of the block call it; ends with a barrier.
+template <int DT, int NT, typename Emit>
+__device__ __forceinline__ void block_exact_topk_of_rows(const uint64_t* keys, int n, int k,
+                                                         const float* __restrict__ q, const void* __restrict__ X,
+                                                         int dim, int metric, double* d64, int* cid,
+                                                         double (*best_d)[256], int (*best_id)[256], int tid,
+                                                         Emit emit) {
+  const double kInf = __longlong_as_double(0x7ff0000000000000ll);
+  int nb = 0, cur = 0;   // entries of the running list, and which of the two buffers holds it
+  for (int c0 = 0; c0 < n; c0 += 256) {
+    const int nc = n - c0 < 256 ? n - c0 : 256;
+    block_candidate_distances<DT, NT / 64>(keys + c0, nc, q, X, dim, d64, cid, tid, metric);
+    __syncthreads();
+    // rank the union of the running list and the chunk; the best k go to the other buffer in rank order
+    const int total = nb + nc;
+    for (int e = tid; e < total; e += NT) {
+      const double d = e < nb ? best_d[cur][e] : d64[e - nb];
+      const int id = e < nb ? best_id[cur][e] : cid[e - nb];
+      int rank = 0;
+      for (int o = 0; o < total; ++o) {
+        const double od = o < nb ? best_d[cur][o] : d64[o - nb];
+        const int oid = o < nb ? best_id[cur][o] : cid[o - nb];
+        rank += (od < d || (od == d && oid < id) || (od == d && oid == id && o < e)) ? 1 : 0;
+      }
+      if (rank < k) {
+        best_d[cur ^ 1][rank] = d;
+        best_id[cur ^ 1][rank] = id;
+      }
+    }
+    __syncthreads();
+    nb = total < k ? total : k;
+    cur ^= 1;
+  }
+  for (int r = tid; r < k; r += NT) {
+    if (r < nb && best_id[cur][r] != 0x7fffffff)
+      emit(r, int64_t(best_id[cur][r]), best_d[cur][r]);
+    else
+      emit(r, -1ll, kInf);
+  }
+  __syncthreads();
+}
+
 // Fills result rows of the listed queries with "no document" (used when the
-// instance has no corpus): ids -1, distances +inf.
+// instance has no corpus): ids -1, distances +inf (res_dists may be null).
 __global__ void fill_empty_results_kernel(const int* __restrict__ qlist, const int* __restrict__ m_count_ptr,
                                           int m_limit, int k, int64_t* __restrict__ res_ids,
                                           float* __restrict__ res_dists) {
@@ -260,7 +388,7 @@ __global__ void fill_empty_results_kernel(const int* __restrict__ qlist, const i
   const int qrow = qlist ? qlist[m] : m;
   for (int i = threadIdx.x; i < k; i += blockDim.x) {
     res_ids[long(qrow) * k + i] = -1;
-    res_dists[long(qrow) * k + i] = __uint_as_float(0x7f800000u);
+    if (res_dists) res_dists[long(qrow) * k + i] = __uint_as_float(0x7f800000u);
   }
 }
 
@@ -351,7 +479,8 @@ __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ 
 // distance to the query in float64 (direct-difference form for the Euclidean distance; one wave per
 // candidate row, rows fetched concurrently), ranks them by
 // (distance, id) and writes the first k ids and distances to row `qrow` of the
-// result arrays.  Padding candidates (id -1) get distance +inf and id -1.
+// result arrays.  Padding candidates (id -1) get distance +inf and id -1.  Last it checks that the
+// list was long enough for the result to be exact (block_list_sufficient).
 constexpr int kRerankThreads = 1024;
 constexpr int kRerankMergeKeys = 2048;  // n_lists * kp may not exceed this
 template <int DT>
@@ -362,7 +491,8 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
                                                          const int* __restrict__ qlist,
                                                          const int* __restrict__ m_count_ptr, int m_limit,
                                                          int64_t* __restrict__ res_ids,
-                                                         float* __restrict__ res_dists, int metric) {
+                                                         float* __restrict__ res_dists, int metric,
+                                                         SlackState* __restrict__ slack, RedoBuffers redo) {
   const int m = blockIdx.x;
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   if (m >= m_total) return;
@@ -374,6 +504,8 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
   __shared__ uint64_t list[kRerankMergeKeys];
   __shared__ uint64_t mins[kRerankThreads / 64];
   __shared__ int count;
+  __shared__ double kth_d, red[2];
+  __shared__ float thr;
 
   const uint64_t* mine = cand + long(m) * n_lists * kp;
   if (n_lists > 1) {
@@ -384,7 +516,16 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
   block_candidate_distances<DT, kRerankThreads / 64>(mine, kp, q, X, dim, d64, ids, threadIdx.x, metric);
   __syncthreads();
   block_write_ranked(d64, ids, kp, k, res_ids + long(qrow) * k, res_dists + long(qrow) * k, threadIdx.x,
-                     kRerankThreads);
+                     kRerankThreads, &kth_d);
+  __syncthreads();
+  // Was the list long enough?  If that cannot be shown the query is noted for the second ranking
+  // (redo_collect_kernel / redo_rank_kernel), which overwrites this row of the result.
+  if (!block_list_sufficient(mine, kp, kth_d, q, dim, metric, slack, red, &thr, threadIdx.x) && threadIdx.x == 0) {
+    atomicAdd(&slack->exhausted, 1ull);
+    const int pos = atomicAdd(&slack->redo_count, 1);   // below the call's row count: one note per query
+    redo.list[pos] = m;
+    redo.thr[pos] = thr;
+  }
 }
 
 template <int DT, int E, int NT>
@@ -392,7 +533,7 @@ __global__ __launch_bounds__(NT) void select_finish_small_kernel(
     const float* __restrict__ S, long ldS, long len, int kp, int k, int k_out, uint64_t* __restrict__ lists,
     int n_seg, int phase, const void* __restrict__ X, int dim, const float* __restrict__ Qbase,
     const int* __restrict__ qlist, const int* __restrict__ m_count_ptr, int m_limit, int m_begin, SmallRouting rt,
-    int64_t* __restrict__ out_ids, float* __restrict__ out_d, int metric) {
+    int64_t* __restrict__ out_ids, float* __restrict__ out_d, int metric, SlackState* __restrict__ slack) {
   constexpr int SEG = E * NT;
   const int q = m_begin + blockIdx.y;   // position in the miss list; S rows are relative to m_begin
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
@@ -406,6 +547,10 @@ __global__ __launch_bounds__(NT) void select_finish_small_kernel(
   __shared__ int cid[256];
   __shared__ int64_t fin_ids[256];
   __shared__ float fin_d[256];
+  __shared__ double best_d[2][256];
+  __shared__ int best_id[2][256];
+  __shared__ double kth_d, red[2];
+  __shared__ float thr;
 
   if (phase != 2) {
   // ---- this block's segment of the dense scores -> kp sorted keys (as select_kernel<true>) ----
@@ -464,8 +609,39 @@ __global__ __launch_bounds__(NT) void select_finish_small_kernel(
       fin_ids[rank] = id == 0x7fffffff ? -1ll : int64_t(id);
       fin_d[rank] = float(d);
     }
+    if (rank == k - 1) kth_d = d;
   }
   __syncthreads();
+
+  // ---- was the list long enough?  If that cannot be shown, rank again from every row whose float32 score
+  // (still at hand: the dense score row) is at most t_k + E ----
+  if (!block_list_sufficient(list, kp, kth_d, qv, dim, metric, slack, red, &thr, tid)) {
+    if (tid == 0) {
+      atomicAdd(&slack->exhausted, 1ull);
+      count = 0;
+    }
+    __syncthreads();
+    const float bound_sc = thr;
+    for (long j = tid; j < len; j += NT) {
+      const float sc = S[long(blockIdx.y) * ldS + j];
+      if (sc <= bound_sc) {
+        const int pos = atomicAdd(&count, 1);
+        if (pos < kWideCap) list[pos] = pack_key(sc, uint32_t(j));
+      }
+    }
+    __syncthreads();
+    const int cnt = count;
+    if (cnt > kWideCap) {
+      if (tid == 0) atomicAdd(&slack->unresolved, 1ull);
+    } else {
+      block_exact_topk_of_rows<DT, NT>(list, cnt, k, qv, X, dim, metric, d64, cid, best_d, best_id, tid,
+                                       [&](int r, int64_t id, double d) {
+                                         fin_ids[r] = id;
+                                         fin_d[r] = float(d);
+                                       });
+    }
+    __syncthreads();
+  }
 
   // ---- routing (as finalize_kernel): k ranked entries are this query's result; the caller gets
   // the first k_out, the cache slot all k (k > k_out with a re-ranking factor, Section 3.3.4) ----

@@ -34,10 +34,12 @@ def assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref_queries, dist_rto
     float64 distances agree with the oracle's, position by position, to
     ID_TIE_RTOL.  Returned distances must be within dist_rtol.
     Returns the number of rows that needed the tie allowance.  `metric`: the index's distance
-    function; inner products and cosine distances can be close to zero, so for them the two
-    comparisons also allow 1e-6 absolute.
+    function.  A cosine distance is evaluated as 1 - c with c near 1 and a negated inner product as a sum
+    of terms of both signs, so a value near zero carries the absolute rounding error of its terms (a few
+    1e-16 times |q||x| in float64, 6e-8 of the value once stored as float32) however small it is: for these
+    two functions values are compared with an absolute allowance of 1e-12 beside the relative one.
     """
-    atol = 0 if metric == po.METRIC_L2 else 1e-6
+    atol = 0 if metric == po.METRIC_L2 else 1e-12
     assert ids.shape == o_ids.shape, what
     excused = 0
     bad_rows = np.flatnonzero((ids != o_ids).any(axis=1))
@@ -47,7 +49,7 @@ def assert_lists_match(ids, dists, o_ids, o_dists, corpus, ref_queries, dist_rto
         assert (valid == (o_ids[t] >= 0)).all(), f"{what} row {t}: padding differs"
         assert len(set(ids[t][valid].tolist())) == valid.sum(), f"{what} row {t}: duplicate ids"
         d_true = po.metric_distances(ref_queries[t], corpus[ids[t][valid]], metric)
-        np.testing.assert_allclose(d_true, o_dists[t][valid], rtol=ID_TIE_RTOL, atol=atol * ID_TIE_RTOL,
+        np.testing.assert_allclose(d_true, o_dists[t][valid], rtol=ID_TIE_RTOL, atol=atol,
                                    err_msg=f"{what} row {t}: ids differ beyond near-ties")
         excused += 1
     fin = np.isfinite(o_dists)

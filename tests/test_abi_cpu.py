@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol(binding):
 
 
 def test_abi_version_and_struct_layout(binding):
-    assert binding.proximity_abi_version() == 3
+    assert binding.proximity_abi_version() == 4
     assert C.sizeof(binding.ProximityConfig) == 72
     assert C.sizeof(binding.ProximityStats) == 128
     assert C.sizeof(binding.ProximityLaunch) == 16
@@ -86,3 +86,68 @@ def test_null_arguments(binding):
     n = C.c_uint32(0)
     assert b.lib.proximity_cache_dump(None, None, None, None, C.byref(n)) == b.ERR_INVALID_ARG
     b.lib.proximity_destroy(None)  # must be a no-op
+
+
+def test_build_flag_keeps_packed_float32_instructions_out_of_device_code(tmp_path):
+    """The library is compiled with a target-feature switch that stops the compiler from pairing float
+    operations into packed-float32 instructions.  The switch is live: the same two-float kernel compiles to a
+    packed instruction without it and to none with it."""
+    import subprocess
+    from paper_2503_05530_amd.build import NO_PACKED_FP32, HIPCC_FLAGS
+    assert all(f in HIPCC_FLAGS for f in NO_PACKED_FP32)
+    src = tmp_path / "two_floats.hip"
+    src.write_text("#include <hip/hip_runtime.h>\n"
+                   "__global__ void axpy2(const float2* __restrict__ x, float2* __restrict__ y, float a, int n) {\n"
+                   "  int i = blockIdx.x * blockDim.x + threadIdx.x;\n"
+                   "  if (i < n) { float2 v = x[i], w = y[i]; w.x = a * v.x + w.x; w.y = a * v.y + w.y; y[i] = w; }\n"
+                   "}\n")
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    packed = re.compile(r"\bv_pk_(add|mul|fma)_f32\b")
+    counts = {}
+    for name, extra in (("with", NO_PACKED_FP32), ("without", [])):
+        out = tmp_path / f"{name}.s"
+        subprocess.run([hipcc, "-O3", "--offload-arch=gfx950", "--cuda-device-only", "-S", "-o", str(out), str(src),
+                        *extra], check=True, capture_output=True)
+        counts[name] = len(packed.findall(out.read_text()))
+    assert counts["with"] == 0 and counts["without"] > 0, counts
+
+
+def test_score_error_bound_by_hand_and_against_float32_arithmetic(binding):
+    """The bound behind the exactness check of the index search: its closed form worked by hand, and that
+    float32 scores computed in several summation orders really stay within it of the float64 scores."""
+    import numpy as np
+    b = binding
+    E = b.lib.proximity_score_error_bound
+    u = 2.0 ** -24
+    # dim 768: g = (3 * 768 + 16) u = 2320 u
+    g = 2320 * u
+    assert E(0, 768, 1.0, 1.0) == pytest.approx(g * 3.0, rel=1e-15)
+    assert E(0, 768, 2.0, 0.5) == pytest.approx(g * (0.25 + 2.0), rel=1e-15)
+    assert E(1, 768, 2.0, 0.5) == pytest.approx(g * 2.0, rel=1e-15)
+    assert E(2, 768, 2.0, 123.0) == pytest.approx(g * 8.0, rel=1e-15)
+    assert E(0, 32, 1.0, 1.0) == pytest.approx(112 * u * 3.0, rel=1e-15)
+    for bad in ((3, 768, 1.0, 1.0), (0, 0, 1.0, 1.0), (0, 768, -1.0, 1.0), (0, 768, 1.0, float("nan"))):
+        assert np.isnan(E(*bad))
+    rng = np.random.default_rng(40)
+    for dim in (32, 768, 4096):
+        x = (rng.standard_normal((300, dim)) * rng.uniform(0.2, 4.0, (300, 1))).astype(np.float32)
+        q = (rng.standard_normal(dim) * 1.7).astype(np.float32)
+        x64, q64 = x.astype(np.float64), q.astype(np.float64)
+        x_max, q_len = np.sqrt((x64 * x64).sum(1)).max(), np.sqrt((q64 * q64).sum())
+        exact = {0: (x64 * x64).sum(1) - 2 * x64 @ q64, 1: -2 * x64 @ q64,
+                 2: -2 * (x64 @ q64) / np.sqrt((x64 * x64).sum(1))}
+        for order in ("forward", "reverse", "pairwise"):
+            if order == "pairwise":
+                dot = (x * q[None, :]).sum(1, dtype=np.float32)
+                nrm = (x * x).sum(1, dtype=np.float32)
+            else:
+                cols = range(dim) if order == "forward" else range(dim - 1, -1, -1)
+                dot, nrm = np.zeros(300, np.float32), np.zeros(300, np.float32)
+                for c in cols:
+                    dot = dot + x[:, c] * q[c]
+                    nrm = nrm + x[:, c] * x[:, c]
+            got = {0: nrm - np.float32(2) * dot, 1: np.float32(-2) * dot,
+                   2: np.float32(-2) * dot * (np.float32(1) / np.sqrt(nrm))}
+            for metric in (0, 1, 2):
+                err = np.abs(got[metric].astype(np.float64) - exact[metric]).max()
+                assert err <= E(metric, dim, q_len, x_max), (dim, order, metric, err)

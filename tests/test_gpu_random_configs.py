@@ -3,8 +3,8 @@
 how the stream is cut into calls), on streams that mix rewordings at several radii, exact repeats and fresh
 vectors, so that distances fall on both sides of the tolerance.  Seeds 0..79 use the Euclidean index, seeds
 from 80 on alternate between the inner-product and the cosine index on corpora whose rows have lengths
-0.3..3 (for cosine the queries get lengths 0.5..2 as well, and the tolerance becomes tau^2 / 2, the cosine
-distance of unit vectors tau apart)."""
+0.3..3 (for cosine the queries get other lengths as well, and the tolerance becomes tau^2 / 2, the cosine
+distance of unit vectors tau apart; tau = 0 included)."""
 import numpy as np
 import pytest
 import torch
@@ -46,10 +46,18 @@ def draw_case(seed):
         r0 += step
     metric = po.METRIC_L2 if seed < 80 else (po.METRIC_IP if seed % 2 == 0 else po.METRIC_COSINE)
     if metric == po.METRIC_COSINE:
-        q = (q * rng.uniform(0.5, 2.0, size=(n, 1))).astype(np.float32)
-        # a repeat is now the same direction at another length.  Exactly zero is not a usable tolerance here:
-        # in float64 the cosine distance of a vector to its own multiple is a few 1e-16 either side of zero
-        tau = min(1e9, max(tau * tau / 2.0, 1e-12))
+        tau = min(1e9, tau * tau / 2.0)
+        if tau == 0.0 or rng.random() < 0.5:
+            # lengths that are powers of two scale every term of the cosine distance exactly, so a repeat at
+            # another length is at distance exactly 0 on both sides and tau = 0 is the exact-match cache of
+            # Section 3.3.3 (bit-identical repeats, and their exact multiples, hit; nothing else does)
+            q = (q * rng.choice([0.5, 1.0, 2.0, 4.0], size=(n, 1))).astype(np.float32)
+        else:
+            # arbitrary lengths: a repeat is the same direction rounded to float32 at another length, whose
+            # cosine distance is a few 1e-16 either side of zero in any float64 evaluation -- a comparison
+            # of that with zero is rounding noise on both sides, so these streams keep tau above it
+            q = (q * rng.uniform(0.5, 2.0, size=(n, 1))).astype(np.float32)
+            tau = max(tau, 1e-12)
     return dict(dim=dim, k=k, rho=rho, n_docs=n_docs, bf16=bf16, lsh_bits=lsh_bits, capacity=capacity, policy=policy,
                 tau=tau, q=q, cuts=cuts, seed=seed, metric=metric)
 
