@@ -144,29 +144,31 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
             "mfma_dtype": "bf16 x3 split, f32 accumulate" if bf16x3 else "f32", **common}
 
 
-def recall_sweep(args, torch, np, W, Proximity, device):
-    """Hit rate and database k-recall as Section 4 defines it: the fraction of the k documents the cache
-    hands out that are among the k the index returns for the same query.  The index's own answers come from
-    the library's plain search (proximity_knn_batch); the overlap is counted with tensor operations here,
-    outside the method."""
-    w = W.WORKLOADS[args.workload]
-    batch = 64 if args.batch is None else args.batch
-    n_q = (args.steps if args.steps is not None else 200) * batch
-    corpus_dev = torch.from_numpy(W.corpus_for(w, args.n_docs)).to(device)
-    q_dev = torch.from_numpy(W.stream_for(w, n_q)).to(device)
+def k_recall_per_query(ids, truth):
+    """Database k-recall of Section 4, per query: the fraction of the k documents handed out (`ids`, [n][k]) that
+    are among the k the index itself returns for that query (`truth`, [n][k]).  Padding ids (-1) count as
+    documents that were not found.  Tensor arithmetic on whatever device the arguments live on."""
+    found = (ids[:, :, None] == truth[:, None, :]) & (ids[:, :, None] >= 0)
+    return found.any(dim=2).float().mean(dim=1)
+
+
+def recall_sweep_rows(torch, W, Proximity, device, w, corpus_dev, q_dev, batch, rho, lsh_bits, bucket_capacity, taus):
+    """Hit rate and database k-recall for every tolerance in `taus`, flat and bucketed cache, re-ranking factor 1
+    and `rho`.  The index's own answers come from the library's plain search (proximity_knn_batch); the overlap
+    is counted here, outside the method."""
+    n_q = q_dev.shape[0]
     truth = torch.empty((n_q, w.k), dtype=torch.int64, device=device)
     plain = Proximity(corpus_dev, w.dim, 0, w.k, w.policy, batch)
     for r0 in range(0, n_q, batch):
         plain.knn_batch(q_dev[r0:r0 + batch], out_ids=truth[r0:r0 + batch])
     plain.close()
     rows = []
-    bits = args.lsh_bits if args.lsh_bits > 0 else 4
-    planes = torch.from_numpy(W.lsh_planes(bits, w.dim, w.seed)).to(device)
-    caches = (("flat", w.capacity, None), (f"bucketed {1 << bits}x{args.bucket_capacity}", args.bucket_capacity, planes))
+    planes = torch.from_numpy(W.lsh_planes(lsh_bits, w.dim, w.seed)).to(device)
+    caches = (("flat", w.capacity, None), (f"bucketed {1 << lsh_bits}x{bucket_capacity}", bucket_capacity, planes))
     for name, cap, pl in caches:
-        for rho in sorted({1, args.rho}):
-            px = Proximity(corpus_dev, w.dim, cap, w.k, w.policy, batch, rerank_factor=rho, lsh_planes=pl)
-            for tau in (w.taus or (0.0, 0.1, 0.25, 0.5, 1.0)):
+        for r in sorted({1, rho}):
+            px = Proximity(corpus_dev, w.dim, cap, w.k, w.policy, batch, rerank_factor=r, lsh_planes=pl)
+            for tau in taus:
                 px.clear()
                 ids = torch.empty((n_q, w.k), dtype=torch.int64, device=device)
                 hit = torch.empty((n_q,), dtype=torch.uint8, device=device)
@@ -177,13 +179,28 @@ def recall_sweep(args, torch, np, W, Proximity, device):
                                     want_dists=False)
                 torch.cuda.synchronize(device)
                 dt = time.perf_counter() - t0
-                same = (ids[:, :, None] == truth[:, None, :]).any(dim=2).float().mean(dim=1)   # per query
+                same = k_recall_per_query(ids, truth)
                 hits = hit.bool()
-                rows.append({"cache": name, "rerank_factor": rho, "tau": tau, "hit_rate": round(float(hits.float().mean()), 4),
+                rows.append({"cache": name, "rerank_factor": r, "tau": tau,
+                             "hit_rate": round(float(hits.float().mean()), 4),
                              "k_recall": round(float(same.mean()), 4),
                              "k_recall_on_hits": round(float(same[hits].mean()), 4) if bool(hits.any()) else None,
                              "queries_per_s": round(n_q / dt, 1)})
             px.close()
+    return rows
+
+
+def recall_sweep(args, torch, np, W, Proximity, device):
+    """Hit rate and database k-recall as Section 4 defines it: the fraction of the k documents the cache
+    hands out that are among the k the index returns for the same query."""
+    w = W.WORKLOADS[args.workload]
+    batch = 64 if args.batch is None else args.batch
+    n_q = (args.steps if args.steps is not None else 200) * batch
+    corpus_dev = torch.from_numpy(W.corpus_for(w, args.n_docs)).to(device)
+    q_dev = torch.from_numpy(W.stream_for(w, n_q)).to(device)
+    bits = args.lsh_bits if args.lsh_bits > 0 else 4
+    rows = recall_sweep_rows(torch, W, Proximity, device, w, corpus_dev, q_dev, batch, args.rho, bits,
+                             args.bucket_capacity, w.taus or (0.0, 0.1, 0.25, 0.5, 1.0))
     print(json.dumps({"metric": "database_k_recall_sweep", "unit": "fraction", "n_gpus": 1, "data": "synthetic",
                       "config": {"workload": w.name, "queries": n_q, "batch": batch, "k": w.k}, "rows": rows}))
 
