@@ -75,6 +75,9 @@ enum { PROXIMITY_METRIC_L2 = 0, PROXIMITY_METRIC_IP = 1, PROXIMITY_METRIC_COSINE
 #define PROXIMITY_MAX_DIM 4096u
 #define PROXIMITY_MAX_BATCH 8192u
 #define PROXIMITY_MAX_CAPACITY (1u << 20)
+/* Limits of proximity_knn_static(), whose workspace is built into the library. */
+#define PROXIMITY_STATIC_MAX_DOCS (1u << 18)
+#define PROXIMITY_STATIC_MAX_QUERIES 4u
 
 typedef struct proximity proximity_t;
 
@@ -222,6 +225,42 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
  */
 int proximity_knn_batch(proximity_t* h, const float* queries, uint32_t n, uint32_t k,
                         int64_t* out_ids, float* out_dists, void* hip_stream);
+
+/*
+ * proximity_knn_batch() for callers that cannot allocate device memory at all -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc -- and so cannot call
+ * proximity_create() either.  No instance: the call takes the corpus itself, and the workspace the
+ * search needs (row terms, dense scores, per-segment candidate lists: 5.5 MiB) is an array that is part of
+ * the loaded library, of which every device holds one copy until the process ends.  The call performs no
+ * hipMalloc / hipFree and calls no allocating routine; it is asynchronous like the other search calls.
+ *
+ *   corpus        DEVICE [n_docs][dim], float32 or bfloat16 (corpus_dtype), 16-byte aligned; read only
+ *   n_docs        0..PROXIMITY_STATIC_MAX_DOCS; more is rejected with INVALID_ARG (the workspace has a
+ *                 fixed size: use an instance for larger corpora)
+ *   dim           multiple of 32, <= PROXIMITY_MAX_DIM
+ *   metric        PROXIMITY_METRIC_*
+ *   queries       DEVICE [n][dim] float32, 16-byte aligned
+ *   n             0..PROXIMITY_STATIC_MAX_QUERIES (more: BATCH_TOO_LARGE).  n = 0 enqueues nothing
+ *                 and only performs the set-up described below
+ *   k             1..PROXIMITY_MAX_K
+ *   out_ids       DEVICE [n][k] int64, out_dists DEVICE [n][k] float32 or NULL: as proximity_knn_batch
+ *   device        HIP device ordinal the pointers belong to
+ *   hip_stream    the hipStream_t to enqueue on (NULL = the default stream)
+ *
+ * Results are those of proximity_knn_batch() on an instance over the same corpus, bit for bit (the same
+ * kernels run; the squared row norms an instance computes once are recomputed by every call here).
+ * The first call on a device looks up the address of that device's copy of the workspace
+ * (hipGetSymbolAddress, no allocation); make that call (n = 0 suffices) before starting a graph capture.
+ * All calls on one device share that device's workspace, which keeps the last call's contents: every
+ * call overwrites what it reads, so nothing needs clearing, but two calls whose work overlaps on one
+ * device (different streams, or threads) race -- issue them on one stream, or order them with events.
+ * The exactness check behind proximity_stats_t.slack_exhausted runs here as well, but without an instance
+ * its counters are not reported.
+ * Errors: INVALID_ARG, BATCH_TOO_LARGE, HIP; text from proximity_last_error(NULL).
+ */
+int proximity_knn_static(const void* corpus, uint64_t n_docs, uint32_t dim, uint32_t corpus_dtype, uint32_t metric,
+                         const float* queries, uint32_t n, uint32_t k, int64_t* out_ids, float* out_dists,
+                         int32_t device, void* hip_stream);
 
 /* Copies the counters to *out (HOST).  Waits for the handle's last stream. */
 int proximity_stats(const proximity_t* h, proximity_stats_t* out);

@@ -22,6 +22,7 @@ POLICY_FIFO, POLICY_LRU = 0, 1
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
 ABI_VERSION = 4
 MAX_K, MAX_DIM, MAX_BATCH, MAX_CAPACITY = 240, 4096, 8192, 1 << 20   # PROXIMITY_MAX_* of the header
+STATIC_MAX_DOCS, STATIC_MAX_QUERIES = 1 << 18, 4                      # PROXIMITY_STATIC_MAX_* of the header
 
 
 class ProximityConfig(C.Structure):
@@ -65,6 +66,9 @@ lib.proximity_search_batch.argtypes = [_H, C.c_void_p, C.c_uint32, C.c_uint32, C
                                        C.c_void_p, C.c_void_p]
 lib.proximity_knn_batch.restype = C.c_int
 lib.proximity_knn_batch.argtypes = [_H, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+lib.proximity_knn_static.restype = C.c_int
+lib.proximity_knn_static.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint32,
+                                     C.c_uint32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
 lib.proximity_stats.restype = C.c_int
 lib.proximity_stats.argtypes = [_H, C.POINTER(ProximityStats)]
 lib.proximity_cache_dump.restype = C.c_int
@@ -77,7 +81,7 @@ lib.proximity_profile_stop.restype = C.c_int
 lib.proximity_profile_stop.argtypes = [_H, C.POINTER(ProximityLaunch), C.c_uint32, C.POINTER(C.c_uint32)]
 
 EXPORTED = ("proximity_abi_version", "proximity_score_error_bound", "proximity_last_error", "proximity_create", "proximity_destroy",
-            "proximity_search_batch", "proximity_knn_batch", "proximity_stats", "proximity_cache_dump",
+            "proximity_search_batch", "proximity_knn_batch", "proximity_knn_static", "proximity_stats", "proximity_cache_dump",
             "proximity_clear", "proximity_profile_start", "proximity_profile_stop")
 
 
@@ -98,6 +102,21 @@ def proximity_abi_version() -> int:
 
 def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def proximity_knn_static(corpus: torch.Tensor, queries: torch.Tensor, k: int, out_ids: torch.Tensor,
+                         out_dists: Optional[torch.Tensor] = None, metric: int = METRIC_L2,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
+    """The index search without an instance and without any allocation (proximity_knn_static): the caller
+    passes every buffer, outputs included."""
+    dtype = DTYPE_BF16 if corpus.dtype == torch.bfloat16 else DTYPE_F32
+    dev = corpus.device
+    s = torch.cuda.current_stream(dev) if stream is None else stream
+    rc = lib.proximity_knn_static(_ptr(corpus), corpus.shape[0], corpus.shape[1], dtype, int(metric), _ptr(queries),
+                                  queries.shape[0], int(k), _ptr(out_ids), _ptr(out_dists),
+                                  dev.index if dev.index is not None else 0, C.c_void_p(s.cuda_stream))
+    if rc != OK:
+        raise ProximityError(rc, last_error(None))
 
 
 class Proximity:

@@ -18,6 +18,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -55,6 +56,35 @@ static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is par
 static_assert(sizeof(proximity_launch_t) == 16, "proximity_launch_t layout is part of the ABI");
 
 thread_local std::string g_create_error;
+
+// ---- proximity_knn_static: workspace that is part of the loaded library, not of any allocation ----
+// Layout (all offsets multiples of 256 bytes): the state of the exactness check (1 KiB); row terms
+// [kStaticMaxDocs] float32; dense scores
+// [kStaticMaxQueries][kStaticMaxDocs] float32; per-segment top-k lists
+// [kStaticMaxQueries][kStaticMaxDocs / kSelSeg][256] packed keys.
+constexpr size_t kStaticMaxDocs = PROXIMITY_STATIC_MAX_DOCS;
+constexpr size_t kStaticMaxQueries = PROXIMITY_STATIC_MAX_QUERIES;
+static_assert(kStaticMaxQueries == size_t(kStreamMaxQueries), "the static search runs the streaming kernels");
+static_assert(kStaticMaxDocs % kSelSeg == 0 && kStaticMaxDocs % 64 == 0, "whole selection segments");
+constexpr size_t kStaticOffSlack = 0;   // SlackState (the largest row length, the counters of the exactness check)
+static_assert(sizeof(SlackState) <= 1024, "the state must fit the first KiB of the workspace");
+constexpr size_t kStaticOffNorms = 1024;
+constexpr size_t kStaticOffScores = kStaticOffNorms + kStaticMaxDocs * sizeof(float);
+constexpr size_t kStaticOffLists = kStaticOffScores + kStaticMaxQueries * kStaticMaxDocs * sizeof(float);
+constexpr size_t kStaticScratchBytes =
+    kStaticOffLists + kStaticMaxQueries * (kStaticMaxDocs / kSelSeg) * 256 * sizeof(uint64_t);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Every device holds its own copy of `scratch` at its own address.  In host code the array's name is
+// only a handle for hipGetSymbolAddress: the address a kernel may use is looked up once per device,
+// with that device current, and kept here.
+constexpr int kStaticMaxDevices = 64;
+struct StaticDevice {
+  unsigned char* ptr = nullptr;
+  int n_cu = 0;
+};
+StaticDevice g_static_dev[kStaticMaxDevices];
+std::mutex g_static_mutex;
 
 struct DeviceGuard {
   int prev = -1;
@@ -683,6 +713,104 @@ int proximity_knn_batch(proximity_t* h, const float* queries, uint32_t n, uint32
   if (h->prof_on) ++h->prof_call;
   if (rc != PROXIMITY_OK) return rc;
   return check_launch(h, "proximity_knn_batch");
+}
+
+int proximity_knn_static(const void* corpus, uint64_t n_docs, uint32_t dim, uint32_t corpus_dtype, uint32_t metric,
+                         const float* queries, uint32_t n, uint32_t k, int64_t* out_ids, float* out_dists,
+                         int32_t device, void* hip_stream) {
+  // argument checks first: nothing is enqueued and nothing on the device changes when one fails
+  if (dim == 0 || dim % 32 != 0 || dim > PROXIMITY_MAX_DIM)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "dim=%u must be a multiple of 32 in 32..%u", dim, PROXIMITY_MAX_DIM);
+  if (k == 0 || k > PROXIMITY_MAX_K)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "k=%u must be in 1..%u", k, PROXIMITY_MAX_K);
+  if (n_docs > kStaticMaxDocs)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG,
+                "n_docs=%llu exceeds PROXIMITY_STATIC_MAX_DOCS=%zu, the corpus size the library's built-in "
+                "workspace holds (use proximity_create / proximity_knn_batch for larger corpora)",
+                (unsigned long long)n_docs, kStaticMaxDocs);
+  if (n > kStaticMaxQueries)
+    return fail(nullptr, PROXIMITY_ERR_BATCH_TOO_LARGE, "n=%u exceeds PROXIMITY_STATIC_MAX_QUERIES=%zu", n,
+                kStaticMaxQueries);
+  if (corpus_dtype != PROXIMITY_DTYPE_F32 && corpus_dtype != PROXIMITY_DTYPE_BF16)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown corpus_dtype %u", corpus_dtype);
+  if (metric > PROXIMITY_METRIC_COSINE) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown metric %u", metric);
+  if (n_docs > 0 && !corpus) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "corpus is null but n_docs > 0");
+  if (n > 0 && (!queries || !out_ids)) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "queries or out_ids is null");
+  if (reinterpret_cast<uintptr_t>(corpus) % 16 != 0 || reinterpret_cast<uintptr_t>(queries) % 16 != 0)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "corpus and queries must be 16-byte aligned");
+  if (device < 0 || device >= kStaticMaxDevices)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "device=%d must be in 0..%d", device, kStaticMaxDevices - 1);
+  DeviceGuard guard(device);
+  if (!guard.ok) return fail(nullptr, PROXIMITY_ERR_HIP, "device %d cannot be made current", device);
+
+  // once per device: where this device keeps its copy of the workspace, and its size in compute units
+  StaticDevice dev;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticDevice& slot = g_static_dev[device];
+    if (!slot.ptr) {
+      void* p = nullptr;
+      hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p)
+        return fail(nullptr, PROXIMITY_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d failed: %s", device,
+                    hipGetErrorString(e));
+      int n_cu = 0;
+      e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device);
+      if (e != hipSuccess || n_cu <= 0)
+        return fail(nullptr, PROXIMITY_ERR_HIP, "could not read the compute-unit count of device %d", device);
+      slot.n_cu = n_cu;
+      slot.ptr = static_cast<unsigned char*>(p);
+    }
+    dev = slot;
+  }
+  if (n == 0) return PROXIMITY_OK;
+
+  // The search itself is the one proximity_knn_batch runs for a handful of queries (row terms, streaming
+  // scores, selection, float64 ranking), with every buffer of the instance replaced by a piece of the
+  // workspace.
+  proximity view;
+  view.cfg.dim = dim;
+  view.cfg.corpus = corpus;
+  view.cfg.n_docs = n_docs;
+  view.cfg.corpus_dtype = corpus_dtype;
+  view.cfg.k = k;
+  view.cfg.metric = metric;
+  view.cfg.max_batch = uint32_t(kStaticMaxQueries);
+  view.K = int(k);
+  view.n_cu = dev.n_cu;
+  view.slack = reinterpret_cast<SlackState*>(dev.ptr + kStaticOffSlack);
+  view.xnrm = reinterpret_cast<float*>(dev.ptr + kStaticOffNorms);
+  view.S = reinterpret_cast<float*>(dev.ptr + kStaticOffScores);
+  view.ldS = long(kStaticMaxDocs);
+  view.pairs[0] = reinterpret_cast<uint64_t*>(dev.ptr + kStaticOffLists);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (n_docs > 0) {
+    // the one piece of the workspace that must start at zero: the state of the exactness check (the largest
+    // row length is gathered with an atomic maximum); cleared by a kernel, not a memset, so that the call
+    // can be captured into a graph
+    slack_reset_kernel<<<dim3(1), dim3(256), 0, s>>>(view.slack);
+    if (corpus_dtype == PROXIMITY_DTYPE_BF16)
+      launch_row_norms<kDtypeBF16>(&view, corpus, long(n_docs), int(dim), view.xnrm, s);
+    else
+      launch_row_norms<kDtypeF32>(&view, corpus, long(n_docs), int(dim), view.xnrm, s);
+    {
+      long g = (long(n_docs) + 255) / 256;
+      if (g > long(dev.n_cu) * 8) g = long(dev.n_cu) * 8;
+      max_norm_kernel<<<dim3((unsigned)g), dim3(256), 0, s>>>(view.xnrm, long(n_docs), view.slack);
+    }
+    if (metric != PROXIMITY_METRIC_L2) {
+      long g = (long(n_docs) + 255) / 256;
+      if (g > long(dev.n_cu) * 8) g = long(dev.n_cu) * 8;
+      row_terms_kernel<<<dim3((unsigned)g), dim3(256), 0, s>>>(view.xnrm, long(n_docs),
+                                                               metric == PROXIMITY_METRIC_COSINE ? 1 : 0);
+    }
+  }
+  SmallRouting no_cache{};
+  int rc = enqueue_scan(&view, queries, nullptr, nullptr, int(n), int(k), int(k), out_ids, out_dists, &no_cache, s);
+  if (rc != PROXIMITY_OK) return fail(nullptr, rc, "%s", view.err.c_str());
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, PROXIMITY_ERR_HIP, "proximity_knn_static: %s", hipGetErrorString(e));
+  return PROXIMITY_OK;
 }
 
 int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uint32_t k, float tau,

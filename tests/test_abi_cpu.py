@@ -88,6 +88,29 @@ def test_null_arguments(binding):
     b.lib.proximity_destroy(None)  # must be a no-op
 
 
+def test_static_search_rejects_bad_arguments_before_any_gpu_work(binding):
+    """proximity_knn_static has a workspace of fixed size: sizes beyond it, and every other bad argument,
+    are refused with a message before the device is touched."""
+    b = binding
+    call = lambda **kw: b.lib.proximity_knn_static(*[dict(dict(
+        corpus=4096, n_docs=100, dim=768, dtype=0, metric=0, queries=8192, n=1, k=10, out_ids=4096, out_dists=None,
+        device=0, stream=None), **kw)[name] for name in (
+        "corpus", "n_docs", "dim", "dtype", "metric", "queries", "n", "k", "out_ids", "out_dists", "device", "stream")])
+    text = open(os.path.join(ROOT, "include", "proximity.h")).read()
+    limits = {m.group(1): eval(m.group(2).replace("u", "")) for m in
+              re.finditer(r"#define PROXIMITY_STATIC_MAX_(\w+)\s+(\(?[0-9u <]+\)?)", text)}
+    assert limits == {"DOCS": b.STATIC_MAX_DOCS, "QUERIES": b.STATIC_MAX_QUERIES}
+    assert call(n_docs=b.STATIC_MAX_DOCS + 1) == b.ERR_INVALID_ARG
+    assert "PROXIMITY_STATIC_MAX_DOCS" in b.last_error(None)
+    assert call(n=b.STATIC_MAX_QUERIES + 1) == b.ERR_BATCH_TOO_LARGE
+    assert "PROXIMITY_STATIC_MAX_QUERIES" in b.last_error(None)
+    for kw in (dict(dim=0), dict(dim=100), dict(dim=8192), dict(k=0), dict(k=241), dict(dtype=2), dict(metric=3),
+               dict(corpus=None), dict(queries=None), dict(out_ids=None), dict(corpus=4100), dict(queries=8200),
+               dict(device=-1), dict(device=64)):
+        assert call(**kw) == b.ERR_INVALID_ARG, kw
+        assert b.last_error(None) != ""
+
+
 def test_build_flag_keeps_packed_float32_instructions_out_of_device_code(tmp_path):
     """The library is compiled with a target-feature switch that stops the compiler from pairing float
     operations into packed-float32 instructions.  The switch is live: the same two-float kernel compiles to a
