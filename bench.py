@@ -65,16 +65,31 @@ def run_region(px, q_dev, tau, batch, first, n_calls, outs):
         px.search_batch(q_dev[r0:r0 + batch], tau, ids[r0:r0 + batch], dists[r0:r0 + batch], hit[r0:r0 + batch])
 
 
-def timed_run(torch, px, q_dev, tau, batch, warmup, steps, outs, device):
+PREROLL_BATCH = 64
+
+
+def preroll(px, q_dev, tau, rows, outs):
+    """Untimed: the first `rows` rows of the stream (a multiple of 64) go through the cache in calls of 64, so
+    that the timed calls meet the cache in the state the workload keeps it in (capacity full, steady hit
+    rate) however few of them there are.  Any split of a stream into calls leaves the same cache."""
+    run_region(px, q_dev, tau, PREROLL_BATCH, 0, rows // PREROLL_BATCH, outs)
+
+
+def timed_run(torch, px, q_dev, tau, batch, warmup, steps, outs, device, preroll_rows=0):
+    """Clears the cache, replays preroll_rows untimed, then `warmup` untimed and `steps` timed calls of `batch`
+    rows on the rows that follow.  Returns seconds, hit rate of the timed rows, first timed row."""
     px.clear()
-    run_region(px, q_dev, tau, batch, 0, warmup, outs)
+    preroll(px, q_dev, tau, preroll_rows, outs)
+    first = preroll_rows // batch          # in calls of `batch` rows
+    run_region(px, q_dev, tau, batch, first * batch, warmup, outs)
     torch.cuda.synchronize(device)
     t0 = time.perf_counter()
-    run_region(px, q_dev, tau, batch, warmup * batch, steps, outs)
+    run_region(px, q_dev, tau, batch, (first + warmup) * batch, steps, outs)
     torch.cuda.synchronize(device)
     dt = time.perf_counter() - t0
-    hit = outs[2][warmup * batch:(warmup + steps) * batch]
-    return dt, float(hit.float().mean().item())
+    r0 = (first + warmup) * batch
+    hit = outs[2][r0:r0 + steps * batch]
+    return dt, float(hit.float().mean().item()), r0
 
 
 def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, device):
@@ -129,6 +144,9 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
         kernel = "scan_mfma_dma_kernel" if elem_bytes == 4 and dim >= 64 else "scan_mfma_topk_kernel"
     tile = 0 if batch <= 4 else (32 if avg_q <= 32 else 64 if avg_q <= 64 else 128)
     counted = COUNTER_TRAFFIC.get((kernel, tile, n_docs, dim, elem_bytes))
+    if counted is not None:
+        counted = dict(counted, measured_in_this_run=False,
+                       note="HBM bytes per launch from the rocprofv3 --pmc runs summarised in `source`; not re-measured here")
     common = {"traffic": None if counted is None else counted["fetch_bytes"] + counted["write_bytes"],
               "traffic_counters": counted, "kernel": kernel,
               "launches_timed": len(busy), "avg_launch_ms": round(avg_ms, 5),
@@ -240,11 +258,12 @@ def probe_scaling(args, torch, np, W, Proximity, device):
                       "data": "synthetic", "config": {"dim": dim, "tau": tau, "policy": "LRU"}, "rows": rows}))
 
 
-def probe_microbench(args, torch, np, W, Proximity, device):
-    """Cache probe alone: 10 000 resident keys, batches of 4 096 queries, no corpus behind the cache."""
+def probe_microbench(args, torch, np, W, Proximity, device, steps=None, warmup=None):
+    """Cache probe alone: 10 000 resident keys, batches of 4 096 queries, no corpus behind the cache.
+    Returns the result line."""
     n_keys, dim, batch, tau = W.PROBE_KEYS, W.PROBE_DIM, W.PROBE_BATCH, W.PROBE_TAU
-    steps = args.steps if args.steps is not None else 20
-    warmup = args.warmup if args.warmup is not None else 2
+    steps = steps if steps is not None else (args.steps if args.steps is not None else 20)
+    warmup = warmup if warmup is not None else (args.warmup if args.warmup is not None else 2)
     planes = None
     if args.lsh_bits > 0:
         planes = torch.from_numpy(W.lsh_planes(args.lsh_bits, dim, 0)).to(device)
@@ -296,9 +315,8 @@ def probe_microbench(args, torch, np, W, Proximity, device):
                                        f"tau={tau}, LRU, no corpus",
                            "hit_rate": round(hits / (steps * batch), 4), "resident_keys": px.stats()["size"]},
                 "roofline": None, "cpu_baseline": None}
-        print(json.dumps(line))
         px.close()
-        return
+        return line
     line = {"metric": "cache_probes_per_sec", "value": round(batch / (ms * 1e-3), 1), "unit": "queries/s",
             "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
@@ -311,8 +329,8 @@ def probe_microbench(args, torch, np, W, Proximity, device):
                          "note": "whole call (probe contraction, candidate extraction, resolver, insertion) "
                                  "against the probe contraction's 2*B*(c+B)*d flops"},
             "cpu_baseline": None}
-    print(json.dumps(line))
     px.close()
+    return line
 
 
 def cpu_model():
@@ -350,112 +368,100 @@ def main():
     if args.probe_scaling:
         return probe_scaling(args, torch, np, W, Proximity, device)
     if args.workload == "probe":
-        return probe_microbench(args, torch, np, W, Proximity, device)
+        print(json.dumps(probe_microbench(args, torch, np, W, Proximity, device)))
+        return
     if args.recall_sweep:
         return recall_sweep(args, torch, np, W, Proximity, device)
     w = W.WORKLOADS[args.workload]
-    tau = w.tau if args.tau is None else args.tau
-    batch = w.batch if args.batch is None else args.batch
-    n_docs = w.n_docs if args.n_docs is None else args.n_docs
-    steps = args.steps if args.steps is not None else (20000 if batch == 1 else 1000)
-    warmup = args.warmup if args.warmup is not None else (2000 if batch == 1 else 50)
-    if (steps + warmup) * batch > w.n_stream * 3 // 4:
-        steps = w.n_stream * 3 // 4 // batch - warmup
-    max_batch = max(batch, 64)
+    line = measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=args.tau, batch=args.batch,
+                                   steps=args.steps, warmup=args.warmup, headline=True)
+    print(json.dumps(line))
 
-    t_gen = time.perf_counter()
-    queries = W.stream_for(w)
-    on_device = n_docs >= 8_000_000          # large corpora are drawn on the device, chunk by chunk
-    if on_device:
-        corpus = None
+
+def make_corpus(torch, W, device, w, n_docs):
+    """(host copy or None, device tensor): corpora of 8 M rows and more are drawn on the device, chunk by chunk."""
+    if n_docs >= 8_000_000:
         corpus_dev = torch.empty((n_docs, w.dim), device=device,
                                  dtype=torch.bfloat16 if w.corpus_dtype == W.DTYPE_BF16 else torch.float32)
         for r0, chunk in W.device_corpus_chunks(n_docs, w.dim, w.seed, device, w.corpus_dtype):
             corpus_dev[r0:r0 + chunk.shape[0]] = chunk
-    else:
-        corpus = W.corpus_for(w, n_docs)
-        corpus_dev = torch.from_numpy(corpus).to(device)
+        return None, corpus_dev
+    corpus = W.corpus_for(w, n_docs)
+    return corpus, torch.from_numpy(corpus).to(device)
+
+
+def default_preroll(w, batch):
+    """Rows replayed untimed before the warm-up calls: enough misses to fill the cache and settle the hit rate."""
+    rows = 2048 if w.capacity <= 300 else 4096
+    return min(rows, w.n_stream // 4) // PREROLL_BATCH * PREROLL_BATCH
+
+
+def measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=None, batch=None, steps=None, warmup=None,
+                            headline=False):
+    """One workload through proximity_search_batch: throughput of the timed calls, roofline of the scan kernel
+    they launched.  With `headline` (the mid workload of the default run) also the sweep over the other
+    (tau, batch) points and the other benchmark configurations, and the CPU oracle beside it."""
+    tau = w.tau if tau is None else tau
+    batch = w.batch if batch is None else batch
+    n_docs = w.n_docs if args.n_docs is None or not headline else args.n_docs
+    steps = steps if steps is not None else (20000 if batch == 1 else 1000)
+    warmup = warmup if warmup is not None else (2000 if batch == 1 else 50)
+    pre = default_preroll(w, batch)
+    if pre + (steps + warmup) * batch > w.n_stream * 3 // 4:
+        steps = max(1, (w.n_stream * 3 // 4 - pre) // batch - warmup)
+    max_batch = max(batch, PREROLL_BATCH)
+
+    t_gen = time.perf_counter()
+    queries = W.stream_for(w)
+    corpus, corpus_dev = make_corpus(torch, W, device, w, n_docs)
     q_dev = torch.from_numpy(queries).to(device)
     t_gen = time.perf_counter() - t_gen
     elem = 2 if w.corpus_dtype == W.DTYPE_BF16 else 4
 
     planes = planes_host = None
-    if args.lsh_bits > 0:
+    if headline and args.lsh_bits > 0:
         planes_host = W.lsh_planes(args.lsh_bits, w.dim, w.seed)
         planes = torch.from_numpy(planes_host).to(device)
     capacity = args.bucket_capacity if planes is not None else w.capacity
-    metric = {"l2": 0, "ip": 1, "cosine": 2}[args.metric]
+    rho = args.rho if headline else 1
+    metric_name = args.metric if headline else "l2"
+    metric = {"l2": 0, "ip": 1, "cosine": 2}[metric_name]
     if metric == 2:
         tau = tau * tau / 2.0
-    px = Proximity(corpus_dev, w.dim, capacity, w.k, w.policy, max_batch, rerank_factor=args.rho, lsh_planes=planes,
+    px = Proximity(corpus_dev, w.dim, capacity, w.k, w.policy, max_batch, rerank_factor=rho, lsh_planes=planes,
                    metric=metric)
     n_rows = len(queries)
     outs = (torch.empty((n_rows, w.k), dtype=torch.int64, device=device),
             torch.empty((n_rows, w.k), dtype=torch.float32, device=device),
             torch.empty((n_rows,), dtype=torch.uint8, device=device))
 
-    dt, hit_rate = timed_run(torch, px, q_dev, tau, batch, warmup, steps, outs, device)
+    dt, hit_rate, first_row = timed_run(torch, px, q_dev, tau, batch, warmup, steps, outs, device, pre)
     qps = steps * batch / dt
 
     # roofline of the dominant kernel, the corpus-scan distance kernel: HBM-bound while a launch serves
     # few queries, matrix-core-bound once 2*M flops per 4 corpus bytes pass the ridge (157.3 TF / 8 TB/s)
-    n_prof = min(steps, 4000 if batch <= 8 else 400, w.n_stream // batch - warmup - steps)
-    busy = profiled_scan(torch, px, q_dev, tau, batch, warmup + steps, n_prof, outs, device)
+    next_call = first_row // batch + steps
+    n_prof = max(1, min(steps, 4000 if batch <= 8 else 400, w.n_stream // batch - next_call))
+    busy = profiled_scan(torch, px, q_dev, tau, batch, next_call, n_prof, outs, device)
     roofline = scan_roofline(busy, n_docs, w.dim, batch, elem)
+    checks = px.stats()
 
     sweep = []
-    if not args.no_sweep and args.workload == "mid":
+    if headline and not args.no_sweep and w.name == "mid":
         for s_tau, s_batch, s_warm, s_steps in ((0.0, 1, 100, 2000), (0.25, 64, 30, 300), (0.0, 64, 10, 200)):
             run_tau = s_tau * s_tau / 2.0 if metric == 2 else s_tau
-            s_dt, s_hit = timed_run(torch, px, q_dev, run_tau, s_batch, s_warm, s_steps, outs, device)
-            s_busy = profiled_scan(torch, px, q_dev, run_tau, s_batch, s_warm + s_steps, min(s_steps, 200), outs,
-                                   device)
-            sweep.append({"tau": s_tau, "batch": s_batch, "steps": s_steps, "warmup": s_warm,
+            s_dt, s_hit, s_first = timed_run(torch, px, q_dev, run_tau, s_batch, s_warm, s_steps, outs, device, pre)
+            s_busy = profiled_scan(torch, px, q_dev, run_tau, s_batch, s_first // s_batch + s_steps,
+                                   min(s_steps, 200), outs, device)
+            sweep.append({"workload": "mid", "tau": s_tau, "batch": s_batch, "steps": s_steps, "warmup": s_warm,
+                          "cache_preroll_rows": pre,
                           "queries_per_s": round(s_steps * s_batch / s_dt, 1), "hit_rate": round(s_hit, 4),
                           "ms_per_step": round(1e3 * s_dt / s_steps, 4),
                           "roofline": scan_roofline(s_busy, n_docs, w.dim, s_batch, elem)})
 
     cpu = None
-    if not args.no_cpu_baseline and corpus is not None:
-        from oracle import proximity_oracle as po
-        first = warmup * batch
-        k_store = args.rho * w.k
-        no_db = lambda q: (np.full(k_store, -1, np.int64), np.full(k_store, np.inf))
-        if planes_host is not None:
-            orc = po.LshCacheOracle(corpus, planes_host, capacity, w.k, w.policy, retrieve=no_db,
-                                    rerank_factor=args.rho, metric=metric)
-        else:
-            orc = po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy, rerank_factor=args.rho, retrieve=no_db,
-                                     metric=metric)
-        orc.lookup_stream(queries[:first], tau)            # decisions only: brings the cache to the timed region's state
-        orc.retrieve = lambda q: po.exact_knn(corpus, q, k_store, metric=metric)
-        n_s = min(args.cpu_sample, len(queries) - first)
-        t0 = time.perf_counter()
-        o_ids, o_d, o_hit, _ = orc.lookup_stream(queries[first:first + n_s], tau)
-        cdt = time.perf_counter() - t0
-        cpu = {"value": round(n_s / cdt, 4), "unit": "queries/s", "cores": 1, "kind": "oracle",
-               "sample": f"stream rows {first}..{first + n_s - 1} of the same workload after a decisions-only "
-                         f"replay of rows 0..{first - 1}; {int((o_hit == 0).sum())} misses, "
-                         f"{cdt:.1f} s, float64 numpy (single-threaded element-wise code)",
-               "host_cpus": os.cpu_count(), "cpu_model": cpu_model()}
-        # the two pieces on their own, oracle code as it stands: one cache probe (distances to c keys and the
-        # nearest) at two cache sizes, and one database call (all distances and the ranking) on this corpus
-        parts = {}
-        for c_keys in (300, 10000):
-            keys64 = po.as_f64_rows(corpus[:c_keys])
-            t0 = time.perf_counter()
-            for t in range(20):
-                po.l2_distances(queries[t], keys64).argmin()
-            parts[f"probe_us_c{c_keys}"] = round((time.perf_counter() - t0) / 20 * 1e6, 1)
-        t0 = time.perf_counter()
-        po.exact_knn(corpus, queries[0], w.k)
-        parts[f"scan_s_{n_docs}_docs"] = round(time.perf_counter() - t0, 3)
-        # the oracle's batched form (float64 matrix product per block of rows, multi-threaded BLAS) on 64 queries:
-        # the fastest the oracle's own code answers misses on this host
-        t0 = time.perf_counter()
-        po.batched_exact_knn(corpus, queries[:64], w.k, metric=metric)
-        parts["batched_scan_s_64_queries_all_cores"] = round(time.perf_counter() - t0, 3)
-        cpu["parts"] = parts
+    if headline and not args.no_cpu_baseline and corpus is not None:
+        cpu = cpu_baseline(args, np, w, corpus, queries, tau, capacity, planes_host, metric, first_row)
 
     line = {
         "metric": "retrieval_queries_per_sec", "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1,
@@ -466,15 +472,126 @@ def main():
                                f"{w.choice}({w.zipf_s}) stream of "
                                f"{w.n_stream} over {w.n_bases} bases (perturbation {w.radius}), capacity "
                                f"{w.capacity}, {'LRU' if w.policy else 'FIFO'}, k={w.k}",
-                   "tau": tau, "batch": batch, "rerank_factor": args.rho, "distance": args.metric,
+                   "tau": tau, "batch": batch, "rerank_factor": rho, "distance": metric_name,
                    "cache": (f"bucketed: {1 << args.lsh_bits} buckets x {capacity}" if planes is not None
                              else f"flat: {w.capacity}"),
+                   "cache_preroll_rows": pre, "first_timed_row": first_row,
                    "hit_rate": round(hit_rate, 4),
-                   "queries_timed": steps * batch, "setup_s": round(t_gen, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
+                   "queries_timed": steps * batch, "setup_s": round(t_gen, 1),
+                   "searches_ranked_twice": checks["slack_exhausted"], "searches_not_proven_exact": checks["slack_unresolved"]},
+        "roofline": roofline, "cpu_baseline": cpu,
     }
-    print(json.dumps(line))
     px.close()
+    del px, corpus_dev, q_dev, outs
+    torch.cuda.empty_cache()
+    if headline:
+        # the other benchmark configurations, each measured like the headline (own corpus, own roofline)
+        if not args.no_sweep and w.name == "mid" and args.n_docs is None:
+            for name, o_steps, o_warm in (("lowreuse", 150, 10), ("large", 40, 4)):
+                free, _ = torch.cuda.mem_get_info(device)
+                ow = W.WORKLOADS[name]
+                need = ow.n_docs * ow.dim * (2 if ow.corpus_dtype == W.DTYPE_BF16 else 4) * 1.25
+                if free < need:
+                    sweep.append({"workload": name, "skipped": f"needs {need / 2**30:.0f} GiB of free device memory"})
+                    continue
+                o = measure_stream_workload(args, torch, np, W, Proximity, device, ow, steps=o_steps, warmup=o_warm)
+                sweep.append({"workload": name, "tau": o["config"]["tau"], "batch": o["config"]["batch"],
+                              "steps": o["steps"], "warmup": o["warmup"],
+                              "cache_preroll_rows": o["config"]["cache_preroll_rows"],
+                              "queries_per_s": o["value"], "hit_rate": o["config"]["hit_rate"],
+                              "ms_per_step": o["ms_per_step"], "dtype": o["dtype"], "setup_s": o["config"]["setup_s"],
+                              "roofline": o["roofline"]})
+            p = probe_microbench(args, torch, np, W, Proximity, device, steps=20, warmup=2)
+            sweep.append({"workload": "probe", "tau": W.PROBE_TAU, "batch": W.PROBE_BATCH, "steps": p["steps"],
+                          "warmup": p["warmup"], "queries_per_s": p["value"], "hit_rate": p["config"]["hit_rate"],
+                          "ms_per_step": p["ms_per_step"], "roofline": p["roofline"]})
+        line["sweep"] = sweep
+    return line
+
+
+def cpu_baseline(args, np, w, corpus, queries, tau, capacity, planes_host, metric, first):
+    """The oracle as it stands on this host, on a bounded sample of the same workload.
+    `value`: the literal oracle (Algorithm 1 with the brute-force database call, element-wise float64 numpy) on
+    `--cpu-sample` stream rows that follow the timed region's first row, after a decisions-only replay of the
+    rows before them, with the BLAS pool held to one thread; `cores` is measured (CPU seconds / wall seconds).
+    Beside it: an estimate for the first 2 000 rows of the stream (their decisions replayed and timed, every
+    miss charged the sample's mean database call), the oracle's batched form on all cores with the BLAS
+    thread count the pool reports, and the two pieces on their own."""
+    from oracle import proximity_oracle as po
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        pools = [p for p in threadpool_info() if p.get("user_api") == "blas"]
+        blas_threads = max([p["num_threads"] for p in pools], default=1)
+    except ImportError:
+        threadpool_limits = None
+        blas_threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    k_store = args.rho * w.k
+    no_db = lambda q: (np.full(k_store, -1, np.int64), np.full(k_store, np.inf))
+
+    def fresh_oracle(retrieve):
+        if planes_host is not None:
+            return po.LshCacheOracle(corpus, planes_host, capacity, w.k, w.policy, retrieve=retrieve,
+                                     rerank_factor=args.rho, metric=metric)
+        return po.FlatCacheOracle(corpus, w.capacity, w.k, w.policy, rerank_factor=args.rho, retrieve=retrieve,
+                                  metric=metric)
+
+    def timed(fn):
+        c0, t0 = os.times(), time.perf_counter()
+        out = fn()
+        wall = time.perf_counter() - t0
+        c1 = os.times()
+        return out, wall, (c1.user - c0.user + c1.system - c0.system) / max(wall, 1e-9)
+
+    class one_thread:
+        def __enter__(self):
+            self.ctx = threadpool_limits(limits=1) if threadpool_limits else None
+            if self.ctx:
+                self.ctx.__enter__()
+
+        def __exit__(self, *a):
+            if self.ctx:
+                self.ctx.__exit__(*a)
+
+    # (1) the literal oracle on a short stretch, one thread
+    orc = fresh_oracle(no_db)
+    orc.lookup_stream(queries[:first], tau)            # decisions only: the cache state of the timed region
+    orc.retrieve = lambda q: po.exact_knn(corpus, q, k_store, metric=metric)
+    n_s = min(args.cpu_sample, len(queries) - first)
+    with one_thread():
+        (o_ids, o_d, o_hit, _), cdt, cores = timed(lambda: orc.lookup_stream(queries[first:first + n_s], tau))
+    misses = int((o_hit == 0).sum())
+    cpu = {"value": round(n_s / cdt, 4), "unit": "queries/s", "cores": max(1, round(cores)), "kind": "oracle",
+           "sample": f"stream rows {first}..{first + n_s - 1} of the same workload after a decisions-only "
+                     f"replay of rows 0..{first - 1}; {misses} misses, {cdt:.1f} s, literal float64 numpy oracle, "
+                     f"BLAS pool limited to 1 thread",
+           "cores_measured": round(cores, 2), "host_cpus": os.cpu_count(), "cpu_model": cpu_model(),
+           "blas_threads_available": blas_threads}
+    # (2) the first 2 000 rows of the stream: decisions replayed and timed; each miss charged one database call
+    n_est = min(2000, len(queries))
+    with one_thread():
+        (e_hit, _, _), e_dt, _ = timed(lambda: po.simulate_decisions(queries[:n_est], tau, capacity, w.policy,
+                                                                     planes=planes_host, metric=metric))
+        _, scan_dt, _ = timed(lambda: po.exact_knn(corpus, queries[0], k_store, metric=metric))
+    e_miss = int((e_hit == 0).sum())
+    cpu["first_2000_rows_estimate"] = {
+        "queries_per_s": round(n_est / (e_dt + e_miss * scan_dt), 4), "rows": n_est, "misses": e_miss,
+        "decisions_s": round(e_dt, 3), "one_database_call_s": round(scan_dt, 3),
+        "note": "decisions measured on all rows; database calls measured once and multiplied by the misses"}
+    # (3) the pieces, oracle code as it stands: one cache probe (distances to c keys and the nearest) at two
+    # cache sizes, one database call, and the batched form (float64 matrix product per block of rows) on all cores
+    parts = {}
+    with one_thread():
+        for c_keys in (300, 10000):
+            keys64 = po.as_f64_rows(corpus[:c_keys])
+            _, p_dt, _ = timed(lambda: [po.l2_distances(queries[t], keys64).argmin() for t in range(20)])
+            parts[f"probe_us_c{c_keys}"] = round(p_dt / 20 * 1e6, 1)
+    parts[f"scan_s_{len(corpus)}_docs_one_thread"] = round(scan_dt, 3)
+    _, b_dt, b_cores = timed(lambda: po.batched_exact_knn(corpus, queries[:64], w.k, metric=metric))
+    parts["batched_scan_s_64_queries_all_cores"] = round(b_dt, 3)
+    parts["batched_scan_cores_measured"] = round(b_cores, 2)
+    parts["batched_scan_blas_threads"] = blas_threads
+    cpu["parts"] = parts
+    return cpu
 
 
 if __name__ == "__main__":
