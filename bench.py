@@ -130,15 +130,19 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
     avg_q = sum(q for _, q in busy) / len(busy)
     gbs = bytes_per_launch / (avg_ms * 1e-3) / 1e9
     tflops = sum(2.0 * q * n_docs * dim for _, q in busy) / (sum(ms for ms, _ in busy) * 1e-3) / 1e12
-    # a bfloat16 corpus is scanned on the bfloat16 matrix cores with the queries split into three bfloat16
-    # terms: three multiply-adds of that type per term of the inner product
-    bf16x3 = elem_bytes == 2 and dim >= 64 and batch > 4
-    mfma_peak = BF16_MFMA_PEAK_TFLOPS if bf16x3 else F32_MFMA_PEAK_TFLOPS
-    per_term = 3.0 if bf16x3 else 1.0
+    # A bfloat16 corpus is scanned on the bfloat16 matrix cores with the float32 queries split into bfloat16
+    # terms: one multiply-add of that type per term of the split and of the inner product.  The scan with the
+    # queries resident in registers (the dimensions it is built for) multiplies two terms, the general one three.
+    regq = batch > 4 and ((elem_bytes == 4 and dim in (768, 384)) or (elem_bytes == 2 and dim in (384, 256)))
+    bf16_split = elem_bytes == 2 and dim >= 64 and batch > 4
+    mfma_peak = BF16_MFMA_PEAK_TFLOPS if bf16_split else F32_MFMA_PEAK_TFLOPS
+    per_term = (2.0 if regq else 3.0) if bf16_split else 1.0
     ridge_q = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9) * elem_bytes / (2 * per_term)  # queries per launch at the ridge
     if batch <= 4:
         kernel = "scores_stream_kernel"
-    elif bf16x3:
+    elif regq:
+        kernel = "scan_regq_kernel"
+    elif bf16_split:
         kernel = "scan_bf16x3_kernel"
     else:
         kernel = "scan_mfma_dma_kernel" if elem_bytes == 4 and dim >= 64 else "scan_mfma_topk_kernel"
@@ -159,7 +163,7 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
                 "frac": round(gbs / HBM_PEAK_GBS, 4), **common}
     return {"bound": "mfma", "achieved": round(tflops * per_term, 2), "peak": mfma_peak, "unit": "TFLOP/s",
             "frac": round(tflops * per_term / mfma_peak, 4),
-            "mfma_dtype": "bf16 x3 split, f32 accumulate" if bf16x3 else "f32", **common}
+            "mfma_dtype": f"bf16, queries split in {int(per_term)} terms, f32 accumulate" if bf16_split else "f32", **common}
 
 
 def k_recall_per_query(ids, truth):

@@ -167,9 +167,10 @@ uint32_t proximity_abi_version(void);
  * the exact ranked list).  With E this bound, W the worst kept float32 score and t the k-th smallest exact
  * score among the kept rows, W - E > t proves that no other row belongs to the k nearest; a search for
  * which it fails is ranked again from all rows scoring at most t + E (counted in slack_exhausted).
- *   E = g (X^2 + 2 |q| X)   L2          g = (3 dim + 16) 2^-24: every product and partial sum of a dim-term
- *   E = g 2 |q| X           IP              inner product rounds once (three products per term when a
- *   E = g 4 |q|             COSINE          bfloat16 corpus is searched with the query split in three)
+ *   E = g (X^2 + 2 |q| X)   L2          g = (3 dim + 16) 2^-24 + 2^-17: every product and partial sum of a
+ *   E = g 2 |q| X           IP              dim-term inner product rounds once; a bfloat16 corpus is searched with
+ *   E = g 4 |q|             COSINE          the query split into bfloat16 terms (up to three products per term),
+ *                                           of which the batched scan drops what lies below 2^-18 |q_i|
  * |q| = query_length, X = max_row_length (the longest corpus row).  NaN for a bad argument.
  */
 double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_length, double max_row_length);

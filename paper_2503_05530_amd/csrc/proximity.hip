@@ -27,6 +27,7 @@
 #include "cache_kernels.hpp"
 #include "lsh_kernels.hpp"
 #include "mfma_kernels.hpp"
+#include "regq_kernels.hpp"
 #include "bf16x3_kernels.hpp"
 #include "resolver_lds.hpp"
 #include "scan_kernels.hpp"
@@ -129,6 +130,7 @@ struct proximity {
   uint64_t* topk_buf = nullptr;  // batched scan: [query tiles][scan blocks][tile queries][kTopkCap]
   uint16_t* qplanes = nullptr;   // bfloat16 corpus: the three bfloat16 planes of a call's queries, [3][max_batch][dim]
   int scan_blocks = 1;           // blocks that share the corpus in the batched scan
+  int scan_blocks_regq = 1;      // the same for the scan that keeps its queries in registers (one block per CU)
   int64_t* res_ids = nullptr;
   float* res_d = nullptr;
   SlackState* slack = nullptr;   // is the float32 candidate list long enough? (select_kernels.hpp)
@@ -345,6 +347,54 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
 #undef PROX_SCAN
 }
 
+// The same pass with the query tile resident in registers (regq_kernels.hpp), for the corpus types and
+// dimensions that kernel is instantiated for.  The queries base .. base+span-1 go in slices of 64 (float32)
+// or 128 (bfloat16); per slice the shape for every range of "queries from the slice's start on" that the
+// call can reach is launched, and the ones whose range does not contain the device-side count return at once.
+template <int DT, int DIM>
+void launch_regq_dim(proximity* h, long n_rows, int G, const float* Qbase, const int* qlist,
+                     const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
+                     uint64_t* out, hipStream_t s) {
+  constexpr bool F32 = DT == kDtypeF32;
+  constexpr int NT = F32 ? 256 : 512, SLICE = F32 ? 64 : 128;
+  const int cosine = h->cfg.metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
+  const long plane_stride = long(h->cfg.max_batch) * DIM;
+  const bool known = m_count_ptr == nullptr;  // then M = m_limit and only its own shape is launched
+  for (int mb = base; mb < base + span; mb += SLICE) {
+    const int rem_max = m_limit - mb;         // the most queries this slice can have to serve
+#define PROX_REGQ(WQ, LO, HI)                                                                                   \
+  if (rem_max > (LO) && (!known || rem_max <= (HI)))                                                             \
+  scan_regq_kernel<DT, DIM, WQ><<<dim3(G), dim3(NT), 0, s>>>(h->cfg.corpus, h->xnrm, n_rows, Qbase, qlist, h->qplanes, \
+                                                             plane_stride, m_count_ptr, m_limit, mb, LO, HI, kp, seed,  \
+                                                             h->topk_buf, out, cosine)
+    PROX_REGQ(1, 0, 16);
+    PROX_REGQ(2, 16, 32);
+    if constexpr (F32) {
+      PROX_REGQ(4, 32, 0x7fffffff);
+    } else {
+      PROX_REGQ(4, 32, 64);
+      PROX_REGQ(8, 64, 0x7fffffff);
+    }
+#undef PROX_REGQ
+  }
+}
+
+void launch_regq_scan(proximity* h, long n_rows, int G, const float* Qbase, const int* qlist,
+                      const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
+                      uint64_t* out, hipStream_t s) {
+  const int dim = int(h->cfg.dim);
+#define PROX_REGQ_DIM(DT, D)                                                                                  \
+  launch_regq_dim<DT, D>(h, n_rows, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, out, s)
+  if (h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16) {
+    if (dim == 384) PROX_REGQ_DIM(kDtypeBF16, 384);
+    else PROX_REGQ_DIM(kDtypeBF16, 256);
+  } else {
+    if (dim == 768) PROX_REGQ_DIM(kDtypeF32, 768);
+    else PROX_REGQ_DIM(kDtypeF32, 384);
+  }
+#undef PROX_REGQ_DIM
+}
+
 // Merge per-query lists of `len` keys in pairs[cur] down to one sorted list of kp keys per
 // query, ping-ponging between the two key buffers.  Returns the index of the buffer that
 // holds the result.
@@ -438,12 +488,16 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       seed = h->pairs[cur];
       cur ^= 1;  // the full scan writes into the other buffer
     }
-    const int G = h->scan_blocks;
+    const bool regq = regq_supported(int(h->cfg.corpus_dtype), dim);
+    const int G = regq ? h->scan_blocks_regq : h->scan_blocks;
     for (int base = 0; base < m_limit; base += kScanPassQueries) {
       const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
       prof_begin(h, s);
-      launch_batched_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], false,
-                          s);
+      if (regq)
+        launch_regq_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], s);
+      else
+        launch_batched_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], false,
+                            s);
       prof_end(h, s, base, span);
     }
     // the last merge level happens inside the ranking kernel
@@ -589,10 +643,17 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   if (B > size_t(kStreamMaxQueries) && N > 0) {
     const size_t tiles256 = (N + 255) / 256;
     h->scan_blocks = int(tiles256 < size_t(2 * h->n_cu) ? tiles256 : size_t(2 * h->n_cu));
+    const size_t tiles128 = (N + kRegqTileRows - 1) / kRegqTileRows;
+    h->scan_blocks_regq = int(tiles128 < size_t(h->n_cu) ? tiles128 : size_t(h->n_cu));
     if (size_t(h->scan_blocks) > lists) lists = size_t(h->scan_blocks);
+    if (size_t(h->scan_blocks_regq) > lists) lists = size_t(h->scan_blocks_regq);
     if (size_t(kSeedRows + kp - 1) / kp > lists) lists = size_t(kSeedRows + kp - 1) / kp;  // dumped head scores
     const size_t pass_q = (B < size_t(kScanPassQueries) ? B : size_t(kScanPassQueries)) + 127;
-    TRY_ALLOC(h->topk_buf, size_t(h->scan_blocks) * pass_q * kTopkCap, false);
+    // candidate buffers: per (block, query of the launch's tile); the register-resident scan runs one slice
+    // of at most 128 queries per launch
+    size_t cand_sets = size_t(h->scan_blocks) * pass_q;
+    if (size_t(h->scan_blocks_regq) * 128 > cand_sets) cand_sets = size_t(h->scan_blocks_regq) * 128;
+    TRY_ALLOC(h->topk_buf, cand_sets * kTopkCap, false);
     if (cfg->corpus_dtype == PROXIMITY_DTYPE_BF16) TRY_ALLOC(h->qplanes, 3 * B * d, true);
   }
   h->pairs_elems = long(B * lists * kp);

@@ -264,10 +264,12 @@ __device__ __forceinline__ void block_rerank_stored_any(int kind, const int64_t*
 // provably holds the true k nearest -- and counted in `exhausted`; if that set outgrows its buffer
 // (kWideCap rows) the query keeps the float64 ranking of its kp candidates and is counted in `unresolved`.
 //
-// E: a float32 inner product of dim terms, summed in any order, is within g |q| |x| of the exact one with
-// g = (terms + 2) 2^-24 (each product and each partial sum rounds once; the three-term bfloat16 split has
-// 3 dim exact products and a remainder below 2^-24 |q| per element); the squared length of a row carries
-// the same relative error; the final multiply-add rounds once more.  With X the largest row length:
+// E: a float32 inner product of dim terms, summed in any order, is within (terms + 2) 2^-24 |q| |x| of the
+// exact one (each product and each partial sum rounds once); a bfloat16 corpus is scanned with the query split
+// into bfloat16 planes: up to 3 dim exact products, and where only two planes are multiplied a remainder below
+// 2^-18 |q_i| per element, 2^-17 |q| |x| in a score.  g = (3 dim + 16) 2^-24 + 2^-17 covers every scan kernel.
+// The squared length of a row carries the same relative error; the final multiply-add rounds once more.
+// With X the largest row length:
 //   Euclidean      score = |x|^2 - 2 q.x          E = g (X^2 + 2 |q| X)
 //   inner product  score = -2 q.x                 E = g 2 |q| X
 //   cosine         score = -2 q.x / |x|           E = g 4 |q|     (the reciprocal length rounds as well)
@@ -290,7 +292,7 @@ struct RedoBuffers {
 };
 
 __host__ __device__ inline double score_error_bound(int metric, int dim, double q_len, double x_max) {
-  const double g = (3.0 * double(dim) + 16.0) * 5.9604644775390625e-08;
+  const double g = (3.0 * double(dim) + 16.0) * 5.9604644775390625e-08 + 7.62939453125e-06;
   if (metric == kMetricL2) return g * (x_max * x_max + 2.0 * q_len * x_max);
   if (metric == kMetricIP) return g * 2.0 * q_len * x_max;
   return g * 4.0 * q_len;

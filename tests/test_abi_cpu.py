@@ -142,13 +142,13 @@ def test_score_error_bound_by_hand_and_against_float32_arithmetic(binding):
     b = binding
     E = b.lib.proximity_score_error_bound
     u = 2.0 ** -24
-    # dim 768: g = (3 * 768 + 16) u = 2320 u
-    g = 2320 * u
+    # dim 768: g = (3 * 768 + 16) u + 2^-17 = 2320 u + 128 u
+    g = 2448 * u
     assert E(0, 768, 1.0, 1.0) == pytest.approx(g * 3.0, rel=1e-15)
     assert E(0, 768, 2.0, 0.5) == pytest.approx(g * (0.25 + 2.0), rel=1e-15)
     assert E(1, 768, 2.0, 0.5) == pytest.approx(g * 2.0, rel=1e-15)
     assert E(2, 768, 2.0, 123.0) == pytest.approx(g * 8.0, rel=1e-15)
-    assert E(0, 32, 1.0, 1.0) == pytest.approx(112 * u * 3.0, rel=1e-15)
+    assert E(0, 32, 1.0, 1.0) == pytest.approx(240 * u * 3.0, rel=1e-15)
     for bad in ((3, 768, 1.0, 1.0), (0, 0, 1.0, 1.0), (0, 768, -1.0, 1.0), (0, 768, 1.0, float("nan"))):
         assert np.isnan(E(*bad))
     rng = np.random.default_rng(40)
