@@ -51,6 +51,7 @@ static_assert(kResolverLdsMax + kResolverStaticLds <= 160 * 1024 - 256, "the res
 constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32 tiles use the split-column kernel
 constexpr size_t kLshLdsMax = 144 * 1024;  // dynamic LDS the bucket resolver may ask for (query + bucket keys)
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
+constexpr long kSeedRows2 = 262144;    // second sample of a long corpus (register-resident scan)
 
 static_assert(sizeof(proximity_config) == 72, "proximity_config layout is part of the ABI");
 static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is part of the ABI");
@@ -352,11 +353,10 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
 // or 128 (bfloat16); per slice the shape for every range of "queries from the slice's start on" that the
 // call can reach is launched, and the ones whose range does not contain the device-side count return at once.
 template <int DT, int DIM>
-void launch_regq_dim(proximity* h, long n_rows, int G, const float* Qbase, const int* qlist,
+void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows, int G, const float* Qbase, const int* qlist,
                      const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
                      uint64_t* out, hipStream_t s) {
-  constexpr bool F32 = DT == kDtypeF32;
-  constexpr int NT = F32 ? 256 : 512, SLICE = F32 ? 64 : 128;
+  constexpr int QW = regq_queries_per_wave(DT), SLICE = 4 * QW;   // queries per wave and per block at most
   const int cosine = h->cfg.metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
   const long plane_stride = long(h->cfg.max_batch) * DIM;
   const bool known = m_count_ptr == nullptr;  // then M = m_limit and only its own shape is launched
@@ -364,27 +364,22 @@ void launch_regq_dim(proximity* h, long n_rows, int G, const float* Qbase, const
     const int rem_max = m_limit - mb;         // the most queries this slice can have to serve
 #define PROX_REGQ(WQ, LO, HI)                                                                                   \
   if (rem_max > (LO) && (!known || rem_max <= (HI)))                                                             \
-  scan_regq_kernel<DT, DIM, WQ><<<dim3(G), dim3(NT), 0, s>>>(h->cfg.corpus, h->xnrm, n_rows, Qbase, qlist, h->qplanes, \
-                                                             plane_stride, m_count_ptr, m_limit, mb, LO, HI, kp, seed,  \
-                                                             h->topk_buf, out, cosine)
-    PROX_REGQ(1, 0, 16);
-    PROX_REGQ(2, 16, 32);
-    if constexpr (F32) {
-      PROX_REGQ(4, 32, 0x7fffffff);
-    } else {
-      PROX_REGQ(4, 32, 64);
-      PROX_REGQ(8, 64, 0x7fffffff);
-    }
+  scan_regq_kernel<DT, DIM, WQ><<<dim3(G), dim3(256), 0, s>>>(X, xnrm, n_rows, Qbase, qlist, h->qplanes,               \
+                                                              plane_stride, m_count_ptr, m_limit, mb, LO, HI, kp, seed, \
+                                                              h->topk_buf, out, cosine)
+    PROX_REGQ(1, 0, QW);
+    PROX_REGQ(2, QW, 2 * QW);
+    PROX_REGQ(4, 2 * QW, 0x7fffffff);
 #undef PROX_REGQ
   }
 }
 
-void launch_regq_scan(proximity* h, long n_rows, int G, const float* Qbase, const int* qlist,
+void launch_regq_scan(proximity* h, const void* X, const float* xnrm, long n_rows, int G, const float* Qbase, const int* qlist,
                       const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
                       uint64_t* out, hipStream_t s) {
   const int dim = int(h->cfg.dim);
 #define PROX_REGQ_DIM(DT, D)                                                                                  \
-  launch_regq_dim<DT, D>(h, n_rows, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, out, s)
+  launch_regq_dim<DT, D>(h, X, xnrm, n_rows, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, out, s)
   if (h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16) {
     if (dim == 384) PROX_REGQ_DIM(kDtypeBF16, 384);
     else PROX_REGQ_DIM(kDtypeBF16, 256);
@@ -490,11 +485,30 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     }
     const bool regq = regq_supported(int(h->cfg.corpus_dtype), dim);
     const int G = regq ? h->scan_blocks_regq : h->scan_blocks;
+    if (regq && seed && N >= 128L * kSeedRows) {
+      // A long corpus gets a second, longer sample (the next N / 32 rows, at most kSeedRows2), scanned with the
+      // first sample's bound: the bound it yields lets through a sixteenth of the rows the first one would, and
+      // with one wave per SIMD in the register-resident scan every candidate appended is matrix time lost.
+      long rows2 = N / 32 < kSeedRows2 ? N / 32 : kSeedRows2;
+      rows2 -= rows2 % 128;
+      int g2 = int(rows2 / 1024);   // eight tiles per block
+      if (g2 > G) g2 = G;
+      const char* X2 = static_cast<const char*>(h->cfg.corpus) + size_t(kSeedRows) * dim * (bf16 ? 2 : 4);
+      for (int base = 0; base < m_limit; base += kScanPassQueries) {
+        const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
+        launch_regq_scan(h, X2, h->xnrm + kSeedRows, rows2, g2, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed,
+                         h->pairs[cur], s);
+      }
+      cur = enqueue_merge_levels(h, cur, long(g2) * kp, kp, m_count_ptr, m_limit, s, kp);
+      seed = h->pairs[cur];   // (row numbers in these keys count from the sample's first row; only scores are used)
+      cur ^= 1;
+    }
     for (int base = 0; base < m_limit; base += kScanPassQueries) {
       const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
       prof_begin(h, s);
       if (regq)
-        launch_regq_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], s);
+        launch_regq_scan(h, h->cfg.corpus, h->xnrm, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed,
+                         h->pairs[cur], s);
       else
         launch_batched_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], false,
                             s);
