@@ -142,7 +142,12 @@ typedef struct proximity_stats_t {
                                 k + 8 candidates because the second ranking had no room: more than
                                 2048 rows within the bound of the k-th (thousands of identical
                                 documents).  0 means every list returned so far is provably exact  */
-  uint64_t reserved[6];
+  uint64_t probe_workspace_bytes; /* device memory the flat cache's probe holds beside keys and values:
+                                     float32 scores of two row ranges of a batch against every key, the
+                                     candidate lists, the resolver's state between ranges.  Fixed at
+                                     creation; at most about 0.5 GiB unless capacity + max_batch
+                                     exceeds a million                                              */
+  uint64_t reserved[5];
 } proximity_stats_t;
 
 /*

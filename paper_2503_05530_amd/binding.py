@@ -36,7 +36,7 @@ class ProximityConfig(C.Structure):
 class ProximityStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("queries", "hits", "misses", "inserts", "evictions", "size",
                                           "inbatch_hits", "dense_resolves", "slack_exhausted",
-                                          "slack_unresolved")] + [("reserved", C.c_uint64 * 6)]
+                                          "slack_unresolved", "probe_workspace_bytes")] + [("reserved", C.c_uint64 * 5)]
 
 
 class ProximityLaunch(C.Structure):

@@ -100,8 +100,9 @@ __device__ __forceinline__ float prefilter_bound(double tau, float qn, float sn,
 __global__ __launch_bounds__(256) void probe_candidates_kernel(
     const float* __restrict__ D32, long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm,
     int dim, int c, int n, const CacheState* __restrict__ st, double tau, int cosine, int cap,
-    int* __restrict__ cand_cnt, int* __restrict__ cand_src, double* __restrict__ cand_d) {
-  const int i = blockIdx.x;
+    int* __restrict__ cand_cnt, int* __restrict__ cand_src, double* __restrict__ cand_d, int row_begin) {
+  // block b: batch row row_begin + b, whose probe row is D32 + b * ldD
+  const int i = row_begin + blockIdx.x;
   if (i >= n) return;
   __shared__ int count;
   __shared__ int list[256];  // cap <= 256
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(256) void probe_candidates_kernel(
   __syncthreads();
   const int size0 = st->size;
   const float qn = srcnrm[c + i];
-  const float* row = D32 + long(i) * ldD;
+  const float* row = D32 + long(blockIdx.x) * ldD;
   for (int s = threadIdx.x; s < size0; s += blockDim.x) {
     const float sn = srcnrm[s];
     if (probe_value(row[s], qn, sn, cosine) <= prefilter_bound(tau, qn, sn, dim, cosine)) {
@@ -188,14 +189,18 @@ __global__ __launch_bounds__(64) void resolver_kernel(
     long long* slot_seq, int* slot_next, int* slot_prev, const int* __restrict__ cand_cnt,
     const int* __restrict__ cand_src, const double* __restrict__ cand_d, int cap, const float* __restrict__ D32,
     long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm, uint8_t* __restrict__ hit_out,
-    int* __restrict__ src_out, int* row_slot, int* __restrict__ miss_list, int* __restrict__ miss_count) {
+    int* __restrict__ src_out, int* row_slot, int* __restrict__ miss_list, int* __restrict__ miss_count,
+    int row_begin, int row_end) {
+  // Rows row_begin .. row_end - 1 of the batch (a batch may take several launches, in row order: all state is
+  // in device memory, and the list of missing rows grows from launch to launch); D32 holds the dense probe
+  // rows of this range, row i at D32 + (i - row_begin) * ldD.
   const int lane = threadIdx.x;
   int size = st->size, head = st->head, tail = st->tail;
   unsigned long long hits = 0, misses = 0, inserts = 0, evictions = 0, inbatch = 0, dense = 0;
-  int M = 0;
+  int M = row_begin > 0 ? *miss_count : 0;
   const double kInf = __longlong_as_double(0x7ff0000000000000ll);
 
-  for (int i = 0; i < n; ++i) {
+  for (int i = row_begin; i < row_end; ++i) {
     const int cnt = cand_cnt ? cand_cnt[i] : 0;  // no probe ran when the cache is disabled
     ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
     if (cnt > 0 && cnt <= cap) {
@@ -221,7 +226,7 @@ __global__ __launch_bounds__(64) void resolver_kernel(
     } else if (cnt > cap) {
       ++dense;
       const float qn = srcnrm[c + i];
-      const float* row = D32 + long(i) * ldD;
+      const float* row = D32 + long(i - row_begin) * ldD;
       float mn = 3.4e38f, snmax = 0.f;
       for (int t = lane; t < size; t += 64) {
         const long long sq = slot_seq[t];
@@ -318,7 +323,7 @@ __global__ __launch_bounds__(64) void resolver_kernel(
     st->size = size;
     st->head = head;
     st->tail = tail;
-    st->queries += (unsigned long long)n;
+    st->queries += (unsigned long long)(row_end - row_begin);
     st->hits += hits;
     st->misses += misses;
     st->inserts += inserts;

@@ -48,6 +48,8 @@ static_assert(kStreamMaxQueries == kSmallRows, "the fused small-call kernels pai
 constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
 constexpr size_t kResolverLdsMax = 147 * 1024;  // dynamic LDS the LDS-state resolver may ask for
 static_assert(kResolverLdsMax + kResolverStaticLds <= 160 * 1024 - 256, "the resolver block must fit the LDS of one CU");
+constexpr size_t kProbeRangeRows = 1024;             // rows of a batch probed and resolved together, at most
+constexpr size_t kProbeScoreBudget = size_t(512) << 20;  // bytes the dense probe scores may take (two ranges)
 constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32 tiles use the split-column kernel
 constexpr size_t kLshLdsMax = 144 * 1024;  // dynamic LDS the bucket resolver may ask for (query + bucket keys)
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
@@ -146,8 +148,17 @@ struct proximity {
   int* slot_next = nullptr;
   int* slot_prev = nullptr;
   CacheState* state = nullptr;
-  float* D32 = nullptr;  // probe scores [max_batch][ldD]
+  float* D32 = nullptr;  // probe scores: [max_batch][ldD], or two buffers of [probe_rows][ldD] (see probe_rows)
   long ldD = 0;
+  // A batch of more than probe_rows rows is probed and resolved in row ranges of that many: the probe of a
+  // range runs on the caller's stream while the resolver walks the range before it on `side`, and the dense
+  // probe scores exist for two ranges at a time.
+  int probe_rows = 0;
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> ev_probe, ev_res;  // per range: its candidates are ready / it has been resolved
+  int* res_image = nullptr;                  // the LDS resolver's state between the ranges of a batch
+  ResolverCarry* res_carry = nullptr;
+  size_t probe_ws_bytes = 0;                 // device memory of the flat cache's probe (scores, lists, carry)
   int* cand_cnt = nullptr;
   int* cand_src = nullptr;
   double* cand_d = nullptr;
@@ -632,6 +643,9 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   DeviceGuard guard(cfg->device);
   auto bail = [&](int code) {
     g_create_error = h->err;
+    for (hipEvent_t e : h->ev_probe) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : h->ev_res) if (e) (void)hipEventDestroy(e);
+    if (h->side) (void)hipStreamDestroy(h->side);
     for (void* p : h->allocs) (void)hipFree(p);
     delete h;
     return code;
@@ -692,10 +706,35 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   TRY_ALLOC(h->state, 1, true);
   h->ldD = long((c + B + 63) / 64 * 64);
   if (!lsh) {  // the dense probe and its candidate lists belong to the flat cache
-    TRY_ALLOC(h->D32, B * size_t(h->ldD), true);
+    // rows per range: as many as two score buffers of that many rows fit the budget, 64..kProbeRangeRows
+    size_t R = kProbeRangeRows;
+    while (R > 64 && 2 * R * size_t(h->ldD) * sizeof(float) > kProbeScoreBudget) R /= 2;
+    h->probe_rows = int(R);
+    const size_t score_rows = B <= R ? B : 2 * R;
+    TRY_ALLOC(h->D32, score_rows * size_t(h->ldD), true);
     TRY_ALLOC(h->cand_cnt, B, true);
     TRY_ALLOC(h->cand_src, B * kCandCap, true);
     TRY_ALLOC(h->cand_d, B * kCandCap, true);
+    TRY_ALLOC(h->res_image, kResolverLdsMax / sizeof(int), false);
+    TRY_ALLOC(h->res_carry, 1, true);
+    h->probe_ws_bytes = score_rows * size_t(h->ldD) * sizeof(float) + B * sizeof(int) +
+                        B * kCandCap * (sizeof(int) + sizeof(double)) + kResolverLdsMax + sizeof(ResolverCarry);
+    if (B > R) {
+      const size_t ranges = (B + R - 1) / R;
+      if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) {
+        h->side = nullptr;
+        h->err = "could not create the resolver's stream";
+        return bail(PROXIMITY_ERR_HIP);
+      }
+      h->ev_probe.assign(ranges, nullptr);
+      h->ev_res.assign(ranges, nullptr);
+      for (size_t i = 0; i < ranges; ++i)
+        if (hipEventCreateWithFlags(&h->ev_probe[i], hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&h->ev_res[i], hipEventDisableTiming) != hipSuccess) {
+          h->err = "could not create the events that order probe and resolver";
+          return bail(PROXIMITY_ERR_HIP);
+        }
+    }
   } else {
     const size_t nb = size_t(1) << h->lsh_bits;
     TRY_ALLOC(h->lsh_planes, size_t(h->lsh_bits) * d, false);
@@ -770,6 +809,9 @@ void proximity_destroy(proximity_t* h) {
   (void)hipDeviceSynchronize();
   for (hipEvent_t e : h->ev0) (void)hipEventDestroy(e);
   for (hipEvent_t e : h->ev1) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->ev_probe) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->ev_res) if (e) (void)hipEventDestroy(e);
+  if (h->side) (void)hipStreamDestroy(h->side);
   for (void* p : h->allocs) (void)hipFree(p);
   delete h;
 }
@@ -969,40 +1011,64 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   } else {
   // the rows into the batch buffer and their norms, in one launch
   copy_rows_norms_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(queries, nn, dim, batch_rows, h->srcnrm + c);
-  int have_probe = 0;
-  if (c > 0) {
-    have_probe = 1;
+  const int have_probe = c > 0 ? 1 : 0;
+  const int lru = h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0;
+  // scores and candidate lists of rows r0 .. r1-1 against the slots and the batch rows before r1
+  auto enqueue_probe = [&](int r0, int r1, float* D) {
+    const int rows = r1 - r0, n_src = c + r1;
+    const float* Q = batch_rows + size_t(r0) * dim;
     if (nn <= kStreamMaxQueries) {
       const int mq = stream_group(dim, nn);
       for (int m0 = 0; m0 < nn; m0 += mq)
         launch_scores_stream<kDtypeF32, false>(h, mq, h->srcs, h->srcnrm, long(c) + nn, dim, batch_rows, nullptr, nullptr,
-                                        nn, m0, h->D32 + size_t(m0) * h->ldD, h->ldD, 0, s);
-    } else if (long((c + nn + 31) / 32) * ((nn + 31) / 32) <= kProbeSmallBlocks) {
-      probe_mfma_small_kernel<<<dim3((c + nn + 31) / 32, (nn + 31) / 32), dim3(256), 0, s>>>(
-          h->srcs, h->srcnrm, c + nn, batch_rows, nn, dim, h->D32, h->ldD);
+                                        nn, m0, D + size_t(m0) * h->ldD, h->ldD, 0, s);
+    } else if (long((n_src + 31) / 32) * ((rows + 31) / 32) <= kProbeSmallBlocks) {
+      probe_mfma_small_kernel<<<dim3((n_src + 31) / 32, (rows + 31) / 32), dim3(256), 0, s>>>(
+          h->srcs, h->srcnrm, n_src, Q, rows, dim, D, h->ldD);
     } else {
-      probe_mfma_dense_kernel<<<dim3((c + nn + 127) / 128, (nn + 127) / 128), dim3(256), 0, s>>>(
-          h->srcs, h->srcnrm, c + nn, batch_rows, nn, dim, h->D32, h->ldD);
+      probe_mfma_dense_kernel<<<dim3((n_src + 127) / 128, (rows + 127) / 128), dim3(256), 0, s>>>(
+          h->srcs, h->srcnrm, n_src, Q, rows, dim, D, h->ldD);
     }
-    probe_candidates_kernel<<<dim3(nn), dim3(256), 0, s>>>(h->D32, h->ldD, h->srcs, h->srcnrm, dim, c, nn, h->state,
-                                                           tau_key, cos_keys, kCandCap, h->cand_cnt, h->cand_src,
-                                                           h->cand_d);
-  }
-  // the sequential resolver: with its state in LDS whenever that fits
+    probe_candidates_kernel<<<dim3(rows), dim3(256), 0, s>>>(D, h->ldD, h->srcs, h->srcnrm, dim, c, nn, h->state, tau_key,
+                                                             cos_keys, kCandCap, h->cand_cnt, h->cand_src, h->cand_d, r0);
+  };
+  // The sequential resolver over rows r0 .. r1-1, with its state in LDS whenever that fits.
   // Bringing the eviction order on chip costs about 2.5 ns per key; walking it in device memory about
   // 1.5 us per row.  A few rows against a large cache are cheaper in place.
   const bool few_rows = long(nn) * 600 < long(c);
-  if (have_probe && !few_rows && resolver_lds_fits(size_t(c), size_t(nn), kResolverLdsMax)) {
-    resolver_lds_kernel<<<dim3(1), dim3(kResolverThreads), resolver_lds_bytes(size_t(c), size_t(nn)), s>>>(
-        nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq, tau_key, cos_keys, h->state, h->slot_seq,
-        h->slot_next, h->slot_prev, h->cand_cnt, h->cand_src, h->cand_d, kCandCap, h->D32, h->ldD, h->srcs, h->srcnrm,
-        out_hit, h->src, h->row_slot, h->miss_list, h->miss_count);
+  const bool in_lds = have_probe && !few_rows && resolver_lds_fits(size_t(c), size_t(nn), kResolverLdsMax);
+  auto enqueue_resolver = [&](int r0, int r1, const float* D, hipStream_t rs) {
+    if (in_lds)
+      resolver_lds_kernel<<<dim3(1), dim3(kResolverThreads), resolver_lds_bytes(size_t(c), size_t(nn)), rs>>>(
+          nn, c, dim, lru, base_seq, tau_key, cos_keys, h->state, h->slot_seq, h->slot_next, h->slot_prev, h->cand_cnt,
+          h->cand_src, h->cand_d, kCandCap, D, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot, h->miss_list,
+          h->miss_count, r0, r1, r0 == 0 ? 1 : 0, r1 == nn ? 1 : 0, h->res_image, h->res_carry);
+    else
+      resolver_kernel<<<dim3(1), dim3(64), 0, rs>>>(nn, c, dim, lru, base_seq, tau_key, cos_keys, h->state, h->slot_seq,
+                                                    h->slot_next, h->slot_prev, have_probe ? h->cand_cnt : nullptr,
+                                                    h->cand_src, h->cand_d, kCandCap, D, h->ldD, h->srcs, h->srcnrm,
+                                                    out_hit, h->src, h->row_slot, h->miss_list, h->miss_count, r0, r1);
+  };
+  const int R = h->probe_rows;
+  if (!have_probe || nn <= R) {
+    if (have_probe) enqueue_probe(0, nn, h->D32);
+    enqueue_resolver(0, nn, h->D32, s);
   } else {
-    resolver_kernel<<<dim3(1), dim3(64), 0, s>>>(nn, c, dim, h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0, base_seq,
-                                                 tau_key, cos_keys, h->state, h->slot_seq, h->slot_next, h->slot_prev,
-                                                 have_probe ? h->cand_cnt : nullptr, h->cand_src, h->cand_d, kCandCap,
-                                                 h->D32, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot,
-                                                 h->miss_list, h->miss_count);
+    // Row ranges: the probe of range g on the caller's stream, its resolution on the side stream, which so walks
+    // range g while range g + 1 is being multiplied.  A score buffer is written again two ranges later, once the
+    // resolver has left it.  The side stream joins the caller's stream before anything else is enqueued.
+    const int ranges = (nn + R - 1) / R;
+    for (int g = 0; g < ranges; ++g) {
+      const int r0 = g * R, r1 = r0 + R < nn ? r0 + R : nn;
+      float* D = h->D32 + size_t(g & 1) * size_t(R) * size_t(h->ldD);
+      if (g >= 2) HIP_TRY(h, hipStreamWaitEvent(s, h->ev_res[g - 2], 0));
+      enqueue_probe(r0, r1, D);
+      HIP_TRY(h, hipEventRecord(h->ev_probe[g], s));
+      HIP_TRY(h, hipStreamWaitEvent(h->side, h->ev_probe[g], 0));
+      enqueue_resolver(r0, r1, D, h->side);
+      HIP_TRY(h, hipEventRecord(h->ev_res[g], h->side));
+    }
+    HIP_TRY(h, hipStreamWaitEvent(s, h->ev_res[ranges - 1], 0));
   }
   }
   const void* X = h->cfg.n_docs > 0 ? h->cfg.corpus : nullptr;
@@ -1040,6 +1106,7 @@ int proximity_stats(const proximity_t* h, proximity_stats_t* out) {
   HIP_TRY(hh, hipMemcpy(&sl, h->slack, sizeof sl, hipMemcpyDeviceToHost));
   out->slack_exhausted = sl.exhausted;
   out->slack_unresolved = sl.unresolved;
+  out->probe_workspace_bytes = h->probe_ws_bytes;
   return PROXIMITY_OK;
 }
 

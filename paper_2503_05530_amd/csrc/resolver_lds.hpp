@@ -63,9 +63,17 @@ struct ResolverChunk {
 
 constexpr size_t kResolverStaticLds = 2 * sizeof(ResolverChunk) + 256;
 
+// A batch may be resolved in several launches, each over a range of rows (the probe of later rows then runs
+// beside the walk of earlier ones, and the dense probe rows need to exist for one range at a time only).
+// Between the launches the LDS state lives in device memory as it is (an image of the dynamic LDS) together
+// with the walk's scalars; the linked list is read by the first launch and rewritten by the last.
+struct ResolverCarry {
+  int size, qnext, qtail, hits, evictions, inbatch, dense, M;
+};
+
 // Dynamic LDS of the kernel: queue [c + n], qpos [c], row-of-slot [c], slot-of-row [n], source-of-row [n],
 // 16 bits each; the list ranking at entry uses the same memory as two buffers of c packed words.
-inline size_t resolver_lds_bytes(size_t c, size_t n) {
+__host__ __device__ inline size_t resolver_lds_bytes(size_t c, size_t n) {
   const size_t state = 2 * (c + n) + 2 * c + 2 * c + 2 * n + 2 * n;
   const size_t rank = 8 * c;
   return ((state > rank ? state : rank) + 15) & ~size_t(15);
@@ -99,7 +107,10 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
     const int* __restrict__ cand_src, const double* __restrict__ cand_d, int cap, const float* __restrict__ D32,
     long ldD, const float* __restrict__ srcs, const float* __restrict__ srcnrm, uint8_t* __restrict__ hit_out,
     int* __restrict__ src_out, int* __restrict__ row_slot, int* __restrict__ miss_list,
-    int* __restrict__ miss_count) {
+    int* __restrict__ miss_count, int row_begin, int row_end, int first, int last, int* __restrict__ image,
+    ResolverCarry* __restrict__ carry) {
+  // rows row_begin .. row_end - 1 (row_begin a multiple of 64); D32 holds the dense probe rows of this range,
+  // row i at D32 + (i - row_begin) * ldD
   extern __shared__ int lds_raw[];
   __shared__ ResolverChunk chunk[2];
   __shared__ int wave_total[kResolverThreads / 64];
@@ -116,7 +127,7 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
     for (int e = t; e < 64 * kStageCands; e += nt) {
       const int r = e / kStageCands, p = e % kStageCands;
       const int i = i0 + r;
-      const int cn = i < n ? cand_cnt[i] : -1;  // rows past the end: neither empty nor a list
+      const int cn = i < row_end ? cand_cnt[i] : -1;  // rows past the end: neither empty nor a list
       if (p == 0) ch.cnt[r] = cn;
       if (cn <= cap && p < cn) {
         ch.src[r][p] = cand_src[long(i) * cap + p];
@@ -127,7 +138,8 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
 
   // ---- the eviction order: linked list -> queue (position = size - 1 - distance to the tail) ----
   const int size0 = __builtin_amdgcn_readfirstlane(st->size);
-  {
+  const int image_words = int(resolver_lds_bytes(size_t(c), size_t(n)) / 4);
+  if (first) {
     unsigned* from = reinterpret_cast<unsigned*>(lds_raw);  // packed: next slot << 16 | distance to the tail so far
     unsigned* to = from + c;
     for (int s = tid; s < size0; s += NT) {
@@ -167,23 +179,36 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
       }
     }
   }
-  for (int s = tid; s < c; s += NT) lrow[s] = -1;
-  for (int i = tid; i < n; i += NT) lslot[i] = (unsigned short)kNone;
-  stage_chunk(0, chunk[0], tid, NT);
+  if (first) {
+    for (int s = tid; s < c; s += NT) lrow[s] = -1;
+    for (int i = tid; i < n; i += NT) lslot[i] = (unsigned short)kNone;
+  } else {
+    for (int w = tid; w < image_words; w += NT) lds_raw[w] = image[w];
+  }
+  stage_chunk(row_begin, chunk[0], tid, NT);
   __syncthreads();
 
   // walked by the first wave only
-  int size = size0;
-  int qnext = 0, qtail = size0; // queue positions: next one the window has not seen, end
+  // (a later launch of the batch takes the scalars up where the one before left them; the window is loaded
+  // again from the position it was last loaded from: which of its entries are still current follows from qpos)
+  const bool resume = !first;
+  int size = resume ? __builtin_amdgcn_readfirstlane(carry->size) : size0;
+  int qnext = resume ? __builtin_amdgcn_readfirstlane(carry->qnext) : 0;       // queue positions: next one the window has not seen,
+  int qtail = resume ? __builtin_amdgcn_readfirstlane(carry->qtail) : size0;   // end
+  int qwin = qnext;             // where the window in registers was loaded from
   int wslot = int(kNone);       // window: this lane's queue entry
   unsigned long long wmask = 0; //         lanes whose entry is still current and not taken
-  // counters of this call; every miss inserts, so misses and insertions both equal M
-  int hits = 0, evictions = 0, inbatch = 0, dense = 0;
-  int M = 0;
+  // counters of this batch; every miss inserts, so misses and insertions both equal M
+  int hits = resume ? __builtin_amdgcn_readfirstlane(carry->hits) : 0;
+  int evictions = resume ? __builtin_amdgcn_readfirstlane(carry->evictions) : 0;
+  int inbatch = resume ? __builtin_amdgcn_readfirstlane(carry->inbatch) : 0;
+  int dense = resume ? __builtin_amdgcn_readfirstlane(carry->dense) : 0;
+  int M = resume ? __builtin_amdgcn_readfirstlane(carry->M) : 0;
   const double kInf = __longlong_as_double(0x7ff0000000000000ll);
-  const int n_chunks = (n + 63) / 64;
+  const int ck_begin = row_begin / 64, ck_end = (row_end + 63) / 64;
 
   auto window_load = [&]() {
+    qwin = qnext;
     const int pos = qnext + lane;
     int sl = int(kNone);
     bool cur = false;
@@ -265,15 +290,15 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
     if (policy_lru) touch(s < c ? s : uniform(lslot[s - c]));  // also when it is at the back already
   };
 
-  for (int ck = 0; ck < n_chunks; ++ck) {
+  for (int ck = ck_begin; ck < ck_end; ++ck) {
     const int i0 = ck * 64;
     // (the wave number as a scalar: the compiler then sees that whole waves take one side, and
     // the walk's state does not pass through the join of a divergent branch)
     if (__builtin_amdgcn_readfirstlane(wib) != 0) {
-      if (ck + 1 < n_chunks) stage_chunk(i0 + 64, chunk[(ck + 1) & 1], tid - 64, NT - 64);
+      if (ck + 1 < ck_end) stage_chunk(i0 + 64, chunk[(ck + 1 - ck_begin) & 1], tid - 64, NT - 64);
     } else {
-      const ResolverChunk& ch = chunk[ck & 1];
-      const int rows = n - i0 < 64 ? n - i0 : 64;
+      const ResolverChunk& ch = chunk[(ck - ck_begin) & 1];
+      const int rows = row_end - i0 < 64 ? row_end - i0 : 64;
       const int my_cnt = ch.cnt[lane];
       int my_s0 = -1;
       bool my_within = false;
@@ -365,7 +390,7 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
           ++dense;
           ResolverBest best{kInf, 0x7fffffffffffffffll, -1};
           const float qn = srcnrm[c + i];
-          const float* row = D32 + long(i) * ldD;
+          const float* row = D32 + long(i - row_begin) * ldD;
           float mn = 3.4e38f, snmax = 0.f;
           for (int t = lane; t < size; t += 64) {
             const int s = lrow[t] >= 0 ? c + lrow[t] : t;
@@ -420,16 +445,25 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
   if (tid == 0) {
     walk_out[0] = size;
     walk_out[1] = qtail;
-    st->queries += (unsigned long long)n;
-    st->hits += (unsigned long long)hits;
-    st->misses += (unsigned long long)M;
-    st->inserts += (unsigned long long)M;
-    st->evictions += (unsigned long long)evictions;
-    st->inbatch_hits += (unsigned long long)inbatch;
-    st->dense_resolves += (unsigned long long)dense;
-    *miss_count = M;
+    if (last) {
+      st->queries += (unsigned long long)n;
+      st->hits += (unsigned long long)hits;
+      st->misses += (unsigned long long)M;
+      st->inserts += (unsigned long long)M;
+      st->evictions += (unsigned long long)evictions;
+      st->inbatch_hits += (unsigned long long)inbatch;
+      st->dense_resolves += (unsigned long long)dense;
+      *miss_count = M;
+    } else {
+      const ResolverCarry out{size, wmask ? qwin : qnext, qtail, hits, evictions, inbatch, dense, M};
+      *carry = out;
+    }
   }
   __syncthreads();
+  if (!last) {
+    for (int w = tid; w < image_words; w += NT) image[w] = lds_raw[w];
+    return;
+  }
   const int size_end = walk_out[0], q_end = walk_out[1];
   for (int s = tid; s < c; s += NT)
     if (lrow[s] >= 0) slot_seq[s] = base_seq + lrow[s];
