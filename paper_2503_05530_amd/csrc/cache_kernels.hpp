@@ -142,6 +142,17 @@ __global__ __launch_bounds__(256) void probe_candidates_kernel(
   }
 }
 
+// Before the first probe of a batch: empty candidate lists and overflow lists, and the number of live
+// slots as it is now (the resolver of an early range may change the state while a later range is probed).
+__global__ __launch_bounds__(256) void probe_prepare_kernel(int n, int* __restrict__ cand_cnt, int n_ranges,
+                                                            int* __restrict__ ovf_cnt, const CacheState* __restrict__ st,
+                                                            int* __restrict__ live_slots) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t < n) cand_cnt[t] = 0;
+  if (t < n_ranges) ovf_cnt[t] = 0;
+  if (t == 0) *live_slots = st->size;
+}
+
 // ---------------------------------------------------------------------------
 // Order-preserving resolver: Algorithm 1 after the distances (nearest key, tolerance test,
 // eviction, insertion) for rows 0..n-1 in order,

@@ -612,21 +612,18 @@ __global__ __launch_bounds__(256, TM == 96 ? 1 : 2) void scan_mfma_dma_kernel(
 #undef PROX_RING
 }
 
-// ---------------------------------------------------------------------------
-// Cache probe, dense output.  Operand A = batch rows (queries), operand B =
-// sources [slot keys ; batch rows]; D[(m) * ldD + s] = |s|^2 - 2 q_m . s.
-// Grid: x = source tiles of 128, y = query tiles of 128.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void probe_mfma_dense_kernel(const float* __restrict__ srcs,
-                                                                  const float* __restrict__ srcnrm, int n_src,
-                                                                  const float* __restrict__ Q, int n_q, int dim,
-                                                                  float* __restrict__ D, long ldD) {
+// One 128 x 128 tile of the dense probe (see probe_mfma_dense_kernel): source tile tile_x, query tile tile_y.
+// With row_list, query m is row row_list[m] of Q and its scores go to row row_list[m] - row_origin of D.
+__device__ __forceinline__ void probe_mfma_dense_tile(const float* __restrict__ srcs, const float* __restrict__ srcnrm,
+                                                      int n_src, const float* __restrict__ Q, int n_q, int dim,
+                                                      float* __restrict__ D, long ldD, const int* __restrict__ row_list,
+                                                      int row_origin, int tile_x, int tile_y) {
   constexpr int T = 128, RB = 2, CB = 2;
   __shared__ __attribute__((aligned(16))) float As[T * kLdsK];
   __shared__ __attribute__((aligned(16))) float Bs[T * kLdsK];
   const int tid = threadIdx.x, lane = tid & 63, wib = tid >> 6;
   const int a_row0 = (wib & 1) * 64, b_row0 = (wib >> 1) * 64;
-  const int q0 = blockIdx.y * T, s0 = blockIdx.x * T;
+  const int q0 = tile_y * T, s0 = tile_x * T;
 
   SlabF32<T> qa, sb;
   const float* qrows[SlabF32<T>::NCH];
@@ -634,7 +631,7 @@ __global__ __launch_bounds__(256, 2) void probe_mfma_dense_kernel(const float* _
 #pragma unroll
   for (int i = 0; i < SlabF32<T>::NCH; ++i) {
     const int r = (tid + 256 * i) >> 3;
-    qrows[i] = q0 + r < n_q ? Q + long(q0 + r) * dim : nullptr;
+    qrows[i] = q0 + r < n_q ? Q + long(row_list ? row_list[q0 + r] : q0 + r) * dim : nullptr;
     srows[i] = s0 + r < n_src ? srcs + long(s0 + r) * dim : nullptr;
   }
   f32x16 acc[RB][CB];
@@ -668,8 +665,37 @@ __global__ __launch_bounds__(256, 2) void probe_mfma_dense_kernel(const float* _
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int q = q0 + a_row0 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (q < n_q && sidx < n_src) D[long(q) * ldD + sidx] = sn - 2.f * acc[i][j][e];
+        if (q < n_q && sidx < n_src) D[long(row_list ? row_list[q] - row_origin : q) * ldD + sidx] = sn - 2.f * acc[i][j][e];
       }
+  }
+}
+
+
+// ---------------------------------------------------------------------------
+// Cache probe, dense output.  Operand A = batch rows (queries), operand B =
+// sources [slot keys ; batch rows]; D[(m) * ldD + s] = |s|^2 - 2 q_m . s.
+// Grid: x = source tiles of 128, y = query tiles of 128.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256, 2) void probe_mfma_dense_kernel(const float* __restrict__ srcs,
+                                                                  const float* __restrict__ srcnrm, int n_src,
+                                                                  const float* __restrict__ Q, int n_q, int dim,
+                                                                  float* __restrict__ D, long ldD) {
+  probe_mfma_dense_tile(srcs, srcnrm, n_src, Q, n_q, dim, D, ldD, nullptr, 0, blockIdx.x, blockIdx.y);
+}
+
+// The same for the rows row_list[0 .. *row_count) of Q, whose scores go to row row_list[m] - row_origin of D: the
+// dense rows of just those batch rows whose candidate list overflowed.  The grid does not depend on their number
+// (which the host does not know, and which is zero as a rule): blocks share the tiles round robin.
+__global__ __launch_bounds__(256, 2) void probe_mfma_dense_listed_kernel(
+    const float* __restrict__ srcs, const float* __restrict__ srcnrm, int n_src, const float* __restrict__ Q, int dim,
+    float* __restrict__ D, long ldD, const int* __restrict__ row_list, const int* __restrict__ row_count,
+    int row_origin) {
+  const int n_q = *row_count;
+  if (n_q == 0) return;
+  const int tx = (n_src + 127) / 128, ty = (n_q + 127) / 128;
+  for (int t = blockIdx.x; t < tx * ty; t += gridDim.x) {
+    __syncthreads();  // the tile before has been read out of LDS
+    probe_mfma_dense_tile(srcs, srcnrm, n_src, Q, n_q, dim, D, ldD, row_list, row_origin, t % tx, t / tx);
   }
 }
 

@@ -48,7 +48,7 @@ static_assert(kStreamMaxQueries == kSmallRows, "the fused small-call kernels pai
 constexpr int kScanPassQueries = 1024; // queries one launch of the batched scan covers
 constexpr size_t kResolverLdsMax = 147 * 1024;  // dynamic LDS the LDS-state resolver may ask for
 static_assert(kResolverLdsMax + kResolverStaticLds <= 160 * 1024 - 256, "the resolver block must fit the LDS of one CU");
-constexpr size_t kProbeRangeRows = 1024;             // rows of a batch probed and resolved together, at most
+constexpr size_t kProbeRangeRows = 1536;             // rows of a batch probed and resolved together, at most
 constexpr size_t kProbeScoreBudget = size_t(512) << 20;  // bytes the dense probe scores may take (two ranges)
 constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32 tiles use the split-column kernel
 constexpr size_t kLshLdsMax = 144 * 1024;  // dynamic LDS the bucket resolver may ask for (query + bucket keys)
@@ -155,7 +155,10 @@ struct proximity {
   // probe scores exist for two ranges at a time.
   int probe_rows = 0;
   hipStream_t side = nullptr;
-  std::vector<hipEvent_t> ev_probe, ev_res;  // per range: its candidates are ready / it has been resolved
+  std::vector<hipEvent_t> ev_probe, ev_go, ev_res;  // per range: candidates ready / resolver next in line / resolved
+  int* ovf_cnt = nullptr;                    // per range: rows whose candidate list overflowed, and which
+  int* ovf_list = nullptr;
+  int* live_slots = nullptr;                 // keys resident when the batch started
   int* res_image = nullptr;                  // the LDS resolver's state between the ranges of a batch
   ResolverCarry* res_carry = nullptr;
   size_t probe_ws_bytes = 0;                 // device memory of the flat cache's probe (scores, lists, carry)
@@ -377,7 +380,7 @@ void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows
   if (rem_max > (LO) && (!known || rem_max <= (HI)))                                                             \
   scan_regq_kernel<DT, DIM, WQ><<<dim3(G), dim3(256), 0, s>>>(X, xnrm, n_rows, Qbase, qlist, h->qplanes,               \
                                                               plane_stride, m_count_ptr, m_limit, mb, LO, HI, kp, seed, \
-                                                              h->topk_buf, out, cosine)
+                                                              h->topk_buf, out, cosine, RegqEmit{})
     PROX_REGQ(1, 0, QW);
     PROX_REGQ(2, QW, 2 * QW);
     PROX_REGQ(4, 2 * QW, 0x7fffffff);
@@ -644,6 +647,8 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   auto bail = [&](int code) {
     g_create_error = h->err;
     for (hipEvent_t e : h->ev_probe) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : h->ev_go) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->ev_go) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_res) if (e) (void)hipEventDestroy(e);
     if (h->side) (void)hipStreamDestroy(h->side);
     for (void* p : h->allocs) (void)hipFree(p);
@@ -708,28 +713,33 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   if (!lsh) {  // the dense probe and its candidate lists belong to the flat cache
     // rows per range: as many as two score buffers of that many rows fit the budget, 64..kProbeRangeRows
     size_t R = kProbeRangeRows;
-    while (R > 64 && 2 * R * size_t(h->ldD) * sizeof(float) > kProbeScoreBudget) R /= 2;
+    while (R > 64 && 2 * R * size_t(h->ldD) * sizeof(float) > kProbeScoreBudget) R = (R / 2 + 63) / 64 * 64;
     h->probe_rows = int(R);
     const size_t score_rows = B <= R ? B : 2 * R;
     TRY_ALLOC(h->D32, score_rows * size_t(h->ldD), true);
     TRY_ALLOC(h->cand_cnt, B, true);
     TRY_ALLOC(h->cand_src, B * kCandCap, true);
     TRY_ALLOC(h->cand_d, B * kCandCap, true);
+    TRY_ALLOC(h->ovf_cnt, (B + 63) / 64 + 4, true);
+    TRY_ALLOC(h->ovf_list, B, true);
+    TRY_ALLOC(h->live_slots, 1, true);
     TRY_ALLOC(h->res_image, kResolverLdsMax / sizeof(int), false);
     TRY_ALLOC(h->res_carry, 1, true);
-    h->probe_ws_bytes = score_rows * size_t(h->ldD) * sizeof(float) + B * sizeof(int) +
+    h->probe_ws_bytes = score_rows * size_t(h->ldD) * sizeof(float) + 3 * B * sizeof(int) +
                         B * kCandCap * (sizeof(int) + sizeof(double)) + kResolverLdsMax + sizeof(ResolverCarry);
     if (B > R) {
-      const size_t ranges = (B + R - 1) / R;
+      const size_t ranges = B / 64 + 4;
       if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) {
         h->side = nullptr;
         h->err = "could not create the resolver's stream";
         return bail(PROXIMITY_ERR_HIP);
       }
       h->ev_probe.assign(ranges, nullptr);
+      h->ev_go.assign(ranges, nullptr);
       h->ev_res.assign(ranges, nullptr);
       for (size_t i = 0; i < ranges; ++i)
         if (hipEventCreateWithFlags(&h->ev_probe[i], hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&h->ev_go[i], hipEventDisableTiming) != hipSuccess ||
             hipEventCreateWithFlags(&h->ev_res[i], hipEventDisableTiming) != hipSuccess) {
           h->err = "could not create the events that order probe and resolver";
           return bail(PROXIMITY_ERR_HIP);
@@ -810,6 +820,7 @@ void proximity_destroy(proximity_t* h) {
   for (hipEvent_t e : h->ev0) (void)hipEventDestroy(e);
   for (hipEvent_t e : h->ev1) (void)hipEventDestroy(e);
   for (hipEvent_t e : h->ev_probe) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->ev_go) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : h->ev_res) if (e) (void)hipEventDestroy(e);
   if (h->side) (void)hipStreamDestroy(h->side);
   for (void* p : h->allocs) (void)hipFree(p);
@@ -1013,10 +1024,38 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   copy_rows_norms_kernel<<<dim3((nn + 3) / 4), dim3(256), 0, s>>>(queries, nn, dim, batch_rows, h->srcnrm + c);
   const int have_probe = c > 0 ? 1 : 0;
   const int lru = h->cfg.policy == PROXIMITY_POLICY_LRU ? 1 : 0;
-  // scores and candidate lists of rows r0 .. r1-1 against the slots and the batch rows before r1
-  auto enqueue_probe = [&](int r0, int r1, float* D) {
+  // Candidate lists of rows r0 .. r1-1 (range g) against the slots and the batch rows before them.
+  // Euclidean keys of the dimensions the register-resident kernel is built for: that kernel lists the candidates
+  // itself, and dense scores are made for the rows whose list overflowed only (worth its set-up from a couple
+  // of thousand sources on).  Otherwise: dense scores of every row of the range, and the lists from those.
+  const bool listing = have_probe && !cos_keys && regq_supported(kDtypeF32, dim) && nn >= 64 && long(c) + nn >= 2048;
+  if (listing)
+    probe_prepare_kernel<<<dim3((nn + 255) / 256), dim3(256), 0, s>>>(nn, h->cand_cnt, (nn + 63) / 64 + 4, h->ovf_cnt,
+                                                                       h->state, h->live_slots);
+  auto enqueue_probe = [&](int g, int r0, int r1, float* D, bool beside_resolver) {
     const int rows = r1 - r0, n_src = c + r1;
     const float* Q = batch_rows + size_t(r0) * dim;
+    if (listing) {
+      // Blocks: 64 rows each, a slice's sources shared by the blocks that serve it; one block per CU.  Beside the
+      // resolver, whose block needs a CU to itself, eight CUs stay free: workgroups go to the eight XCDs in turn
+      // whatever their load, so a free CU helps the resolver only if it is in the XCD its block is sent to
+      // (with 255 blocks the resolver waited for most of a probe).
+      const int slices = (rows + 63) / 64, tiles = (n_src + 127) / 128;
+      long nb = h->n_cu - (beside_resolver ? 8 : 0);
+      if (nb > long(slices) * tiles) nb = long(slices) * tiles;
+      if (nb < slices) nb = slices;
+      const RegqEmit em{c,         h->live_slots,  tau_key,         kCandCap, h->cand_cnt, h->cand_src,
+                        h->cand_d, h->ovf_cnt + g, h->ovf_list + r0};
+      if (dim == 768)
+        scan_regq_kernel<kDtypeF32, 768, 4, true><<<dim3((unsigned)nb), dim3(256), 0, s>>>(
+            h->srcs, h->srcnrm, n_src, batch_rows, nullptr, nullptr, 0, nullptr, r1, r0, slices, 0, 0, nullptr, nullptr,
+            nullptr, 0, em);
+      else
+        scan_regq_kernel<kDtypeF32, 384, 4, true><<<dim3((unsigned)nb), dim3(256), 0, s>>>(
+            h->srcs, h->srcnrm, n_src, batch_rows, nullptr, nullptr, 0, nullptr, r1, r0, slices, 0, 0, nullptr, nullptr,
+            nullptr, 0, em);
+      return;   // (enqueue_lists follows, on the stream that resolves the range)
+    }
     if (nn <= kStreamMaxQueries) {
       const int mq = stream_group(dim, nn);
       for (int m0 = 0; m0 < nn; m0 += mq)
@@ -1032,14 +1071,22 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
     probe_candidates_kernel<<<dim3(rows), dim3(256), 0, s>>>(D, h->ldD, h->srcs, h->srcnrm, dim, c, nn, h->state, tau_key,
                                                              cos_keys, kCandCap, h->cand_cnt, h->cand_src, h->cand_d, r0);
   };
+  // After the listing probe: dense scores for the rows whose list overflowed (none, as a rule).
+  auto enqueue_lists = [&](int g, int r0, int r1, float* D, hipStream_t rs) {
+    probe_mfma_dense_listed_kernel<<<dim3(h->n_cu), dim3(256), 0, rs>>>(h->srcs, h->srcnrm, c + r1, batch_rows, dim, D, h->ldD,
+                                                                         h->ovf_list + r0, h->ovf_cnt + g, r0);
+  };
   // The sequential resolver over rows r0 .. r1-1, with its state in LDS whenever that fits.
   // Bringing the eviction order on chip costs about 2.5 ns per key; walking it in device memory about
   // 1.5 us per row.  A few rows against a large cache are cheaper in place.
   const bool few_rows = long(nn) * 600 < long(c);
   const bool in_lds = have_probe && !few_rows && resolver_lds_fits(size_t(c), size_t(nn), kResolverLdsMax);
   auto enqueue_resolver = [&](int r0, int r1, const float* D, hipStream_t rs) {
+    // (beside a probe the block asks for all the LDS it may have: no block of the probe then shares its CU, whose
+    // waves would otherwise take issue slots from the one wave that walks the rows)
     if (in_lds)
-      resolver_lds_kernel<<<dim3(1), dim3(kResolverThreads), resolver_lds_bytes(size_t(c), size_t(nn)), rs>>>(
+      resolver_lds_kernel<<<dim3(1), dim3(kResolverThreads),
+                            rs == s ? resolver_lds_bytes(size_t(c), size_t(nn)) : kResolverLdsMax, rs>>>(
           nn, c, dim, lru, base_seq, tau_key, cos_keys, h->state, h->slot_seq, h->slot_next, h->slot_prev, h->cand_cnt,
           h->cand_src, h->cand_d, kCandCap, D, h->ldD, h->srcs, h->srcnrm, out_hit, h->src, h->row_slot, h->miss_list,
           h->miss_count, r0, r1, r0 == 0 ? 1 : 0, r1 == nn ? 1 : 0, h->res_image, h->res_carry);
@@ -1051,21 +1098,69 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   };
   const int R = h->probe_rows;
   if (!have_probe || nn <= R) {
-    if (have_probe) enqueue_probe(0, nn, h->D32);
+    if (have_probe) enqueue_probe(0, 0, nn, h->D32, false);
+    if (listing) enqueue_lists(0, 0, nn, h->D32, s);
     enqueue_resolver(0, nn, h->D32, s);
   } else {
-    // Row ranges: the probe of range g on the caller's stream, its resolution on the side stream, which so walks
-    // range g while range g + 1 is being multiplied.  A score buffer is written again two ranges later, once the
-    // resolver has left it.  The side stream joins the caller's stream before anything else is enqueued.
-    const int ranges = (nn + R - 1) / R;
+    // Row ranges: the probe of a range on the caller's stream, its resolution on the side stream, which so walks
+    // a range while the next one is being multiplied.  What is left when the last probe ends is the resolution
+    // of the last range, so the last R rows go in two halves.  The side stream joins the
+    // caller's stream before anything else is enqueued.
+    int cut[PROXIMITY_MAX_BATCH / 64 + 4];
+    int ranges = 0, r = 0;
+    // The listing probe runs one block per CU, each over whole tiles of 128 sources for 64 rows: the range size
+    // decides how evenly the tiles divide among the blocks (at 10 000 keys, ranges of 1 024 rows leave the
+    // slowest block with 6 tiles where the average is 5.5).  The size with the best rows x tiles per time of
+    // the slowest block is taken, half a tile's time counted as the fixed cost of a launch.
+    auto listing_rows = [&](int from) {
+      int most = nn - from < R ? nn - from : R;
+      if (nn - from - most < 512) most = nn - from - 512;   // (at least 512 rows stay for the two short last ranges)
+      if (most < 512) return nn - from < R ? nn - from : R;
+      const int nb = h->n_cu - 8;
+      int best = most;
+      double best_rate = 0.0;
+      for (int rows = 512; rows <= most; rows += 64) {
+        const int slices = rows / 64, tiles = (c + from + rows + 127) / 128;
+        const int parts = nb / slices > 0 ? nb / slices : 1;
+        const int per = (tiles + parts - 1) / parts;
+        const double rate = double(rows) * tiles / (per + 0.5);
+        if (rate >= best_rate) {
+          best_rate = rate;
+          best = rows;
+        }
+      }
+      return best;
+    };
+    const int tail = listing && R > 1024 ? 1024 : R;   // rows left for the short last ranges, at most
+    while (nn - r > tail) cut[ranges++] = (r += listing ? listing_rows(r) : R);
+    if (nn - r >= 256) cut[ranges++] = (r += ((nn - r) / 2 + 63) / 64 * 64);
+    if (r < nn) cut[ranges++] = nn;
     for (int g = 0; g < ranges; ++g) {
-      const int r0 = g * R, r1 = r0 + R < nn ? r0 + R : nn;
+      const int r0 = g ? cut[g - 1] : 0, r1 = cut[g];
       float* D = h->D32 + size_t(g & 1) * size_t(R) * size_t(h->ldD);
-      if (g >= 2) HIP_TRY(h, hipStreamWaitEvent(s, h->ev_res[g - 2], 0));
-      enqueue_probe(r0, r1, D);
-      HIP_TRY(h, hipEventRecord(h->ev_probe[g], s));
-      HIP_TRY(h, hipStreamWaitEvent(h->side, h->ev_probe[g], 0));
-      enqueue_resolver(r0, r1, D, h->side);
+      if (listing) {
+        // The listing kernel leaves one CU free (the resolver block needs one to itself), so the probes follow
+        // each other without regard to the resolver.  The (as a rule empty) launch for overflowed rows stays on
+        // this stream: beside a probe that holds every register of its CUs it would wait for room.  It writes a
+        // score buffer, which the resolver of two ranges ago has left by now unless it is far behind.
+        enqueue_probe(g, r0, r1, D, true);
+        if (g >= 2) HIP_TRY(h, hipStreamWaitEvent(s, h->ev_res[g - 2], 0));
+        enqueue_lists(g, r0, r1, D, s);
+        HIP_TRY(h, hipEventRecord(h->ev_probe[g], s));
+        HIP_TRY(h, hipStreamWaitEvent(h->side, h->ev_probe[g], 0));
+        enqueue_resolver(r0, r1, D, h->side);
+      } else {
+        // A score buffer is written again two ranges later, once the resolver has left it.  The dense probe
+        // fills every CU and the resolver block needs one to itself: the probe is held until the side stream has
+        // reached the resolver of the range before, which so is dispatched first.
+        if (g >= 2) HIP_TRY(h, hipStreamWaitEvent(s, h->ev_res[g - 2], 0));
+        if (g >= 1) HIP_TRY(h, hipStreamWaitEvent(s, h->ev_go[g - 1], 0));
+        enqueue_probe(g, r0, r1, D, g >= 1);
+        HIP_TRY(h, hipEventRecord(h->ev_probe[g], s));
+        HIP_TRY(h, hipStreamWaitEvent(h->side, h->ev_probe[g], 0));
+        HIP_TRY(h, hipEventRecord(h->ev_go[g], h->side));
+        enqueue_resolver(r0, r1, D, h->side);
+      }
       HIP_TRY(h, hipEventRecord(h->ev_res[g], h->side));
     }
     HIP_TRY(h, hipStreamWaitEvent(s, h->ev_res[ranges - 1], 0));

@@ -57,6 +57,7 @@
 #include <type_traits>
 
 #include "bf16x3_kernels.hpp"
+#include "cache_kernels.hpp"
 #include "mfma_kernels.hpp"
 
 namespace prox {
@@ -152,18 +153,39 @@ __device__ __forceinline__ uint32_t regq_bf16x2_times_minus2(uint32_t w) {
   return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u);
 }
 
-// The kernel serves the queries m_base .. m_base + QW WQ - 1 of the miss list when the number of queries
-// from m_base on, M - m_base, lies in (rem_lo, rem_hi]; otherwise it returns at once, so the host can launch
-// the shapes for few, some and many queries back to back without knowing M.
+// What the cache probe does with the kernel (EMIT): the "corpus" is the array of sources (slot keys, then the
+// batch rows), the queries are batch rows, and instead of a running top-k every (row, source) pair whose score
+// passes the row's bound is handed on: the candidates that the float64 distance then decides.
+struct RegqEmit {
+  int c;                 // cache slots: sources 0..c-1 are slot keys, c + j is batch row j
+  const int* live_slots; // DEVICE: slots holding a key when the batch started; others are skipped
+  double tau;            // tolerance; the bound of a row follows from it and the row's squared length
+  int cap;               // entries a row's list holds
+  int* cand_cnt;         // [batch rows] candidates found per row (may exceed cap), zero before the first launch
+  int* cand_src;         // [batch rows][cap] the first cap of them, in no particular order,
+  double* cand_d;        // ... and their float64 distances to the row
+  int* ovf_cnt;          // number of rows whose list overflowed, zero before the launch
+  int* ovf_list;         // those rows
+};
+
+// Top-k scan (EMIT false).  The kernel serves the queries m_base .. m_base + QW WQ - 1 of the miss list when the
+// number of queries from m_base on, M - m_base, lies in (rem_lo, rem_hi]; otherwise it returns at once, so the
+// host can launch the shapes for few, some and many queries back to back without knowing M.
 // float32: queries are rows qlist[m] (or m) of Qbase.  bfloat16: Qbase is not used; Qplanes[p][m][:] are the
 // planes written by split_bf16x3_kernel.
 // Output as scan_mfma_dma_kernel: out[((m) * gridDim.x + blockIdx.x) * kp ..], kp sorted keys per (query, block).
-template <int DT, int DIM, int WQ>
+//
+// Cache probe (EMIT true, float32 only).  The batch rows m_base .. m_limit - 1 in slices of QW WQ (rem_lo = the
+// number of slices, at most the grid), each slice against the sources 0 .. c + (its last row): a row is only ever
+// answered by a slot or an earlier row.  Row i's
+// bound is the float32 pre-filter of "distance <= tau" (see below); xnrm holds the sources' squared lengths.
+template <int DT, int DIM, int WQ, bool EMIT = false>
 __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     const void* __restrict__ Xv, const float* __restrict__ xnrm, long n_rows, const float* __restrict__ Qbase,
     const int* __restrict__ qlist, const uint16_t* __restrict__ Qplanes, long plane_stride,
     const int* __restrict__ m_count_ptr, int m_limit, int m_base, int rem_lo, int rem_hi, int kp,
-    const uint64_t* __restrict__ seed, uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out, int cosine) {
+    const uint64_t* __restrict__ seed, uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out, int cosine,
+    RegqEmit emit) {
   constexpr bool F32 = DT == kDtypeF32;
   constexpr int NW = 4;                            // waves per block
   constexpr int NT = NW * 64;
@@ -185,13 +207,26 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   static_assert(NS >= 4 && NS <= SPT, "ring must not run more than one tile ahead (row terms are double-buffered)");
   static_assert(DIM % SLAB_COLS == 0, "whole slabs");
 
+  static_assert(!EMIT || F32, "the probe's keys are float32");
   const int M = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
-  const int rem = M - m_base;
-  if (rem <= rem_lo || rem > rem_hi) return;
-  const int m0 = m_base;
+  // probe: rem_lo is the number of row slices; block b serves slice b % slices and is part b / slices of the blocks
+  // that share that slice's sources (the grid need not be a multiple of the slices: a grid of one block per
+  // free CU is then used whole)
+  const int slices = EMIT ? rem_lo : 1;
+  const int slice = int(blockIdx.x) % slices, part = int(blockIdx.x) / slices;
+  const int parts = EMIT ? int(gridDim.x) / slices + (slice < int(gridDim.x) % slices ? 1 : 0) : int(gridDim.x);
+  const int m0 = EMIT ? m_base + slice * TM : m_base;
+  const int rem = M - m0;
+  if (EMIT ? rem <= 0 : (rem <= rem_lo || rem > rem_hi)) return;
+  if (EMIT) {  // the sources that can answer this block's rows
+    const long upto = long(emit.c) + (m0 + TM < M ? m0 + TM : M);
+    n_rows = upto < n_rows ? upto : n_rows;
+  }
 
   __shared__ __attribute__((aligned(1024))) float ring[NS][kRegqStageFloats];
-  __shared__ __attribute__((aligned(16))) uint64_t wave_scratch[NW][kTopkCap];
+  __shared__ __attribute__((aligned(16))) uint64_t wave_scratch[NW][kTopkCap];   // probe: the block's list of pairs
+  constexpr int kPairCap = NW * kTopkCap;
+  __shared__ int pair_count;
   __shared__ __attribute__((aligned(256))) float nrm_ring[2][TN];   // [tile parity][row], filled by DMA
   __shared__ float bound[TM];
   __shared__ int count[TM];
@@ -212,7 +247,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     int m = m0 + q_local;
     m = m < M ? m : M - 1;
     if constexpr (F32) {
-      const float* q = Qbase + long(qlist ? qlist[m] : m) * DIM;
+      const float* q = Qbase + long(!EMIT && qlist ? qlist[m] : m) * DIM;
 #pragma unroll
       for (int t = 0; t < DIM / 16; ++t) {
         const float4 v = *reinterpret_cast<const float4*>(q + 16 * t + 4 * kg);
@@ -238,11 +273,28 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
   for (int i = tid; i < TM; i += NT) {
-    // starting bound: the kp-th best score of a sample of the corpus, if the caller has one
-    // (a padding key gives +inf); any value at or above the true kp-th best score is valid
-    bound[i] = (seed && m0 + i < M) ? key_score(seed[long(m0 + i) * kp + kp - 1]) : __uint_as_float(0x7f800000u);
+    if constexpr (EMIT) {
+      // Row i passes source s on to the float64 distance when |s|^2 - 2 q.s <= bound.  In exact arithmetic
+      // "distance <= tau" is |s|^2 - 2 q.s <= tau^2 - |q|^2; the float32 score is off by less than
+      // rel (|q|^2 + |s|^2) (prefilter_rel: every product and partial sum rounds once), and a source within
+      // tau has |s| <= |q| + tau, which makes the bound independent of the source.  Rounded upwards.
+      float b = -__builtin_inff();
+      if (m0 + i < M) {
+        const double qn = double(xnrm[emit.c + m0 + i]), rel = double(prefilter_rel(DIM));
+        const double reach = sqrt(qn) + emit.tau;
+        const double bd = emit.tau * emit.tau * (1.0 + 1e-3) + rel * (qn + reach * reach) - qn;
+        b = bd > 3.0e38 ? 3.0e38f : __double2float_ru(bd);
+      }
+      bound[i] = b;
+    } else {
+      // starting bound: the kp-th best score of a sample of the corpus, if the caller has one
+      // (a padding key gives +inf); any value at or above the true kp-th best score is valid
+      bound[i] = (seed && m0 + i < M) ? key_score(seed[long(m0 + i) * kp + kp - 1]) : __uint_as_float(0x7f800000u);
+    }
     count[i] = 0;
   }
+  if (tid == 0) pair_count = 0;
+  const int live_slots = EMIT ? __builtin_amdgcn_readfirstlane(*emit.live_slots) : 0;
 
   // (the block's share of the tiles: values every lane holds alike; passing them through readfirstlane keeps
   // the loop control in scalar registers)
@@ -252,8 +304,8 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     return long(((unsigned long)hi << 32) | lo);
   };
   const long n_tiles = (n_rows + TN - 1) / TN;
-  const long t_begin = uniform(n_tiles * blockIdx.x / gridDim.x);
-  const long t_end = uniform(n_tiles * (blockIdx.x + 1) / gridDim.x);
+  const long t_begin = uniform(n_tiles * part / parts);
+  const long t_end = uniform(n_tiles * (part + 1) / parts);
   uint64_t* my_buf = cand_buf + long(blockIdx.x) * long(TM) * kTopkCap;
   const char* X = static_cast<const char*>(Xv);
   constexpr long ROW_BYTES = long(DIM) * (F32 ? 4 : 2);
@@ -442,10 +494,35 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   bool T_stale = true;
   // One candidate: room from the query's counter (written in assembly so that the compiler does not guard it
   // with a wait for the global->LDS loads in flight, which never touch the counters), then a plain store.
+  const uint32_t pair_count_lds = regq_lds_addr(&pair_count), pair_lds = regq_lds_addr(&wave_scratch[0][0]);
+  // probe, the block's LDS list is full (hundreds of candidates per row: a tolerance far above the distances
+  // between keys): the row is marked as overflowed, which sends it to the dense probe row and the resolver's
+  // search over it.  (A row's count is above cap from the first time an addition crosses cap; that addition
+  // puts the row on the overflow list.)
+  auto overflow_row = [&](int i) {
+    const int before = atomicAdd(&emit.cand_cnt[i], emit.cap + 1);
+    if (before <= emit.cap) emit.ovf_list[atomicAdd(emit.ovf_cnt, 1)] = i;
+  };
   auto append = [&](float sc, uint32_t row) {
-    uint32_t pos;
-    asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(pos) : "v"(my_count_lds), "v"(1u) : "memory");
-    my_q_buf[pos] = pack_key(sc, row);
+    if constexpr (EMIT) {
+      // a slot that held no key, the row itself or a later row: not a source of this row
+      const int i = m0 + q_local, src = int(row);
+      if (!(src < live_slots || (src >= emit.c && src < emit.c + i))) return;
+      // Pairs collect in LDS and go out once at the end of the block (an atomic on device memory here would
+      // wait for every load in flight); a full list falls back to the direct way.
+      uint32_t pos;
+      asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(pos) : "v"(pair_count_lds), "v"(1u) : "memory");
+      if (pos < uint32_t(kPairCap)) {
+        const uint64_t pr = (uint64_t(uint32_t(i)) << 32) | uint32_t(src);
+        asm volatile("ds_write_b64 %0, %1" ::"v"(pair_lds + 8u * pos), "v"(pr) : "memory");
+      } else {
+        overflow_row(i);
+      }
+    } else {
+      uint32_t pos;
+      asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(pos) : "v"(my_count_lds), "v"(1u) : "memory");
+      my_q_buf[pos] = pack_key(sc, row);
+    }
   };
   auto end_of_tile = [&](long tile) {
     regq_tie_matrix_done(acc);
@@ -487,6 +564,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
       if (cut) sift(std::false_type{}, std::true_type{}); else sift(std::false_type{}, std::false_type{});
     }
     start_accumulators(tile + 1);
+    if constexpr (EMIT) return;
     // Do any buffers have to be cut back before the next tile?  Every wave reads the same counts
     // after a plain barrier (no memory fence: loads in flight stay in flight), so all agree.
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -532,6 +610,30 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the loads issued past the last tile
 
+  if constexpr (EMIT) {
+    // ---- the block's pairs to the rows' lists, each with its float64 distance: one wave per pair ----
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+    const int n_pairs = pair_count < kPairCap ? pair_count : kPairCap;
+    const uint64_t* pairs = &wave_scratch[0][0];
+    const float* keys = static_cast<const float*>(Xv);
+    for (int e = wib; e < n_pairs; e += NW) {
+      const int i = int(pairs[e] >> 32), src = int(uint32_t(pairs[e]));
+      int pos = 0;
+      if (lane == 0) {
+        pos = atomicAdd(&emit.cand_cnt[i], 1);
+        if (pos == emit.cap) emit.ovf_list[atomicAdd(emit.ovf_cnt, 1)] = i;
+      }
+      pos = __builtin_amdgcn_readfirstlane(pos);
+      if (pos >= emit.cap) continue;
+      const double d = wave_keydist64(keys + long(emit.c + i) * DIM, keys + long(src) * DIM, DIM, lane, 0);
+      if (lane == 0) {
+        emit.cand_src[long(i) * emit.cap + pos] = src;
+        emit.cand_d[long(i) * emit.cap + pos] = d;
+      }
+    }
+    return;
+  }
   // ---- every query's buffer cut to kp sorted entries and written out ----
   __syncthreads();
   for (int q = wib; q < TM; q += NW) {

@@ -127,11 +127,17 @@ __global__ __launch_bounds__(kResolverThreads) void resolver_lds_kernel(
     for (int e = t; e < 64 * kStageCands; e += nt) {
       const int r = e / kStageCands, p = e % kStageCands;
       const int i = i0 + r;
-      const int cn = i < row_end ? cand_cnt[i] : -1;  // rows past the end: neither empty nor a list
+      // (count and entry are fetched side by side, not the entry after the count: beside a probe that keeps the
+      // memory system busy a dependent pair of loads takes about as long as the walk of a chunk; the entries
+      // exist in memory whatever the count, kStageCands <= cap)
+      const bool real = i < row_end;
+      const int cn = real ? cand_cnt[i] : -1;  // rows past the end: neither empty nor a list
+      const int sv = real ? cand_src[long(i) * cap + p] : 0;
+      const double dv = real ? cand_d[long(i) * cap + p] : 0.0;
       if (p == 0) ch.cnt[r] = cn;
       if (cn <= cap && p < cn) {
-        ch.src[r][p] = cand_src[long(i) * cap + p];
-        ch.d[r][p] = cand_d[long(i) * cap + p];
+        ch.src[r][p] = sv;
+        ch.d[r][p] = dv;
       }
     }
   };

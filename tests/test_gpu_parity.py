@@ -593,6 +593,26 @@ def test_many_candidates_take_the_dense_path(B):
         px.close()
 
 
+def test_many_candidates_in_a_call_probed_in_row_ranges(B):
+    """The same with 2 600 rows in one call: the probe goes in row ranges beside the resolver, a row near the end
+    has hundreds of earlier rows within the tolerance, and the blocks of the listing probe run out of room for
+    their (row, source) pairs, so rows reach the dense path both ways (list overflow, block overflow)."""
+    w = W.WORKLOADS["tiny"]
+    corpus = W.corpus_f32(2000, w.dim, 2)
+    base = W.base_queries(3, w.dim, 8)
+    idx = np.random.default_rng(1).integers(0, 3, size=2600)
+    q = W.perturbed_stream(base, idx, 0.1, 9)
+    for policy, cap in ((po.POLICY_LRU, 2), (po.POLICY_FIFO, 300)):
+        want = po.lookup_stream_deferred(corpus, q, 0.25, cap, 5, policy)
+        px = B.Proximity(gpu_corpus(corpus), w.dim, cap, 5, policy, 2600)
+        got = P.run_stream(px, q, 0.25, 2600, DEV)
+        P.assert_stream_parity(got, want[:4], corpus, q, what="dense path, row ranges")
+        seq, _, _ = px.cache_dump()
+        assert seq.tolist() == want[4].dump_seq().tolist()
+        assert px.stats()["dense_resolves"] > 1000
+        px.close()
+
+
 def test_no_corpus_and_no_cache(B):
     w = W.WORKLOADS["tiny"]
     q = W.stream_for(w, 40)
