@@ -113,11 +113,14 @@ def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, devic
 COUNTER_TRAFFIC = {
     ("scores_stream_kernel", 0, 1_000_000, 768, 4):
         {"fetch_bytes": 1_501_992 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scores_stream_mid_b1.md"},
-    ("scan_mfma_dma_kernel", 64, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_504_671 * 2048, "write_bytes": 7_040 * 1024, "source": "profiles/scan_mfma_mid_b64.md"},
-    ("scan_bf16x3_kernel", 128, 8_000_000, 384, 2):
-        {"fetch_bytes": 3_116_246 * 2048, "write_bytes": 233_673 * 1024,
-         "source": "profiles/scan_bf16x3_lowreuse_b128.md"},
+    ("scan_regq_kernel", 64, 1_000_000, 768, 4):
+        {"fetch_bytes": 1_514_307 * 2048, "write_bytes": 4_155 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
+    ("scan_regq_kernel", 128, 8_000_000, 384, 2):
+        {"fetch_bytes": 3_029_431 * 2048, "write_bytes": 38_459 * 1024,
+         "source": "profiles/scan_regq_lowreuse_b128.md"},
+    ("scan_regq_kernel", 64, 24_000_000, 768, 4):
+        {"fetch_bytes": 36_059_366 * 2048, "write_bytes": 12_885 * 1024,
+         "source": "profiles/scan_regq_large_b256.md"},
 }
 
 
