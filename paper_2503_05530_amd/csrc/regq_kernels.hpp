@@ -373,21 +373,27 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   // The first partial sum of every row block starts from the rows' terms (register 4 g + v of block b is row
   // RB b + 8 g + 4 kg + v of the wave's rows: four consecutive floats per read), the others from zero.  The
   // cosine distance multiplies by its row term at the end instead and starts from zero throughout.
+  // (The candidate count of the lane's query comes along with the same wait: `my_count` afterwards.)
+  const uint32_t my_count_lds = regq_lds_addr(&count[0]) + 4u * uint32_t(q_local);
+  int my_count = 0;
   auto start_accumulators = [&](long tile) {
     if (cosine) {
 #pragma unroll
       for (int i = 0; i < NACC; ++i)
 #pragma unroll
         for (int v = 0; v < AV; ++v) acc[i][v] = 0.f;
+      my_count = regq_lds_read_i32(my_count_lds);
       return;
     }
     const uint32_t nr_addr = nrm_lds + uint32_t((int(tile & 1) * TN + row_base + 4 * kg) * 4);
     f32x4 term[NRB * AG];
+    asm volatile("ds_read_b32 %0, %1" : "=v"(my_count) : "v"(my_count_lds));
 #pragma unroll
     for (int b = 0; b < NRB; ++b)
 #pragma unroll
       for (int g = 0; g < AG; ++g) term[b * AG + g] = regq_lds_read128<f32x4>(nr_addr, (RB * b + 8 * g) * 4);
     regq_tie_wait_all(term);
+    asm volatile("" : "+v"(my_count));   // (read before the terms: returned before them)
 #pragma unroll
     for (int b = 0; b < NRB; ++b) {
 #pragma unroll
@@ -488,7 +494,6 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   uint64_t* scratch = wave_scratch[wib];
   const bool q_real = m0 + q_local < M;
   uint64_t* my_q_buf = my_buf + long(q_local) * kTopkCap;
-  const uint32_t my_count_lds = count_lds + 4u * uint32_t(q_local);
 
   float T = -__builtin_inff();   // this lane's query's bound, refreshed from LDS only when a buffer was cut back
   bool T_stale = true;
@@ -533,29 +538,40 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     }
     // (four copies of the comparison code -- cosine or not, last tile of the corpus or not -- so that the usual
     // one carries neither the multiplication nor the test against the number of rows)
+    // Per row block: the smallest score first (v_min3: half an instruction per score), and only a lane whose
+    // smallest passes looks at its scores one by one -- with the bounds the samples give, most blocks pass nothing.
     auto sift = [&](auto cosine_c, auto cut_c) {
       constexpr bool kCosine = decltype(cosine_c)::value, kCut = decltype(cut_c)::value;
       const uint32_t nr_addr = nrm_lds + uint32_t((int(tile & 1) * TN + row_base + 4 * kg) * 4);
 #pragma unroll
-      for (int b = 0; b < NRB; ++b)
+      for (int b = 0; b < NRB; ++b) {
+        Acc& sc = acc[b * NSPLIT];
+        if constexpr (NSPLIT == 2) {
 #pragma unroll
-        for (int g = 0; g < AG; ++g) {
-          f32x4 term[1];
-          if constexpr (kCosine) {   // score = (-2 q.x) / |x|: the row terms hold 1 / |x|
-            term[0] = regq_lds_read128<f32x4>(nr_addr, (RB * b + 8 * g) * 4);
+          for (int v = 0; v < AV; ++v) sc[v] += acc[b * NSPLIT + 1][v];
+        }
+        if constexpr (kCosine) {   // score = (-2 q.x) / |x|: the row terms hold 1 / |x|
+#pragma unroll
+          for (int g = 0; g < AG; ++g) {
+            f32x4 term[1] = {regq_lds_read128<f32x4>(nr_addr, (RB * b + 8 * g) * 4)};
             regq_tie_wait_all(term);
-          }
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            float sc = acc[b * NSPLIT][4 * g + v];
-            if (NSPLIT == 2) sc += acc[b * NSPLIT + 1][4 * g + v];
-            if constexpr (kCosine) sc *= term[0][v];
-            if (sc <= T) {
-              const uint32_t row = row0 + uint32_t(RB * b + 8 * g + v);
-              if (!kCut || row < uint32_t(n_rows)) append(sc, row);
-            }
+            for (int v = 0; v < 4; ++v) sc[4 * g + v] *= term[0][v];
           }
         }
+        float least = sc[0];
+#pragma unroll
+        for (int v = 1; v + 1 < AV; v += 2) least = fminf(least, fminf(sc[v], sc[v + 1]));
+        least = fminf(least, sc[AV - 1]);
+        if (least <= T) {
+#pragma unroll
+          for (int v = 0; v < AV; ++v)
+            if (sc[v] <= T) {
+              const uint32_t row = row0 + uint32_t(RB * b + 8 * (v / 4) + v % 4);
+              if (!kCut || row < uint32_t(n_rows)) append(sc[v], row);
+            }
+        }
+      }
     };
     const bool cut = (tile + 1) * TN > n_rows;   // the corpus ends inside this tile
     if (cosine) {
@@ -565,8 +581,27 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     }
     start_accumulators(tile + 1);
     if constexpr (EMIT) return;
-    // Do any buffers have to be cut back before the next tile?  Every wave reads the same counts
-    // after a plain barrier (no memory fence: loads in flight stay in flight), so all agree.
+    if constexpr (WQ == NW) {
+      // Four query groups: every query is one wave's alone, and so are its buffer, count and bound.  The wave
+      // cuts its own buffers back when one has grown past the trigger, without a word to the others.
+      const bool over = my_count > trigger && kg == 0;   // (one lane per query speaks)
+      if (__any(over)) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the wave's own appends have reached memory
+        unsigned long long todo = __ballot(over);
+        while (todo) {
+          const int l = __ffsll((long long)todo) - 1;
+          todo &= todo - 1;
+          const int q = qg * QW + l;                       // kg == 0: lane l holds query l of the group
+          const int n = __builtin_amdgcn_readlane(my_count, l);
+          const int keep = wave_compact_topk(my_buf + long(q) * kTopkCap, n, kp, scratch, &bound[q], lane);
+          if (lane == 0) count[q] = keep;
+        }
+        T_stale = true;
+      }
+      return;
+    }
+    // Fewer query groups: waves share queries.  Do any buffers have to be cut back before the next tile?  Every
+    // wave reads the same counts after a plain barrier (no memory fence: loads in flight stay in flight), so all agree.
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     const bool mine = regq_lds_read_i32(count_lds + 4u * uint32_t(lane < TM ? lane : 0)) > trigger;   // TM <= 128: lanes
     const bool more = TM > 64 && regq_lds_read_i32(count_lds + 4u * uint32_t(64 + lane < TM ? 64 + lane : 0)) > trigger;
