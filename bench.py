@@ -111,15 +111,15 @@ def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, devic
 # same counters read for a 1 GiB copy (FETCH_SIZE: 2 KiB per count, WRITE_SIZE: 1 KiB per count).
 # Keyed by (kernel, query-tile shape, corpus rows, dim, element bytes); anything else reports null.
 COUNTER_TRAFFIC = {
-    ("scores_stream_kernel", 0, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_501_992 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scores_stream_mid_b1.md"},
+    ("scan_regq_kernel (scores only)", 0, 1_000_000, 768, 4):
+        {"fetch_bytes": 1_512_370 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scan_regq_mid_b1.md"},
     ("scan_regq_kernel", 64, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_514_307 * 2048, "write_bytes": 4_155 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
+        {"fetch_bytes": 1_514_304 * 2048, "write_bytes": 4_139 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
     ("scan_regq_kernel", 128, 8_000_000, 384, 2):
-        {"fetch_bytes": 3_029_431 * 2048, "write_bytes": 38_459 * 1024,
+        {"fetch_bytes": 3_029_422 * 2048, "write_bytes": 38_449 * 1024,
          "source": "profiles/scan_regq_lowreuse_b128.md"},
     ("scan_regq_kernel", 64, 24_000_000, 768, 4):
-        {"fetch_bytes": 36_059_366 * 2048, "write_bytes": 12_885 * 1024,
+        {"fetch_bytes": 36_059_362 * 2048, "write_bytes": 12_860 * 1024,
          "source": "profiles/scan_regq_large_b256.md"},
 }
 
@@ -142,7 +142,10 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
     per_term = (2.0 if regq else 3.0) if bf16_split else 1.0
     ridge_q = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9) * elem_bytes / (2 * per_term)  # queries per launch at the ridge
     if batch <= 4:
-        kernel = "scores_stream_kernel"
+        # single-query calls: the register-resident kernel in its scores-only form on long float32 corpora of the
+        # dimensions it is built for, the register-load streaming kernel otherwise
+        dump = elem_bytes == 4 and dim in (768, 384) and n_docs >= 500_000
+        kernel = "scan_regq_kernel (scores only)" if dump else "scores_stream_kernel"
     elif regq:
         kernel = "scan_regq_kernel"
     elif bf16_split:

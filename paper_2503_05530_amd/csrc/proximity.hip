@@ -53,6 +53,7 @@ constexpr size_t kProbeScoreBudget = size_t(512) << 20;  // bytes the dense prob
 constexpr long kProbeSmallBlocks = 1536;  // probes of at most this many 32 x 32 tiles use the split-column kernel
 constexpr size_t kLshLdsMax = 144 * 1024;  // dynamic LDS the bucket resolver may ask for (query + bucket keys)
 constexpr int kSeedRows = 16384;       // head of the corpus scanned first to seed the top-k bounds
+constexpr long kRegqDumpMinRows = 500000;  // single-query calls: corpora from here on are scored by the register-resident kernel
 constexpr long kSeedRows2 = 262144;    // second sample of a long corpus (register-resident scan)
 
 static_assert(sizeof(proximity_config) == 72, "proximity_config layout is part of the ABI");
@@ -446,12 +447,27 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     const int g1 = int((N + kSelSeg - 1) / kSelSeg);
     for (int m0 = 0; m0 < m_limit; m0 += mq) {
       prof_begin(h, s);
-      if (bf16)
+      if (!bf16 && N >= kRegqDumpMinRows && (dim == 768 || dim == 384)) {
+        // a long float32 corpus of these dimensions: the register-resident kernel's loads stream it faster
+        RegqEmit dump{};
+        dump.S = h->S;
+        dump.ldS = h->ldS;
+        const int upto = m0 + mq < m_limit ? m0 + mq : m_limit;   // S has room for the mq queries of this pass
+        if (dim == 768)
+          scan_regq_kernel<kDtypeF32, 768, 1, kRegqDump><<<dim3(h->scan_blocks_regq), dim3(256), 0, s>>>(
+              h->cfg.corpus, h->xnrm, N, Qbase, qlist, nullptr, 0, m_count_ptr, upto, m0, 0, 0x7fffffff, 0, nullptr, nullptr,
+              nullptr, cosine, dump);
+        else
+          scan_regq_kernel<kDtypeF32, 384, 1, kRegqDump><<<dim3(h->scan_blocks_regq), dim3(256), 0, s>>>(
+              h->cfg.corpus, h->xnrm, N, Qbase, qlist, nullptr, 0, m_count_ptr, upto, m0, 0, 0x7fffffff, 0, nullptr, nullptr,
+              nullptr, cosine, dump);
+      } else if (bf16) {
         launch_scores_stream<kDtypeBF16, true>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
                                          m0, h->S, h->ldS, cosine, s);
-      else
+      } else {
         launch_scores_stream<kDtypeF32, true>(h, mq, h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist, m_count_ptr, m_limit,
                                         m0, h->S, h->ldS, cosine, s);
+      }
       prof_end(h, s, m0, mq);
       if (small_routing) {
         // a handful of queries: selection, float64 ranking and routing in one launch;

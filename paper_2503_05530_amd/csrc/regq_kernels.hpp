@@ -153,9 +153,11 @@ __device__ __forceinline__ uint32_t regq_bf16x2_times_minus2(uint32_t w) {
   return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u);
 }
 
-// What the cache probe does with the kernel (EMIT): the "corpus" is the array of sources (slot keys, then the
+// What the cache probe does with the kernel (MODE kRegqProbe): the "corpus" is the array of sources (slot keys, then the
 // batch rows), the queries are batch rows, and instead of a running top-k every (row, source) pair whose score
 // passes the row's bound is handed on: the candidates that the float64 distance then decides.
+constexpr int kRegqScan = 0, kRegqProbe = 1, kRegqDump = 2;   // what the kernel does with its scores (MODE)
+
 struct RegqEmit {
   int c;                 // cache slots: sources 0..c-1 are slot keys, c + j is batch row j
   const int* live_slots; // DEVICE: slots holding a key when the batch started; others are skipped
@@ -166,20 +168,28 @@ struct RegqEmit {
   double* cand_d;        // ... and their float64 distances to the row
   int* ovf_cnt;          // number of rows whose list overflowed, zero before the launch
   int* ovf_list;         // those rows
+  // kRegqDump only: every score is written out, S[m * ldS + row] for the m-th query from m_base on
+  float* S;
+  long ldS;
 };
 
-// Top-k scan (EMIT false).  The kernel serves the queries m_base .. m_base + QW WQ - 1 of the miss list when the
+// Top-k scan (MODE kRegqScan).  The kernel serves the queries m_base .. m_base + QW WQ - 1 of the miss list when the
 // number of queries from m_base on, M - m_base, lies in (rem_lo, rem_hi]; otherwise it returns at once, so the
 // host can launch the shapes for few, some and many queries back to back without knowing M.
 // float32: queries are rows qlist[m] (or m) of Qbase.  bfloat16: Qbase is not used; Qplanes[p][m][:] are the
 // planes written by split_bf16x3_kernel.
 // Output as scan_mfma_dma_kernel: out[((m) * gridDim.x + blockIdx.x) * kp ..], kp sorted keys per (query, block).
 //
-// Cache probe (EMIT true, float32 only).  The batch rows m_base .. m_limit - 1 in slices of QW WQ (rem_lo = the
+// Scores only (MODE kRegqDump): a handful of queries (at most QW; one query group), every score written to S --
+// the form the selection kernels of single-query calls read.  With one to four queries the kernel is bound by
+// HBM alone, and its loads (global->LDS, 80 KiB in flight per CU) stream a long corpus faster than the
+// register loads of scores_stream_kernel do (6.95 against 6.6 TB/s at 1 M x 768).
+//
+// Cache probe (MODE kRegqProbe, float32 only).  The batch rows m_base .. m_limit - 1 in slices of QW WQ (rem_lo = the
 // number of slices, at most the grid), each slice against the sources 0 .. c + (its last row): a row is only ever
 // answered by a slot or an earlier row.  Row i's
 // bound is the float32 pre-filter of "distance <= tau" (see below); xnrm holds the sources' squared lengths.
-template <int DT, int DIM, int WQ, bool EMIT = false>
+template <int DT, int DIM, int WQ, int MODE = kRegqScan>
 __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     const void* __restrict__ Xv, const float* __restrict__ xnrm, long n_rows, const float* __restrict__ Qbase,
     const int* __restrict__ qlist, const uint16_t* __restrict__ Qplanes, long plane_stride,
@@ -207,7 +217,9 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   static_assert(NS >= 4 && NS <= SPT, "ring must not run more than one tile ahead (row terms are double-buffered)");
   static_assert(DIM % SLAB_COLS == 0, "whole slabs");
 
+  constexpr bool EMIT = MODE == kRegqProbe, DUMP = MODE == kRegqDump;
   static_assert(!EMIT || F32, "the probe's keys are float32");
+  static_assert(!DUMP || WQ == 1, "scores of one query group");
   const int M = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   // probe: rem_lo is the number of row slices; block b serves slice b % slices and is part b / slices of the blocks
   // that share that slice's sources (the grid need not be a multiple of the slices: a grid of one block per
@@ -559,6 +571,23 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
             for (int v = 0; v < 4; ++v) sc[4 * g + v] *= term[0][v];
           }
         }
+        if constexpr (DUMP) {   // every score of a real query goes out: four consecutive rows per store
+          if (q_real) {
+            float* dst = emit.S + long(q_local) * emit.ldS;
+#pragma unroll
+            for (int g = 0; g < AG; ++g) {
+              const uint32_t row = row0 + uint32_t(RB * b + 8 * g);
+              if (!kCut || row + 3 < uint32_t(n_rows)) {
+                *reinterpret_cast<float4*>(dst + row) = make_float4(sc[4 * g], sc[4 * g + 1], sc[4 * g + 2], sc[4 * g + 3]);
+              } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                  if (row + v < uint32_t(n_rows)) dst[row + v] = sc[4 * g + v];
+              }
+            }
+          }
+          continue;
+        }
         float least = sc[0];
 #pragma unroll
         for (int v = 1; v + 1 < AV; v += 2) least = fminf(least, fminf(sc[v], sc[v + 1]));
@@ -580,7 +609,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
       if (cut) sift(std::false_type{}, std::true_type{}); else sift(std::false_type{}, std::false_type{});
     }
     start_accumulators(tile + 1);
-    if constexpr (EMIT) return;
+    if constexpr (EMIT || DUMP) return;
     if constexpr (WQ == NW) {
       // Four query groups: every query is one wave's alone, and so are its buffer, count and bound.  The wave
       // cuts its own buffers back when one has grown past the trigger, without a word to the others.
@@ -669,6 +698,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     }
     return;
   }
+  if constexpr (DUMP) return;
   // ---- every query's buffer cut to kp sorted entries and written out ----
   __syncthreads();
   for (int q = wib; q < TM; q += NW) {
