@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define PROXIMITY_ABI_VERSION 4u
+#define PROXIMITY_ABI_VERSION 5u
 
 enum {
   PROXIMITY_OK = 0,
@@ -179,6 +179,21 @@ uint32_t proximity_abi_version(void);
  * |q| = query_length, X = max_row_length (the longest corpus row).  NaN for a bad argument.
  */
 double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_length, double max_row_length);
+
+/*
+ * The row ranges in which proximity_search_batch() probes and resolves a call of n rows against a flat cache
+ * (host arithmetic, no GPU work; Algorithm 1's distances for the rows of one range are computed while the rows of
+ * the range before are decided, in order, beside them).  ends[g] receives the row after the last row of range g;
+ * the return value is the number of ranges (1: the whole call at once), 0 for a bad argument or when max_ranges
+ * is too small.  Every range but the last ends on a multiple of 64, and none is longer than the number of rows
+ * whose float32 probe scores fit the instance's score buffers (which follows from capacity and max_batch).
+ *   capacity, max_batch  as in proximity_config
+ *   listing              1: Euclidean keys of 768 or 384 columns, probed by the kernel that lists candidates itself
+ *                        (range sizes then also balance that kernel's blocks); 0: every other flat cache
+ *   n_cu                 compute units of the device (256 on MI355X)
+ */
+uint32_t proximity_probe_row_ranges(uint32_t n, uint32_t capacity, uint32_t max_batch, uint32_t listing, uint32_t n_cu,
+                                    uint32_t* ends, uint32_t max_ranges);
 
 /*
  * Create an instance on cfg->device: computes the squared norm of every corpus

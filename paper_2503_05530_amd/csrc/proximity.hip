@@ -589,6 +589,48 @@ int validate_call(proximity* h, const float* queries, uint32_t n, uint32_t k, in
   return PROXIMITY_OK;
 }
 
+// Rows of a call whose dense float32 probe scores are held at a time: as many as two score buffers of that many
+// rows fit the budget, a multiple of 64 between 64 and kProbeRangeRows.
+size_t probe_range_rows(size_t capacity, size_t max_batch) {
+  const size_t ld = (capacity + max_batch + 63) / 64 * 64;
+  const size_t fit = kProbeScoreBudget / (2 * ld * sizeof(float)) / 64 * 64;
+  return fit < 64 ? 64 : fit > kProbeRangeRows ? kProbeRangeRows : fit;
+}
+
+// The row ranges of a call of nn > R rows: cut[g] = row after the last of range g; returns their number.
+// What is left when the last probe ends is the resolution of the last range, so the last rows go in two halves.
+// The listing probe runs one block per CU, each over whole tiles of 128 sources for 64 rows: there the range size
+// decides how evenly the tiles divide among the blocks (at 10 000 keys, ranges of 1 024 rows leave the slowest
+// block with 6 tiles where the average is 5.5).  The size with the best rows x tiles per time of the slowest block
+// is taken, half a tile's time counted as the fixed cost of a launch.
+int probe_range_cuts(int nn, int R, int c, bool listing, int n_cu, int* cut) {
+  int ranges = 0, r = 0;
+  auto listing_rows = [&](int from) {
+    int most = nn - from < R ? nn - from : R;
+    if (nn - from - most < 512) most = nn - from - 512;   // (at least 512 rows stay for the two short last ranges)
+    if (most < 512) return nn - from < R ? nn - from : R;
+    const int nb = n_cu > 8 ? n_cu - 8 : 1;
+    int best = most;
+    double best_rate = 0.0;
+    for (int rows = 512; rows <= most; rows += 64) {
+      const int slices = rows / 64, tiles = (c + from + rows + 127) / 128;
+      const int parts = nb / slices > 0 ? nb / slices : 1;
+      const int per = (tiles + parts - 1) / parts;
+      const double rate = double(rows) * tiles / (per + 0.5);
+      if (rate >= best_rate) {
+        best_rate = rate;
+        best = rows;
+      }
+    }
+    return best;
+  };
+  const int tail = listing && R > 1024 ? 1024 : R;   // rows left for the short last ranges, at most
+  while (nn - r > tail) cut[ranges++] = (r += listing ? listing_rows(r) : R);
+  if (nn - r >= 256) cut[ranges++] = (r += ((nn - r) / 2 + 63) / 64 * 64);
+  if (r < nn) cut[ranges++] = nn;
+  return ranges;
+}
+
 }  // namespace
 
 extern "C" {
@@ -599,6 +641,21 @@ double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_l
   if (metric > PROXIMITY_METRIC_COSINE || dim == 0 || !(query_length >= 0.0) || !(max_row_length >= 0.0))
     return std::nan("");
   return score_error_bound(int(metric), int(dim), query_length, max_row_length);
+}
+
+uint32_t proximity_probe_row_ranges(uint32_t n, uint32_t capacity, uint32_t max_batch, uint32_t listing, uint32_t n_cu,
+                                    uint32_t* ends, uint32_t max_ranges) {
+  if (!ends || n == 0 || n > max_batch || max_batch > PROXIMITY_MAX_BATCH || capacity == 0 ||
+      capacity > PROXIMITY_MAX_CAPACITY || n_cu == 0)
+    return 0;
+  const int R = int(probe_range_rows(capacity, max_batch));
+  int cut[PROXIMITY_MAX_BATCH / 64 + 4];
+  int ranges = 1;
+  cut[0] = int(n);
+  if (int(n) > R) ranges = probe_range_cuts(int(n), R, int(capacity), listing != 0, int(n_cu), cut);
+  if (uint32_t(ranges) > max_ranges) return 0;
+  for (int g = 0; g < ranges; ++g) ends[g] = uint32_t(cut[g]);
+  return uint32_t(ranges);
 }
 
 const char* proximity_last_error(const proximity_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
@@ -728,8 +785,7 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   h->ldD = long((c + B + 63) / 64 * 64);
   if (!lsh) {  // the dense probe and its candidate lists belong to the flat cache
     // rows per range: as many as two score buffers of that many rows fit the budget, 64..kProbeRangeRows
-    size_t R = kProbeRangeRows;
-    while (R > 64 && 2 * R * size_t(h->ldD) * sizeof(float) > kProbeScoreBudget) R = (R / 2 + 63) / 64 * 64;
+    const size_t R = probe_range_rows(c, B);
     h->probe_rows = int(R);
     const size_t score_rows = B <= R ? B : 2 * R;
     TRY_ALLOC(h->D32, score_rows * size_t(h->ldD), true);
@@ -1120,37 +1176,10 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
   } else {
     // Row ranges: the probe of a range on the caller's stream, its resolution on the side stream, which so walks
     // a range while the next one is being multiplied.  What is left when the last probe ends is the resolution
-    // of the last range, so the last R rows go in two halves.  The side stream joins the
+    // of the last range, so the last rows go in two short ranges (probe_range_cuts).  The side stream joins the
     // caller's stream before anything else is enqueued.
     int cut[PROXIMITY_MAX_BATCH / 64 + 4];
-    int ranges = 0, r = 0;
-    // The listing probe runs one block per CU, each over whole tiles of 128 sources for 64 rows: the range size
-    // decides how evenly the tiles divide among the blocks (at 10 000 keys, ranges of 1 024 rows leave the
-    // slowest block with 6 tiles where the average is 5.5).  The size with the best rows x tiles per time of
-    // the slowest block is taken, half a tile's time counted as the fixed cost of a launch.
-    auto listing_rows = [&](int from) {
-      int most = nn - from < R ? nn - from : R;
-      if (nn - from - most < 512) most = nn - from - 512;   // (at least 512 rows stay for the two short last ranges)
-      if (most < 512) return nn - from < R ? nn - from : R;
-      const int nb = h->n_cu - 8;
-      int best = most;
-      double best_rate = 0.0;
-      for (int rows = 512; rows <= most; rows += 64) {
-        const int slices = rows / 64, tiles = (c + from + rows + 127) / 128;
-        const int parts = nb / slices > 0 ? nb / slices : 1;
-        const int per = (tiles + parts - 1) / parts;
-        const double rate = double(rows) * tiles / (per + 0.5);
-        if (rate >= best_rate) {
-          best_rate = rate;
-          best = rows;
-        }
-      }
-      return best;
-    };
-    const int tail = listing && R > 1024 ? 1024 : R;   // rows left for the short last ranges, at most
-    while (nn - r > tail) cut[ranges++] = (r += listing ? listing_rows(r) : R);
-    if (nn - r >= 256) cut[ranges++] = (r += ((nn - r) / 2 + 63) / 64 * 64);
-    if (r < nn) cut[ranges++] = nn;
+    const int ranges = probe_range_cuts(nn, R, c, listing, h->n_cu, cut);
     for (int g = 0; g < ranges; ++g) {
       const int r0 = g ? cut[g - 1] : 0, r1 = cut[g];
       float* D = h->D32 + size_t(g & 1) * size_t(R) * size_t(h->ldD);

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol(binding):
 
 
 def test_abi_version_and_struct_layout(binding):
-    assert binding.proximity_abi_version() == 4
+    assert binding.proximity_abi_version() == 5
     assert C.sizeof(binding.ProximityConfig) == 72
     assert C.sizeof(binding.ProximityStats) == 128
     assert C.sizeof(binding.ProximityLaunch) == 16
@@ -174,3 +174,40 @@ def test_score_error_bound_by_hand_and_against_float32_arithmetic(binding):
             for metric in (0, 1, 2):
                 err = np.abs(got[metric].astype(np.float64) - exact[metric]).max()
                 assert err <= E(metric, dim, q_len, x_max), (dim, order, metric, err)
+
+
+def probe_ranges(b, n, capacity, max_batch, listing, n_cu=256):
+    import ctypes as C
+    out = (C.c_uint32 * 200)()
+    k = b.lib.proximity_probe_row_ranges(n, capacity, max_batch, listing, n_cu, out, 200)
+    return list(out[:k])
+
+
+def test_row_ranges_of_a_call_cover_it_in_order_within_the_score_buffers():
+    """The host rule that cuts a large call into the row ranges probed beside the resolver (host arithmetic behind
+    the C ABI): ranges are contiguous, in order, end on multiples of 64 (the resolver walks chunks of 64 rows),
+    none is longer than the score buffers hold, and the last rows go in short ranges."""
+    import paper_2503_05530_amd.binding as b
+    budget = 512 << 20
+    for capacity, max_batch in ((300, 8192), (10_000, 4096), (200_000, 4096), (1 << 20, 8192), (19_000, 8192)):
+        ld = (capacity + max_batch + 63) // 64 * 64
+        most = min(1536, max(64, budget // (2 * ld * 4) // 64 * 64))       # rows whose scores fit one buffer
+        for listing in (0, 1):
+            for n in list(range(1, 300, 7)) + list(range(most - 3, min(max_batch, most + 1500), 13)) + \
+                    list(range(max(1, max_batch - 700), max_batch + 1, 11)):
+                if n > max_batch:
+                    continue
+                ends = probe_ranges(b, n, capacity, max_batch, listing)
+                assert ends and ends[-1] == n, (capacity, max_batch, listing, n, ends)
+                starts = [0] + ends[:-1]
+                for r0, r1 in zip(starts, ends):
+                    assert 0 < r1 - r0 <= most and r0 % 64 == 0, (capacity, max_batch, listing, n, ends)
+                if n <= most:
+                    assert ends == [n]
+                elif n - most > 1024:
+                    assert ends[-1] - ends[-2] <= max(512, most // 2) + 64   # what remains after the last probe is short
+    # the configuration of the probe microbenchmark: five ranges, the two last of 256 rows
+    assert probe_ranges(b, 4096, 10_000, 4096, 1) == [1216, 2624, 3584, 3840, 4096]
+    # bad arguments
+    assert probe_ranges(b, 0, 10_000, 4096, 1) == [] and probe_ranges(b, 5000, 10_000, 4096, 1) == []
+    assert probe_ranges(b, 64, 0, 4096, 1) == []
