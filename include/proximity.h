@@ -31,6 +31,12 @@
  *     of its calls, so at any time the calls of one handle must be in flight on ONE stream only: before
  *     passing a different stream than the previous call did, wait for that call (hipStreamSynchronize,
  *     or an event the new stream waits on).  Calls that overlap on two streams race.
+ *     A flat cache whose max_batch exceeds one probe range (1536 rows; fewer for caches beyond some 40 000
+ *     keys, see proximity_probe_row_ranges) owns one stream of its own (default priority): inside a call of
+ *     more rows than that the rows are decided there, range by range, beside the distance computation of
+ *     the following range on the caller's stream.  The two are tied by events, and the caller's
+ *     stream waits for the internal one before the call enqueues what follows, so to the caller the call
+ *     is still a piece of work in order on the stream it passed.
  *   - The library allocates all of its device memory in proximity_create().
  *     proximity_search_batch() and proximity_knn_batch() allocate nothing and
  *     never wait for the device: the number of misses is consumed on the
