@@ -48,6 +48,44 @@ def test_knn_matches_oracle_f32(B, n_docs, dim, k, nq):
     px.close()
 
 
+@pytest.mark.parametrize("metric,dim,nq", [(po.METRIC_L2, 384, 1), (po.METRIC_COSINE, 384, 3), (po.METRIC_IP, 768, 4),
+                                           (po.METRIC_L2, 768, 2)])
+def test_few_queries_against_a_long_corpus(B, metric, dim, nq):
+    """Calls of up to four rows on a corpus of half a million rows and more are scored by the register-resident
+    kernel in its scores-only form (768 and 384 float32 columns); the corpus here ends inside a tile."""
+    n_docs, k = 520_077, 7
+    corpus = W.corpus_f32(n_docs, dim, 11)
+    if metric != po.METRIC_L2:
+        corpus *= lengths(n_docs, 0.5, 2.0, 12)
+    q = (1.3 * W.unit_rows(np.random.default_rng(13).standard_normal((nq, dim)))).astype(np.float32)
+    px = B.Proximity(gpu_corpus(corpus), dim, 0, k, B.POLICY_FIFO, 4, metric=metric)
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    o_ids, o_d = po.batched_exact_knn(corpus, q, k, metric=metric)
+    P.assert_lists_match(ids.cpu().numpy(), dists.cpu().numpy(), o_ids, o_d, corpus, q, what=f"long corpus {dim}",
+                         metric=metric)
+    assert px.stats()["slack_unresolved"] == 0
+    px.close()
+
+
+def test_listing_probe_at_384_columns(B):
+    """A cache of 3 000 keys of 384 columns probed with calls of 256 and of 1 700 rows: the probe that lists its
+    candidates itself, in one range and in row ranges, against the oracle's decisions."""
+    dim, cap, k = 384, 3000, 4
+    corpus = W.corpus_f32(3000, dim, 21)
+    base = W.base_queries(2500, dim, 22)
+    idx = np.random.default_rng(23).integers(0, 2500, size=6000)
+    q = W.perturbed_stream(base, idx, 0.1, 24)
+    for policy, batch in ((po.POLICY_LRU, 256), (po.POLICY_FIFO, 1700)):
+        want = po.lookup_stream_deferred(corpus, q, 0.25, cap, k, policy)
+        px = B.Proximity(gpu_corpus(corpus), dim, cap, k, policy, batch)
+        got = P.run_stream(px, q, 0.25, batch, DEV)
+        P.assert_stream_parity(got, want[:4], corpus, q, what=f"listing probe, calls of {batch}")
+        seq, _, _ = px.cache_dump()
+        assert seq.tolist() == want[4].dump_seq().tolist()
+        assert 0.2 < want[2].mean() < 0.8
+        px.close()
+
+
 @pytest.mark.parametrize("nq", [6, 128])
 def test_knn_matches_oracle_bf16(B, nq):
     n_docs, dim, k = 20000, 384, 100
