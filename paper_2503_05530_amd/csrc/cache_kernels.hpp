@@ -205,6 +205,7 @@ __global__ __launch_bounds__(64) void resolver_kernel(
   // Rows row_begin .. row_end - 1 of the batch (a batch may take several launches, in row order: all state is
   // in device memory, and the list of missing rows grows from launch to launch); D32 holds the dense probe
   // rows of this range, row i at D32 + (i - row_begin) * ldD.
+  (void)n;
   const int lane = threadIdx.x;
   int size = st->size, head = st->head, tail = st->tail;
   unsigned long long hits = 0, misses = 0, inserts = 0, evictions = 0, inbatch = 0, dense = 0;

@@ -1117,13 +1117,13 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
       if (nb > long(slices) * tiles) nb = long(slices) * tiles;
       if (nb < slices) nb = slices;
       const RegqEmit em{c,         h->live_slots,  tau_key,         kCandCap, h->cand_cnt, h->cand_src,
-                        h->cand_d, h->ovf_cnt + g, h->ovf_list + r0};
+                        h->cand_d, h->ovf_cnt + g, h->ovf_list + r0, nullptr,      0};
       if (dim == 768)
-        scan_regq_kernel<kDtypeF32, 768, 4, true><<<dim3((unsigned)nb), dim3(256), 0, s>>>(
+        scan_regq_kernel<kDtypeF32, 768, 4, kRegqProbe><<<dim3((unsigned)nb), dim3(256), 0, s>>>(
             h->srcs, h->srcnrm, n_src, batch_rows, nullptr, nullptr, 0, nullptr, r1, r0, slices, 0, 0, nullptr, nullptr,
             nullptr, 0, em);
       else
-        scan_regq_kernel<kDtypeF32, 384, 4, true><<<dim3((unsigned)nb), dim3(256), 0, s>>>(
+        scan_regq_kernel<kDtypeF32, 384, 4, kRegqProbe><<<dim3((unsigned)nb), dim3(256), 0, s>>>(
             h->srcs, h->srcnrm, n_src, batch_rows, nullptr, nullptr, 0, nullptr, r1, r0, slices, 0, 0, nullptr, nullptr,
             nullptr, 0, em);
       return;   // (enqueue_lists follows, on the stream that resolves the range)
