@@ -449,6 +449,8 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       prof_begin(h, s);
       if (!bf16 && N >= kRegqDumpMinRows && (dim == 768 || dim == 384)) {
         // a long float32 corpus of these dimensions: the register-resident kernel's loads stream it faster
+        // (its per-block top-k lists instead of the first selection pass were tried: the scan lost what the
+        // selection had cost)
         RegqEmit dump{};
         dump.S = h->S;
         dump.ldS = h->ldS;
@@ -746,11 +748,13 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   TRY_ALLOC(h->S, size_t(8) * size_t(h->ldS), false);
   const size_t g1 = (N + kSelSeg - 1) / kSelSeg;
   size_t lists = g1 > 0 ? g1 : 1;
+  if (N > 0) {  // (also for instances of single-row calls: the scores-only form of that scan serves them)
+    const size_t tiles128 = (N + kRegqTileRows - 1) / kRegqTileRows;
+    h->scan_blocks_regq = int(tiles128 < size_t(h->n_cu) ? tiles128 : size_t(h->n_cu));
+  }
   if (B > size_t(kStreamMaxQueries) && N > 0) {
     const size_t tiles256 = (N + 255) / 256;
     h->scan_blocks = int(tiles256 < size_t(2 * h->n_cu) ? tiles256 : size_t(2 * h->n_cu));
-    const size_t tiles128 = (N + kRegqTileRows - 1) / kRegqTileRows;
-    h->scan_blocks_regq = int(tiles128 < size_t(h->n_cu) ? tiles128 : size_t(h->n_cu));
     if (size_t(h->scan_blocks) > lists) lists = size_t(h->scan_blocks);
     if (size_t(h->scan_blocks_regq) > lists) lists = size_t(h->scan_blocks_regq);
     if (size_t(kSeedRows + kp - 1) / kp > lists) lists = size_t(kSeedRows + kp - 1) / kp;  // dumped head scores
