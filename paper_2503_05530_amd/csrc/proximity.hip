@@ -494,6 +494,10 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     if (small_routing) return PROXIMITY_OK;
     cur = enqueue_merge_levels(h, 0, long(g1) * kp, kp, m_count_ptr, m_limit, s, kRerankMergeKeys, &left);
   } else {
+    // (the kernels below write through these: never launch them on an instance that was not given the buffers)
+    if (!h->topk_buf || !h->pairs[0] || !h->pairs[1] || (bf16 && dim >= 64 && !h->qplanes))
+      return fail(h, PROXIMITY_ERR_INVALID_ARG, "%d queries in one search on an instance without the batched scan's workspace",
+                  m_limit);
     // Batched scan on the matrix cores, in two steps.  First the head of the corpus
     // (kSeedRows rows) is scanned and merged on its own: its kp-th best score per query is a
     // valid bound for the whole corpus and lets the full scan drop almost every row at once
