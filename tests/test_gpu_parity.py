@@ -103,6 +103,36 @@ def test_knn_matches_oracle_bf16(B, nq):
     px.close()
 
 
+@pytest.mark.parametrize("trial", range(24))
+def test_knn_random_shapes_at_the_register_resident_dimensions(B, trial):
+    """The same at the corpus types and dimensions the scan with its queries in registers is built for
+    (float32 768 / 384, bfloat16 384 / 256), query counts around its one-, two- and four-group shapes and its
+    passes of 64 / 128 queries, corpora that end inside a tile."""
+    rng = np.random.default_rng([trial, 991])
+    bf16 = bool(rng.integers(0, 2))
+    dim = int(rng.choice([384, 256] if bf16 else [768, 384]))
+    n_docs = int(rng.choice([130, 1000, 4097, 20000, 66000, 140000, 300000])) + int(rng.integers(0, 200))
+    nq = int(rng.choice([5, 9, 16, 17, 31, 33, 48, 64, 65, 80, 100, 128, 129, 200]))
+    k = int(rng.choice([1, 5, 10, 32, 100]))
+    metric = int(rng.choice([po.METRIC_L2, po.METRIC_L2, po.METRIC_IP, po.METRIC_COSINE]))
+    x = W.corpus_f32(n_docs, dim, 1000 + trial)
+    if metric != po.METRIC_L2:
+        x *= rng.uniform(0.5, 2.0, size=(n_docs, 1)).astype(np.float32)
+    t = torch.from_numpy(x).to(DEV)
+    if bf16:
+        t = t.to(torch.bfloat16)
+        x = t.to(torch.float32).cpu().numpy()             # exact values the GPU holds
+    q = (rng.uniform(0.5, 1.5) * W.unit_rows(rng.standard_normal((nq, dim)))).astype(np.float32)
+    px = B.Proximity(t, dim, 0, k, B.POLICY_FIFO, nq, metric=metric)
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    o_ids, o_d = po.batched_exact_knn(x, q, k, metric=metric)
+    P.assert_lists_match(ids.cpu().numpy(), dists.cpu().numpy(), o_ids, o_d, x, q,
+                         dist_rtol=P.DIST_RTOL_BF16 if bf16 else P.DIST_RTOL_F32,
+                         what=f"bf16={bf16} dim={dim} n_docs={n_docs} nq={nq} k={k} metric={metric}", metric=metric)
+    assert px.stats()["slack_unresolved"] == 0
+    px.close()
+
+
 @pytest.mark.parametrize("trial", range(30))
 def test_knn_random_shapes(B, trial):
     """The index search alone at shapes drawn at random: dimensions from 32 to 2 048, corpus sizes around
