@@ -160,7 +160,10 @@ typedef struct proximity_stats_t {
  * One timed launch of the corpus-scan distance kernel (see proximity_profile_start).
  * A launch handles the misses number first_query .. first_query+n_queries-1 of its
  * call; it streamed the corpus only if the call had more than first_query misses
- * (otherwise it returned at once), which the caller can tell from out_hit.
+ * (otherwise it returned at once), which the caller can tell from out_hit.  Where the
+ * library launches the kernel in several tile shapes for the same queries (all but one of
+ * which return at once: the number of misses is known on the device only), the record is
+ * that of the longest of them.
  */
 typedef struct proximity_launch_t {
   uint32_t call;         /* ordinal of the search/knn call since proximity_profile_start   */

@@ -377,11 +377,16 @@ void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows
   const bool known = m_count_ptr == nullptr;  // then M = m_limit and only its own shape is launched
   for (int mb = base; mb < base + span; mb += SLICE) {
     const int rem_max = m_limit - mb;         // the most queries this slice can have to serve
+    // (every shape is timed on its own: of the launches of one slice only the one whose range holds the number of
+    // misses does the work, and proximity_profile_stop reports that one)
 #define PROX_REGQ(WQ, LO, HI)                                                                                   \
-  if (rem_max > (LO) && (!known || rem_max <= (HI)))                                                             \
-  scan_regq_kernel<DT, DIM, WQ><<<dim3(G), dim3(256), 0, s>>>(X, xnrm, n_rows, Qbase, qlist, h->qplanes,               \
-                                                              plane_stride, m_count_ptr, m_limit, mb, LO, HI, kp, seed, \
-                                                              h->topk_buf, out, cosine, RegqEmit{})
+  if (rem_max > (LO) && (!known || rem_max <= (HI))) {                                                           \
+    prof_begin(h, s);                                                                                            \
+    scan_regq_kernel<DT, DIM, WQ><<<dim3(G), dim3(256), 0, s>>>(X, xnrm, n_rows, Qbase, qlist, h->qplanes,             \
+                                                                plane_stride, m_count_ptr, m_limit, mb, LO, HI, kp,    \
+                                                                seed, h->topk_buf, out, cosine, RegqEmit{});           \
+    prof_end(h, s, mb, rem_max < SLICE ? rem_max : SLICE);                                                       \
+  }
     PROX_REGQ(1, 0, QW);
     PROX_REGQ(2, QW, 2 * QW);
     PROX_REGQ(4, 2 * QW, 0x7fffffff);
@@ -530,25 +535,29 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       int g2 = int(rows2 / 1024);   // eight tiles per block
       if (g2 > G) g2 = G;
       const char* X2 = static_cast<const char*>(h->cfg.corpus) + size_t(kSeedRows) * dim * (bf16 ? 2 : 4);
+      const bool timing = h->prof_on;   // (the sample's launches are not among the timed scans)
+      h->prof_on = false;
       for (int base = 0; base < m_limit; base += kScanPassQueries) {
         const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
         launch_regq_scan(h, X2, h->xnrm + kSeedRows, rows2, g2, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed,
                          h->pairs[cur], s);
       }
+      h->prof_on = timing;
       cur = enqueue_merge_levels(h, cur, long(g2) * kp, kp, m_count_ptr, m_limit, s, kp);
       seed = h->pairs[cur];   // (row numbers in these keys count from the sample's first row; only scores are used)
       cur ^= 1;
     }
     for (int base = 0; base < m_limit; base += kScanPassQueries) {
       const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
-      prof_begin(h, s);
-      if (regq)
+      if (regq) {
         launch_regq_scan(h, h->cfg.corpus, h->xnrm, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed,
                          h->pairs[cur], s);
-      else
+      } else {
+        prof_begin(h, s);
         launch_batched_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], false,
                             s);
-      prof_end(h, s, base, span);
+        prof_end(h, s, base, span);
+      }
     }
     // the last merge level happens inside the ranking kernel
     cur = enqueue_merge_levels(h, cur, long(G) * kp, kp, m_count_ptr, m_limit, s, kRerankMergeKeys, &left);
@@ -1345,9 +1354,19 @@ int proximity_profile_stop(proximity_t* h, proximity_launch_t* records, uint32_t
   h->prof_on = false;
   HIP_TRY(h, hipStreamSynchronize(h->last_stream));
   uint32_t w = 0;
-  for (size_t i = 0; i < h->ev_used && w < cap; ++i) {
+  for (size_t i = 0; i < h->ev_used; ++i) {
     float ms = 0.f;
     HIP_TRY(h, hipEventElapsedTime(&ms, h->ev0[i], h->ev1[i]));
+    // launches of one call for the same queries (one per tile shape): one record, that of the longest -- the
+    // others returned at once
+    if (w > 0 && records[w - 1].call == h->ev_info[i].call && records[w - 1].first_query == h->ev_info[i].first_query) {
+      if (ms > records[w - 1].ms) {
+        records[w - 1] = h->ev_info[i];
+        records[w - 1].ms = ms;
+      }
+      continue;
+    }
+    if (w >= cap) break;
     records[w] = h->ev_info[i];
     records[w].ms = ms;
     ++w;
