@@ -314,6 +314,31 @@ def probe_microbench(args, torch, np, W, Proximity, device, steps=None, warmup=N
     assert all(sizes_1[key] == sizes_2[key] for key in ("hits", "misses", "evictions", "size")), "replay diverged"
     flops = 2.0 * batch * (n_keys + batch) * dim
     ms = total_ms / steps
+    probe_kernel = None
+    if planes is None:
+        # The probe's distance kernel alone, from the library's HIP events on a further replay of the first timed
+        # batches: one record per row range (first row, rows); a slice of 64 rows meets the slots and the batch rows
+        # up to its own last row.
+        px.clear()
+        for b0 in range(0, n_keys, batch):
+            px.search_batch(keys[b0:b0 + batch], tau)
+        for step in range(warmup):
+            px.search_batch(batches[step], tau, out_ids=out_ids, out_hit=out_hit[step], want_dists=False)
+        px.profile_start()
+        for step in range(warmup, warmup + min(steps, 8)):
+            px.search_batch(batches[step], tau, out_ids=out_ids, out_hit=out_hit[step], want_dists=False)
+        rec = px.profile_stop(kind=1)   # the probe launches
+        k_flops = k_ms = 0.0
+        for _, r0, rows, r_ms in rec:
+            for m0 in range(r0, r0 + rows, 64):
+                k_flops += 2.0 * min(64, r0 + rows - m0) * (n_keys + min(m0 + 64, r0 + rows)) * dim
+            k_ms += r_ms
+        if rec and k_ms > 0:
+            probe_kernel = {"kernel": "scan_regq_kernel (probe form)", "launches_timed": len(rec),
+                            "avg_launch_ms": round(k_ms / len(rec), 5), "launches_per_call": round(len(rec) / min(steps, 8), 2),
+                            "achieved_TFLOPs": round(k_flops / (k_ms * 1e-3) / 1e12, 2),
+                            "frac_of_f32_mfma_peak": round(k_flops / (k_ms * 1e-3) / 1e12 / F32_MFMA_PEAK_TFLOPS, 4),
+                            "algorithmic_flops_per_call": k_flops / min(steps, 8)}
     if planes is not None:
         # bucketed cache: no contraction; per row L inner products and at most b float64 distances
         line = {"metric": "cache_probes_per_sec", "value": round(batch / (ms * 1e-3), 1), "unit": "queries/s",
@@ -337,7 +362,8 @@ def probe_microbench(args, torch, np, W, Proximity, device, steps=None, warmup=N
                          "peak": F32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(flops / (ms * 1e-3) / 1e12 / F32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
                          "note": "whole call (probe contraction, candidate extraction, resolver, insertion) "
-                                 "against the probe contraction's 2*B*(c+B)*d flops"},
+                                 "against the probe contraction's 2*B*(c+B)*d flops",
+                         "probe_kernel": probe_kernel},
             "cpu_baseline": None}
     px.close()
     return line

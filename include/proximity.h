@@ -52,7 +52,7 @@
 extern "C" {
 #endif
 
-#define PROXIMITY_ABI_VERSION 5u
+#define PROXIMITY_ABI_VERSION 6u
 
 enum {
   PROXIMITY_OK = 0,
@@ -157,8 +157,10 @@ typedef struct proximity_stats_t {
 } proximity_stats_t;
 
 /*
- * One timed launch of the corpus-scan distance kernel (see proximity_profile_start).
- * A launch handles the misses number first_query .. first_query+n_queries-1 of its
+ * One timed launch (see proximity_profile_start), of the corpus-scan distance kernel
+ * (kind PROXIMITY_LAUNCH_SCAN) or of the cache probe's (kind PROXIMITY_LAUNCH_PROBE: it
+ * probed rows first_query .. first_query+n_queries-1 of its call against the stored keys
+ * and the call's earlier rows).  A scan launch handles the misses number first_query .. first_query+n_queries-1 of its
  * call; it streamed the corpus only if the call had more than first_query misses
  * (otherwise it returned at once), which the caller can tell from out_hit.  Where the
  * library launches the kernel in several tile shapes for the same queries (all but one of
@@ -170,7 +172,10 @@ typedef struct proximity_launch_t {
   uint32_t first_query;  /* index, within the call's miss list, of the launch's first query */
   uint32_t n_queries;    /* queries the launch is compiled to handle at once               */
   float ms;              /* duration from HIP events recorded on the call's stream         */
+  uint32_t kind;         /* PROXIMITY_LAUNCH_SCAN or PROXIMITY_LAUNCH_PROBE                 */
 } proximity_launch_t;
+#define PROXIMITY_LAUNCH_SCAN 0u
+#define PROXIMITY_LAUNCH_PROBE 1u
 
 uint32_t proximity_abi_version(void);
 
@@ -313,7 +318,10 @@ int proximity_clear(proximity_t* h);
 /*
  * Kernel timing for roofline reports.  After proximity_profile_start() every
  * launch of the corpus-scan distance kernel is bracketed with HIP events on the
- * call's stream (at most 8192 launches; later ones are not timed).
+ * call's stream (at most 8192 launches; later ones are not timed), and so is every
+ * launch of the cache probe that lists its candidates itself (Euclidean keys of 768 or
+ * 384 columns, calls of 64 rows and more): one record of kind PROXIMITY_LAUNCH_PROBE per
+ * row range of the call.
  * proximity_profile_stop() waits for the stream, writes up to cap records to
  * the HOST array `records` (may be NULL with cap 0), sets *n_records to the
  * number written, and stops timing.  Events are created by the start call,

@@ -20,7 +20,7 @@ ERR_INVALID_ARG, ERR_K_MISMATCH, ERR_BATCH_TOO_LARGE, ERR_BAD_TAU, ERR_HIP, ERR_
 DTYPE_F32, DTYPE_BF16 = 0, 1
 POLICY_FIFO, POLICY_LRU = 0, 1
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
-ABI_VERSION = 5
+ABI_VERSION = 6
 MAX_K, MAX_DIM, MAX_BATCH, MAX_CAPACITY = 240, 4096, 8192, 1 << 20   # PROXIMITY_MAX_* of the header
 STATIC_MAX_DOCS, STATIC_MAX_QUERIES = 1 << 18, 4                      # PROXIMITY_STATIC_MAX_* of the header
 
@@ -40,7 +40,11 @@ class ProximityStats(C.Structure):
 
 
 class ProximityLaunch(C.Structure):
-    _fields_ = [("call", C.c_uint32), ("first_query", C.c_uint32), ("n_queries", C.c_uint32), ("ms", C.c_float)]
+    _fields_ = [("call", C.c_uint32), ("first_query", C.c_uint32), ("n_queries", C.c_uint32), ("ms", C.c_float),
+                ("kind", C.c_uint32)]
+
+
+LAUNCH_SCAN, LAUNCH_PROBE = 0, 1
 
 
 if not os.path.exists(LIB_PATH):
@@ -222,11 +226,11 @@ class Proximity:
     def profile_start(self):
         self._check(lib.proximity_profile_start(self.handle))
 
-    def profile_stop(self, cap: int = 8192):
+    def profile_stop(self, cap: int = 8192, kind: int = LAUNCH_SCAN):
         rec = (ProximityLaunch * cap)()
         n = C.c_uint32(0)
         self._check(lib.proximity_profile_stop(self.handle, rec, cap, C.byref(n)))
-        return [(r.call, r.first_query, r.n_queries, r.ms) for r in rec[: n.value]]
+        return [(r.call, r.first_query, r.n_queries, r.ms) for r in rec[: n.value] if r.kind == kind]
 
     def close(self):
         if getattr(self, "handle", None):

@@ -58,7 +58,7 @@ constexpr long kSeedRows2 = 262144;    // second sample of a long corpus (regist
 
 static_assert(sizeof(proximity_config) == 72, "proximity_config layout is part of the ABI");
 static_assert(sizeof(proximity_stats_t) == 128, "proximity_stats_t layout is part of the ABI");
-static_assert(sizeof(proximity_launch_t) == 16, "proximity_launch_t layout is part of the ABI");
+static_assert(sizeof(proximity_launch_t) == 20, "proximity_launch_t layout is part of the ABI");
 
 thread_local std::string g_create_error;
 
@@ -289,10 +289,10 @@ void launch_scores_stream(const proximity* h, int mq, const void* X, const float
 void prof_begin(proximity* h, hipStream_t s) {
   if (h->prof_on && h->ev_used < h->ev0.size()) (void)hipEventRecord(h->ev0[h->ev_used], s);
 }
-void prof_end(proximity* h, hipStream_t s, int first_query, int n_queries) {
+void prof_end(proximity* h, hipStream_t s, int first_query, int n_queries, uint32_t kind = PROXIMITY_LAUNCH_SCAN) {
   if (h->prof_on && h->ev_used < h->ev0.size()) {
     (void)hipEventRecord(h->ev1[h->ev_used], s);
-    h->ev_info[h->ev_used] = proximity_launch_t{h->prof_call, uint32_t(first_query), uint32_t(n_queries), 0.f};
+    h->ev_info[h->ev_used] = proximity_launch_t{h->prof_call, uint32_t(first_query), uint32_t(n_queries), 0.f, kind};
     ++h->ev_used;
   }
 }
@@ -1135,6 +1135,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
       if (nb < slices) nb = slices;
       const RegqEmit em{c,         h->live_slots,  tau_key,         kCandCap, h->cand_cnt, h->cand_src,
                         h->cand_d, h->ovf_cnt + g, h->ovf_list + r0, nullptr,      0};
+      prof_begin(h, s);
       if (dim == 768)
         scan_regq_kernel<kDtypeF32, 768, 4, kRegqProbe><<<dim3((unsigned)nb), dim3(256), 0, s>>>(
             h->srcs, h->srcnrm, n_src, batch_rows, nullptr, nullptr, 0, nullptr, r1, r0, slices, 0, 0, nullptr, nullptr,
@@ -1143,6 +1144,7 @@ int proximity_search_batch(proximity_t* h, const float* queries, uint32_t n, uin
         scan_regq_kernel<kDtypeF32, 384, 4, kRegqProbe><<<dim3((unsigned)nb), dim3(256), 0, s>>>(
             h->srcs, h->srcnrm, n_src, batch_rows, nullptr, nullptr, 0, nullptr, r1, r0, slices, 0, 0, nullptr, nullptr,
             nullptr, 0, em);
+      prof_end(h, s, r0, rows, PROXIMITY_LAUNCH_PROBE);
       return;   // (enqueue_lists follows, on the stream that resolves the range)
     }
     if (nn <= kStreamMaxQueries) {
@@ -1359,7 +1361,8 @@ int proximity_profile_stop(proximity_t* h, proximity_launch_t* records, uint32_t
     HIP_TRY(h, hipEventElapsedTime(&ms, h->ev0[i], h->ev1[i]));
     // launches of one call for the same queries (one per tile shape): one record, that of the longest -- the
     // others returned at once
-    if (w > 0 && records[w - 1].call == h->ev_info[i].call && records[w - 1].first_query == h->ev_info[i].first_query) {
+    if (w > 0 && records[w - 1].call == h->ev_info[i].call && records[w - 1].first_query == h->ev_info[i].first_query &&
+        records[w - 1].kind == h->ev_info[i].kind) {
       if (ms > records[w - 1].ms) {
         records[w - 1] = h->ev_info[i];
         records[w - 1].ms = ms;

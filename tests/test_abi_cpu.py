@@ -34,10 +34,10 @@ def test_library_exports_every_declared_symbol(binding):
 
 
 def test_abi_version_and_struct_layout(binding):
-    assert binding.proximity_abi_version() == 5
+    assert binding.proximity_abi_version() == 6
     assert C.sizeof(binding.ProximityConfig) == 72
     assert C.sizeof(binding.ProximityStats) == 128
-    assert C.sizeof(binding.ProximityLaunch) == 16
+    assert C.sizeof(binding.ProximityLaunch) == 20
     text = open(os.path.join(ROOT, "include", "proximity.h")).read()
     limits = {m.group(1): eval(m.group(2).replace("u", "")) for m in
               re.finditer(r"#define PROXIMITY_MAX_(\w+)\s+(\(?[0-9u <]+\)?)", text)}
