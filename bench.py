@@ -124,8 +124,10 @@ COUNTER_TRAFFIC = {
 }
 
 
-def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
-    """Roofline entry from (duration ms, queries served) of the launches that streamed the corpus."""
+def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4, one_plane=False):
+    """Roofline entry from (duration ms, queries served) of the launches that streamed the corpus.
+    `one_plane`: the instance's batched scans multiplied the first bfloat16 plane of the queries only
+    (its stats say so)."""
     if not busy:
         return None
     bytes_per_launch = n_docs * dim * elem_bytes + n_docs * 4      # corpus rows + their norms, read once
@@ -135,11 +137,13 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
     tflops = sum(2.0 * q * n_docs * dim for _, q in busy) / (sum(ms for ms, _ in busy) * 1e-3) / 1e12
     # A bfloat16 corpus is scanned on the bfloat16 matrix cores with the float32 queries split into bfloat16
     # terms: one multiply-add of that type per term of the split and of the inner product.  The scan with the
-    # queries resident in registers (the dimensions it is built for) multiplies two terms, the general one three.
+    # queries resident in registers (the dimensions it is built for) multiplies two terms -- one while its
+    # exactness checks keep passing with the rounded queries --, the general one three.
     regq = batch > 4 and ((elem_bytes == 4 and dim in (768, 384)) or (elem_bytes == 2 and dim in (384, 256)))
     bf16_split = elem_bytes == 2 and dim >= 64 and batch > 4
     mfma_peak = BF16_MFMA_PEAK_TFLOPS if bf16_split else F32_MFMA_PEAK_TFLOPS
-    per_term = (2.0 if regq else 3.0) if bf16_split else 1.0
+    one_plane = one_plane and regq and bf16_split
+    per_term = (1.0 if one_plane else 2.0 if regq else 3.0) if bf16_split else 1.0
     ridge_q = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9) * elem_bytes / (2 * per_term)  # queries per launch at the ridge
     if batch <= 4:
         # single-query calls: the register-resident kernel in its scores-only form on long float32 corpora of the
@@ -147,7 +151,7 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
         dump = elem_bytes == 4 and dim in (768, 384) and n_docs >= 500_000
         kernel = "scan_regq_kernel (scores only)" if dump else "scores_stream_kernel"
     elif regq:
-        kernel = "scan_regq_kernel"
+        kernel = "scan_regq_kernel (one plane)" if one_plane else "scan_regq_kernel"
     elif bf16_split:
         kernel = "scan_bf16x3_kernel"
     else:
@@ -169,7 +173,7 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4):
                 "frac": round(gbs / HBM_PEAK_GBS, 4), **common}
     return {"bound": "mfma", "achieved": round(tflops * per_term, 2), "peak": mfma_peak, "unit": "TFLOP/s",
             "frac": round(tflops * per_term / mfma_peak, 4),
-            "mfma_dtype": f"bf16, queries split in {int(per_term)} terms, f32 accumulate" if bf16_split else "f32", **common}
+            "mfma_dtype": (f"bf16, {int(per_term)} term(s) of the query split, f32 accumulate") if bf16_split else "f32", **common}
 
 
 def k_recall_per_query(ids, truth):
@@ -479,8 +483,9 @@ def measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=None, 
     next_call = first_row // batch + steps
     n_prof = max(1, min(steps, 4000 if batch <= 8 else 400, w.n_stream // batch - next_call))
     busy = profiled_scan(torch, px, q_dev, tau, batch, next_call, n_prof, outs, device)
-    roofline = scan_roofline(busy, n_docs, w.dim, batch, elem)
     checks = px.stats()
+    one_plane = checks["coarse_scan_calls"] > 0 and checks["coarse_scan_fails"] == 0
+    roofline = scan_roofline(busy, n_docs, w.dim, batch, elem, one_plane)
 
     sweep = []
     if headline and not args.no_sweep and w.name == "mid":
@@ -493,7 +498,7 @@ def measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=None, 
                           "cache_preroll_rows": pre,
                           "queries_per_s": round(s_steps * s_batch / s_dt, 1), "hit_rate": round(s_hit, 4),
                           "ms_per_step": round(1e3 * s_dt / s_steps, 4),
-                          "roofline": scan_roofline(s_busy, n_docs, w.dim, s_batch, elem)})
+                          "roofline": scan_roofline(s_busy, n_docs, w.dim, s_batch, elem, one_plane)})
 
     cpu = None
     if headline and not args.no_cpu_baseline and corpus is not None:
@@ -514,7 +519,8 @@ def measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=None, 
                    "cache_preroll_rows": pre, "first_timed_row": first_row,
                    "hit_rate": round(hit_rate, 4),
                    "queries_timed": steps * batch, "setup_s": round(t_gen, 1),
-                   "searches_ranked_twice": checks["slack_exhausted"], "searches_not_proven_exact": checks["slack_unresolved"]},
+                   "searches_ranked_twice": checks["slack_exhausted"], "searches_not_proven_exact": checks["slack_unresolved"],
+                   "one_plane_scan_calls": checks["coarse_scan_calls"]},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     px.close()

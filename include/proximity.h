@@ -52,7 +52,7 @@
 extern "C" {
 #endif
 
-#define PROXIMITY_ABI_VERSION 6u
+#define PROXIMITY_ABI_VERSION 7u
 
 enum {
   PROXIMITY_OK = 0,
@@ -153,7 +153,12 @@ typedef struct proximity_stats_t {
                                      candidate lists, the resolver's state between ranges.  Fixed at
                                      creation; at most about 0.5 GiB unless capacity + max_batch
                                      exceeds a million                                              */
-  uint64_t reserved[5];
+  uint64_t coarse_scan_calls; /* since creation: calls whose index search multiplied only the first bfloat16
+                                 plane of the queries (see proximity_coarse_score_error)            */
+  uint64_t coarse_scan_fails; /* since creation: lists of such searches that could not be proven to hold
+                                 the k nearest (each also counts in slack_exhausted); once they stop
+                                 being rare the instance searches with two planes again             */
+  uint64_t reserved[3];
 } proximity_stats_t;
 
 /*
@@ -193,6 +198,19 @@ uint32_t proximity_abi_version(void);
  * |q| = query_length, X = max_row_length (the longest corpus row).  NaN for a bad argument.
  */
 double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_length, double max_row_length);
+
+/*
+ * What a one-plane search adds to that bound (host arithmetic, no GPU work).  On a bfloat16 corpus of 384 or 256
+ * columns, calls of more than four rows that ask the index for at most 165 neighbours are pre-ranked with the queries rounded to bfloat16 (the
+ * first plane of the split alone): half the matrix work, which leaves the scan bound by HBM.  A rounded query
+ * differs from the query by at most 2^-9 |q_i| per element, hence the score by at most
+ *   2^-8 |q| X   (L2, IP)        2^-8 |q|   (COSINE)
+ * (times 1.001 for the roundings that follow).  Such a search keeps k + max(32, k/2) candidates instead of k + 8,
+ * and its exactness check uses E + this term, so the lists it returns are as provably exact as the others; when
+ * the check fails more than rarely (coarse_scan_fails) the instance goes back to two planes.  NaN for a bad
+ * argument.
+ */
+double proximity_coarse_score_error(uint32_t metric, double query_length, double max_row_length);
 
 /*
  * The row ranges in which proximity_search_batch() probes and resolves a call of n rows against a flat cache

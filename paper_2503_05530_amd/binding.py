@@ -20,7 +20,7 @@ ERR_INVALID_ARG, ERR_K_MISMATCH, ERR_BATCH_TOO_LARGE, ERR_BAD_TAU, ERR_HIP, ERR_
 DTYPE_F32, DTYPE_BF16 = 0, 1
 POLICY_FIFO, POLICY_LRU = 0, 1
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
-ABI_VERSION = 6
+ABI_VERSION = 7
 MAX_K, MAX_DIM, MAX_BATCH, MAX_CAPACITY = 240, 4096, 8192, 1 << 20   # PROXIMITY_MAX_* of the header
 STATIC_MAX_DOCS, STATIC_MAX_QUERIES = 1 << 18, 4                      # PROXIMITY_STATIC_MAX_* of the header
 
@@ -36,7 +36,8 @@ class ProximityConfig(C.Structure):
 class ProximityStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("queries", "hits", "misses", "inserts", "evictions", "size",
                                           "inbatch_hits", "dense_resolves", "slack_exhausted",
-                                          "slack_unresolved", "probe_workspace_bytes")] + [("reserved", C.c_uint64 * 5)]
+                                          "slack_unresolved", "probe_workspace_bytes", "coarse_scan_calls",
+                                          "coarse_scan_fails")] + [("reserved", C.c_uint64 * 3)]
 
 
 class ProximityLaunch(C.Structure):
@@ -59,6 +60,8 @@ lib.proximity_abi_version.restype = C.c_uint32
 lib.proximity_abi_version.argtypes = []
 lib.proximity_score_error_bound.restype = C.c_double
 lib.proximity_score_error_bound.argtypes = [C.c_uint32, C.c_uint32, C.c_double, C.c_double]
+lib.proximity_coarse_score_error.restype = C.c_double
+lib.proximity_coarse_score_error.argtypes = [C.c_uint32, C.c_double, C.c_double]
 lib.proximity_probe_row_ranges.restype = C.c_uint32
 lib.proximity_probe_row_ranges.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                            C.POINTER(C.c_uint32), C.c_uint32]
@@ -87,7 +90,7 @@ lib.proximity_profile_start.argtypes = [_H]
 lib.proximity_profile_stop.restype = C.c_int
 lib.proximity_profile_stop.argtypes = [_H, C.POINTER(ProximityLaunch), C.c_uint32, C.POINTER(C.c_uint32)]
 
-EXPORTED = ("proximity_abi_version", "proximity_score_error_bound", "proximity_probe_row_ranges", "proximity_last_error", "proximity_create", "proximity_destroy",
+EXPORTED = ("proximity_abi_version", "proximity_score_error_bound", "proximity_coarse_score_error", "proximity_probe_row_ranges", "proximity_last_error", "proximity_create", "proximity_destroy",
             "proximity_search_batch", "proximity_knn_batch", "proximity_knn_static", "proximity_stats", "proximity_cache_dump",
             "proximity_clear", "proximity_profile_start", "proximity_profile_stop")
 

@@ -139,6 +139,11 @@ struct proximity {
   float* res_d = nullptr;
   SlackState* slack = nullptr;   // is the float32 candidate list long enough? (select_kernels.hpp)
   RedoBuffers redo{};            // queries noted for the second ranking of the batched scan, and their rows
+  // One-plane scans of a bfloat16 corpus (kRegqCoarse): whether this instance may run them, the list length
+  // they ask for, the host word the ranking kernel notes its failures in, and what the host has launched so far.
+  bool coarse_capable = false;
+  int* coarse_note = nullptr;
+  uint64_t coarse_calls = 0, coarse_queries = 0;
 
   // cache side
   float* srcs = nullptr;     // [capacity + max_batch][dim]: slot keys, then the current batch
@@ -363,11 +368,28 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
 #undef PROX_SCAN
 }
 
+// Candidates per query that a batched scan hands to the float64 ranking.  One-plane scores order rows less
+// finely than the error of a full score, so such a scan keeps half as many again (at least 32 more): on unit
+// Gaussian rows of 384 columns the rows within the coarse error of the k-th are about a sixth of k.
+inline int coarse_list_length(int k) { return k + (k / 2 > 32 ? k / 2 : 32); }
+constexpr int kCoarseMaxList = 248;
+inline int batched_list_length(const proximity* h, int k) {
+  return h->coarse_capable ? coarse_list_length(k) : k + kSlack;
+}
+// Does the next batched scan multiply one plane only?  Yes while lists that could not be proven sufficient stay
+// rare: each one costs a second ranking from a rescan (more than the plane saves in a whole call), so past
+// eight of them, and one per 1 024 queries scanned, the instance goes back to two planes for good.
+inline bool coarse_now(const proximity* h) {
+  if (!h->coarse_capable || !h->coarse_note) return false;
+  const uint64_t fails = uint64_t(*reinterpret_cast<volatile int*>(h->coarse_note));
+  return fails * 1024 <= h->coarse_queries + 8 * 1024;
+}
+
 // The same pass with the query tile resident in registers (regq_kernels.hpp), for the corpus types and
 // dimensions that kernel is instantiated for.  The queries base .. base+span-1 go in slices of 64 (float32)
 // or 128 (bfloat16); per slice the shape for every range of "queries from the slice's start on" that the
 // call can reach is launched, and the ones whose range does not contain the device-side count return at once.
-template <int DT, int DIM>
+template <int DT, int DIM, int MODE = kRegqScan>
 void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows, int G, const float* Qbase, const int* qlist,
                      const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
                      uint64_t* out, hipStream_t s) {
@@ -382,7 +404,7 @@ void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows
 #define PROX_REGQ(WQ, LO, HI)                                                                                   \
   if (rem_max > (LO) && (!known || rem_max <= (HI))) {                                                           \
     prof_begin(h, s);                                                                                            \
-    scan_regq_kernel<DT, DIM, WQ><<<dim3(G), dim3(256), 0, s>>>(X, xnrm, n_rows, Qbase, qlist, h->qplanes,             \
+    scan_regq_kernel<DT, DIM, WQ, MODE><<<dim3(G), dim3(256), 0, s>>>(X, xnrm, n_rows, Qbase, qlist, h->qplanes,       \
                                                                 plane_stride, m_count_ptr, m_limit, mb, LO, HI, kp,    \
                                                                 seed, h->topk_buf, out, cosine, RegqEmit{});           \
     prof_end(h, s, mb, rem_max < SLICE ? rem_max : SLICE);                                                       \
@@ -396,16 +418,21 @@ void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows
 
 void launch_regq_scan(proximity* h, const void* X, const float* xnrm, long n_rows, int G, const float* Qbase, const int* qlist,
                       const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
-                      uint64_t* out, hipStream_t s) {
+                      uint64_t* out, bool coarse, hipStream_t s) {
   const int dim = int(h->cfg.dim);
-#define PROX_REGQ_DIM(DT, D)                                                                                  \
-  launch_regq_dim<DT, D>(h, X, xnrm, n_rows, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, out, s)
+#define PROX_REGQ_DIM(DT, D, MODE)                                                                                 \
+  launch_regq_dim<DT, D, MODE>(h, X, xnrm, n_rows, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, out, s)
   if (h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16) {
-    if (dim == 384) PROX_REGQ_DIM(kDtypeBF16, 384);
-    else PROX_REGQ_DIM(kDtypeBF16, 256);
+    if (coarse) {
+      if (dim == 384) PROX_REGQ_DIM(kDtypeBF16, 384, kRegqCoarse);
+      else PROX_REGQ_DIM(kDtypeBF16, 256, kRegqCoarse);
+    } else {
+      if (dim == 384) PROX_REGQ_DIM(kDtypeBF16, 384, kRegqScan);
+      else PROX_REGQ_DIM(kDtypeBF16, 256, kRegqScan);
+    }
   } else {
-    if (dim == 768) PROX_REGQ_DIM(kDtypeF32, 768);
-    else PROX_REGQ_DIM(kDtypeF32, 384);
+    if (dim == 768) PROX_REGQ_DIM(kDtypeF32, 768, kRegqScan);
+    else PROX_REGQ_DIM(kDtypeF32, 384, kRegqScan);
   }
 #undef PROX_REGQ_DIM
 }
@@ -429,6 +456,21 @@ int enqueue_merge_levels(proximity* h, int cur, long len, int kp, const int* m_c
   return cur;
 }
 
+// Per-query lists of `len` keys in pairs[cur] down to one sorted list of kp keys: merge levels while a query's
+// keys are too many for one block, then one block per query.  `margin`: see cut_lists_kernel.
+int enqueue_cut(proximity* h, int cur, long len, int kp, const float* Qbase, const int* qlist, const int* m_count_ptr,
+                int m_limit, int margin, hipStream_t s) {
+  long left = len;
+  cur = enqueue_merge_levels(h, cur, len, kp, m_count_ptr, m_limit, s, kCutMaxKeys, &left);
+  if (left > kp || margin) {
+    cut_lists_kernel<<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], left, kp, h->pairs[cur ^ 1], m_count_ptr,
+                                                                    m_limit, margin, Qbase, qlist, int(h->cfg.dim),
+                                                                    int(h->cfg.metric), h->slack);
+    cur ^= 1;
+  }
+  return cur;
+}
+
 // The index search for the queries listed in qlist (or rows 0..m_limit-1 of
 // Qbase when qlist is null): scores, hierarchical top-k, float64 ranking.
 // Results (k entries per query, k <= the instance's K) land in row qlist[m] (or m) of res_ids / res_d.
@@ -442,12 +484,14 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     fill_empty_results_kernel<<<dim3(m_limit), dim3(64), 0, s>>>(qlist, m_count_ptr, m_limit, k, res_ids, res_d);
     return PROXIMITY_OK;
   }
-  const int kp = k + kSlack;
+  const bool batched = m_limit > kStreamMaxQueries;
+  const int kp = batched ? batched_list_length(h, k) : k + kSlack;
   const bool bf16 = h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16;
   const int metric = int(h->cfg.metric), cosine = metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
   int cur = 0;
   long left = kp;  // keys per query handed to the ranking kernel
-  if (m_limit <= kStreamMaxQueries) {
+  bool coarse = false;
+  if (!batched) {
     const int mq = stream_group(dim, m_limit);
     const int g1 = int((N + kSelSeg - 1) / kSelSeg);
     for (int m0 = 0; m0 < m_limit; m0 += mq) {
@@ -511,6 +555,12 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     if (bf16 && dim >= 64)
       split_bf16x3_kernel<<<dim3(m_limit), dim3(256), 0, s>>>(Qbase, qlist, m_count_ptr, m_limit, dim, h->qplanes,
                                                                long(h->cfg.max_batch) * dim);
+    const bool regq = regq_supported(int(h->cfg.corpus_dtype), dim);
+    coarse = regq && coarse_now(h);
+    if (coarse) {
+      ++h->coarse_calls;
+      h->coarse_queries += uint64_t(m_limit);
+    }
     if (N >= 8L * kSeedRows) {
       const int gs = kSeedRows / 128;
       // the head's scores are written out whole and merged; rows of 32 columns only: per-block lists
@@ -520,11 +570,12 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
         launch_batched_scan(h, kSeedRows, gs, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, nullptr,
                             h->pairs[0], dump_seed, s);
       }
-      cur = enqueue_merge_levels(h, 0, dump_seed ? long(kSeedRows) : long(gs) * kp, kp, m_count_ptr, m_limit, s, kp);
+      // (the register-resident scan is not the kernel that scored the head: its bound gets the margin between the two)
+      cur = enqueue_cut(h, 0, dump_seed ? long(kSeedRows) : long(gs) * kp, kp, Qbase, qlist, m_count_ptr, m_limit,
+                        regq ? (coarse ? 2 : 1) : 0, s);
       seed = h->pairs[cur];
       cur ^= 1;  // the full scan writes into the other buffer
     }
-    const bool regq = regq_supported(int(h->cfg.corpus_dtype), dim);
     const int G = regq ? h->scan_blocks_regq : h->scan_blocks;
     if (regq && seed && N >= 128L * kSeedRows) {
       // A long corpus gets a second, longer sample (the next N / 32 rows, at most kSeedRows2), scanned with the
@@ -540,10 +591,10 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       for (int base = 0; base < m_limit; base += kScanPassQueries) {
         const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
         launch_regq_scan(h, X2, h->xnrm + kSeedRows, rows2, g2, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed,
-                         h->pairs[cur], s);
+                         h->pairs[cur], coarse, s);
       }
       h->prof_on = timing;
-      cur = enqueue_merge_levels(h, cur, long(g2) * kp, kp, m_count_ptr, m_limit, s, kp);
+      cur = enqueue_cut(h, cur, long(g2) * kp, kp, Qbase, qlist, m_count_ptr, m_limit, 0, s);
       seed = h->pairs[cur];   // (row numbers in these keys count from the sample's first row; only scores are used)
       cur ^= 1;
     }
@@ -551,7 +602,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
       if (regq) {
         launch_regq_scan(h, h->cfg.corpus, h->xnrm, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed,
-                         h->pairs[cur], s);
+                         h->pairs[cur], coarse, s);
       } else {
         prof_begin(h, s);
         launch_batched_scan(h, N, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, h->pairs[cur], false,
@@ -560,7 +611,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       }
     }
     // the last merge level happens inside the ranking kernel
-    cur = enqueue_merge_levels(h, cur, long(G) * kp, kp, m_count_ptr, m_limit, s, kRerankMergeKeys, &left);
+    cur = enqueue_merge_levels(h, cur, long(G) * kp, kp, m_count_ptr, m_limit, s, kCutMaxKeys, &left);
   }
   const int n_lists = int(left / kp);
   // float64 ranking of the candidates, then -- for queries whose list could not be proven long enough, which
@@ -570,7 +621,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   if (bf16) {
     rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
         h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr, m_limit, res_ids, res_d, metric,
-        h->slack, h->redo);
+        h->slack, h->redo, coarse ? 1 : 0);
     redo_collect_kernel<kDtypeBF16><<<dim3((unsigned)rg), dim3(256), 0, s>>>(h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist,
                                                                              h->slack, h->redo, cosine);
     redo_rank_kernel<kDtypeBF16><<<dim3(m_limit), dim3(1024), 0, s>>>(h->cfg.corpus, dim, Qbase, qlist, h->slack,
@@ -578,7 +629,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   } else {
     rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
         h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr, m_limit, res_ids, res_d, metric,
-        h->slack, h->redo);
+        h->slack, h->redo, 0);
     redo_collect_kernel<kDtypeF32><<<dim3((unsigned)rg), dim3(256), 0, s>>>(h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist,
                                                                             h->slack, h->redo, cosine);
     redo_rank_kernel<kDtypeF32><<<dim3(m_limit), dim3(1024), 0, s>>>(h->cfg.corpus, dim, Qbase, qlist, h->slack,
@@ -656,6 +707,11 @@ double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_l
   if (metric > PROXIMITY_METRIC_COSINE || dim == 0 || !(query_length >= 0.0) || !(max_row_length >= 0.0))
     return std::nan("");
   return score_error_bound(int(metric), int(dim), query_length, max_row_length);
+}
+
+double proximity_coarse_score_error(uint32_t metric, double query_length, double max_row_length) {
+  if (metric > PROXIMITY_METRIC_COSINE || !(query_length >= 0.0) || !(max_row_length >= 0.0)) return std::nan("");
+  return coarse_score_error(int(metric), query_length, max_row_length);
 }
 
 uint32_t proximity_probe_row_ranges(uint32_t n, uint32_t capacity, uint32_t max_batch, uint32_t listing, uint32_t n_cu,
@@ -736,10 +792,10 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     g_create_error = h->err;
     for (hipEvent_t e : h->ev_probe) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_go) if (e) (void)hipEventDestroy(e);
-  for (hipEvent_t e : h->ev_go) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_res) if (e) (void)hipEventDestroy(e);
     if (h->side) (void)hipStreamDestroy(h->side);
     for (void* p : h->allocs) (void)hipFree(p);
+    if (h->coarse_note) (void)hipHostFree(h->coarse_note);
     delete h;
     return code;
   };
@@ -752,7 +808,12 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     h->n_cu = prop.multiProcessorCount;
 
   const size_t c = size_t(h->slots), B = cfg->max_batch, d = cfg->dim, k = size_t(h->K), N = cfg->n_docs;
-  const int kp = int(k) + kSlack;  // sized for the K = rerank_factor * k neighbours a search call asks for
+  // One-plane scans: a bfloat16 corpus of a dimension the register-resident scan has, calls of more than a handful
+  // of rows, and a list length the ranking kernel holds.
+  h->coarse_capable = cfg->corpus_dtype == PROXIMITY_DTYPE_BF16 && regq_supported(kDtypeBF16, int(d)) && N > 0 &&
+                      B > size_t(kStreamMaxQueries) && coarse_list_length(int(k)) <= kCoarseMaxList;
+  // sized for the K = rerank_factor * k neighbours a search call asks for
+  const int kp = h->coarse_capable ? coarse_list_length(int(k)) : int(k) + kSlack;
   int rc;
 #define TRY_ALLOC(ptr, count, zero)                              \
   if ((rc = dev_alloc(h, &(ptr), (count), (zero))) != PROXIMITY_OK) return bail(rc)
@@ -790,6 +851,22 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     TRY_ALLOC(h->redo.thr, B, true);
     TRY_ALLOC(h->redo.cnt, B, true);
     TRY_ALLOC(h->redo.wide, B * size_t(kWideCap), false);
+  }
+  if (h->coarse_capable) {
+    // (pinned host memory the device writes through; without it the instance simply scans with two planes)
+    void* note = nullptr;
+    if (hipHostMalloc(&note, 64, hipHostMallocDefault) == hipSuccess && note) {
+      std::memset(note, 0, 64);
+      void* dev_view = nullptr;
+      if (hipHostGetDevicePointer(&dev_view, note, 0) == hipSuccess && dev_view) {
+        h->coarse_note = static_cast<int*>(note);
+        h->redo.coarse_note = static_cast<int*>(dev_view);
+      } else {
+        (void)hipHostFree(note);
+      }
+    } else {
+      (void)hipGetLastError();
+    }
   }
   TRY_ALLOC(h->srcs, (c + B) * d, true);
   TRY_ALLOC(h->srcnrm, c + B, true);
@@ -913,6 +990,7 @@ void proximity_destroy(proximity_t* h) {
   for (hipEvent_t e : h->ev_res) if (e) (void)hipEventDestroy(e);
   if (h->side) (void)hipStreamDestroy(h->side);
   for (void* p : h->allocs) (void)hipFree(p);
+  if (h->coarse_note) (void)hipHostFree(h->coarse_note);
   delete h;
 }
 
@@ -1266,6 +1344,8 @@ int proximity_stats(const proximity_t* h, proximity_stats_t* out) {
   out->slack_exhausted = sl.exhausted;
   out->slack_unresolved = sl.unresolved;
   out->probe_workspace_bytes = h->probe_ws_bytes;
+  out->coarse_scan_calls = h->coarse_calls;
+  out->coarse_scan_fails = uint64_t(sl.coarse_fails);
   return PROXIMITY_OK;
 }
 

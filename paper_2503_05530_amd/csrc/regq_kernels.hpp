@@ -157,6 +157,11 @@ __device__ __forceinline__ uint32_t regq_bf16x2_times_minus2(uint32_t w) {
 // batch rows), the queries are batch rows, and instead of a running top-k every (row, source) pair whose score
 // passes the row's bound is handed on: the candidates that the float64 distance then decides.
 constexpr int kRegqScan = 0, kRegqProbe = 1, kRegqDump = 2;   // what the kernel does with its scores (MODE)
+// kRegqScan with the first plane of the bfloat16 queries only: half the matrix work, which at 128 queries turns
+// the scan from matrix-bound into HBM-bound.  Its scores are off by up to 2^-8 |q| |x| (coarse_score_error); they
+// only pick the candidates whose float64 distances rank, the caller asks for a longer list than k + 8 and the
+// exactness check of the ranking carries the term, so the ranked lists stay provably exact.
+constexpr int kRegqCoarse = 3;
 
 struct RegqEmit {
   int c;                 // cache slots: sources 0..c-1 are slot keys, c + j is batch row j
@@ -218,6 +223,8 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   static_assert(DIM % SLAB_COLS == 0, "whole slabs");
 
   constexpr bool EMIT = MODE == kRegqProbe, DUMP = MODE == kRegqDump;
+  constexpr int PLANES = MODE == kRegqCoarse ? 1 : kRegqPlanes;
+  static_assert(MODE != kRegqCoarse || !F32, "one plane of a bfloat16 split");
   static_assert(!EMIT || F32, "the probe's keys are float32");
   static_assert(!DUMP || WQ == 1, "scores of one query group");
   const int M = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
@@ -254,7 +261,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   // ---- the wave's queries, times -2, into registers (queries past M repeat the last one; their results are
   // dropped) ----
   f32x4 bq_f[F32 ? DIM / 16 : 1];
-  bf16x8 bq_h[F32 ? 1 : kRegqPlanes][F32 ? 1 : DIM / 16];
+  bf16x8 bq_h[F32 ? 1 : PLANES][F32 ? 1 : DIM / 16];
   {
     int m = m0 + q_local;
     m = m < M ? m : M - 1;
@@ -267,7 +274,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
       }
     } else {
 #pragma unroll
-      for (int p = 0; p < kRegqPlanes; ++p)
+      for (int p = 0; p < PLANES; ++p)
 #pragma unroll
         for (int t = 0; t < DIM / 16; ++t) {
           uint4 w = *reinterpret_cast<const uint4*>(Qplanes + long(p) * plane_stride + long(m) * DIM + 16 * t + 8 * kg);
@@ -487,9 +494,9 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
           for (int bb = 0; bb < GB; ++bb) regq_mfma(acc[(b0 + bb) * NSPLIT + e % NSPLIT], a[c][bb][e], bq_f[t][e]);
       } else {
 #pragma unroll
-        for (int p = 0; p < kRegqPlanes; ++p)
+        for (int p = 0; p < PLANES; ++p)
 #pragma unroll
-          for (int bb = 0; bb < GB; ++bb) regq_mfma(acc[(b0 + bb) * NSPLIT + p % NSPLIT], a[c][bb], bq_h[p][t]);
+          for (int bb = 0; bb < GB; ++bb) regq_mfma(acc[(b0 + bb) * NSPLIT + (PLANES == 1 ? c : p) % NSPLIT], a[c][bb], bq_h[p][t]);
       }
       if (c == NCHUNK / 2 - 1) {
         if (c + 1 < NCHUNK) wait_chunk(a[c + 1], false);  // nothing in flight across the barrier and the loads

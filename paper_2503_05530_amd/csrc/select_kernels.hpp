@@ -280,7 +280,7 @@ struct SlackState {
   unsigned xmax2_bits;      // largest squared row length of the corpus, as float bits (non-negative floats order as unsigned)
   int redo_count;           // queries of the current call whose list could not be proven sufficient
   int redo_ticket;          // blocks of the second ranking that have finished
-  int pad;
+  int coarse_fails;         // lists of a one-plane scan (regq_kernels.hpp) that could not be proven sufficient, ever
   unsigned long long exhausted, unresolved;
 };
 // The queries noted for the second ranking of the batched scan, one entry per row a call can carry.
@@ -289,6 +289,8 @@ struct RedoBuffers {
   float* thr;       // [max_batch] t_k + E of each, rounded up
   int* cnt;         // [max_batch] rows collected for each; zero between calls
   uint64_t* wide;   // [max_batch][kWideCap] the collected rows as packed (score, row) keys
+  int* coarse_note; // HOST memory the device can write (or null): receives coarse_fails whenever it grows, for the
+                    // host to read, without waiting for anything, when it picks the next call's scan
 };
 
 __host__ __device__ inline double score_error_bound(int metric, int dim, double q_len, double x_max) {
@@ -296,6 +298,13 @@ __host__ __device__ inline double score_error_bound(int metric, int dim, double 
   if (metric == kMetricL2) return g * (x_max * x_max + 2.0 * q_len * x_max);
   if (metric == kMetricIP) return g * 2.0 * q_len * x_max;
   return g * 4.0 * q_len;
+}
+// What a scan that multiplies only the first bfloat16 plane of the queries adds to that: the plane is the
+// query rounded to nearest, |q_i - hi_i| <= 2^-9 |q_i|, so the inner product moves by at most 2^-9 |q| |x| and the
+// score by twice that (a thousandth on top for the roundings that follow).
+__host__ __device__ inline double coarse_score_error(int metric, double q_len, double x_max) {
+  const double u = 0.00390625 * 1.001;
+  return metric == kMetricCosine ? u * q_len : u * q_len * x_max;
 }
 // the exact score that goes with a float64 distance (qq = |q|^2)
 __device__ __forceinline__ double score_of_distance(int metric, double d, double qq) {
@@ -306,11 +315,12 @@ __device__ __forceinline__ double score_of_distance(int metric, double d, double
 
 // Block-uniform verdict on a sorted list of kp float32 candidates whose k-th smallest float64 distance is
 // kth_d: true when the list provably holds the k nearest rows.  *thr receives t_k + E (rounded up), the
-// score bound of the second ranking.  `red` is 2 doubles of LDS.  Ends with a barrier.
+// score bound of the second ranking (which scores with the whole query: its bound never carries the coarse
+// term).  `coarse`: the list was ranked by one-plane scores.  `red` is 2 doubles of LDS.  Ends with a barrier.
 __device__ __forceinline__ bool block_list_sufficient(const uint64_t* keys, int kp, double kth_d,
                                                       const float* __restrict__ q, int dim, int metric,
                                                       const SlackState* __restrict__ slack, double* red, float* thr,
-                                                      int tid) {
+                                                      int tid, bool coarse = false) {
   if (tid < 64) {
     double qq = 0.0;
     for (int x = tid; x < dim; x += 64) qq += double(q[x]) * double(q[x]);
@@ -322,8 +332,9 @@ __device__ __forceinline__ bool block_list_sufficient(const uint64_t* keys, int 
       if (key_id(worst) >= 0) {   // a padding entry means every row of the corpus is in the list
         const double x_max = sqrt(double(__uint_as_float(slack->xmax2_bits)));
         const double e = score_error_bound(metric, dim, sqrt(qq), x_max) * (1.0 + 1e-6);
+        const double e_list = coarse ? e + coarse_score_error(metric, sqrt(qq), x_max) : e;
         const double t_k = score_of_distance(metric, kth_d, qq);
-        ok = double(key_score(worst)) - e > t_k;
+        ok = double(key_score(worst)) - e_list > t_k;
         t = __double2float_ru(t_k + e);
       }
       red[0] = ok ? 1.0 : 0.0;
@@ -484,7 +495,7 @@ __device__ __forceinline__ void block_topk_of_keys(const uint64_t* __restrict__ 
 // result arrays.  Padding candidates (id -1) get distance +inf and id -1.  Last it checks that the
 // list was long enough for the result to be exact (block_list_sufficient).
 constexpr int kRerankThreads = 1024;
-constexpr int kRerankMergeKeys = 2048;  // n_lists * kp may not exceed this
+constexpr int kRerankMergeKeys = 2048;  // LDS list of a cut: the keys at or below the block's bound (more: exact ties, folded in)
 template <int DT>
 __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64_t* __restrict__ cand, int n_lists,
                                                          int kp, int k,
@@ -494,7 +505,8 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
                                                          const int* __restrict__ m_count_ptr, int m_limit,
                                                          int64_t* __restrict__ res_ids,
                                                          float* __restrict__ res_dists, int metric,
-                                                         SlackState* __restrict__ slack, RedoBuffers redo) {
+                                                         SlackState* __restrict__ slack, RedoBuffers redo,
+                                                         int coarse) {
   const int m = blockIdx.x;
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   if (m >= m_total) return;
@@ -522,11 +534,61 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
   __syncthreads();
   // Was the list long enough?  If that cannot be shown the query is noted for the second ranking
   // (redo_collect_kernel / redo_rank_kernel), which overwrites this row of the result.
-  if (!block_list_sufficient(mine, kp, kth_d, q, dim, metric, slack, red, &thr, threadIdx.x) && threadIdx.x == 0) {
+  if (!block_list_sufficient(mine, kp, kth_d, q, dim, metric, slack, red, &thr, threadIdx.x, coarse != 0) &&
+      threadIdx.x == 0) {
     atomicAdd(&slack->exhausted, 1ull);
     const int pos = atomicAdd(&slack->redo_count, 1);   // below the call's row count: one note per query
     redo.list[pos] = m;
     redo.thr[pos] = thr;
+    if (coarse) {
+      const int fails = atomicAdd(&slack->coarse_fails, 1) + 1;
+      if (redo.coarse_note) {   // (concurrent notes may land out of order: the host only asks "how many, roughly")
+        *reinterpret_cast<volatile int*>(redo.coarse_note) = fails;
+        __threadfence_system();
+      }
+    }
+  }
+}
+
+// Per-query lists of `len` keys (sorted runs or not) cut to the kp best, sorted: out[m * kp ..].  One block of
+// sixteen waves per query; what the merge levels do for lists too long for one block, in one launch.
+//
+// With `margin` set the list is a sample's and seeds the bound of a scan by another kernel than the one that
+// scored the sample (another order of summation, other planes of the query): a sample row's score in that scan
+// can lie above its score here by both kernels' errors, and the bound taken as it stands could turn away, by a
+// rounding, rows that belong in the list.  The kp-th key (the only one the scans read) then gets that margin
+// added: twice the float32 bound, plus the rounding of the queries when the scan multiplies one plane of them
+// (margin = 2).
+constexpr long kCutMaxKeys = 65536;
+__global__ __launch_bounds__(kRerankThreads) void cut_lists_kernel(const uint64_t* __restrict__ in, long len, int kp,
+                                                                   uint64_t* __restrict__ out,
+                                                                   const int* __restrict__ m_count_ptr, int m_limit,
+                                                                   int margin, const float* __restrict__ Qbase,
+                                                                   const int* __restrict__ qlist, int dim, int metric,
+                                                                   const SlackState* __restrict__ slack) {
+  const int m = blockIdx.x, tid = threadIdx.x;
+  const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
+  if (m >= m_total) return;
+  __shared__ uint64_t list[kRerankMergeKeys];
+  __shared__ uint64_t mins[kRerankThreads / 64];
+  __shared__ int count;
+  block_topk_of_keys<kRerankThreads>(in + long(m) * len, len, kp, list, kRerankMergeKeys, mins, &count, tid);
+  __syncthreads();
+  uint64_t* o = out + long(m) * kp;
+  for (int i = tid; i < kp - 1; i += kRerankThreads) o[i] = list[i];
+  if (tid < 64) {
+    uint64_t key = list[kp - 1];
+    if (margin && key_id(key) >= 0) {   // (a padding key is +inf already)
+      const float* q = Qbase + long(qlist ? qlist[m] : m) * dim;
+      double qq = 0.0;
+      for (int x = tid; x < dim; x += 64) qq += double(q[x]) * double(q[x]);
+      qq = wave_sum(qq);
+      const double x_max = sqrt(double(__uint_as_float(slack->xmax2_bits)));
+      double e = 2.0 * score_error_bound(metric, dim, sqrt(qq), x_max);
+      if (margin == 2) e += coarse_score_error(metric, sqrt(qq), x_max);
+      key = pack_key(__double2float_ru(double(key_score(key)) + e * (1.0 + 1e-6)), uint32_t(key_id(key)));
+    }
+    if (tid == 0) o[kp - 1] = key;
   }
 }
 

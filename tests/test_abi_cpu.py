@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol(binding):
 
 
 def test_abi_version_and_struct_layout(binding):
-    assert binding.proximity_abi_version() == 6
+    assert binding.proximity_abi_version() == 7
     assert C.sizeof(binding.ProximityConfig) == 72
     assert C.sizeof(binding.ProximityStats) == 128
     assert C.sizeof(binding.ProximityLaunch) == 20
@@ -174,6 +174,50 @@ def test_score_error_bound_by_hand_and_against_float32_arithmetic(binding):
             for metric in (0, 1, 2):
                 err = np.abs(got[metric].astype(np.float64) - exact[metric]).max()
                 assert err <= E(metric, dim, q_len, x_max), (dim, order, metric, err)
+
+
+def test_coarse_score_error_by_hand_and_against_rounded_queries(binding):
+    """What a search that multiplies only the bfloat16 rounding of a query may add to the score error: the
+    closed form by hand, and scores formed in float32 from rounded queries against bfloat16 rows really stay
+    within the sum of both bounds of the float64 scores of the unrounded query."""
+    import numpy as np
+    b = binding
+    E, C1 = b.lib.proximity_score_error_bound, b.lib.proximity_coarse_score_error
+    u = 2.0 ** -8 * 1.001
+    assert C1(0, 2.0, 0.5) == pytest.approx(u * 1.0, rel=1e-15)
+    assert C1(1, 2.0, 0.5) == pytest.approx(u * 1.0, rel=1e-15)
+    assert C1(2, 2.0, 123.0) == pytest.approx(u * 2.0, rel=1e-15)
+    for bad in ((3, 1.0, 1.0), (0, -1.0, 1.0), (0, 1.0, float("nan"))):
+        assert np.isnan(C1(*bad))
+
+    def to_bf16(v):          # round to nearest even, as float32 values
+        bits = v.astype(np.float32).view(np.uint32).astype(np.uint64)
+        bits = ((bits + 0x7fff + ((bits >> 16) & 1)) >> 16) << 16
+        return bits.astype(np.uint32).view(np.float32)
+
+    rng = np.random.default_rng(41)
+    worst = 0.0
+    for dim in (256, 384):
+        x = to_bf16(rng.standard_normal((400, dim)) * rng.uniform(0.2, 3.0, (400, 1)))
+        for trial in range(6):
+            q = (rng.standard_normal(dim) * rng.uniform(0.1, 5.0)).astype(np.float32)
+            if trial == 5:      # every element as far from its rounding as it gets, all to the same side
+                q = (to_bf16(q).astype(np.float64) * (1.0 + 2.0 ** -9 * 0.999)).astype(np.float32)
+            hi = to_bf16(q)
+            x64, q64 = x.astype(np.float64), q.astype(np.float64)
+            x_max, q_len = np.sqrt((x64 * x64).sum(1)).max(), np.sqrt((q64 * q64).sum())
+            exact = {0: (x64 * x64).sum(1) - 2 * x64 @ q64, 1: -2 * x64 @ q64,
+                     2: -2 * (x64 @ q64) / np.sqrt((x64 * x64).sum(1))}
+            dot = (x * hi[None, :]).sum(1, dtype=np.float32)
+            nrm = (x * x).sum(1, dtype=np.float32)
+            got = {0: nrm - np.float32(2) * dot, 1: np.float32(-2) * dot,
+                   2: np.float32(-2) * dot * (np.float32(1) / np.sqrt(nrm))}
+            for metric in (0, 1, 2):
+                err = np.abs(got[metric].astype(np.float64) - exact[metric]).max()
+                bound = E(metric, dim, q_len, x_max) + C1(metric, q_len, x_max)
+                assert err <= bound, (dim, trial, metric, err, bound)
+                worst = max(worst, err / bound)
+    assert worst > 0.02          # (the bound is not vacuous: aligned roundings come within two orders of it)
 
 
 def probe_ranges(b, n, capacity, max_batch, listing, n_cu=256):

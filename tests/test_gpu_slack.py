@@ -84,10 +84,11 @@ def test_crowded_rows_under_the_other_distance_functions(B, metric, n_queries):
 
 @pytest.mark.parametrize("n_queries", [2, 128])
 def test_duplicated_documents_in_a_bfloat16_corpus(B, n_queries):
-    """Fifty identical rows (bfloat16 cannot hold nearer-than-identical neighbours): equal distances rank by
-    index, on the three-term matrix-core scan and on the streaming scan alike."""
+    """Eighty identical rows (bfloat16 cannot hold nearer-than-identical neighbours; more of them than the longest
+    candidate list, k + 32 on the one-plane scan): equal distances rank by index, on the matrix-core scan and on
+    the streaming scan alike."""
     dim, k = 384, 20
-    x, where, centre = crowded_corpus(9000, dim, 50, 0.0, 62)
+    x, where, centre = crowded_corpus(9000, dim, 80, 0.0, 62)
     x16 = torch.from_numpy(x).to(DEV).to(torch.bfloat16)
     xh = x16.to(torch.float32).cpu().numpy()
     rng = np.random.default_rng(9)
@@ -131,3 +132,67 @@ def test_ordinary_corpora_pass_the_check(B):
         st = px.stats()
         assert st["slack_exhausted"] == 0 and st["slack_unresolved"] == 0, (dim, k, st)
         px.close()
+
+
+def bf16_corpus(x):
+    """The rows as bfloat16 on the device, and the same values as float32 on the host for the oracle."""
+    x16 = torch.from_numpy(x).to(DEV).to(torch.bfloat16)
+    return x16, x16.to(torch.float32).cpu().numpy()
+
+
+@pytest.mark.parametrize("dim,k,n_docs,n_queries", [(384, 100, 300_000, 128), (256, 10, 200_000, 40),
+                                                    (384, 3, 150_000, 5), (256, 160, 140_000, 70)])
+def test_one_plane_scan_of_ordinary_bfloat16_rows(B, dim, k, n_docs, n_queries):
+    """Calls of more than four rows on a bfloat16 corpus are pre-ranked with the queries rounded to bfloat16
+    (one plane of the split), with a longer candidate list and the rounding's error in the exactness check:
+    on unit Gaussian rows the check passes for every query, and the lists are the oracle's."""
+    x16, xh = bf16_corpus(W.corpus_f32(n_docs, dim, 5))
+    q = W.stream_for(W.WORKLOADS["lowreuse"], n_queries)[:, :dim].copy()
+    o_ids, o_d = po.batched_exact_knn(xh, q, k)
+    px = B.Proximity(x16, dim, 0, k, B.POLICY_FIFO, n_queries)
+    ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+    torch.cuda.synchronize(DEV)
+    assert (ids.cpu().numpy() == o_ids).all()
+    np.testing.assert_allclose(dists.cpu().numpy(), o_d, rtol=1e-6)
+    st = px.stats()
+    assert st["coarse_scan_calls"] == 1 and st["coarse_scan_fails"] == 0, st
+    assert st["slack_exhausted"] == 0 and st["slack_unresolved"] == 0, st
+    px.close()
+
+
+def test_more_neighbours_than_a_one_plane_list_holds_scan_with_two_planes(B):
+    dim, k, n_queries = 384, 170, 24          # 170 + 85 candidates: more than the ranking kernel holds
+    x16, xh = bf16_corpus(W.corpus_f32(140_000, dim, 6))
+    q = W.stream_for(W.WORKLOADS["lowreuse"], n_queries)
+    o_ids, _ = po.batched_exact_knn(xh, q, k)
+    px = B.Proximity(x16, dim, 0, k, B.POLICY_FIFO, n_queries)
+    ids, _ = px.knn_batch(torch.from_numpy(q).to(DEV))
+    assert (ids.cpu().numpy() == o_ids).all()
+    st = px.stats()
+    assert st["coarse_scan_calls"] == 0 and st["slack_exhausted"] == 0, st
+    px.close()
+
+
+@pytest.mark.parametrize("metric", [po.METRIC_L2, po.METRIC_IP, po.METRIC_COSINE])
+def test_a_crowd_within_the_rounding_of_the_queries(B, metric):
+    """Two hundred rows whose scores differ by less than the error a rounded query can cause (about a quarter of
+    it from one to the next at most), more of them than the one-plane list holds: the check fails for every query
+    of the first call, the second ranking still returns the oracle's lists, and the instance scans with two planes
+    from then on."""
+    dim, k, n_queries = 384, 10, 64
+    x, where, centre = crowded_corpus(140_000, dim, 200, 5e-4, 64)
+    x16, xh = bf16_corpus(x)
+    rng = np.random.default_rng(10)
+    q = (1.3 * (centre[None, :] + 0.05 * W.unit_rows(rng.standard_normal((n_queries, dim))))).astype(np.float32)
+    o_ids, o_d = po.batched_exact_knn(xh, q, k, metric=metric)
+    assert np.isin(o_ids, where).all()
+    px = B.Proximity(x16, dim, 0, k, B.POLICY_FIFO, n_queries, metric=metric)
+    for call in range(3):
+        ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+        torch.cuda.synchronize(DEV)
+        assert (ids.cpu().numpy() == o_ids).all(), call
+        np.testing.assert_allclose(dists.cpu().numpy(), o_d, rtol=1e-5, atol=1e-9)
+        st = px.stats()
+        assert st["coarse_scan_calls"] == 1 and st["coarse_scan_fails"] == n_queries, (call, st)
+        assert st["slack_exhausted"] >= n_queries and st["slack_unresolved"] == 0, (call, st)
+    px.close()
