@@ -114,12 +114,12 @@ COUNTER_TRAFFIC = {
     ("scan_regq_kernel (scores only)", 0, 1_000_000, 768, 4):
         {"fetch_bytes": 1_512_370 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scan_regq_mid_b1.md"},
     ("scan_regq_kernel", 64, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_514_304 * 2048, "write_bytes": 4_139 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
-    ("scan_regq_kernel", 128, 8_000_000, 384, 2):
-        {"fetch_bytes": 3_029_422 * 2048, "write_bytes": 38_449 * 1024,
+        {"fetch_bytes": 1_514_326 * 2048, "write_bytes": 4_199 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
+    ("scan_regq_kernel (one plane)", 128, 8_000_000, 384, 2):
+        {"fetch_bytes": 3_029_956 * 2048, "write_bytes": 55_165 * 1024,
          "source": "profiles/scan_regq_lowreuse_b128.md"},
     ("scan_regq_kernel", 64, 24_000_000, 768, 4):
-        {"fetch_bytes": 36_059_362 * 2048, "write_bytes": 12_860 * 1024,
+        {"fetch_bytes": 36_059_377 * 2048, "write_bytes": 12_885 * 1024,
          "source": "profiles/scan_regq_large_b256.md"},
 }
 
