@@ -126,8 +126,8 @@ COUNTER_TRAFFIC = {
 
 def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4, one_plane=False):
     """Roofline entry from (duration ms, queries served) of the launches that streamed the corpus.
-    `one_plane`: the instance's batched scans multiplied the first bfloat16 plane of the queries only
-    (its stats say so)."""
+    `one_plane`: the instance's batched scans ran on rounded operands -- the first bfloat16 plane of the queries,
+    and float32 rows rounded to bfloat16 on their way into the matrix instruction (its stats say so)."""
     if not busy:
         return None
     bytes_per_launch = n_docs * dim * elem_bytes + n_docs * 4      # corpus rows + their norms, read once
@@ -140,9 +140,9 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4, one_plane=False):
     # queries resident in registers (the dimensions it is built for) multiplies two terms -- one while its
     # exactness checks keep passing with the rounded queries --, the general one three.
     regq = batch > 4 and ((elem_bytes == 4 and dim in (768, 384)) or (elem_bytes == 2 and dim in (384, 256)))
-    bf16_split = elem_bytes == 2 and dim >= 64 and batch > 4
+    one_plane = one_plane and regq
+    bf16_split = (elem_bytes == 2 and dim >= 64 and batch > 4) or one_plane     # multiplied on the bfloat16 matrix cores
     mfma_peak = BF16_MFMA_PEAK_TFLOPS if bf16_split else F32_MFMA_PEAK_TFLOPS
-    one_plane = one_plane and regq and bf16_split
     per_term = (1.0 if one_plane else 2.0 if regq else 3.0) if bf16_split else 1.0
     ridge_q = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9) * elem_bytes / (2 * per_term)  # queries per launch at the ridge
     if batch <= 4:
@@ -151,12 +151,15 @@ def scan_roofline(busy, n_docs, dim, batch, elem_bytes=4, one_plane=False):
         dump = elem_bytes == 4 and dim in (768, 384) and n_docs >= 500_000
         kernel = "scan_regq_kernel (scores only)" if dump else "scores_stream_kernel"
     elif regq:
-        kernel = "scan_regq_kernel (one plane)" if one_plane else "scan_regq_kernel"
+        kernel = "scan_regq_kernel" if not one_plane else \
+            "scan_regq_kernel (one plane)" if elem_bytes == 2 else "scan_regq_kernel (rounded operands)"
     elif bf16_split:
         kernel = "scan_bf16x3_kernel"
     else:
         kernel = "scan_mfma_dma_kernel" if elem_bytes == 4 and dim >= 64 else "scan_mfma_topk_kernel"
     tile = 0 if batch <= 4 else (32 if avg_q <= 32 else 64 if avg_q <= 64 else 128)
+    if one_plane and elem_bytes == 4:
+        tile = 128 if avg_q > 64 else 64        # (the counters were taken on launches of these shapes)
     counted = COUNTER_TRAFFIC.get((kernel, tile, n_docs, dim, elem_bytes))
     if counted is not None:
         counted = dict(counted, measured_in_this_run=False,

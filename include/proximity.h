@@ -52,7 +52,7 @@
 extern "C" {
 #endif
 
-#define PROXIMITY_ABI_VERSION 7u
+#define PROXIMITY_ABI_VERSION 8u
 
 enum {
   PROXIMITY_OK = 0,
@@ -127,8 +127,11 @@ typedef struct proximity_config {
                              query-key distances are evaluated in float64, the cosine one as
                              1 - q.k / sqrt((q.q)(k.k)), which is exactly 0 for a key identical
                              to the query, so tau = 0 is an exact-match cache here too          */
-  uint32_t reserved0;     /* must be 0                                                        */
+  uint32_t flags;         /* PROXIMITY_FLAG_* or 0                                            */
 } proximity_config;
+/* Never pre-rank on rounded operands (see proximity_coarse_score_error): every batched index search multiplies
+ * the corpus as it is stored.  The results are the same either way; this is for comparing the two. */
+#define PROXIMITY_FLAG_NO_ROUNDED_SCAN 1u
 
 /* Counters since creation or the last proximity_clear(). */
 typedef struct proximity_stats_t {
@@ -141,11 +144,12 @@ typedef struct proximity_stats_t {
   uint64_t inbatch_hits;   /* hits on a key stored by an earlier row of the same call        */
   uint64_t dense_resolves; /* rows whose nearest key was found by the full-row fallback      */
   uint64_t slack_exhausted;  /* index searches (since creation or the last clear, proximity_knn_batch
-                                included) whose float32 candidate list of k + 8 rows could not be
+                                included) whose float32 candidate list (k + 8 rows; more after a one-plane
+                                search, see proximity_coarse_score_error) could not be
                                 proven to hold the k nearest under the float32 error bound, and were
                                 ranked again from every row within that bound of the k-th          */
   uint64_t slack_unresolved; /* of those, searches that stayed with the float64 ranking of their
-                                k + 8 candidates because the second ranking had no room: more than
+                                candidates because the second ranking had no room: more than
                                 2048 rows within the bound of the k-th (thousands of identical
                                 documents).  0 means every list returned so far is provably exact  */
   uint64_t probe_workspace_bytes; /* device memory the flat cache's probe holds beside keys and values:
@@ -153,11 +157,11 @@ typedef struct proximity_stats_t {
                                      candidate lists, the resolver's state between ranges.  Fixed at
                                      creation; at most about 0.5 GiB unless capacity + max_batch
                                      exceeds a million                                              */
-  uint64_t coarse_scan_calls; /* since creation: calls whose index search multiplied only the first bfloat16
-                                 plane of the queries (see proximity_coarse_score_error)            */
+  uint64_t coarse_scan_calls; /* since creation: calls whose index search ran on rounded operands (see
+                                 proximity_coarse_score_error)                                      */
   uint64_t coarse_scan_fails; /* since creation: lists of such searches that could not be proven to hold
                                  the k nearest (each also counts in slack_exhausted); once they stop
-                                 being rare the instance searches with two planes again             */
+                                 being rare the instance searches on the operands as they are       */
   uint64_t reserved[3];
 } proximity_stats_t;
 
@@ -200,17 +204,22 @@ uint32_t proximity_abi_version(void);
 double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_length, double max_row_length);
 
 /*
- * What a one-plane search adds to that bound (host arithmetic, no GPU work).  On a bfloat16 corpus of 384 or 256
- * columns, calls of more than four rows that ask the index for at most 165 neighbours are pre-ranked with the queries rounded to bfloat16 (the
- * first plane of the split alone): half the matrix work, which leaves the scan bound by HBM.  A rounded query
- * differs from the query by at most 2^-9 |q_i| per element, hence the score by at most
- *   2^-8 |q| X   (L2, IP)        2^-8 |q|   (COSINE)
- * (times 1.001 for the roundings that follow).  Such a search keeps k + max(32, k/2) candidates instead of k + 8,
- * and its exactness check uses E + this term, so the lists it returns are as provably exact as the others; when
- * the check fails more than rarely (coarse_scan_fails) the instance goes back to two planes.  NaN for a bad
+ * What a search on rounded operands adds to that bound (host arithmetic, no GPU work).  Calls of more than four
+ * rows on a corpus of 768 or 384 float32 columns, or 384 or 256 bfloat16 columns, are pre-ranked on the bfloat16
+ * matrix cores with the queries rounded to bfloat16 (the first plane of the split alone) and float32 rows rounded
+ * likewise on their way into the matrix instruction: the scan is then bound by HBM alone at up to 128 queries.
+ * A rounded value differs from the value by at most 2^-9 of it, hence the score by at most
+ *   2^-8 |q| X   (L2, IP)        2^-8 |q|   (COSINE)          bfloat16 corpus: queries rounded
+ *   2.002 times that                                          float32 corpus: rows rounded too
+ * (times 1.001 for the roundings that follow).  Such a search keeps more candidates than k + 8 -- as many as
+ * isotropic rows would put within this error of the k-th, and a margin: 46 for k = 10 in 1 M x 768 float32 rows,
+ * 159 for k = 100 in 8 M x 384 bfloat16 rows; it is used when that is at most 248 -- and its exactness check uses
+ * E + this term, so the lists it returns are as provably exact as the others; when the check fails more than
+ * rarely (coarse_scan_fails) the instance goes back to multiplying the operands as they are.  NaN for a bad
  * argument.
  */
-double proximity_coarse_score_error(uint32_t metric, double query_length, double max_row_length);
+double proximity_coarse_score_error(uint32_t metric, uint32_t corpus_dtype, double query_length,
+                                    double max_row_length);
 
 /*
  * The row ranges in which proximity_search_batch() probes and resolves a call of n rows against a flat cache

@@ -20,7 +20,8 @@ ERR_INVALID_ARG, ERR_K_MISMATCH, ERR_BATCH_TOO_LARGE, ERR_BAD_TAU, ERR_HIP, ERR_
 DTYPE_F32, DTYPE_BF16 = 0, 1
 POLICY_FIFO, POLICY_LRU = 0, 1
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
-ABI_VERSION = 7
+ABI_VERSION = 8
+FLAG_NO_ROUNDED_SCAN = 1
 MAX_K, MAX_DIM, MAX_BATCH, MAX_CAPACITY = 240, 4096, 8192, 1 << 20   # PROXIMITY_MAX_* of the header
 STATIC_MAX_DOCS, STATIC_MAX_QUERIES = 1 << 18, 4                      # PROXIMITY_STATIC_MAX_* of the header
 
@@ -30,7 +31,7 @@ class ProximityConfig(C.Structure):
                 ("n_docs", C.c_uint64), ("corpus_dtype", C.c_uint32), ("capacity", C.c_uint32),
                 ("k", C.c_uint32), ("policy", C.c_uint32), ("max_batch", C.c_uint32), ("device", C.c_int32),
                 ("rerank_factor", C.c_uint32), ("lsh_bits", C.c_uint32), ("lsh_planes", C.c_void_p),
-                ("metric", C.c_uint32), ("reserved0", C.c_uint32)]
+                ("metric", C.c_uint32), ("flags", C.c_uint32)]
 
 
 class ProximityStats(C.Structure):
@@ -61,7 +62,7 @@ lib.proximity_abi_version.argtypes = []
 lib.proximity_score_error_bound.restype = C.c_double
 lib.proximity_score_error_bound.argtypes = [C.c_uint32, C.c_uint32, C.c_double, C.c_double]
 lib.proximity_coarse_score_error.restype = C.c_double
-lib.proximity_coarse_score_error.argtypes = [C.c_uint32, C.c_double, C.c_double]
+lib.proximity_coarse_score_error.argtypes = [C.c_uint32, C.c_uint32, C.c_double, C.c_double]
 lib.proximity_probe_row_ranges.restype = C.c_uint32
 lib.proximity_probe_row_ranges.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                            C.POINTER(C.c_uint32), C.c_uint32]
@@ -134,9 +135,10 @@ class Proximity:
 
     def __init__(self, corpus: Optional[torch.Tensor], dim: int, capacity: int, k: int, policy: int,
                  max_batch: int, device: Optional[torch.device] = None, rerank_factor: int = 1,
-                 lsh_planes: Optional[torch.Tensor] = None, metric: int = METRIC_L2):
+                 lsh_planes: Optional[torch.Tensor] = None, metric: int = METRIC_L2, flags: int = 0):
         """``lsh_planes`` (device float32 [L][dim]) selects the bucketed cache of Section 3.2: 2^L buckets of
-        ``capacity`` entries each.  ``metric`` is the index's distance function (METRIC_*)."""
+        ``capacity`` entries each.  ``metric`` is the index's distance function (METRIC_*), ``flags`` a sum of
+        FLAG_*."""
         if corpus is not None:
             if not corpus.is_cuda or not corpus.is_contiguous() or corpus.dim() != 2:
                 raise ValueError("corpus must be a contiguous 2-D device tensor")
@@ -167,7 +169,7 @@ class Proximity:
         cfg = ProximityConfig(C.sizeof(ProximityConfig), dim, corpus.data_ptr() if corpus is not None else None,
                               n_docs, dtype, capacity, k, policy, max_batch,
                               device.index if device.index is not None else 0, int(rerank_factor), self.lsh_bits,
-                              lsh_planes.data_ptr() if self.lsh_bits else None, int(metric), 0)
+                              lsh_planes.data_ptr() if self.lsh_bits else None, int(metric), int(flags))
         self.metric = int(metric)
         self.handle = _H()
         rc = lib.proximity_create(C.byref(cfg), C.byref(self.handle))

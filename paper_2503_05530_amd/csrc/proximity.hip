@@ -142,6 +142,7 @@ struct proximity {
   // One-plane scans of a bfloat16 corpus (kRegqCoarse): whether this instance may run them, the list length
   // they ask for, the host word the ranking kernel notes its failures in, and what the host has launched so far.
   bool coarse_capable = false;
+  int coarse_level = 0;          // 1: queries rounded (bfloat16 corpus); 2: rows rounded too (float32 corpus)
   int* coarse_note = nullptr;
   uint64_t coarse_calls = 0, coarse_queries = 0;
 
@@ -368,13 +369,23 @@ void launch_batched_scan(proximity* h, long n_rows, int G, const float* Qbase, c
 #undef PROX_SCAN
 }
 
-// Candidates per query that a batched scan hands to the float64 ranking.  One-plane scores order rows less
-// finely than the error of a full score, so such a scan keeps half as many again (at least 32 more): on unit
-// Gaussian rows of 384 columns the rows within the coarse error of the k-th are about a sixth of k.
-inline int coarse_list_length(int k) { return k + (k / 2 > 32 ? k / 2 : 32); }
+// Candidates per query that a batched scan hands to the float64 ranking.  Scores of rounded operands order rows
+// less finely than the error of a full score, so such a scan keeps more than k + 8: as many as a corpus of
+// isotropic rows would put within the rounding error E of the k-th, and a margin.  There a score has standard
+// deviation sigma = 2 |q| |x| / sqrt(d), so E = f 2^-8 |q| |x| is delta = f 2^-9 sqrt(d) of them (f = 1, or
+// 2.002 when the rows are rounded too); the k-th of N rows sits z = sqrt(2 ln(N / k)) deviations out, where the
+// density grows by e^z per deviation: k (e^(z delta) - 1) rows more on average, plus five times their spread,
+// plus 16.  (Low-reuse workload: 159; 1 M x 768 float32, k = 10: 46; 24 M x 768, k = 32: 97.)  Rows that crowd
+// more than that fail the exactness check and are ranked again, exactly; see coarse_now.
+inline int coarse_list_length(int k, int level, int dim, double n_docs) {
+  const double delta = std::sqrt(double(dim)) / 512.0 * (level >= 2 ? 2.002 : 1.0);
+  const double ratio = n_docs / double(k) > 2.0 ? n_docs / double(k) : 2.0;
+  const double more = double(k) * std::expm1(std::sqrt(2.0 * std::log(ratio)) * delta);
+  return k + int(std::ceil(more + 5.0 * std::sqrt(more) + 16.0));
+}
 constexpr int kCoarseMaxList = 248;
 inline int batched_list_length(const proximity* h, int k) {
-  return h->coarse_capable ? coarse_list_length(k) : k + kSlack;
+  return h->coarse_capable ? coarse_list_length(k, h->coarse_level, int(h->cfg.dim), double(h->cfg.n_docs)) : k + kSlack;
 }
 // Does the next batched scan multiply one plane only?  Yes while lists that could not be proven sufficient stay
 // rare: each one costs a second ranking from a rescan (more than the plane saves in a whole call), so past
@@ -393,7 +404,7 @@ template <int DT, int DIM, int MODE = kRegqScan>
 void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows, int G, const float* Qbase, const int* qlist,
                      const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
                      uint64_t* out, hipStream_t s) {
-  constexpr int QW = regq_queries_per_wave(DT), SLICE = 4 * QW;   // queries per wave and per block at most
+  constexpr int QW = regq_queries_per_wave(DT, MODE == kRegqCoarse), SLICE = 4 * QW;   // queries per wave and per block at most
   const int cosine = h->cfg.metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
   const long plane_stride = long(h->cfg.max_batch) * DIM;
   const bool known = m_count_ptr == nullptr;  // then M = m_limit and only its own shape is launched
@@ -430,6 +441,9 @@ void launch_regq_scan(proximity* h, const void* X, const float* xnrm, long n_row
       if (dim == 384) PROX_REGQ_DIM(kDtypeBF16, 384, kRegqScan);
       else PROX_REGQ_DIM(kDtypeBF16, 256, kRegqScan);
     }
+  } else if (coarse) {
+    if (dim == 768) PROX_REGQ_DIM(kDtypeF32, 768, kRegqCoarse);
+    else PROX_REGQ_DIM(kDtypeF32, 384, kRegqCoarse);
   } else {
     if (dim == 768) PROX_REGQ_DIM(kDtypeF32, 768, kRegqScan);
     else PROX_REGQ_DIM(kDtypeF32, 384, kRegqScan);
@@ -544,7 +558,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     cur = enqueue_merge_levels(h, 0, long(g1) * kp, kp, m_count_ptr, m_limit, s, kRerankMergeKeys, &left);
   } else {
     // (the kernels below write through these: never launch them on an instance that was not given the buffers)
-    if (!h->topk_buf || !h->pairs[0] || !h->pairs[1] || (bf16 && dim >= 64 && !h->qplanes))
+    if (!h->topk_buf || !h->pairs[0] || !h->pairs[1] || (((bf16 && dim >= 64) || h->coarse_capable) && !h->qplanes))
       return fail(h, PROXIMITY_ERR_INVALID_ARG, "%d queries in one search on an instance without the batched scan's workspace",
                   m_limit);
     // Batched scan on the matrix cores, in two steps.  First the head of the corpus
@@ -552,11 +566,11 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     // valid bound for the whole corpus and lets the full scan drop almost every row at once
     // instead of learning a bound block by block.  Then the full scan, then the merge.
     const uint64_t* seed = nullptr;
-    if (bf16 && dim >= 64)
-      split_bf16x3_kernel<<<dim3(m_limit), dim3(256), 0, s>>>(Qbase, qlist, m_count_ptr, m_limit, dim, h->qplanes,
-                                                               long(h->cfg.max_batch) * dim);
     const bool regq = regq_supported(int(h->cfg.corpus_dtype), dim);
     coarse = regq && coarse_now(h);
+    if ((bf16 && dim >= 64) || coarse)
+      split_bf16x3_kernel<<<dim3(m_limit), dim3(256), 0, s>>>(Qbase, qlist, m_count_ptr, m_limit, dim, h->qplanes,
+                                                               long(h->cfg.max_batch) * dim);
     if (coarse) {
       ++h->coarse_calls;
       h->coarse_queries += uint64_t(m_limit);
@@ -572,7 +586,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       }
       // (the register-resident scan is not the kernel that scored the head: its bound gets the margin between the two)
       cur = enqueue_cut(h, 0, dump_seed ? long(kSeedRows) : long(gs) * kp, kp, Qbase, qlist, m_count_ptr, m_limit,
-                        regq ? (coarse ? 2 : 1) : 0, s);
+                        regq ? (coarse ? 1 + h->coarse_level : 1) : 0, s);
       seed = h->pairs[cur];
       cur ^= 1;  // the full scan writes into the other buffer
     }
@@ -621,7 +635,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   if (bf16) {
     rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
         h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr, m_limit, res_ids, res_d, metric,
-        h->slack, h->redo, coarse ? 1 : 0);
+        h->slack, h->redo, coarse ? h->coarse_level : 0);
     redo_collect_kernel<kDtypeBF16><<<dim3((unsigned)rg), dim3(256), 0, s>>>(h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist,
                                                                              h->slack, h->redo, cosine);
     redo_rank_kernel<kDtypeBF16><<<dim3(m_limit), dim3(1024), 0, s>>>(h->cfg.corpus, dim, Qbase, qlist, h->slack,
@@ -629,7 +643,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   } else {
     rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
         h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr, m_limit, res_ids, res_d, metric,
-        h->slack, h->redo, 0);
+        h->slack, h->redo, coarse ? h->coarse_level : 0);
     redo_collect_kernel<kDtypeF32><<<dim3((unsigned)rg), dim3(256), 0, s>>>(h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist,
                                                                             h->slack, h->redo, cosine);
     redo_rank_kernel<kDtypeF32><<<dim3(m_limit), dim3(1024), 0, s>>>(h->cfg.corpus, dim, Qbase, qlist, h->slack,
@@ -709,9 +723,11 @@ double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_l
   return score_error_bound(int(metric), int(dim), query_length, max_row_length);
 }
 
-double proximity_coarse_score_error(uint32_t metric, double query_length, double max_row_length) {
-  if (metric > PROXIMITY_METRIC_COSINE || !(query_length >= 0.0) || !(max_row_length >= 0.0)) return std::nan("");
-  return coarse_score_error(int(metric), query_length, max_row_length);
+double proximity_coarse_score_error(uint32_t metric, uint32_t corpus_dtype, double query_length, double max_row_length) {
+  if (metric > PROXIMITY_METRIC_COSINE || corpus_dtype > PROXIMITY_DTYPE_BF16 || !(query_length >= 0.0) ||
+      !(max_row_length >= 0.0))
+    return std::nan("");
+  return coarse_score_error(int(metric), query_length, max_row_length, corpus_dtype == PROXIMITY_DTYPE_BF16 ? 1 : 2);
 }
 
 uint32_t proximity_probe_row_ranges(uint32_t n, uint32_t capacity, uint32_t max_batch, uint32_t listing, uint32_t n_cu,
@@ -773,7 +789,8 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "corpus must be 16-byte aligned (rows are read 16 bytes at a time)");
   if (cfg->metric > PROXIMITY_METRIC_COSINE)
     return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown metric %u", cfg->metric);
-  if (cfg->reserved0 != 0) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "reserved0 must be 0");
+  if ((cfg->flags & ~PROXIMITY_FLAG_NO_ROUNDED_SCAN) != 0)
+    return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "unknown flags %#x", cfg->flags);
   if (cfg->device < 0) return fail(nullptr, PROXIMITY_ERR_INVALID_ARG, "device=%d is negative", cfg->device);
 
   int n_dev = 0;
@@ -808,12 +825,14 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     h->n_cu = prop.multiProcessorCount;
 
   const size_t c = size_t(h->slots), B = cfg->max_batch, d = cfg->dim, k = size_t(h->K), N = cfg->n_docs;
-  // One-plane scans: a bfloat16 corpus of a dimension the register-resident scan has, calls of more than a handful
-  // of rows, and a list length the ranking kernel holds.
-  h->coarse_capable = cfg->corpus_dtype == PROXIMITY_DTYPE_BF16 && regq_supported(kDtypeBF16, int(d)) && N > 0 &&
-                      B > size_t(kStreamMaxQueries) && coarse_list_length(int(k)) <= kCoarseMaxList;
+  // Scans on rounded operands: a corpus of a type and dimension the register-resident scan has, calls of more than
+  // a handful of rows, and a list length the ranking kernel holds.
+  h->coarse_level = cfg->corpus_dtype == PROXIMITY_DTYPE_BF16 ? 1 : 2;
+  h->coarse_capable = regq_supported(int(cfg->corpus_dtype), int(d)) && N > 0 && B > size_t(kStreamMaxQueries) &&
+                      coarse_list_length(int(k), h->coarse_level, int(d), double(N)) <= kCoarseMaxList &&
+                      (cfg->flags & PROXIMITY_FLAG_NO_ROUNDED_SCAN) == 0;
   // sized for the K = rerank_factor * k neighbours a search call asks for
-  const int kp = h->coarse_capable ? coarse_list_length(int(k)) : int(k) + kSlack;
+  const int kp = h->coarse_capable ? coarse_list_length(int(k), h->coarse_level, int(d), double(N)) : int(k) + kSlack;
   int rc;
 #define TRY_ALLOC(ptr, count, zero)                              \
   if ((rc = dev_alloc(h, &(ptr), (count), (zero))) != PROXIMITY_OK) return bail(rc)
@@ -838,7 +857,7 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
     size_t cand_sets = size_t(h->scan_blocks) * pass_q;
     if (size_t(h->scan_blocks_regq) * 128 > cand_sets) cand_sets = size_t(h->scan_blocks_regq) * 128;
     TRY_ALLOC(h->topk_buf, cand_sets * kTopkCap, false);
-    if (cfg->corpus_dtype == PROXIMITY_DTYPE_BF16) TRY_ALLOC(h->qplanes, 3 * B * d, true);
+    if (cfg->corpus_dtype == PROXIMITY_DTYPE_BF16 || h->coarse_capable) TRY_ALLOC(h->qplanes, 3 * B * d, true);
   }
   h->pairs_elems = long(B * lists * kp);
   TRY_ALLOC(h->pairs[0], size_t(h->pairs_elems), false);

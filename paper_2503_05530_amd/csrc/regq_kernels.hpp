@@ -81,8 +81,11 @@ __host__ __device__ constexpr int regq_stages(int slabs_per_tile) {
 __host__ __device__ constexpr bool regq_supported(int dtype, int dim) {
   return dtype == kDtypeF32 ? (dim == 768 || dim == 384) : (dim == 384 || dim == 256);
 }
-// queries one wave holds
-__host__ __device__ constexpr int regq_queries_per_wave(int dtype) { return dtype == kDtypeF32 ? 16 : 32; }
+// queries one wave holds: 16 with the float32 matrix instruction, 32 with the bfloat16 one (`coarse`: see
+// kRegqCoarse, which multiplies float32 rows on the bfloat16 matrix cores too)
+__host__ __device__ constexpr int regq_queries_per_wave(int dtype, bool coarse = false) {
+  return dtype == kDtypeF32 && !coarse ? 16 : 32;
+}
 
 // 16 bytes from LDS into registers without a wait; a later s_waitcnt (regq_tie with the value as operand)
 // orders the use of the value after the read.  LDS reads return in order, so "at most n reads issued after
@@ -138,6 +141,20 @@ __device__ __forceinline__ void regq_tie_matrix_done(V (&v)[N]) {
     PROX_RQ_TIE4("", v[4], v[5], v[6], v[7]);
   }
 }
+// The other direction: accumulators that ordinary instructions have just set (zeroes, copies) must have settled
+// before a matrix instruction reads them -- two idle states -- and the compiler, left alone, is free to sink
+// such moves down to right in front of the assembly statement that uses the registers.  Passing every
+// accumulator through this statement pins the moves before it.
+template <int N, typename V>
+__device__ __forceinline__ void regq_tie_settled(V (&v)[N]) {
+  static_assert(N == 2 || N == 4 || N == 8, "operand count");
+  if constexpr (N == 2) PROX_RQ_TIE2("s_nop 1", v[0], v[1]);
+  if constexpr (N == 4) PROX_RQ_TIE4("s_nop 1", v[0], v[1], v[2], v[3]);
+  if constexpr (N == 8) {
+    PROX_RQ_TIE4("", v[0], v[1], v[2], v[3]);
+    PROX_RQ_TIE4("s_nop 1", v[4], v[5], v[6], v[7]);
+  }
+}
 __device__ __forceinline__ int regq_lds_read_i32(uint32_t addr) {
   int v;
   asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr));
@@ -161,7 +178,19 @@ constexpr int kRegqScan = 0, kRegqProbe = 1, kRegqDump = 2;   // what the kernel
 // the scan from matrix-bound into HBM-bound.  Its scores are off by up to 2^-8 |q| |x| (coarse_score_error); they
 // only pick the candidates whose float64 distances rank, the caller asks for a longer list than k + 8 and the
 // exactness check of the ranking carries the term, so the ranked lists stay provably exact.
+// On float32 rows the same mode rounds the rows to bfloat16 as well, on their way from LDS to the matrix
+// instruction (two 16-byte reads and four v_cvt_pk_bf16_f32 per operand): sixteen times the float32 matrix rate
+// for twice the rounding error, and a scan of up to 128 queries that is bound by HBM alone.  The rows' terms
+// |x|^2 stay the exact float32 ones.
 constexpr int kRegqCoarse = 3;
+struct RegqRaw8 {   // eight consecutive float32 of a row, as two LDS reads return them
+  f32x4 lo, hi;
+};
+__device__ __forceinline__ bf16x8 regq_round_bf16(const RegqRaw8& r) {   // round to nearest even
+  typedef float f32x8 __attribute__((ext_vector_type(8)));
+  const f32x8 v = __builtin_shufflevector(r.lo, r.hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_convertvector(v, bf16x8);
+}
 
 struct RegqEmit {
   int c;                 // cache slots: sources 0..c-1 are slot keys, c + j is batch row j
@@ -201,20 +230,22 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     const int* __restrict__ m_count_ptr, int m_limit, int m_base, int rem_lo, int rem_hi, int kp,
     const uint64_t* __restrict__ seed, uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out, int cosine,
     RegqEmit emit) {
-  constexpr bool F32 = DT == kDtypeF32;
+  constexpr bool ROWS32 = DT == kDtypeF32;         // float32 rows in memory and in LDS
+  constexpr bool HYB = ROWS32 && MODE == kRegqCoarse;   // ... multiplied as bfloat16
+  constexpr bool F32 = ROWS32 && !HYB;             // the float32 matrix instruction
   constexpr int NW = 4;                            // waves per block
   constexpr int NT = NW * 64;
-  constexpr int QW = regq_queries_per_wave(DT);    // queries per wave = rows per row block (square result tiles)
+  constexpr int QW = regq_queries_per_wave(DT, HYB);   // queries per wave = rows per row block (square result tiles)
   constexpr int RB = QW;
   constexpr int AV = F32 ? 4 : 16;                 // result registers per row block
   constexpr int AG = AV / 4;                       // ... in groups of four consecutive rows
-  constexpr int KS = F32 ? 2 : 4;                  // operand reads (16 columns each) per row block and slab
+  constexpr int KS = ROWS32 ? 2 : 4;               // operands (16 columns each) per row block and slab
   constexpr int WR = NW / WQ;                      // row groups
   constexpr int TM = QW * WQ;                      // queries per block
   constexpr int TN = kRegqTileRows;
   constexpr int RPW = TN / WR;                     // rows of a tile one wave multiplies
   constexpr int NRB = RPW / RB;                    // row blocks of those
-  constexpr int SLAB_COLS = F32 ? 32 : 64;         // columns per slab (128 bytes per row)
+  constexpr int SLAB_COLS = ROWS32 ? 32 : 64;      // columns per slab (128 bytes per row)
   constexpr int SPT = DIM / SLAB_COLS;             // slabs per tile
   constexpr int NS = regq_stages(SPT);             // stages of the ring
   constexpr int NL = 16 / NW;                      // 1 KiB loads per wave per slab (a stage is 16 of them)
@@ -224,7 +255,6 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
 
   constexpr bool EMIT = MODE == kRegqProbe, DUMP = MODE == kRegqDump;
   constexpr int PLANES = MODE == kRegqCoarse ? 1 : kRegqPlanes;
-  static_assert(MODE != kRegqCoarse || !F32, "one plane of a bfloat16 split");
   static_assert(!EMIT || F32, "the probe's keys are float32");
   static_assert(!DUMP || WQ == 1, "scores of one query group");
   const int M = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
@@ -327,7 +357,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   const long t_end = uniform(n_tiles * (part + 1) / parts);
   uint64_t* my_buf = cand_buf + long(blockIdx.x) * long(TM) * kTopkCap;
   const char* X = static_cast<const char*>(Xv);
-  constexpr long ROW_BYTES = long(DIM) * (F32 ? 4 : 2);
+  constexpr long ROW_BYTES = long(DIM) * (ROWS32 ? 4 : 2);
 
   // ---- load duty of this lane: load i of the wave covers stage rows 8 (wib NL + i) .. +7 ----
   // A load's address is a wave-uniform base (tile and slab: scalar registers, scalar arithmetic) plus a 32-bit
@@ -402,6 +432,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
 #pragma unroll
         for (int v = 0; v < AV; ++v) acc[i][v] = 0.f;
       my_count = regq_lds_read_i32(my_count_lds);
+      regq_tie_settled(acc);
       return;
     }
     const uint32_t nr_addr = nrm_lds + uint32_t((int(tile & 1) * TN + row_base + 4 * kg) * 4);
@@ -422,6 +453,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
 #pragma unroll
         for (int v = 0; v < AV; ++v) acc[b * NSPLIT + h][v] = 0.f;
     }
+    regq_tie_settled(acc);
   };
 
   // One slab (number S within its tile) = KS NRB operand reads, each feeding one group of matrix instructions.
@@ -433,24 +465,55 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   // (row / 2) % 8 = (rl / 2) % 8 (row_base and RB b are multiples of 16); the step enters by xor as well
   // because kg < 8 / KS.  The address is a per-lane register plus an immediate: stage * 16 KiB + row block
   // offset must stay below 64 KiB, so stages 4.. use registers 64 KiB up.
-  using AFrag = typename std::conditional<F32, f32x4, bf16x8>::type;
+  using AFrag = typename std::conditional<F32, f32x4, typename std::conditional<HYB, RegqRaw8, bf16x8>::type>::type;
   constexpr int NCHUNK = KS * NRB / GB;            // chunk c: row blocks (c / KS) * GB .., step c % KS
   const uint32_t ring_lds = regq_lds_addr(&ring[0][0]);
-  uint32_t lane_lo[KS], lane_hi[KS];
+  // (float32 rows multiplied as bfloat16: a lane's eight columns of a step are the two chunks 2 kg and 2 kg + 1 of
+  // the step's four; the second sits 16 bytes from the first, before or after it as the swizzle has it)
+  uint32_t lane_lo[KS], lane_hi[KS], lane_lo2[HYB ? KS : 1], lane_hi2[HYB ? KS : 1];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
-    lane_lo[ks] = ring_lds + (uint32_t((row_base + rl) * 128 + ((kg ^ ((rl >> 1) & 7)) * 16)) ^ uint32_t(ks * (128 / KS)));
+    const int first_chunk = HYB ? 2 * kg : kg;
+    lane_lo[ks] = ring_lds + (uint32_t((row_base + rl) * 128 + ((first_chunk ^ ((rl >> 1) & 7)) * 16)) ^ uint32_t(ks * (128 / KS)));
     lane_hi[ks] = lane_lo[ks] + 65536u;
+    if constexpr (HYB) {
+      lane_lo2[ks] = lane_lo[ks] ^ 16u;
+      lane_hi2[ks] = lane_lo2[ks] + 65536u;
+    }
   }
   auto read_chunk = [&](AFrag(&dst)[GB], const int stage, const int c) {
 #pragma unroll
-    for (int bb = 0; bb < GB; ++bb)
-      dst[bb] = regq_lds_read128<AFrag>(stage < 4 ? lane_lo[c % KS] : lane_hi[c % KS],
-                                        (stage & 3) * (kRegqStageFloats * 4) + ((c / KS) * GB + bb) * (RB * 128));
+    for (int bb = 0; bb < GB; ++bb) {
+      const int off = (stage & 3) * (kRegqStageFloats * 4) + ((c / KS) * GB + bb) * (RB * 128);
+      if constexpr (HYB) {
+        dst[bb].lo = regq_lds_read128<f32x4>(stage < 4 ? lane_lo[c % KS] : lane_hi[c % KS], off);
+        dst[bb].hi = regq_lds_read128<f32x4>(stage < 4 ? lane_lo2[c % KS] : lane_hi2[c % KS], off);
+      } else {
+        dst[bb] = regq_lds_read128<AFrag>(stage < 4 ? lane_lo[c % KS] : lane_hi[c % KS], off);
+      }
+    }
   };
   // the chunk is complete once at most GB (or no) later reads are outstanding: LDS reads return in order
   auto wait_chunk = [&](AFrag(&f)[GB], const bool later_reads) {
-    if constexpr (GB == 4) {
+    if constexpr (HYB) {   // two reads per operand
+      if constexpr (GB == 4) {
+        if (later_reads)
+          PROX_RQ_TIE4("s_waitcnt lgkmcnt(8)\n\ts_nop 0", f[0].lo, f[0].hi, f[1].lo, f[1].hi);
+        else
+          PROX_RQ_TIE4("s_waitcnt lgkmcnt(0)\n\ts_nop 0", f[0].lo, f[0].hi, f[1].lo, f[1].hi);
+        PROX_RQ_TIE4("", f[2].lo, f[2].hi, f[3].lo, f[3].hi);
+      } else if constexpr (GB == 2) {
+        if (later_reads)
+          PROX_RQ_TIE4("s_waitcnt lgkmcnt(4)\n\ts_nop 0", f[0].lo, f[0].hi, f[1].lo, f[1].hi);
+        else
+          PROX_RQ_TIE4("s_waitcnt lgkmcnt(0)\n\ts_nop 0", f[0].lo, f[0].hi, f[1].lo, f[1].hi);
+      } else {
+        if (later_reads)
+          PROX_RQ_TIE2("s_waitcnt lgkmcnt(2)\n\ts_nop 0", f[0].lo, f[0].hi);
+        else
+          PROX_RQ_TIE2("s_waitcnt lgkmcnt(0)\n\ts_nop 0", f[0].lo, f[0].hi);
+      }
+    } else if constexpr (GB == 4) {
       if (later_reads)
         PROX_RQ_TIE4("s_waitcnt lgkmcnt(4)\n\ts_nop 0", f[0], f[1], f[2], f[3]);
       else
@@ -492,11 +555,23 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
         for (int e = 0; e < 4; ++e)
 #pragma unroll
           for (int bb = 0; bb < GB; ++bb) regq_mfma(acc[(b0 + bb) * NSPLIT + e % NSPLIT], a[c][bb][e], bq_f[t][e]);
+      } else if constexpr (HYB) {
+        // the chunk's rows rounded to bfloat16 (ordinary instructions; the empty statement keeps two idle
+        // states between the last of them and the matrix instructions that read their results)
+        bf16x8 rounded[GB];
+#pragma unroll
+        for (int bb = 0; bb < GB; ++bb) rounded[bb] = regq_round_bf16(a[c][bb]);
+        if constexpr (GB == 4) PROX_RQ_TIE4("s_nop 1", rounded[0], rounded[1], rounded[2], rounded[3]);
+        if constexpr (GB == 2) PROX_RQ_TIE2("s_nop 1", rounded[0], rounded[1]);
+        if constexpr (GB == 1) PROX_RQ_TIE1("s_nop 1", rounded[0]);
+#pragma unroll
+        for (int bb = 0; bb < GB; ++bb) regq_mfma(acc[(b0 + bb) * NSPLIT + c % NSPLIT], rounded[bb], bq_h[0][t]);
       } else {
 #pragma unroll
         for (int p = 0; p < PLANES; ++p)
 #pragma unroll
-          for (int bb = 0; bb < GB; ++bb) regq_mfma(acc[(b0 + bb) * NSPLIT + (PLANES == 1 ? c : p) % NSPLIT], a[c][bb], bq_h[p][t]);
+          for (int bb = 0; bb < GB; ++bb)
+            regq_mfma(acc[(b0 + bb) * NSPLIT + (PLANES == 1 ? c : p) % NSPLIT], a[c][bb], bq_h[p][t]);
       }
       if (c == NCHUNK / 2 - 1) {
         if (c + 1 < NCHUNK) wait_chunk(a[c + 1], false);  // nothing in flight across the barrier and the loads

@@ -299,11 +299,12 @@ __host__ __device__ inline double score_error_bound(int metric, int dim, double 
   if (metric == kMetricIP) return g * 2.0 * q_len * x_max;
   return g * 4.0 * q_len;
 }
-// What a scan that multiplies only the first bfloat16 plane of the queries adds to that: the plane is the
-// query rounded to nearest, |q_i - hi_i| <= 2^-9 |q_i|, so the inner product moves by at most 2^-9 |q| |x| and the
-// score by twice that (a thousandth on top for the roundings that follow).
-__host__ __device__ inline double coarse_score_error(int metric, double q_len, double x_max) {
-  const double u = 0.00390625 * 1.001;
+// What a scan that multiplies only the first bfloat16 plane of the queries adds to that (level 1): the plane is
+// the query rounded to nearest, |q_i - hi_i| <= 2^-9 |q_i|, so the inner product moves by at most 2^-9 |q| |x| and
+// the score by twice that (a thousandth on top for the roundings that follow).  Level 2: float32 rows rounded to
+// bfloat16 as well, |q.x - hi(q).hi(x)| <= |q - hi(q)| |x| + |hi(q)| |x - hi(x)| <= (2 + 2^-9) 2^-9 |q| |x|.
+__host__ __device__ inline double coarse_score_error(int metric, double q_len, double x_max, int level = 1) {
+  const double u = 0.00390625 * 1.001 * (level >= 2 ? 2.002 : 1.0);
   return metric == kMetricCosine ? u * q_len : u * q_len * x_max;
 }
 // the exact score that goes with a float64 distance (qq = |q|^2)
@@ -316,11 +317,11 @@ __device__ __forceinline__ double score_of_distance(int metric, double d, double
 // Block-uniform verdict on a sorted list of kp float32 candidates whose k-th smallest float64 distance is
 // kth_d: true when the list provably holds the k nearest rows.  *thr receives t_k + E (rounded up), the
 // score bound of the second ranking (which scores with the whole query: its bound never carries the coarse
-// term).  `coarse`: the list was ranked by one-plane scores.  `red` is 2 doubles of LDS.  Ends with a barrier.
+// term).  `coarse`: the list was ranked by scores of rounded operands (level of coarse_score_error, 0: no).  `red` is 2 doubles of LDS.  Ends with a barrier.
 __device__ __forceinline__ bool block_list_sufficient(const uint64_t* keys, int kp, double kth_d,
                                                       const float* __restrict__ q, int dim, int metric,
                                                       const SlackState* __restrict__ slack, double* red, float* thr,
-                                                      int tid, bool coarse = false) {
+                                                      int tid, int coarse = 0) {
   if (tid < 64) {
     double qq = 0.0;
     for (int x = tid; x < dim; x += 64) qq += double(q[x]) * double(q[x]);
@@ -332,7 +333,7 @@ __device__ __forceinline__ bool block_list_sufficient(const uint64_t* keys, int 
       if (key_id(worst) >= 0) {   // a padding entry means every row of the corpus is in the list
         const double x_max = sqrt(double(__uint_as_float(slack->xmax2_bits)));
         const double e = score_error_bound(metric, dim, sqrt(qq), x_max) * (1.0 + 1e-6);
-        const double e_list = coarse ? e + coarse_score_error(metric, sqrt(qq), x_max) : e;
+        const double e_list = coarse ? e + coarse_score_error(metric, sqrt(qq), x_max, coarse) : e;
         const double t_k = score_of_distance(metric, kth_d, qq);
         ok = double(key_score(worst)) - e_list > t_k;
         t = __double2float_ru(t_k + e);
@@ -534,7 +535,7 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
   __syncthreads();
   // Was the list long enough?  If that cannot be shown the query is noted for the second ranking
   // (redo_collect_kernel / redo_rank_kernel), which overwrites this row of the result.
-  if (!block_list_sufficient(mine, kp, kth_d, q, dim, metric, slack, red, &thr, threadIdx.x, coarse != 0) &&
+  if (!block_list_sufficient(mine, kp, kth_d, q, dim, metric, slack, red, &thr, threadIdx.x, coarse) &&
       threadIdx.x == 0) {
     atomicAdd(&slack->exhausted, 1ull);
     const int pos = atomicAdd(&slack->redo_count, 1);   // below the call's row count: one note per query
@@ -557,8 +558,8 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
 // scored the sample (another order of summation, other planes of the query): a sample row's score in that scan
 // can lie above its score here by both kernels' errors, and the bound taken as it stands could turn away, by a
 // rounding, rows that belong in the list.  The kp-th key (the only one the scans read) then gets that margin
-// added: twice the float32 bound, plus the rounding of the queries when the scan multiplies one plane of them
-// (margin = 2).
+// added: twice the float32 bound, plus the rounding term of a scan on rounded operands (margin = 1 + level of
+// coarse_score_error).
 constexpr long kCutMaxKeys = 65536;
 __global__ __launch_bounds__(kRerankThreads) void cut_lists_kernel(const uint64_t* __restrict__ in, long len, int kp,
                                                                    uint64_t* __restrict__ out,
@@ -585,7 +586,7 @@ __global__ __launch_bounds__(kRerankThreads) void cut_lists_kernel(const uint64_
       qq = wave_sum(qq);
       const double x_max = sqrt(double(__uint_as_float(slack->xmax2_bits)));
       double e = 2.0 * score_error_bound(metric, dim, sqrt(qq), x_max);
-      if (margin == 2) e += coarse_score_error(metric, sqrt(qq), x_max);
+      if (margin >= 2) e += coarse_score_error(metric, sqrt(qq), x_max, margin - 1);
       key = pack_key(__double2float_ru(double(key_score(key)) + e * (1.0 + 1e-6)), uint32_t(key_id(key)));
     }
     if (tid == 0) o[kp - 1] = key;

@@ -34,10 +34,11 @@ def crowded_corpus(n_docs, dim, n_near, spread, seed):
 @pytest.mark.parametrize("n_queries", [1, 3, 24, 70, 128])
 @pytest.mark.parametrize("dim,k", [(64, 10), (768, 10), (384, 32)])
 def test_rows_float32_cannot_tell_apart_are_ranked_exactly(B, n_queries, dim, k):
-    """Forty rows within 3e-8 per element of each other, the queries a small step away from them: their
+    """A hundred rows within 3e-8 per element of each other, the queries a small step away from them: their
     distances to a query differ in the ninth digit, so the k nearest are decided among them by float64 alone,
-    and the float32 list of k + 8 is an arbitrary subset of the forty."""
-    x, where, centre = crowded_corpus(7000, dim, 40, 3e-8, 50 + dim)
+    and the float32 candidate list (k + 8, or the longer one of a scan on rounded operands) is an arbitrary
+    subset of the hundred."""
+    x, where, centre = crowded_corpus(7000, dim, 100, 3e-8, 50 + dim)
     rng = np.random.default_rng(7)
     q = (centre[None, :] + 0.02 * W.unit_rows(rng.standard_normal((n_queries, dim)))).astype(np.float32)
     o_ids, o_d = po.batched_exact_knn(x, q, k)
@@ -134,22 +135,28 @@ def test_ordinary_corpora_pass_the_check(B):
         px.close()
 
 
-def bf16_corpus(x):
-    """The rows as bfloat16 on the device, and the same values as float32 on the host for the oracle."""
-    x16 = torch.from_numpy(x).to(DEV).to(torch.bfloat16)
+def device_corpus(x, kind):
+    """The rows on the device as float32 or bfloat16, and the same values as float32 on the host for the oracle."""
+    xd = torch.from_numpy(x).to(DEV)
+    if kind == "f32":
+        return xd, x
+    x16 = xd.to(torch.bfloat16)
     return x16, x16.to(torch.float32).cpu().numpy()
 
 
-@pytest.mark.parametrize("dim,k,n_docs,n_queries", [(384, 100, 300_000, 128), (256, 10, 200_000, 40),
-                                                    (384, 3, 150_000, 5), (256, 160, 140_000, 70)])
-def test_one_plane_scan_of_ordinary_bfloat16_rows(B, dim, k, n_docs, n_queries):
-    """Calls of more than four rows on a bfloat16 corpus are pre-ranked with the queries rounded to bfloat16
-    (one plane of the split), with a longer candidate list and the rounding's error in the exactness check:
-    on unit Gaussian rows the check passes for every query, and the lists are the oracle's."""
-    x16, xh = bf16_corpus(W.corpus_f32(n_docs, dim, 5))
-    q = W.stream_for(W.WORKLOADS["lowreuse"], n_queries)[:, :dim].copy()
+@pytest.mark.parametrize("kind,dim,k,n_docs,n_queries", [
+    ("bf16", 384, 100, 300_000, 128), ("bf16", 256, 10, 200_000, 40), ("bf16", 384, 3, 150_000, 5),
+    ("bf16", 256, 160, 140_000, 70), ("f32", 768, 10, 200_000, 64), ("f32", 384, 100, 150_000, 128),
+    ("f32", 768, 32, 250_000, 100), ("f32", 384, 5, 140_000, 7), ("f32", 768, 120, 140_000, 33)])
+def test_scan_on_rounded_operands_of_ordinary_rows(B, kind, dim, k, n_docs, n_queries):
+    """Calls of more than four rows are pre-ranked on the bfloat16 matrix cores with the queries rounded to
+    bfloat16 (one plane of the split) and float32 rows rounded likewise, with a longer candidate list and the
+    rounding's error in the exactness check: on unit Gaussian rows the check passes for every query, and the
+    lists are the oracle's."""
+    xd, xh = device_corpus(W.corpus_f32(n_docs, dim, 5), kind)
+    q = W.stream_for(W.WORKLOADS["mid" if dim == 768 else "lowreuse"], n_queries)[:, :dim].copy()
     o_ids, o_d = po.batched_exact_knn(xh, q, k)
-    px = B.Proximity(x16, dim, 0, k, B.POLICY_FIFO, n_queries)
+    px = B.Proximity(xd, dim, 0, k, B.POLICY_FIFO, n_queries)
     ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
     torch.cuda.synchronize(DEV)
     assert (ids.cpu().numpy() == o_ids).all()
@@ -158,14 +165,21 @@ def test_one_plane_scan_of_ordinary_bfloat16_rows(B, dim, k, n_docs, n_queries):
     assert st["coarse_scan_calls"] == 1 and st["coarse_scan_fails"] == 0, st
     assert st["slack_exhausted"] == 0 and st["slack_unresolved"] == 0, st
     px.close()
+    # the same search with the operands as they are: the same lists
+    pe = B.Proximity(xd, dim, 0, k, B.POLICY_FIFO, n_queries, flags=B.FLAG_NO_ROUNDED_SCAN)
+    ids_e, _ = pe.knn_batch(torch.from_numpy(q).to(DEV))
+    assert (ids_e.cpu().numpy() == o_ids).all()
+    assert pe.stats()["coarse_scan_calls"] == 0
+    pe.close()
 
 
-def test_more_neighbours_than_a_one_plane_list_holds_scan_with_two_planes(B):
-    dim, k, n_queries = 384, 170, 24          # 170 + 85 candidates: more than the ranking kernel holds
-    x16, xh = bf16_corpus(W.corpus_f32(140_000, dim, 6))
+@pytest.mark.parametrize("kind,k", [("bf16", 200), ("f32", 160)])
+def test_more_neighbours_than_a_list_of_rounded_scores_holds(B, kind, k):
+    dim, n_queries = 384, 24          # 272 and 264 candidates: more than the ranking kernel holds
+    xd, xh = device_corpus(W.corpus_f32(140_000, dim, 6), kind)
     q = W.stream_for(W.WORKLOADS["lowreuse"], n_queries)
     o_ids, _ = po.batched_exact_knn(xh, q, k)
-    px = B.Proximity(x16, dim, 0, k, B.POLICY_FIFO, n_queries)
+    px = B.Proximity(xd, dim, 0, k, B.POLICY_FIFO, n_queries)
     ids, _ = px.knn_batch(torch.from_numpy(q).to(DEV))
     assert (ids.cpu().numpy() == o_ids).all()
     st = px.stats()
@@ -174,19 +188,19 @@ def test_more_neighbours_than_a_one_plane_list_holds_scan_with_two_planes(B):
 
 
 @pytest.mark.parametrize("metric", [po.METRIC_L2, po.METRIC_IP, po.METRIC_COSINE])
-def test_a_crowd_within_the_rounding_of_the_queries(B, metric):
-    """Two hundred rows whose scores differ by less than the error a rounded query can cause (about a quarter of
-    it from one to the next at most), more of them than the one-plane list holds: the check fails for every query
-    of the first call, the second ranking still returns the oracle's lists, and the instance scans with two planes
-    from then on."""
-    dim, k, n_queries = 384, 10, 64
+@pytest.mark.parametrize("kind,dim", [("bf16", 384), ("f32", 768), ("f32", 384)])
+def test_a_crowd_within_the_rounding_of_the_operands(B, kind, dim, metric):
+    """Two hundred rows whose scores differ by less than the error rounded operands can cause, more of them than
+    the list of a scan on rounded operands holds: the check fails for every query of the first call, the second
+    ranking still returns the oracle's lists, and the instance scans the operands as they are from then on."""
+    k, n_queries = 10, 64
     x, where, centre = crowded_corpus(140_000, dim, 200, 5e-4, 64)
-    x16, xh = bf16_corpus(x)
+    xd, xh = device_corpus(x, kind)
     rng = np.random.default_rng(10)
     q = (1.3 * (centre[None, :] + 0.05 * W.unit_rows(rng.standard_normal((n_queries, dim))))).astype(np.float32)
     o_ids, o_d = po.batched_exact_knn(xh, q, k, metric=metric)
     assert np.isin(o_ids, where).all()
-    px = B.Proximity(x16, dim, 0, k, B.POLICY_FIFO, n_queries, metric=metric)
+    px = B.Proximity(xd, dim, 0, k, B.POLICY_FIFO, n_queries, metric=metric)
     for call in range(3):
         ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
         torch.cuda.synchronize(DEV)
