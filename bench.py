@@ -45,6 +45,9 @@ def parse_args():
                     help="bucketed cache (Section 3.2): 2^L buckets; 0 = the flat cache")
     ap.add_argument("--bucket-capacity", type=int, default=20, help="entries per bucket when --lsh-bits > 0")
     ap.add_argument("--n-docs", type=int, default=None, help="override corpus rows (debugging only)")
+    ap.add_argument("--exact-scan", action="store_true",
+                    help="never pre-rank on rounded operands (PROXIMITY_FLAG_NO_ROUNDED_SCAN): the scan that "
+                         "multiplies the corpus as it is stored")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=24, help="queries the oracle is timed on")
@@ -112,14 +115,17 @@ def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, devic
 # Keyed by (kernel, query-tile shape, corpus rows, dim, element bytes); anything else reports null.
 COUNTER_TRAFFIC = {
     ("scan_regq_kernel (scores only)", 0, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_512_370 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scan_regq_mid_b1.md"},
+        {"fetch_bytes": 1_512_368 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scan_regq_mid_b1.md"},
+    ("scan_regq_kernel (rounded operands)", 64, 1_000_000, 768, 4):
+        {"fetch_bytes": 1_514_280 * 2048, "write_bytes": 16_227 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
     ("scan_regq_kernel", 64, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_514_326 * 2048, "write_bytes": 4_199 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
+        {"fetch_bytes": 1_514_329 * 2048, "write_bytes": 4_197 * 1024,
+         "source": "profiles/scan_regq_mid_b64_exact.md"},
     ("scan_regq_kernel (one plane)", 128, 8_000_000, 384, 2):
-        {"fetch_bytes": 3_029_956 * 2048, "write_bytes": 55_165 * 1024,
+        {"fetch_bytes": 3_030_128 * 2048, "write_bytes": 58_780 * 1024,
          "source": "profiles/scan_regq_lowreuse_b128.md"},
-    ("scan_regq_kernel", 64, 24_000_000, 768, 4):
-        {"fetch_bytes": 36_059_377 * 2048, "write_bytes": 12_885 * 1024,
+    ("scan_regq_kernel (rounded operands)", 64, 24_000_000, 768, 4):
+        {"fetch_bytes": 36_060_076 * 2048, "write_bytes": 34_658 * 1024,
          "source": "profiles/scan_regq_large_b256.md"},
 }
 
@@ -472,7 +478,7 @@ def measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=None, 
     if metric == 2:
         tau = tau * tau / 2.0
     px = Proximity(corpus_dev, w.dim, capacity, w.k, w.policy, max_batch, rerank_factor=rho, lsh_planes=planes,
-                   metric=metric)
+                   metric=metric, flags=1 if args.exact_scan else 0)      # (1: PROXIMITY_FLAG_NO_ROUNDED_SCAN)
     n_rows = len(queries)
     outs = (torch.empty((n_rows, w.k), dtype=torch.int64, device=device),
             torch.empty((n_rows, w.k), dtype=torch.float32, device=device),
@@ -502,6 +508,20 @@ def measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=None, 
                           "queries_per_s": round(s_steps * s_batch / s_dt, 1), "hit_rate": round(s_hit, 4),
                           "ms_per_step": round(1e3 * s_dt / s_steps, 4),
                           "roofline": scan_roofline(s_busy, n_docs, w.dim, s_batch, elem, one_plane)})
+        if one_plane:
+            # the same all-miss point with the operands multiplied as they are stored (float32 matrix instruction):
+            # the scan that the rounded one falls back to when its exactness checks stop passing
+            from paper_2503_05530_amd.binding import FLAG_NO_ROUNDED_SCAN
+            pe = Proximity(corpus_dev, w.dim, capacity, w.k, w.policy, max_batch, rerank_factor=rho, lsh_planes=planes,
+                           metric=metric, flags=FLAG_NO_ROUNDED_SCAN)
+            e_dt, e_hit, e_first = timed_run(torch, pe, q_dev, 0.0, 64, 10, 200, outs, device, pre)
+            e_busy = profiled_scan(torch, pe, q_dev, 0.0, 64, e_first // 64 + 200, 200, outs, device)
+            sweep.append({"workload": "mid", "tau": 0.0, "batch": 64, "steps": 200, "warmup": 10,
+                          "scan": "operands as stored (PROXIMITY_FLAG_NO_ROUNDED_SCAN)", "cache_preroll_rows": pre,
+                          "queries_per_s": round(200 * 64 / e_dt, 1), "hit_rate": round(e_hit, 4),
+                          "ms_per_step": round(1e3 * e_dt / 200, 4),
+                          "roofline": scan_roofline(e_busy, n_docs, w.dim, 64, elem, False)})
+            pe.close()
 
     cpu = None
     if headline and not args.no_cpu_baseline and corpus is not None:
