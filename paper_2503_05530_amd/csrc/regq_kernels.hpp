@@ -26,6 +26,9 @@
 // the planes rounds only where a float32 contraction rounds).  One 1 KiB operand read feeds 64 cycles of the
 // matrix pipe (with the 16x16x32 form it feeds 32, and four SIMDs then ask LDS for exactly its peak rate).
 // Result register j of lane l is row 8 (j / 4) + 4 (l / 32) + j % 4, query l % 32.
+// Rounded operands (kRegqCoarse): only the first plane of the queries is multiplied, and float32 rows take the
+// bfloat16 instruction too -- they stay float32 in HBM and LDS, and a lane rounds its eight columns of a step
+// (two ds_read_b128) to bfloat16 on the way in.  Such scores only pick candidates; see kRegqCoarse below.
 //
 // Scores without arithmetic.  The registers hold -2 q instead of q (an exact scaling) and the accumulators of a
 // tile start from the rows' terms |x|^2 (0 for the inner product), read from LDS straight into them: what the

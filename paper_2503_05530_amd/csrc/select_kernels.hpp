@@ -317,7 +317,8 @@ __device__ __forceinline__ double score_of_distance(int metric, double d, double
 // Block-uniform verdict on a sorted list of kp float32 candidates whose k-th smallest float64 distance is
 // kth_d: true when the list provably holds the k nearest rows.  *thr receives t_k + E (rounded up), the
 // score bound of the second ranking (which scores with the whole query: its bound never carries the coarse
-// term).  `coarse`: the list was ranked by scores of rounded operands (level of coarse_score_error, 0: no).  `red` is 2 doubles of LDS.  Ends with a barrier.
+// term).  `coarse`: the list was ranked by scores of rounded operands (level of coarse_score_error, 0: no).
+// `red` is 2 doubles of LDS.  Ends with a barrier.
 __device__ __forceinline__ bool block_list_sufficient(const uint64_t* keys, int kp, double kth_d,
                                                       const float* __restrict__ q, int dim, int metric,
                                                       const SlackState* __restrict__ slack, double* red, float* thr,
