@@ -543,7 +543,7 @@ def measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=None, 
                    "hit_rate": round(hit_rate, 4),
                    "queries_timed": steps * batch, "setup_s": round(t_gen, 1),
                    "searches_ranked_twice": checks["slack_exhausted"], "searches_not_proven_exact": checks["slack_unresolved"],
-                   "one_plane_scan_calls": checks["coarse_scan_calls"]},
+                   "rounded_scan_calls": checks["coarse_scan_calls"]},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     px.close()
