@@ -404,7 +404,7 @@ template <int DT, int DIM, int MODE = kRegqScan>
 void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows, int G, const float* Qbase, const int* qlist,
                      const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
                      uint64_t* out, hipStream_t s) {
-  constexpr int QW = regq_queries_per_wave(DT, MODE == kRegqCoarse), SLICE = 4 * QW;   // queries per wave and per block at most
+  constexpr int QW = regq_queries_per_wave(DT, regq_mode_rounds(MODE)), SLICE = 4 * QW;   // queries per wave and per block at most
   const int cosine = h->cfg.metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
   const long plane_stride = long(h->cfg.max_batch) * DIM;
   const bool known = m_count_ptr == nullptr;  // then M = m_limit and only its own shape is launched
@@ -429,11 +429,20 @@ void launch_regq_dim(proximity* h, const void* X, const float* xnrm, long n_rows
 
 void launch_regq_scan(proximity* h, const void* X, const float* xnrm, long n_rows, int G, const float* Qbase, const int* qlist,
                       const int* m_count_ptr, int m_limit, int base, int span, int kp, const uint64_t* seed,
-                      uint64_t* out, bool coarse, hipStream_t s) {
+                      uint64_t* out, bool coarse, hipStream_t s, bool keys = false) {
+  // (keys: every score of the rows written out as a key, rounded operands only: the sample of a rounded scan)
   const int dim = int(h->cfg.dim);
 #define PROX_REGQ_DIM(DT, D, MODE)                                                                                 \
   launch_regq_dim<DT, D, MODE>(h, X, xnrm, n_rows, G, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, seed, out, s)
-  if (h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16) {
+  if (keys) {
+    if (h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16) {
+      if (dim == 384) PROX_REGQ_DIM(kDtypeBF16, 384, kRegqCoarseKeys);
+      else PROX_REGQ_DIM(kDtypeBF16, 256, kRegqCoarseKeys);
+    } else {
+      if (dim == 768) PROX_REGQ_DIM(kDtypeF32, 768, kRegqCoarseKeys);
+      else PROX_REGQ_DIM(kDtypeF32, 384, kRegqCoarseKeys);
+    }
+  } else if (h->cfg.corpus_dtype == PROXIMITY_DTYPE_BF16) {
     if (coarse) {
       if (dim == 384) PROX_REGQ_DIM(kDtypeBF16, 384, kRegqCoarse);
       else PROX_REGQ_DIM(kDtypeBF16, 256, kRegqCoarse);
@@ -579,14 +588,22 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       const int gs = kSeedRows / 128;
       // the head's scores are written out whole and merged; rows of 32 columns only: per-block lists
       const bool dump_seed = dim >= 64;
+      const bool timing = h->prof_on;   // (the sample's launches are not among the timed scans)
+      h->prof_on = false;
       for (int base = 0; base < m_limit; base += kScanPassQueries) {
         const int span = m_limit - base < kScanPassQueries ? m_limit - base : kScanPassQueries;
-        launch_batched_scan(h, kSeedRows, gs, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, nullptr,
-                            h->pairs[0], dump_seed, s);
+        if (coarse)   // the scan's own kernel and arithmetic, every score written out
+          launch_regq_scan(h, h->cfg.corpus, h->xnrm, kSeedRows, gs, Qbase, qlist, m_count_ptr, m_limit, base, span, kp,
+                           nullptr, h->pairs[0], true, s, true);
+        else
+          launch_batched_scan(h, kSeedRows, gs, Qbase, qlist, m_count_ptr, m_limit, base, span, kp, nullptr,
+                              h->pairs[0], dump_seed, s);
       }
-      // (the register-resident scan is not the kernel that scored the head: its bound gets the margin between the two)
+      h->prof_on = timing;
+      // (the register-resident scan on the operands as stored is not the kernel that scored the head: its bound
+      // gets the margin between the two; the rounded scan scored its own sample, the margin stays all the same)
       cur = enqueue_cut(h, 0, dump_seed ? long(kSeedRows) : long(gs) * kp, kp, Qbase, qlist, m_count_ptr, m_limit,
-                        regq ? (coarse ? 1 + h->coarse_level : 1) : 0, s);
+                        regq ? 1 : 0, s);
       seed = h->pairs[cur];
       cur ^= 1;  // the full scan writes into the other buffer
     }

@@ -186,6 +186,12 @@ constexpr int kRegqScan = 0, kRegqProbe = 1, kRegqDump = 2;   // what the kernel
 // for twice the rounding error, and a scan of up to 128 queries that is bound by HBM alone.  The rows' terms
 // |x|^2 stay the exact float32 ones.
 constexpr int kRegqCoarse = 3;
+// The same scores, every one written out as a packed (score, row) key -- out[m * n_rows + row] for the m-th query
+// of the miss list -- instead of filtered: the form in which the first rows of the corpus are scored as a sample
+// whose kp-th best score then starts the bounds of the scan proper (same instructions in the same order, so a row
+// scores the same in both).
+constexpr int kRegqCoarseKeys = 5;
+__host__ __device__ constexpr bool regq_mode_rounds(int mode) { return mode == kRegqCoarse || mode == kRegqCoarseKeys; }
 struct RegqRaw8 {   // eight consecutive float32 of a row, as two LDS reads return them
   f32x4 lo, hi;
 };
@@ -234,7 +240,7 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
     const uint64_t* __restrict__ seed, uint64_t* __restrict__ cand_buf, uint64_t* __restrict__ out, int cosine,
     RegqEmit emit) {
   constexpr bool ROWS32 = DT == kDtypeF32;         // float32 rows in memory and in LDS
-  constexpr bool HYB = ROWS32 && MODE == kRegqCoarse;   // ... multiplied as bfloat16
+  constexpr bool HYB = ROWS32 && regq_mode_rounds(MODE);   // ... multiplied as bfloat16
   constexpr bool F32 = ROWS32 && !HYB;             // the float32 matrix instruction
   constexpr int NW = 4;                            // waves per block
   constexpr int NT = NW * 64;
@@ -256,10 +262,10 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
   static_assert(NS >= 4 && NS <= SPT, "ring must not run more than one tile ahead (row terms are double-buffered)");
   static_assert(DIM % SLAB_COLS == 0, "whole slabs");
 
-  constexpr bool EMIT = MODE == kRegqProbe, DUMP = MODE == kRegqDump;
-  constexpr int PLANES = MODE == kRegqCoarse ? 1 : kRegqPlanes;
+  constexpr bool EMIT = MODE == kRegqProbe, KEYS = MODE == kRegqCoarseKeys, DUMP = MODE == kRegqDump || KEYS;
+  constexpr int PLANES = regq_mode_rounds(MODE) ? 1 : kRegqPlanes;
   static_assert(!EMIT || F32, "the probe's keys are float32");
-  static_assert(!DUMP || WQ == 1, "scores of one query group");
+  static_assert(!DUMP || KEYS || WQ == 1, "scores of one query group");
   const int M = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   // probe: rem_lo is the number of row slices; block b serves slice b % slices and is part b / slices of the blocks
   // that share that slice's sources (the grid need not be a multiple of the slices: a grid of one block per
@@ -656,7 +662,17 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
             for (int v = 0; v < 4; ++v) sc[4 * g + v] *= term[0][v];
           }
         }
-        if constexpr (DUMP) {   // every score of a real query goes out: four consecutive rows per store
+        if constexpr (KEYS) {   // every score of a real query goes out as a key
+          if (q_real) {
+            uint64_t* dst = out + long(m0 + q_local) * n_rows;
+#pragma unroll
+            for (int v = 0; v < AV; ++v) {
+              const uint32_t row = row0 + uint32_t(RB * b + 8 * (v / 4) + v % 4);
+              if (!kCut || row < uint32_t(n_rows)) dst[row] = pack_key(sc[v], row);
+            }
+          }
+          continue;
+        } else if constexpr (DUMP) {   // every score of a real query goes out: four consecutive rows per store
           if (q_real) {
             float* dst = emit.S + long(q_local) * emit.ldS;
 #pragma unroll
