@@ -689,17 +689,28 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
           }
           continue;
         }
-        float least = sc[0];
+        // (sixteen scores per lane: by groups of four, so that a lane with one score to hand on looks at eight
+        // values instead of sixteen -- with one wave per SIMD every compare-and-branch is paid in full, and at
+        // the usual one candidate per two row blocks that walk was a seventh of the low-reuse scan)
+        float least_of[AG];
 #pragma unroll
-        for (int v = 1; v + 1 < AV; v += 2) least = fminf(least, fminf(sc[v], sc[v + 1]));
-        least = fminf(least, sc[AV - 1]);
+        for (int g = 0; g < AG; ++g)
+          least_of[g] = fminf(fminf(sc[4 * g], fminf(sc[4 * g + 1], sc[4 * g + 2])), sc[4 * g + 3]);
+        float least = least_of[0];
+#pragma unroll
+        for (int g = 1; g + 1 < AG; g += 2) least = fminf(least, fminf(least_of[g], least_of[g + 1]));
+        if constexpr (AG > 1 && AG % 2 == 0) least = fminf(least, least_of[AG - 1]);
         if (least <= T) {
 #pragma unroll
-          for (int v = 0; v < AV; ++v)
-            if (sc[v] <= T) {
-              const uint32_t row = row0 + uint32_t(RB * b + 8 * (v / 4) + v % 4);
-              if (!kCut || row < uint32_t(n_rows)) append(sc[v], row);
-            }
+          for (int g = 0; g < AG; ++g) {
+            if (AG > 1 && !(least_of[g] <= T)) continue;
+#pragma unroll
+            for (int v = 4 * g; v < 4 * g + 4; ++v)
+              if (sc[v] <= T) {
+                const uint32_t row = row0 + uint32_t(RB * b + 8 * (v / 4) + v % 4);
+                if (!kCut || row < uint32_t(n_rows)) append(sc[v], row);
+              }
+          }
         }
       }
     };
