@@ -138,6 +138,7 @@ struct proximity {
   int64_t* res_ids = nullptr;
   float* res_d = nullptr;
   SlackState* slack = nullptr;   // is the float32 candidate list long enough? (select_kernels.hpp)
+  float* seed_bound = nullptr;   // [max_batch] the score bound a batched scan of the current call started from
   RedoBuffers redo{};            // queries noted for the second ranking of the batched scan, and their rows
   // One-plane scans of a bfloat16 corpus (kRegqCoarse): whether this instance may run them, the list length
   // they ask for, the host word the ranking kernel notes its failures in, and what the host has launched so far.
@@ -482,16 +483,14 @@ int enqueue_merge_levels(proximity* h, int cur, long len, int kp, const int* m_c
 // Per-query lists of `len` keys in pairs[cur] down to one sorted list of kp keys: merge levels while a query's
 // keys are too many for one block, then one block per query.  `margin`: see cut_lists_kernel.
 int enqueue_cut(proximity* h, int cur, long len, int kp, const float* Qbase, const int* qlist, const int* m_count_ptr,
-                int m_limit, int margin, hipStream_t s) {
+                int m_limit, int margin, int bound_rank, bool first, hipStream_t s) {
   long left = len;
   cur = enqueue_merge_levels(h, cur, len, kp, m_count_ptr, m_limit, s, kCutMaxKeys, &left);
-  if (left > kp || margin) {
-    cut_lists_kernel<<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(h->pairs[cur], left, kp, h->pairs[cur ^ 1], m_count_ptr,
-                                                                    m_limit, margin, Qbase, qlist, int(h->cfg.dim),
-                                                                    int(h->cfg.metric), h->slack);
-    cur ^= 1;
-  }
-  return cur;
+  // (always launched: it publishes the bound, also to the exactness check)
+  cut_lists_kernel<<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
+      h->pairs[cur], left, kp, h->pairs[cur ^ 1], m_count_ptr, m_limit, margin, Qbase, qlist, int(h->cfg.dim),
+      int(h->cfg.metric), h->slack, bound_rank, h->seed_bound, first ? 1 : 0);
+  return cur ^ 1;
 }
 
 // The index search for the queries listed in qlist (or rows 0..m_limit-1 of
@@ -513,7 +512,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   const int metric = int(h->cfg.metric), cosine = metric == PROXIMITY_METRIC_COSINE ? 1 : 0;
   int cur = 0;
   long left = kp;  // keys per query handed to the ranking kernel
-  bool coarse = false;
+  bool coarse = false, seeded = false;   // (seeded: the scan started from a sample's bound)
   if (!batched) {
     const int mq = stream_group(dim, m_limit);
     const int g1 = int((N + kSelSeg - 1) / kSelSeg);
@@ -567,7 +566,8 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     cur = enqueue_merge_levels(h, 0, long(g1) * kp, kp, m_count_ptr, m_limit, s, kRerankMergeKeys, &left);
   } else {
     // (the kernels below write through these: never launch them on an instance that was not given the buffers)
-    if (!h->topk_buf || !h->pairs[0] || !h->pairs[1] || (((bf16 && dim >= 64) || h->coarse_capable) && !h->qplanes))
+    if (!h->topk_buf || !h->pairs[0] || !h->pairs[1] || !h->seed_bound ||
+        (((bf16 && dim >= 64) || h->coarse_capable) && !h->qplanes))
       return fail(h, PROXIMITY_ERR_INVALID_ARG, "%d queries in one search on an instance without the batched scan's workspace",
                   m_limit);
     // Batched scan on the matrix cores, in two steps.  First the head of the corpus
@@ -575,6 +575,8 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
     // valid bound for the whole corpus and lets the full scan drop almost every row at once
     // instead of learning a bound block by block.  Then the full scan, then the merge.
     const uint64_t* seed = nullptr;
+    // which entry of a sample's list bounds the scan: the last of a list of k + 8, the same rank of a longer one
+    const int bound_rank = k + kSlack < kp ? k + kSlack : kp;
     const bool regq = regq_supported(int(h->cfg.corpus_dtype), dim);
     coarse = regq && coarse_now(h);
     if ((bf16 && dim >= 64) || coarse)
@@ -603,8 +605,9 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
       // (the register-resident scan on the operands as stored is not the kernel that scored the head: its bound
       // gets the margin between the two; the rounded scan scored its own sample, the margin stays all the same)
       cur = enqueue_cut(h, 0, dump_seed ? long(kSeedRows) : long(gs) * kp, kp, Qbase, qlist, m_count_ptr, m_limit,
-                        regq ? 1 : 0, s);
+                        regq ? 1 : 0, bound_rank, true, s);
       seed = h->pairs[cur];
+      seeded = true;
       cur ^= 1;  // the full scan writes into the other buffer
     }
     const int G = regq ? h->scan_blocks_regq : h->scan_blocks;
@@ -625,7 +628,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
                          h->pairs[cur], coarse, s);
       }
       h->prof_on = timing;
-      cur = enqueue_cut(h, cur, long(g2) * kp, kp, Qbase, qlist, m_count_ptr, m_limit, 0, s);
+      cur = enqueue_cut(h, cur, long(g2) * kp, kp, Qbase, qlist, m_count_ptr, m_limit, 0, bound_rank, false, s);
       seed = h->pairs[cur];   // (row numbers in these keys count from the sample's first row; only scores are used)
       cur ^= 1;
     }
@@ -652,7 +655,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   if (bf16) {
     rerank_f64_kernel<kDtypeBF16><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
         h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr, m_limit, res_ids, res_d, metric,
-        h->slack, h->redo, coarse ? h->coarse_level : 0);
+        h->slack, h->redo, coarse ? h->coarse_level : 0, h->seed_bound, seeded ? 1 : 0);
     redo_collect_kernel<kDtypeBF16><<<dim3((unsigned)rg), dim3(256), 0, s>>>(h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist,
                                                                              h->slack, h->redo, cosine);
     redo_rank_kernel<kDtypeBF16><<<dim3(m_limit), dim3(1024), 0, s>>>(h->cfg.corpus, dim, Qbase, qlist, h->slack,
@@ -660,7 +663,7 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
   } else {
     rerank_f64_kernel<kDtypeF32><<<dim3(m_limit), dim3(kRerankThreads), 0, s>>>(
         h->pairs[cur], n_lists, kp, k, h->cfg.corpus, dim, Qbase, qlist, m_count_ptr, m_limit, res_ids, res_d, metric,
-        h->slack, h->redo, coarse ? h->coarse_level : 0);
+        h->slack, h->redo, coarse ? h->coarse_level : 0, h->seed_bound, seeded ? 1 : 0);
     redo_collect_kernel<kDtypeF32><<<dim3((unsigned)rg), dim3(256), 0, s>>>(h->cfg.corpus, h->xnrm, N, dim, Qbase, qlist,
                                                                             h->slack, h->redo, cosine);
     redo_rank_kernel<kDtypeF32><<<dim3(m_limit), dim3(1024), 0, s>>>(h->cfg.corpus, dim, Qbase, qlist, h->slack,
@@ -882,6 +885,7 @@ int proximity_create(const proximity_config* cfg, proximity_t** out) {
   TRY_ALLOC(h->res_ids, B * k, true);
   TRY_ALLOC(h->res_d, B * k, true);
   TRY_ALLOC(h->slack, 1, true);
+  TRY_ALLOC(h->seed_bound, B, true);
   if (N > 0) {
     TRY_ALLOC(h->redo.list, B, true);
     TRY_ALLOC(h->redo.thr, B, true);

@@ -322,7 +322,12 @@ __device__ __forceinline__ double score_of_distance(int metric, double d, double
 __device__ __forceinline__ bool block_list_sufficient(const uint64_t* keys, int kp, double kth_d,
                                                       const float* __restrict__ q, int dim, int metric,
                                                       const SlackState* __restrict__ slack, double* red, float* thr,
-                                                      int tid, int coarse = 0) {
+                                                      int tid, int coarse = 0,
+                                                      float seed_bound = __builtin_inff()) {
+  // (seed_bound: the score bound the scan started from, +inf if it started from none; a row the scan turned away
+  // scores above it.  A value, not a pointer: a load through a pointer that may be null, placed under a
+  // condition that differs from lane to lane, is issued as a scalar load whatever the lanes decide -- scalar
+  // instructions ignore the execution mask -- and faults.)
   if (tid < 64) {
     double qq = 0.0;
     for (int x = tid; x < dim; x += 64) qq += double(q[x]) * double(q[x]);
@@ -331,12 +336,19 @@ __device__ __forceinline__ bool block_list_sufficient(const uint64_t* keys, int 
       const uint64_t worst = keys[kp - 1];
       bool ok = true;
       float t = __uint_as_float(0x7f800000u);
-      if (key_id(worst) >= 0) {   // a padding entry means every row of the corpus is in the list
+      // A list with a padding entry holds every row the scan did not turn away at its starting bound (bounds
+      // tighten only where a buffer has filled, and merges cut only full lists): without a starting bound that is
+      // every row of the corpus, with one the rows outside score above that bound, which then stands in for the
+      // worst kept score.
+      const bool full = key_id(worst) >= 0;
+      const bool bounded = !full && seed_bound < __uint_as_float(0x7f800000u);
+      if (full || bounded) {
+        const double worst_kept = full ? double(key_score(worst)) : double(seed_bound);
         const double x_max = sqrt(double(__uint_as_float(slack->xmax2_bits)));
         const double e = score_error_bound(metric, dim, sqrt(qq), x_max) * (1.0 + 1e-6);
         const double e_list = coarse ? e + coarse_score_error(metric, sqrt(qq), x_max, coarse) : e;
         const double t_k = score_of_distance(metric, kth_d, qq);
-        ok = double(key_score(worst)) - e_list > t_k;
+        ok = worst_kept - e_list > t_k;
         t = __double2float_ru(t_k + e);
       }
       red[0] = ok ? 1.0 : 0.0;
@@ -508,10 +520,13 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
                                                          int64_t* __restrict__ res_ids,
                                                          float* __restrict__ res_dists, int metric,
                                                          SlackState* __restrict__ slack, RedoBuffers redo,
-                                                         int coarse) {
+                                                         int coarse, const float* __restrict__ seed_bound,
+                                                         int seeded) {
+  // (seed_bound: an array of a float per query, always readable; it holds the scans' starting bounds if `seeded`)
   const int m = blockIdx.x;
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   if (m >= m_total) return;
+  const float started_from = seeded ? seed_bound[m] : __builtin_inff();
   const int qrow = qlist ? qlist[m] : m;
   const float* q = Qbase + long(qrow) * dim;
 
@@ -536,7 +551,7 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
   __syncthreads();
   // Was the list long enough?  If that cannot be shown the query is noted for the second ranking
   // (redo_collect_kernel / redo_rank_kernel), which overwrites this row of the result.
-  if (!block_list_sufficient(mine, kp, kth_d, q, dim, metric, slack, red, &thr, threadIdx.x, coarse) &&
+  if (!block_list_sufficient(mine, kp, kth_d, q, dim, metric, slack, red, &thr, threadIdx.x, coarse, started_from) &&
       threadIdx.x == 0) {
     atomicAdd(&slack->exhausted, 1ull);
     const int pos = atomicAdd(&slack->redo_count, 1);   // below the call's row count: one note per query
@@ -561,16 +576,28 @@ __global__ __launch_bounds__(kRerankThreads) void rerank_f64_kernel(const uint64
 // rounding, rows that belong in the list.  The kp-th key (the only one the scans read) then gets that margin
 // added: twice the float32 bound, plus the rounding term of a scan on rounded operands (margin = 1 + level of
 // coarse_score_error).
+// The key published in the list's last place -- the one that seeds a scan's bound -- is the list's entry number
+// bound_rank (counting from 1; kp: the last entry itself).  Any rank from k on keeps the ranking sound: that many
+// rows of the corpus score at or below the bound, so the scan's list holds at least so many rows, and the
+// exactness check knows the bound (bound_out) for the case that the list does not fill.  A scan that keeps a long
+// list because its scores are coarse starts from rank k + 8 all the same: its candidates are a matter of time, not
+// of correctness.  Where the list is shorter than bound_rank (a second sample that the first one's bound let few
+// rows of through) the earlier bound is passed on instead.
 constexpr long kCutMaxKeys = 65536;
 __global__ __launch_bounds__(kRerankThreads) void cut_lists_kernel(const uint64_t* __restrict__ in, long len, int kp,
                                                                    uint64_t* __restrict__ out,
                                                                    const int* __restrict__ m_count_ptr, int m_limit,
                                                                    int margin, const float* __restrict__ Qbase,
                                                                    const int* __restrict__ qlist, int dim, int metric,
-                                                                   const SlackState* __restrict__ slack) {
+                                                                   const SlackState* __restrict__ slack, int bound_rank,
+                                                                   float* bound_io, int first) {
+  // (bound_io: a float per query, always readable -- see block_list_sufficient on loads through pointers that may
+  // be null; unless `first`, it holds the bound of the sample before this one on entry; the bound published here
+  // on exit)
   const int m = blockIdx.x, tid = threadIdx.x;
   const int m_total = m_count_ptr ? min(*m_count_ptr, m_limit) : m_limit;
   if (m >= m_total) return;
+  const float earlier_bound = first ? __builtin_inff() : bound_io[m];
   __shared__ uint64_t list[kRerankMergeKeys];
   __shared__ uint64_t mins[kRerankThreads / 64];
   __shared__ int count;
@@ -579,8 +606,10 @@ __global__ __launch_bounds__(kRerankThreads) void cut_lists_kernel(const uint64_
   uint64_t* o = out + long(m) * kp;
   for (int i = tid; i < kp - 1; i += kRerankThreads) o[i] = list[i];
   if (tid < 64) {
-    uint64_t key = list[kp - 1];
-    if (margin && key_id(key) >= 0) {   // (a padding key is +inf already)
+    uint64_t key = list[bound_rank - 1];
+    if (key_id(key) < 0) {
+      key = pack_key(earlier_bound, 0u);   // (margin and all; +inf when there was none)
+    } else if (margin && key_id(key) >= 0) {   // (a padding key is +inf already)
       const float* q = Qbase + long(qlist ? qlist[m] : m) * dim;
       double qq = 0.0;
       for (int x = tid; x < dim; x += 64) qq += double(q[x]) * double(q[x]);
@@ -590,7 +619,10 @@ __global__ __launch_bounds__(kRerankThreads) void cut_lists_kernel(const uint64_
       if (margin >= 2) e += coarse_score_error(metric, sqrt(qq), x_max, margin - 1);
       key = pack_key(__double2float_ru(double(key_score(key)) + e * (1.0 + 1e-6)), uint32_t(key_id(key)));
     }
-    if (tid == 0) o[kp - 1] = key;
+    if (tid == 0) {
+      o[kp - 1] = key;
+      bound_io[m] = key_score(key);
+    }
   }
 }
 

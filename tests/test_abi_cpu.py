@@ -135,7 +135,7 @@ def test_build_flag_keeps_packed_float32_instructions_out_of_device_code(tmp_pat
     assert counts["with"] == 0 and counts["without"] > 0, counts
 
 
-def test_no_vector_write_right_in_front_of_a_matrix_instruction_that_reads_it(tmp_path):
+def test_device_assembly_is_free_of_two_patterns_the_compiler_does_not_guard(tmp_path):
     """The register-resident scan writes its matrix instructions in assembly, where the compiler inserts no idle
     states for them: an ordinary vector instruction that writes a register must be at least two issue slots ahead
     of a matrix instruction that reads it (accumulators set to zero by moves that the compiler sinks down to the
@@ -187,6 +187,23 @@ def test_no_vector_write_right_in_front_of_a_matrix_instruction_that_reads_it(tm
         recent = recent[-8:]
     assert n_matrix > 2000          # (the scan kernels are in there, unrolled)
     assert not found, found[:4]
+
+    # A second pattern in the same assembly: a scalar load through a pointer that is not the kernel's argument
+    # block, sitting in a stretch where the execution mask was narrowed and no branch skips it.  Scalar
+    # instructions ignore the mask, so such a load is issued whatever the lanes decided -- and a pointer that the
+    # source dereferences only "if it is not null" is then read at address zero (this faulted a GPU once: the
+    # compiler turns `cond_per_lane && p ? *p : x` into exactly this when p is the same for all lanes).
+    lines = [l.strip() for l in out.read_text().splitlines()]
+    lines = [l for l in lines if l and l[0] not in ";."]
+    unguarded = []
+    for i, text in enumerate(lines):
+        if not text.startswith("s_load_dword") or "s[0:1]" in text:
+            continue
+        before = lines[max(0, i - 6):i]
+        narrowed = [j for j, b in enumerate(before) if "saveexec" in b or re.search(r"s_(and|xor|andn2)_b64 exec,", b)]
+        if narrowed and not any("s_cbranch_exec" in b or b.endswith(":") for b in before[narrowed[-1]:]):
+            unguarded.append((text, before[narrowed[-1]:]))
+    assert not unguarded, unguarded[:3]
 
 
 def test_score_error_bound_by_hand_and_against_float32_arithmetic(binding):
