@@ -210,3 +210,38 @@ def test_a_crowd_within_the_rounding_of_the_operands(B, kind, dim, metric):
         assert st["coarse_scan_calls"] == 1 and st["coarse_scan_fails"] == n_queries, (call, st)
         assert st["slack_exhausted"] >= n_queries and st["slack_unresolved"] == 0, (call, st)
     px.close()
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+@pytest.mark.parametrize("spread", ["apart", "together"])
+def test_a_candidate_list_that_does_not_fill(B, kind, spread):
+    """A corpus in an order that defeats the sample: the only rows anywhere near the queries, eighteen of them, sit
+    among its first 16 384 rows, so the bound a scan on rounded operands takes from that sample (its eighteenth
+    best score, k + 8) lets through those eighteen rows and nothing else, and the list of about forty does not
+    fill.  The exactness check then compares the bound itself, not a kept score, with the k-th distance: where
+    the eighteen lie well apart the list is proven exact as it stands; where they lie closer together than the
+    rounding can tell it is not, and the second ranking returns the exact list."""
+    dim, k, n_docs, n_queries = 384, 10, 140_000, 24
+    rng = np.random.default_rng(21)
+    x = 3.0 * W.corpus_f32(n_docs, dim, 9)                       # far from everything below
+    centre = W.unit_rows(rng.standard_normal(dim))
+    where = np.sort(rng.choice(16_000, size=18, replace=False))
+    steps = 0.05 * np.arange(1, 19) if spread == "apart" else 0.4 + 1e-4 * np.arange(18)
+    x[where] = (centre[None, :] + steps[:, None] * W.unit_rows(rng.standard_normal((18, dim)))).astype(np.float32)
+    xd, xh = device_corpus(x, kind)
+    q = (centre[None, :] + 0.01 * W.unit_rows(rng.standard_normal((n_queries, dim)))).astype(np.float32)
+    o_ids, o_d = po.batched_exact_knn(xh, q, k)
+    assert np.isin(o_ids, where).all()
+    px = B.Proximity(xd, dim, 0, k, B.POLICY_FIFO, n_queries)
+    for call in range(2):
+        ids, dists = px.knn_batch(torch.from_numpy(q).to(DEV))
+        torch.cuda.synchronize(DEV)
+        assert (ids.cpu().numpy() == o_ids).all(), call
+        np.testing.assert_allclose(dists.cpu().numpy(), o_d, rtol=1e-5)
+    st = px.stats()
+    assert st["slack_unresolved"] == 0, st
+    if spread == "apart":
+        assert st["slack_exhausted"] == 0 and st["coarse_scan_calls"] == 2, st
+    else:
+        assert st["slack_exhausted"] >= n_queries and st["coarse_scan_fails"] == n_queries, st
+    px.close()
