@@ -115,17 +115,17 @@ def profiled_scan(torch, px, q_dev, tau, batch, first_call, n_calls, outs, devic
 # Keyed by (kernel, query-tile shape, corpus rows, dim, element bytes); anything else reports null.
 COUNTER_TRAFFIC = {
     ("scan_regq_kernel (scores only)", 0, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_512_369 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scan_regq_mid_b1.md"},
+        {"fetch_bytes": 1_512_366 * 2048, "write_bytes": 3_906 * 1024, "source": "profiles/scan_regq_mid_b1.md"},
     ("scan_regq_kernel (rounded operands)", 64, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_513_989 * 2048, "write_bytes": 13_357 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
+        {"fetch_bytes": 1_513_890 * 2048, "write_bytes": 8_473 * 1024, "source": "profiles/scan_regq_mid_b64.md"},
     ("scan_regq_kernel", 64, 1_000_000, 768, 4):
-        {"fetch_bytes": 1_514_330 * 2048, "write_bytes": 4_201 * 1024,
+        {"fetch_bytes": 1_514_328 * 2048, "write_bytes": 4_203 * 1024,
          "source": "profiles/scan_regq_mid_b64_exact.md"},
     ("scan_regq_kernel (one plane)", 128, 8_000_000, 384, 2):
-        {"fetch_bytes": 3_030_133 * 2048, "write_bytes": 58_183 * 1024,
+        {"fetch_bytes": 3_029_002 * 2048, "write_bytes": 52_286 * 1024,
          "source": "profiles/scan_regq_lowreuse_b128.md"},
     ("scan_regq_kernel (rounded operands)", 64, 24_000_000, 768, 4):
-        {"fetch_bytes": 36_060_078 * 2048, "write_bytes": 34_662 * 1024,
+        {"fetch_bytes": 36_058_895 * 2048, "write_bytes": 16_415 * 1024,
          "source": "profiles/scan_regq_large_b256.md"},
 }
 
