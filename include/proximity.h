@@ -52,7 +52,7 @@
 extern "C" {
 #endif
 
-#define PROXIMITY_ABI_VERSION 8u
+#define PROXIMITY_ABI_VERSION 9u
 
 enum {
   PROXIMITY_OK = 0,
@@ -220,6 +220,16 @@ double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_l
  */
 double proximity_coarse_score_error(uint32_t metric, uint32_t corpus_dtype, double query_length,
                                     double max_row_length);
+
+/*
+ * How many candidates per query a search on rounded operands hands to the float64 ranking when it is asked for k
+ * neighbours (k times the re-ranking factor) of n_docs rows of `dim` columns (host arithmetic, no GPU work):
+ *   k + ceil(m + 5 sqrt(m) + 16),   m = k (exp(z delta) - 1),   z = sqrt(2 ln(max(n_docs / k, 2))),
+ *   delta = sqrt(dim) / 512  (bfloat16 corpus)  or  2.002 sqrt(dim) / 512  (float32 corpus)
+ * -- m is the number of rows that isotropic data puts within the rounding error of the k-th.  Instances for which
+ * this exceeds 248 search on the operands as stored.  0 for a bad argument.
+ */
+uint32_t proximity_rounded_scan_list_length(uint32_t k, uint32_t corpus_dtype, uint32_t dim, uint64_t n_docs);
 
 /*
  * The row ranges in which proximity_search_batch() probes and resolves a call of n rows against a flat cache

@@ -20,7 +20,7 @@ ERR_INVALID_ARG, ERR_K_MISMATCH, ERR_BATCH_TOO_LARGE, ERR_BAD_TAU, ERR_HIP, ERR_
 DTYPE_F32, DTYPE_BF16 = 0, 1
 POLICY_FIFO, POLICY_LRU = 0, 1
 METRIC_L2, METRIC_IP, METRIC_COSINE = 0, 1, 2
-ABI_VERSION = 8
+ABI_VERSION = 9
 FLAG_NO_ROUNDED_SCAN = 1
 MAX_K, MAX_DIM, MAX_BATCH, MAX_CAPACITY = 240, 4096, 8192, 1 << 20   # PROXIMITY_MAX_* of the header
 STATIC_MAX_DOCS, STATIC_MAX_QUERIES = 1 << 18, 4                      # PROXIMITY_STATIC_MAX_* of the header
@@ -63,6 +63,8 @@ lib.proximity_score_error_bound.restype = C.c_double
 lib.proximity_score_error_bound.argtypes = [C.c_uint32, C.c_uint32, C.c_double, C.c_double]
 lib.proximity_coarse_score_error.restype = C.c_double
 lib.proximity_coarse_score_error.argtypes = [C.c_uint32, C.c_uint32, C.c_double, C.c_double]
+lib.proximity_rounded_scan_list_length.restype = C.c_uint32
+lib.proximity_rounded_scan_list_length.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint64]
 lib.proximity_probe_row_ranges.restype = C.c_uint32
 lib.proximity_probe_row_ranges.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                            C.POINTER(C.c_uint32), C.c_uint32]
@@ -91,7 +93,7 @@ lib.proximity_profile_start.argtypes = [_H]
 lib.proximity_profile_stop.restype = C.c_int
 lib.proximity_profile_stop.argtypes = [_H, C.POINTER(ProximityLaunch), C.c_uint32, C.POINTER(C.c_uint32)]
 
-EXPORTED = ("proximity_abi_version", "proximity_score_error_bound", "proximity_coarse_score_error", "proximity_probe_row_ranges", "proximity_last_error", "proximity_create", "proximity_destroy",
+EXPORTED = ("proximity_abi_version", "proximity_score_error_bound", "proximity_coarse_score_error", "proximity_rounded_scan_list_length", "proximity_probe_row_ranges", "proximity_last_error", "proximity_create", "proximity_destroy",
             "proximity_search_batch", "proximity_knn_batch", "proximity_knn_static", "proximity_stats", "proximity_cache_dump",
             "proximity_clear", "proximity_profile_start", "proximity_profile_stop")
 

@@ -743,6 +743,11 @@ double proximity_score_error_bound(uint32_t metric, uint32_t dim, double query_l
   return score_error_bound(int(metric), int(dim), query_length, max_row_length);
 }
 
+uint32_t proximity_rounded_scan_list_length(uint32_t k, uint32_t corpus_dtype, uint32_t dim, uint64_t n_docs) {
+  if (k == 0 || k > PROXIMITY_MAX_K || corpus_dtype > PROXIMITY_DTYPE_BF16 || dim == 0 || dim > PROXIMITY_MAX_DIM) return 0;
+  return uint32_t(coarse_list_length(int(k), corpus_dtype == PROXIMITY_DTYPE_BF16 ? 1 : 2, int(dim), double(n_docs)));
+}
+
 double proximity_coarse_score_error(uint32_t metric, uint32_t corpus_dtype, double query_length, double max_row_length) {
   if (metric > PROXIMITY_METRIC_COSINE || corpus_dtype > PROXIMITY_DTYPE_BF16 || !(query_length >= 0.0) ||
       !(max_row_length >= 0.0))

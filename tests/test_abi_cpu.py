@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol(binding):
 
 
 def test_abi_version_and_struct_layout(binding):
-    assert binding.proximity_abi_version() == 8
+    assert binding.proximity_abi_version() == 9
     assert C.sizeof(binding.ProximityConfig) == 72
     assert C.sizeof(binding.ProximityStats) == 128
     assert C.sizeof(binding.ProximityLaunch) == 20
@@ -299,6 +299,31 @@ def test_coarse_score_error_by_hand_and_against_rounded_operands(binding):
                     assert err <= bound, (corpus_dtype, dim, trial, metric, err, bound)
                     worst[corpus_dtype] = max(worst[corpus_dtype], err / bound)
     assert worst[0] > 0.02 and worst[1] > 0.02     # (not vacuous: aligned roundings come within two orders of it)
+
+
+def test_list_length_of_a_search_on_rounded_operands(binding):
+    """The candidates such a search keeps: the closed form worked here from its definition, the values the header
+    quotes, growth with k, with the corpus and with the dimension, and the float32 corpus (rows rounded too)
+    asking for more than the bfloat16 one."""
+    import math
+    L = binding.lib.proximity_rounded_scan_list_length
+
+    def by_hand(k, dtype, dim, n):
+        delta = math.sqrt(dim) / 512 * (1.0 if dtype == 1 else 2.002)
+        m = k * (math.exp(math.sqrt(2 * math.log(max(n / k, 2))) * delta) - 1)
+        return k + math.ceil(m + 5 * math.sqrt(m) + 16)
+
+    assert L(10, 0, 768, 1_000_000) == 46 and L(100, 1, 384, 8_000_000) == 159 and L(32, 0, 768, 24_000_000) == 97
+    for k in (1, 10, 100, 240):
+        for dtype in (0, 1):
+            for dim in (256, 384, 768):
+                for n in (1, 500, 1_000_000, 1 << 40):
+                    assert L(k, dtype, dim, n) == by_hand(k, dtype, dim, n), (k, dtype, dim, n)
+                    assert L(k, dtype, dim, n) >= k + 16
+    assert L(10, 0, 768, 10**6) > L(10, 1, 768, 10**6) and L(10, 0, 768, 10**8) > L(10, 0, 768, 10**6)
+    assert L(10, 0, 768, 10**6) > L(10, 0, 384, 10**6) and L(50, 0, 768, 10**6) > L(10, 0, 768, 10**6)
+    for bad in ((0, 0, 768, 100), (241, 0, 768, 100), (10, 2, 768, 100), (10, 0, 0, 100), (10, 0, 5000, 100)):
+        assert L(*bad) == 0
 
 
 def probe_ranges(b, n, capacity, max_batch, listing, n_cu=256):
