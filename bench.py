@@ -530,7 +530,9 @@ def measure_stream_workload(args, torch, np, W, Proximity, device, w, tau=None, 
     line = {
         "metric": "retrieval_queries_per_sec", "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(1e3 * dt / steps, 5), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if (elem == 2 and w.dim >= 64 and batch > 4) else "f32",
+        "scaling": "weak", "vs_baseline": None,
+        # the type the scan's products are formed in (the ranking that decides every list is float64 throughout)
+        "dtype": "bf16" if (elem == 2 and w.dim >= 64 and batch > 4) or (batch > 4 and one_plane) else "f32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: corpus {n_docs}x{w.dim} {'bf16' if elem == 2 else 'f32'} unit Gaussian, "
                                f"{w.choice}({w.zipf_s}) stream of "
