@@ -65,3 +65,36 @@ def test_recall_sweep_equals_oracle_hit_rates_and_recalls():
                 else:
                     assert row["k_recall_on_hits"] is None and row["k_recall"] == 1.0
     assert some_hits >= 6
+
+
+def test_roofline_entry_by_hand():
+    """bench.py's roofline entry for the scan kernel, worked by hand: which roof a launch is priced against (the
+    ridge is peak flops x bytes per element / (2 x planes x HBM peak) queries per launch), achieved = algorithmic
+    bytes or flops over the mean launch time, and the kernel the stats name."""
+    n, d = 1_000_000, 768
+    bytes_f32 = n * d * 4 + n * 4
+    # one query per launch, 0.46 ms: HBM-bound, the scores-only form of the register-resident kernel
+    r = bench.scan_roofline([(0.46, 1)] * 5, n, d, 1)
+    assert r["bound"] == "hbm" and r["kernel"] == "scan_regq_kernel (scores only)"
+    assert r["achieved"] == pytest.approx(bytes_f32 / 0.46e-3 / 1e9, rel=1e-4)
+    assert r["frac"] == pytest.approx(bytes_f32 / 0.46e-3 / 1e9 / 8000.0, abs=1e-4)
+    assert r["algorithmic_bytes_per_launch"] == bytes_f32 and r["traffic_counters"]["measured_in_this_run"] is False
+    # 64 queries on the operands as stored: float32 matrix-bound (ridge 157.3e12 / 8e12 * 4 / 2 = 39 queries)
+    r = bench.scan_roofline([(0.77, 64)] * 3, n, d, 64)
+    assert r["bound"] == "mfma" and r["kernel"] == "scan_regq_kernel" and r["peak"] == 157.3
+    assert r["achieved"] == pytest.approx(2.0 * 64 * n * d / 0.77e-3 / 1e12, rel=1e-3)
+    # the same launch on rounded operands: bfloat16 matrix cores, one plane: ridge at 625 queries, so HBM-bound
+    r = bench.scan_roofline([(0.5, 64)] * 3, n, d, 64, 4, True)
+    assert r["bound"] == "hbm" and r["kernel"] == "scan_regq_kernel (rounded operands)"
+    assert r["achieved"] == pytest.approx(bytes_f32 / 0.5e-3 / 1e9, rel=1e-4)
+    assert r["achieved_TFLOPs"] == pytest.approx(2.0 * 64 * n * d / 0.5e-3 / 1e12, rel=1e-3)
+    # a bfloat16 corpus, 128 queries: two planes put the ridge at 156 queries, one plane at 312
+    nb, db = 8_000_000, 384
+    r2 = bench.scan_roofline([(1.5, 127)] * 2, nb, db, 128, 2, False)
+    r1 = bench.scan_roofline([(1.1, 127)] * 2, nb, db, 128, 2, True)
+    assert r2["bound"] == "hbm" and r2["kernel"] == "scan_regq_kernel" and r1["kernel"] == "scan_regq_kernel (one plane)"
+    assert r2["achieved_TFLOPs"] == pytest.approx(2 * 2.0 * 127 * nb * db / 1.5e-3 / 1e12, rel=1e-3)
+    assert r1["achieved_TFLOPs"] == pytest.approx(2.0 * 127 * nb * db / 1.1e-3 / 1e12, rel=1e-3)
+    r3 = bench.scan_roofline([(1.5, 200)] * 2, nb, db, 256, 2, False)        # past the two-plane ridge
+    assert r3["bound"] == "mfma" and r3["peak"] == 2500.0
+    assert bench.scan_roofline([], n, d, 1) is None
