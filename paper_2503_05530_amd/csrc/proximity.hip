@@ -570,10 +570,10 @@ int enqueue_scan(proximity* h, const float* Qbase, const int* qlist, const int* 
         (((bf16 && dim >= 64) || h->coarse_capable) && !h->qplanes))
       return fail(h, PROXIMITY_ERR_INVALID_ARG, "%d queries in one search on an instance without the batched scan's workspace",
                   m_limit);
-    // Batched scan on the matrix cores, in two steps.  First the head of the corpus
-    // (kSeedRows rows) is scanned and merged on its own: its kp-th best score per query is a
-    // valid bound for the whole corpus and lets the full scan drop almost every row at once
-    // instead of learning a bound block by block.  Then the full scan, then the merge.
+    // Batched scan on the matrix cores, in two steps.  First the head of the corpus (kSeedRows rows) is scanned
+    // and cut on its own: one of its best scores per query (bound_rank below) is a valid bound for the whole
+    // corpus and lets the full scan drop almost every row at once instead of learning a bound block by block.
+    // Then the full scan, then the merge.
     const uint64_t* seed = nullptr;
     // which entry of a sample's list bounds the scan: the last of a list of k + 8, the same rank of a longer one
     const int bound_rank = k + kSlack < kp ? k + kSlack : kp;

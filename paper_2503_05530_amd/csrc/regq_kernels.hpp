@@ -188,7 +188,7 @@ constexpr int kRegqScan = 0, kRegqProbe = 1, kRegqDump = 2;   // what the kernel
 constexpr int kRegqCoarse = 3;
 // The same scores, every one written out as a packed (score, row) key -- out[m * n_rows + row] for the m-th query
 // of the miss list -- instead of filtered: the form in which the first rows of the corpus are scored as a sample
-// whose kp-th best score then starts the bounds of the scan proper (same instructions in the same order, so a row
+// one of whose best scores then starts the bounds of the scan proper (same instructions in the same order, so a row
 // scores the same in both).
 constexpr int kRegqCoarseKeys = 5;
 __host__ __device__ constexpr bool regq_mode_rounds(int mode) { return mode == kRegqCoarse || mode == kRegqCoarseKeys; }
@@ -345,8 +345,10 @@ __global__ __launch_bounds__(256, 1) void scan_regq_kernel(
       }
       bound[i] = b;
     } else {
-      // starting bound: the kp-th best score of a sample of the corpus, if the caller has one
-      // (a padding key gives +inf); any value at or above the true kp-th best score is valid
+      // starting bound: the last key of the caller's seed list, if it has one -- the kp-th best score of a
+      // sample of the corpus, or a better-ranked one that cut_lists_kernel put there (a padding key gives +inf).
+      // At least k + 8 rows of the corpus score at or below it, which is all the ranking needs; the exactness
+      // check is told the bound for the case that fewer than kp do
       bound[i] = (seed && m0 + i < M) ? key_score(seed[long(m0 + i) * kp + kp - 1]) : __uint_as_float(0x7f800000u);
     }
     count[i] = 0;
